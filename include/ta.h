@@ -1,0 +1,176 @@
+/*
+ * ta.h -- C ABI of the paged-KV attention hot path for AMD MI355X (gfx950).
+ *
+ * The paper this library serves (ThunderAgent) schedules long-lived agent
+ * programs over inference backends.  Each program's context only grows and is
+ * kept as a KV cache between turns (Sec. 2.1); a step prefills the new
+ * tool-output tokens against the retained prefix and then decodes (the two
+ * productive terms of the cost decomposition, Sec. 4.2, Eq. 3); a paused
+ * program loses its pages and a restored one needs them back (Sec. 4.3,
+ * Eq. 4-5; host offloading in App. A.2 and A.4).  The paper treats the backend
+ * as a black box; this library is the device-side part of that backend:
+ *
+ *   ta_paged_decode      one new token per program attends to the program's
+ *                        whole cached context;
+ *   ta_append_prefill    n new tokens per program attend causally to prefix +
+ *                        themselves;
+ *   ta_kv_page_restore   pages held in pinned host memory are written back
+ *                        into free slots of the device page pool.
+ *
+ * Common conventions
+ *   - Every pointer is labelled DEVICE or HOST.  DEVICE pointers are HIP device
+ *     allocations on the current device; the library never allocates or frees.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and the call returns without synchronising.
+ *     HOST arrays are consumed before the call returns.
+ *   - bf16 values are 16-bit patterns (upper half of an IEEE fp32).
+ *   - Token j of program b lives in page block_table[b*stride + j/page_size],
+ *     row j % page_size.  With the default pool layout [P][Hkv][page_size][d]
+ *     one (page, kv head) tile is 4 KiB contiguous.  Query head h reads kv head
+ *     h / (Hq/Hkv).  Pages may be shared between programs; the attention calls
+ *     only read the pools.
+ *   - Block-table entries beyond ceil(context_len/page_size) are ignored.  Rows
+ *     of the last page beyond the context length are never read into a result.
+ *   - Device-resident metadata is not validated: a block-table entry outside
+ *     the pool or a context length beyond stride*page_size is undefined
+ *     behaviour.  Everything the host can see is validated before any launch.
+ *   - Return value: TA_OK (0) or a negative ta_status.  No exceptions, no
+ *     aborts, nothing is printed.  batch == 0, total_q == 0 and n_pages == 0
+ *     are valid and do nothing.
+ */
+#ifndef TA_H
+#define TA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ta_status {
+    TA_OK = 0,
+    TA_ERR_INVALID_ARG = -1, /* null pointer, negative size, Hq % Hkv != 0, workspace too small,
+                                slot out of range or duplicated, ... */
+    TA_ERR_UNSUPPORTED = -2, /* head_dim != 128, page_size != 16, group size not in {1,2,4,8},
+                                token stride != head_dim, misaligned strides */
+    TA_ERR_HIP = -3          /* a HIP call failed; see ta_last_hip_error() */
+} ta_status;
+
+typedef struct ta_attn_desc {
+    int32_t num_q_heads;       /* Hq */
+    int32_t num_kv_heads;      /* Hkv, divides Hq; Hq/Hkv in {1,2,4,8} */
+    int32_t head_dim;          /* 128 */
+    int32_t page_size;         /* 16 tokens */
+    float scale;               /* multiplies q.k; 0.0f selects 1/sqrt(head_dim) */
+    int32_t reserved;          /* must be 0 */
+    int64_t pool_stride_page;  /* elements between pages;       0 selects Hkv*page_size*head_dim */
+    int64_t pool_stride_head;  /* elements between kv heads;    0 selects page_size*head_dim */
+    int64_t pool_stride_token; /* elements between token rows;  0 selects head_dim (only value supported) */
+} ta_attn_desc;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t ta_version(void);
+
+/* Text for a ta_status value (static storage). */
+const char *ta_strerror(int status);
+
+/* The hipError_t (as int) of the last failed HIP call on this thread, 0 if none. */
+int ta_last_hip_error(void);
+
+/*
+ * Bytes of DEVICE workspace that ta_paged_decode (max_q_len <= 1) or
+ * ta_append_prefill needs for `batch` programs, at most `max_q_len` query
+ * tokens per program and at most `max_context_len` cached tokens per program.
+ * Returns 0 for an invalid descriptor.  The workspace holds the work plan and
+ * the split-K partial results (running max, sum and unnormalised output per
+ * chunk of the key axis); its contents need not survive between calls.
+ */
+size_t ta_workspace_bytes(const ta_attn_desc *desc, int32_t batch, int32_t max_q_len,
+                          int32_t max_context_len);
+
+/*
+ * Decode (Sec. 2.1: the emission is sampled conditioned on the whole context;
+ * Sec. 4.3: context lengths keep growing during decoding).  For every program
+ * b and query head h:
+ *     out[b][h][:] = softmax_j(scale * <q[b][h], K_j>) . V_j,   j < context_lens[b]
+ * computed with bf16 inputs, fp32 accumulation, bf16 output (round to nearest
+ * even).  context_lens[b] counts every cached token including the newest one.
+ * A program with context length 0 gets a zero row and lse = -inf.
+ *
+ *   q             DEVICE bf16 [batch][Hq][128]
+ *   k_pool,v_pool DEVICE bf16, layout given by desc, read only, 16-byte aligned
+ *   block_table   DEVICE int32 [batch][block_table_stride]
+ *   context_lens  DEVICE int32 [batch]
+ *   max_context_len  HOST upper bound on context_lens[]; sizes the launch, so no
+ *                 device-to-host copy is needed.  Lengths above it are undefined.
+ *   out           DEVICE bf16 [batch][Hq][128]
+ *   lse           DEVICE fp32 [batch][Hq] natural-log sum of exponentials, or NULL
+ *   workspace     DEVICE, at least ta_workspace_bytes(desc, batch, 1, max_context_len),
+ *                 256-byte aligned
+ */
+int ta_paged_decode(const ta_attn_desc *desc, const void *q, const void *k_pool,
+                    const void *v_pool, const int32_t *block_table, int32_t block_table_stride,
+                    const int32_t *context_lens, int32_t batch, int32_t max_context_len,
+                    void *out, float *lse, void *workspace, size_t workspace_bytes,
+                    void *hip_stream);
+
+/*
+ * Append-prefill (Sec. 4.2: incremental prefilling of tool-execution results,
+ * as opposed to recomputation over the full context).  Program b owns
+ * n_b = cu_q_lens[b+1] - cu_q_lens[b] new tokens whose keys and values are
+ * ALREADY in its pages, so context_lens[b] = prefix_b + n_b.  New token i
+ * (0-based) sees keys 0 .. prefix_b + i, itself included:
+ *     out[cu_q_lens[b]+i][h][:] = softmax_j(scale * <q, K_j>) . V_j,  j <= prefix_b + i
+ * bf16 inputs, fp32 accumulation on the matrix cores, bf16 output.
+ *
+ *   q             DEVICE bf16 [total_q][Hq][128], programs packed back to back
+ *   cu_q_lens     DEVICE int32 [batch+1], non-decreasing, cu_q_lens[0] = 0
+ *   total_q       HOST, equals cu_q_lens[batch]
+ *   max_q_len     HOST upper bound on n_b
+ *   max_context_len HOST upper bound on context_lens[]
+ *   out           DEVICE bf16 [total_q][Hq][128]
+ *   lse           DEVICE fp32 [total_q][Hq] or NULL
+ *   workspace     DEVICE, at least ta_workspace_bytes(desc, batch, max_q_len, max_context_len)
+ * Other arguments as for ta_paged_decode.
+ */
+int ta_append_prefill(const ta_attn_desc *desc, const void *q, const int32_t *cu_q_lens,
+                      const void *k_pool, const void *v_pool, const int32_t *block_table,
+                      int32_t block_table_stride, const int32_t *context_lens, int32_t batch,
+                      int32_t total_q, int32_t max_q_len, int32_t max_context_len, void *out,
+                      float *lse, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Bytes of DEVICE staging that ta_kv_page_restore needs at least (the slot
+ * list), and the size from which it switches from reading the pinned host
+ * pages directly inside the scatter kernel to staging them through large
+ * host-to-device copies.
+ */
+size_t ta_restore_staging_min_bytes(int32_t n_pages);
+size_t ta_restore_staging_full_bytes(int32_t n_pages, size_t page_bytes);
+
+/*
+ * KV page restore (Sec. 4.3: Restore re-admits a paused program whose KV cache
+ * was released; App. A.2/A.4: the pages come back from host memory over the
+ * host link).  Bytes only, bit-exact:
+ *     k_pool[dst_slots[i]] = host_k[i],  v_pool[dst_slots[i]] = host_v[i],  i < n_pages
+ * Pages not named in dst_slots are left untouched.
+ *
+ *   k_pool,v_pool DEVICE, pool_pages pages of page_bytes each, contiguous
+ *   page_bytes    bytes of one page of K over all kv heads (Hkv*16*128*2), multiple of 16
+ *   host_k,host_v HOST, pinned (hipHostMalloc), [n_pages][page_bytes] contiguous;
+ *                 must stay valid until the stream reaches the end of this call
+ *   dst_slots     HOST int32 [n_pages], distinct, each in [0, pool_pages); copied before return
+ *   staging       DEVICE scratch of staging_bytes >= ta_restore_staging_min_bytes(n_pages).
+ *                 With at least ta_restore_staging_full_bytes() the pages travel as
+ *                 large host-to-device copies into staging and a kernel scatters them;
+ *                 with less, the scatter kernel reads the pinned host pages directly.
+ */
+int ta_kv_page_restore(void *k_pool, void *v_pool, size_t page_bytes, const void *host_k,
+                       const void *host_v, const int32_t *dst_slots, int32_t n_pages,
+                       int32_t pool_pages, void *staging, size_t staging_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TA_H */

@@ -1,0 +1,15 @@
+"""fp64 CPU oracle for attention over a paged KV cache (test infrastructure only).
+
+Only the tests, the smoke check and the benchmark's cpu_baseline leg may import
+this package.  It never imports the HIP library or its Python binding.
+"""
+from .ta_oracle import (  # noqa: F401
+    Geometry,
+    append_prefill,
+    attend_rows,
+    build,
+    kv_page_restore,
+    num_threads,
+    paged_decode,
+    row_probs,
+)
