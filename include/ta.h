@@ -48,6 +48,9 @@
 extern "C" {
 #endif
 
+/* Exported symbols keep default visibility; everything else in the library is hidden. */
+#define TA_API __attribute__((visibility("default")))
+
 typedef enum ta_status {
     TA_OK = 0,
     TA_ERR_INVALID_ARG = -1, /* null pointer, negative size, Hq % Hkv != 0, workspace too small,
@@ -70,13 +73,13 @@ typedef struct ta_attn_desc {
 } ta_attn_desc;
 
 /* Library version, major*10000 + minor*100 + patch. */
-int32_t ta_version(void);
+TA_API int32_t ta_version(void);
 
 /* Text for a ta_status value (static storage). */
-const char *ta_strerror(int status);
+TA_API const char *ta_strerror(int status);
 
 /* The hipError_t (as int) of the last failed HIP call on this thread, 0 if none. */
-int ta_last_hip_error(void);
+TA_API int ta_last_hip_error(void);
 
 /*
  * Bytes of DEVICE workspace that ta_paged_decode (max_q_len <= 1) or
@@ -86,7 +89,7 @@ int ta_last_hip_error(void);
  * the split-K partial results (running max, sum and unnormalised output per
  * chunk of the key axis); its contents need not survive between calls.
  */
-size_t ta_workspace_bytes(const ta_attn_desc *desc, int32_t batch, int32_t max_q_len,
+TA_API size_t ta_workspace_bytes(const ta_attn_desc *desc, int32_t batch, int32_t max_q_len,
                           int32_t max_context_len);
 
 /*
@@ -109,7 +112,7 @@ size_t ta_workspace_bytes(const ta_attn_desc *desc, int32_t batch, int32_t max_q
  *   workspace     DEVICE, at least ta_workspace_bytes(desc, batch, 1, max_context_len),
  *                 256-byte aligned
  */
-int ta_paged_decode(const ta_attn_desc *desc, const void *q, const void *k_pool,
+TA_API int ta_paged_decode(const ta_attn_desc *desc, const void *q, const void *k_pool,
                     const void *v_pool, const int32_t *block_table, int32_t block_table_stride,
                     const int32_t *context_lens, int32_t batch, int32_t max_context_len,
                     void *out, float *lse, void *workspace, size_t workspace_bytes,
@@ -134,7 +137,7 @@ int ta_paged_decode(const ta_attn_desc *desc, const void *q, const void *k_pool,
  *   workspace     DEVICE, at least ta_workspace_bytes(desc, batch, max_q_len, max_context_len)
  * Other arguments as for ta_paged_decode.
  */
-int ta_append_prefill(const ta_attn_desc *desc, const void *q, const int32_t *cu_q_lens,
+TA_API int ta_append_prefill(const ta_attn_desc *desc, const void *q, const int32_t *cu_q_lens,
                       const void *k_pool, const void *v_pool, const int32_t *block_table,
                       int32_t block_table_stride, const int32_t *context_lens, int32_t batch,
                       int32_t total_q, int32_t max_q_len, int32_t max_context_len, void *out,
@@ -146,8 +149,8 @@ int ta_append_prefill(const ta_attn_desc *desc, const void *q, const int32_t *cu
  * pages directly inside the scatter kernel to staging them through large
  * host-to-device copies.
  */
-size_t ta_restore_staging_min_bytes(int32_t n_pages);
-size_t ta_restore_staging_full_bytes(int32_t n_pages, size_t page_bytes);
+TA_API size_t ta_restore_staging_min_bytes(int32_t n_pages);
+TA_API size_t ta_restore_staging_full_bytes(int32_t n_pages, size_t page_bytes);
 
 /*
  * KV page restore (Sec. 4.3: Restore re-admits a paused program whose KV cache
@@ -166,7 +169,7 @@ size_t ta_restore_staging_full_bytes(int32_t n_pages, size_t page_bytes);
  *                 large host-to-device copies into staging and a kernel scatters them;
  *                 with less, the scatter kernel reads the pinned host pages directly.
  */
-int ta_kv_page_restore(void *k_pool, void *v_pool, size_t page_bytes, const void *host_k,
+TA_API int ta_kv_page_restore(void *k_pool, void *v_pool, size_t page_bytes, const void *host_k,
                        const void *host_v, const int32_t *dst_slots, int32_t n_pages,
                        int32_t pool_pages, void *staging, size_t staging_bytes, void *hip_stream);
 

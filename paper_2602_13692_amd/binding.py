@@ -1,0 +1,192 @@
+"""ctypes binding of the HIP library: same names as the C ABI, argument marshalling only.
+
+Tensors are torch tensors (device memory and streams are torch's); every step
+of the computation runs in the library's kernels.  If the library is missing
+the import of any entry point fails loudly; there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libta_hip.so")
+
+TA_OK = 0
+TA_ERR_INVALID_ARG = -1
+TA_ERR_UNSUPPORTED = -2
+TA_ERR_HIP = -3
+
+EXPORTS = (
+    "ta_version", "ta_strerror", "ta_last_hip_error", "ta_workspace_bytes", "ta_paged_decode",
+    "ta_append_prefill", "ta_restore_staging_min_bytes", "ta_restore_staging_full_bytes",
+    "ta_kv_page_restore",
+)
+
+
+class TaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        text = _lib().ta_strerror(status).decode()
+        extra = f" (hipError {_lib().ta_last_hip_error()})" if status == TA_ERR_HIP else ""
+        super().__init__(f"{where}: {text}{extra}")
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [
+        ("num_q_heads", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("page_size", ctypes.c_int32),
+        ("scale", ctypes.c_float),
+        ("reserved", ctypes.c_int32),
+        ("pool_stride_page", ctypes.c_int64),
+        ("pool_stride_head", ctypes.c_int64),
+        ("pool_stride_token", ctypes.c_int64),
+    ]
+
+
+@dataclass
+class Desc:
+    num_q_heads: int
+    num_kv_heads: int
+    head_dim: int = 128
+    page_size: int = 16
+    scale: float = 0.0
+    pool_stride_page: int = 0
+    pool_stride_head: int = 0
+    pool_stride_token: int = 0
+
+    def c(self) -> AttnDesc:
+        return AttnDesc(self.num_q_heads, self.num_kv_heads, self.head_dim, self.page_size,
+                        self.scale, 0, self.pool_stride_page, self.pool_stride_head,
+                        self.pool_stride_token)
+
+
+_LIB = None
+
+
+def _lib():
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2602_13692_amd.build` "
+                "(there is no fallback path)")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        lib.ta_version.restype = i32
+        lib.ta_strerror.restype = ctypes.c_char_p
+        lib.ta_strerror.argtypes = [ctypes.c_int]
+        lib.ta_last_hip_error.restype = ctypes.c_int
+        lib.ta_workspace_bytes.restype = sz
+        lib.ta_workspace_bytes.argtypes = [vp, i32, i32, i32]
+        lib.ta_paged_decode.restype = ctypes.c_int
+        lib.ta_paged_decode.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, sz, vp]
+        lib.ta_append_prefill.restype = ctypes.c_int
+        lib.ta_append_prefill.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, vp, vp,
+                                          vp, sz, vp]
+        lib.ta_restore_staging_min_bytes.restype = sz
+        lib.ta_restore_staging_min_bytes.argtypes = [i32]
+        lib.ta_restore_staging_full_bytes.restype = sz
+        lib.ta_restore_staging_full_bytes.argtypes = [i32, sz]
+        lib.ta_kv_page_restore.restype = ctypes.c_int
+        lib.ta_kv_page_restore.argtypes = [vp, vp, sz, vp, vp, vp, i32, i32, vp, sz, vp]
+        _LIB = lib
+    return _LIB
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != TA_OK:
+        raise TaError(status, where)
+
+
+def ta_version() -> int:
+    return int(_lib().ta_version())
+
+
+def ta_strerror(status: int) -> str:
+    return _lib().ta_strerror(status).decode()
+
+
+def ta_last_hip_error() -> int:
+    return int(_lib().ta_last_hip_error())
+
+
+def ta_workspace_bytes(desc: Desc, batch: int, max_q_len: int, max_context_len: int) -> int:
+    d = desc.c()
+    return int(_lib().ta_workspace_bytes(ctypes.byref(d), batch, max_q_len, max_context_len))
+
+
+def ta_paged_decode(desc: Desc, q, k_pool, v_pool, block_table, context_lens, max_context_len: int,
+                    out, lse, workspace, stream=None, check: bool = True) -> int:
+    """q,out bf16 [B,Hq,128]; pools bf16; block_table int32 [B,stride]; context_lens int32 [B]."""
+    d = desc.c()
+    rc = _lib().ta_paged_decode(
+        ctypes.byref(d), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
+        int(block_table.shape[1]) if block_table is not None and block_table.dim() == 2 else 0,
+        _ptr(context_lens), int(context_lens.shape[0]) if context_lens is not None else 0,
+        int(max_context_len), _ptr(out), _ptr(lse), _ptr(workspace),
+        int(workspace.numel() * workspace.element_size()) if workspace is not None else 0,
+        _stream(stream))
+    if check:
+        _check(rc, "ta_paged_decode")
+    return rc
+
+
+def ta_append_prefill(desc: Desc, q, cu_q_lens, k_pool, v_pool, block_table, context_lens,
+                      total_q: int, max_q_len: int, max_context_len: int, out, lse, workspace,
+                      stream=None, check: bool = True) -> int:
+    """q,out bf16 [total_q,Hq,128]; cu_q_lens int32 [B+1]; the rest as for ta_paged_decode."""
+    d = desc.c()
+    rc = _lib().ta_append_prefill(
+        ctypes.byref(d), _ptr(q), _ptr(cu_q_lens), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
+        int(block_table.shape[1]) if block_table is not None and block_table.dim() == 2 else 0,
+        _ptr(context_lens), int(context_lens.shape[0]) if context_lens is not None else 0,
+        int(total_q), int(max_q_len), int(max_context_len), _ptr(out), _ptr(lse), _ptr(workspace),
+        int(workspace.numel() * workspace.element_size()) if workspace is not None else 0,
+        _stream(stream))
+    if check:
+        _check(rc, "ta_append_prefill")
+    return rc
+
+
+def ta_restore_staging_min_bytes(n_pages: int) -> int:
+    return int(_lib().ta_restore_staging_min_bytes(n_pages))
+
+
+def ta_restore_staging_full_bytes(n_pages: int, page_bytes: int) -> int:
+    return int(_lib().ta_restore_staging_full_bytes(n_pages, page_bytes))
+
+
+def ta_kv_page_restore(k_pool, v_pool, page_bytes: int, host_k, host_v, dst_slots, pool_pages: int,
+                       staging, stream=None, check: bool = True) -> int:
+    """host_k/host_v: pinned CPU tensors [n,...]; dst_slots: CPU int32 tensor [n]."""
+    n = int(dst_slots.shape[0]) if dst_slots is not None else 0
+    rc = _lib().ta_kv_page_restore(
+        _ptr(k_pool), _ptr(v_pool), int(page_bytes), _ptr(host_k), _ptr(host_v), _ptr(dst_slots), n,
+        int(pool_pages), _ptr(staging),
+        int(staging.numel() * staging.element_size()) if staging is not None else 0, _stream(stream))
+    if check:
+        _check(rc, "ta_kv_page_restore")
+    return rc
+
+
+def alloc_workspace(desc: Desc, batch: int, max_q_len: int, max_context_len: int, device="cuda"):
+    """A uint8 device tensor of ta_workspace_bytes (torch's allocator aligns to 512 bytes)."""
+    n = ta_workspace_bytes(desc, batch, max_q_len, max_context_len)
+    if n == 0:
+        raise TaError(TA_ERR_INVALID_ARG, "ta_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)

@@ -1,0 +1,463 @@
+// Paged decode attention for gfx950: one query token per program attends to the
+// program's whole cached context (ThunderAgent Sec. 2.1; the decode term of the
+// cost decomposition, Sec. 4.2, Eq. 3).
+//
+// Three kernels per call:
+//   plan    cuts every program's pages into fixed-length chunks of the key axis
+//           and lists them flat, so ragged batches keep all CUs busy;
+//   chunk   one workgroup per (chunk, kv head): streams the chunk's K and V
+//           pages from HBM once, serves all Hq/Hkv query heads of the group
+//           from the same registers, keeps an online softmax per 16-lane row,
+//           writes one partial (max, sum, unnormalised output) per query head;
+//   merge   combines the partials of a (program, query head) and writes bf16.
+//
+// The work is HBM-bound (4 flop per KV byte at group size 4), so it runs on the
+// vector ALUs: packed bf16 dot products for q.k, fp32 FMAs for p.v.
+#include "ta_internal.h"
+
+namespace ta {
+namespace {
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int kChunkThreads = 256;  // 4 waves
+constexpr int kChunkWaves = 4;
+
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b),
+                                           acc, false);
+}
+
+// Sum over the 16 lanes of a DPP row; every lane of the row ends with the total.
+__device__ __forceinline__ float row16_sum(float x) {
+    // quad_perm [1,0,3,2]
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0xB1, 0xF, 0xF, true));
+    // quad_perm [2,3,0,1]
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x4E, 0xF, 0xF, true));
+    // row_half_mirror: lane i <-> 7 - i, crosses the two quads of a half row
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x141, 0xF, 0xF, true));
+    // row_mirror: lane i <-> 15 - i, crosses the two half rows
+    x += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x140, 0xF, 0xF, true));
+    return x;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
+
+__device__ __forceinline__ uint16_t to_bf16_rne(float f) {
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40);  // quiet NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+
+// ---------------------------------------------------------------------------
+// plan: exclusive scan of ceil(L_b / chunk_tokens) and the flat item list
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void plan_chunks_kernel(const int32_t* __restrict__ context_lens,
+                                                           int32_t batch, int32_t chunk_tokens,
+                                                           int32_t max_per_program,
+                                                           int32_t* __restrict__ chunk_start,
+                                                           int2* __restrict__ items) {
+    __shared__ int32_t scan[1024];
+    __shared__ int32_t carry;
+    const int tid = threadIdx.x;
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < batch; base += 1024) {
+        const int b = base + tid;
+        int n = 0;
+        if (b < batch) {
+            const int L = context_lens[b];
+            n = L > 0 ? (L + chunk_tokens - 1) / chunk_tokens : 0;
+            n = n > max_per_program ? max_per_program : n;  // lengths above the host bound are clipped
+        }
+        scan[tid] = n;
+        __syncthreads();
+        for (int off = 1; off < 1024; off <<= 1) {
+            const int v = tid >= off ? scan[tid - off] : 0;
+            __syncthreads();
+            scan[tid] += v;
+            __syncthreads();
+        }
+        const int first = carry + scan[tid] - n;
+        if (b < batch) {
+            chunk_start[b] = first;
+            for (int c = 0; c < n; ++c) items[first + c] = make_int2(b, c);
+        }
+        __syncthreads();
+        if (tid == 1023) carry += scan[1023];
+        __syncthreads();
+    }
+    if (tid == 0) chunk_start[batch] = carry;
+}
+
+// ---------------------------------------------------------------------------
+// chunk kernel
+// ---------------------------------------------------------------------------
+struct ChunkParams {
+    const uint16_t* q;
+    const char* k_pool;
+    const char* v_pool;
+    const int32_t* block_table;
+    const int32_t* context_lens;
+    const int32_t* chunk_start;  // [batch + 1]
+    const int2* items;
+    float* part_ml;
+    float* part_o;
+    int64_t stride_page_bytes;
+    int64_t stride_head_bytes;
+    int32_t block_table_stride;
+    int32_t batch;
+    int32_t num_q_heads;
+    int32_t num_kv_heads;
+    int32_t chunk_pages;
+    float scale_log2;
+};
+
+struct PageRegs {
+    u32x4 k[4];  // k[i]: token 4*i + (lane / 16), dims 8 * (lane % 16) .. + 7
+    u32x4 v[4];
+};
+
+// The K/V stream is software-pipelined in source: the loads of the next page are
+// written before the arithmetic on the current one, and a scheduling barrier
+// right after them keeps the compiler from moving them back down next to their
+// first use.  The waits themselves (s_waitcnt vmcnt) are the compiler's, so every
+// register is known to have landed before it is read.
+__device__ __forceinline__ void load_page(PageRegs& r, const char* k_tile, const char* v_tile, int lane) {
+    const u32x4* kp = reinterpret_cast<const u32x4*>(k_tile) + lane;
+    const u32x4* vp = reinterpret_cast<const u32x4*>(v_tile) + lane;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r.k[i] = __builtin_nontemporal_load(kp + i * 64);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r.v[i] = __builtin_nontemporal_load(vp + i * 64);
+}
+
+// One 16-token page against the G query heads of the group.
+//   qreg[h][0..3]  this lane's 8 dims of query head h, packed bf16
+//   m, l, o        online-softmax state of this lane's 16-lane row (raw-score max,
+//                  sum of weights, unnormalised output for this lane's 8 dims)
+//   valid          tokens of this page that exist (16 unless MASKED)
+template <int G, bool MASKED>
+__device__ __forceinline__ void process_page(const PageRegs& pg, const uint32_t (&qreg)[G][4],
+                                             float (&m)[G], float (&l)[G], float (&o)[G][8],
+                                             float scale_log2, int row, int valid) {
+    float s[4][G];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t kw[4] = {pg.k[i].x, pg.k[i].y, pg.k[i].z, pg.k[i].w};
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) acc = dot2_bf16(kw[w], qreg[h][w], acc);
+            s[i][h] = acc;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int h = 0; h < G; ++h) s[i][h] = row16_sum(s[i][h]);
+
+    if (MASKED) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bool ok = (4 * i + row) < valid;
+#pragma unroll
+            for (int h = 0; h < G; ++h) s[i][h] = ok ? s[i][h] : -INFINITY;
+        }
+    }
+
+    float p[4][G];
+    float alpha[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        const float mx = fmaxf(fmaxf(s[0][h], s[1][h]), fmaxf(s[2][h], s[3][h]));
+        const float m_new = fmaxf(m[h], mx);
+        alpha[h] = fast_exp2((m[h] - m_new) * scale_log2);
+        const float bias = -m_new * scale_log2;
+        float psum = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            p[i][h] = fast_exp2(fmaf(s[i][h], scale_log2, bias));
+            psum += p[i][h];
+        }
+        m[h] = m_new;
+        l[h] = fmaf(l[h], alpha[h], psum);
+    }
+
+    uint32_t vw[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        vw[i][0] = pg.v[i].x; vw[i][1] = pg.v[i].y; vw[i][2] = pg.v[i].z; vw[i][3] = pg.v[i].w;
+    }
+    if (MASKED) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bool ok = (4 * i + row) < valid;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) vw[i][w] = ok ? vw[i][w] : 0u;
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) o[h][c] *= alpha[h];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                o[h][2 * w] = fmaf(p[i][h], bf16_lo(vw[i][w]), o[h][2 * w]);
+                o[h][2 * w + 1] = fmaf(p[i][h], bf16_hi(vw[i][w]), o[h][2 * w + 1]);
+            }
+        }
+    }
+}
+
+template <int G>
+__global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams p) {
+    const int n_items = p.chunk_start[p.batch];
+    const int item = blockIdx.x / p.num_kv_heads;
+    if (item >= n_items) return;
+    const int g = blockIdx.x - item * p.num_kv_heads;
+    const int2 it = p.items[item];
+    const int b = it.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int row = lane >> 4;
+    const int col = lane & 15;
+
+    const int L = p.context_lens[b];
+    const int n_pages_b = (L + kPageSize - 1) / kPageSize;
+    const int page0 = it.y * p.chunk_pages;
+    int n_here = n_pages_b - page0;
+    n_here = n_here > p.chunk_pages ? p.chunk_pages : n_here;
+    const int tail_valid = L - (n_pages_b - 1) * kPageSize;           // 1..16
+    const bool has_tail = (page0 + n_here == n_pages_b) && tail_valid < kPageSize;
+    const int n_full = has_tail ? n_here - 1 : n_here;                // pages processed unmasked
+
+    // page ids of this chunk, one per lane (chunk_pages <= 64)
+    int my_id = 0;
+    if (lane < n_here) my_id = p.block_table[int64_t(b) * p.block_table_stride + page0 + lane];
+
+    // queries of the group: 8 dims per lane, the same in all four rows
+    uint32_t qreg[G][4];
+    {
+        const uint16_t* qb = p.q + (int64_t(b) * p.num_q_heads + g * G) * kHeadDim + col * 8;
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            const uint4 t = *reinterpret_cast<const uint4*>(qb + h * kHeadDim);
+            qreg[h][0] = t.x; qreg[h][1] = t.y; qreg[h][2] = t.z; qreg[h][3] = t.w;
+        }
+    }
+
+    float m[G], l[G], o[G][8];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        m[h] = kNegBig;
+        l[h] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) o[h][c] = 0.0f;
+    }
+
+    const char* k_head = p.k_pool + int64_t(g) * p.stride_head_bytes;
+    const char* v_head = p.v_pool + int64_t(g) * p.stride_head_bytes;
+
+    // this wave's full pages: chunk pages wave, wave + 4, ...
+    const int n_mine = n_full > wave ? (n_full - wave + kChunkWaves - 1) / kChunkWaves : 0;
+    if (n_mine > 0) {
+        auto tile_of = [&](int j) -> int64_t {
+            const int jj = j < n_mine ? j : n_mine - 1;  // past the end: re-read the last page
+            const int id = __builtin_amdgcn_readlane(my_id, wave + kChunkWaves * jj);
+            return int64_t(id) * p.stride_page_bytes;
+        };
+        PageRegs bufA, bufB;
+        int64_t off = tile_of(0);
+        load_page(bufA, k_head + off, v_head + off, lane);
+        int j = 0;
+        // two pages per trip, one basic block: each buffer is refilled right after
+        // its page has been consumed and is consumed one page later
+        for (; j + 2 <= n_mine; j += 2) {
+            off = tile_of(j + 1);
+            load_page(bufB, k_head + off, v_head + off, lane);
+            __builtin_amdgcn_sched_barrier(0);
+            process_page<G, false>(bufA, qreg, m, l, o, p.scale_log2, row, kPageSize);
+            off = tile_of(j + 2);
+            load_page(bufA, k_head + off, v_head + off, lane);
+            __builtin_amdgcn_sched_barrier(0);
+            process_page<G, false>(bufB, qreg, m, l, o, p.scale_log2, row, kPageSize);
+        }
+        if (j < n_mine) process_page<G, false>(bufA, qreg, m, l, o, p.scale_log2, row, kPageSize);
+    }
+    if (has_tail && ((n_here - 1) & (kChunkWaves - 1)) == wave) {
+        PageRegs t;
+        const int id = __builtin_amdgcn_readlane(my_id, n_here - 1);
+        const int64_t off = int64_t(id) * p.stride_page_bytes;
+        load_page(t, k_head + off, v_head + off, lane);
+        process_page<G, true>(t, qreg, m, l, o, p.scale_log2, row, tail_valid);
+    }
+
+    // merge the four rows of the wave
+    __shared__ float sm_o[kChunkWaves][G][kHeadDim];
+    __shared__ float sm_m[kChunkWaves][G];
+    __shared__ float sm_l[kChunkWaves][G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        float mt = fmaxf(m[h], __shfl_xor(m[h], 16));
+        mt = fmaxf(mt, __shfl_xor(mt, 32));
+        const float w = fast_exp2((m[h] - mt) * p.scale_log2);
+        float lt = l[h] * w;
+        lt += __shfl_xor(lt, 16);
+        lt += __shfl_xor(lt, 32);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            float x = o[h][c] * w;
+            x += __shfl_xor(x, 16);
+            x += __shfl_xor(x, 32);
+            o[h][c] = x;
+        }
+        if (lane < 16) {
+            float4* dst = reinterpret_cast<float4*>(&sm_o[wave][h][col * 8]);
+            dst[0] = make_float4(o[h][0], o[h][1], o[h][2], o[h][3]);
+            dst[1] = make_float4(o[h][4], o[h][5], o[h][6], o[h][7]);
+        }
+        if (lane == 0) {
+            sm_m[wave][h] = mt;
+            sm_l[wave][h] = lt;
+        }
+    }
+    __syncthreads();
+
+    // merge the four waves; thread t owns outputs t, t + 256, ...
+    for (int idx = threadIdx.x; idx < G * kHeadDim; idx += kChunkThreads) {
+        const int h = idx / kHeadDim;
+        const int c = idx % kHeadDim;
+        float mt = sm_m[0][h];
+#pragma unroll
+        for (int w = 1; w < kChunkWaves; ++w) mt = fmaxf(mt, sm_m[w][h]);
+        float lt = 0.0f, acc = 0.0f;
+#pragma unroll
+        for (int w = 0; w < kChunkWaves; ++w) {
+            const float wt = fast_exp2((sm_m[w][h] - mt) * p.scale_log2);
+            lt = fmaf(sm_l[w][h], wt, lt);
+            acc = fmaf(sm_o[w][h][c], wt, acc);
+        }
+        const int64_t rowid = int64_t(item) * p.num_q_heads + g * G + h;
+        p.part_o[rowid * kHeadDim + c] = acc;
+        if (c == 0) {
+            p.part_ml[rowid * 2 + 0] = mt * p.scale_log2;  // max in the log2 domain
+            p.part_ml[rowid * 2 + 1] = lt;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// merge kernel: one wave per (program, query head)
+// ---------------------------------------------------------------------------
+struct MergeParams {
+    const int32_t* chunk_start;
+    const float* part_ml;
+    const float* part_o;
+    uint16_t* out;
+    float* lse;
+    int32_t batch;
+    int32_t num_q_heads;
+};
+
+__global__ __launch_bounds__(256) void decode_merge_kernel(MergeParams p) {
+    const int lane = threadIdx.x & 63;
+    const int64_t rid = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (rid >= int64_t(p.batch) * p.num_q_heads) return;
+    const int b = static_cast<int>(rid / p.num_q_heads);
+    const int h = static_cast<int>(rid % p.num_q_heads);
+    const int c0 = p.chunk_start[b];
+    const int c1 = p.chunk_start[b + 1];
+
+    float mt = kNegBig;
+    for (int c = c0 + lane; c < c1; c += 64)
+        mt = fmaxf(mt, p.part_ml[(int64_t(c) * p.num_q_heads + h) * 2]);
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) mt = fmaxf(mt, __shfl_xor(mt, s));
+
+    float lt = 0.0f, o0 = 0.0f, o1 = 0.0f;
+    for (int c = c0; c < c1; ++c) {
+        const int64_t r = int64_t(c) * p.num_q_heads + h;
+        const float wt = fast_exp2(p.part_ml[r * 2] - mt);
+        lt = fmaf(p.part_ml[r * 2 + 1], wt, lt);
+        const float2 v = *reinterpret_cast<const float2*>(p.part_o + r * kHeadDim + 2 * lane);
+        o0 = fmaf(v.x, wt, o0);
+        o1 = fmaf(v.y, wt, o1);
+    }
+    const float inv = lt > 0.0f ? 1.0f / lt : 0.0f;
+    const uint32_t packed = uint32_t(to_bf16_rne(o0 * inv)) | (uint32_t(to_bf16_rne(o1 * inv)) << 16);
+    reinterpret_cast<uint32_t*>(p.out + rid * kHeadDim)[lane] = packed;
+    if (p.lse != nullptr && lane == 0)
+        p.lse[rid] = lt > 0.0f ? (mt + __builtin_amdgcn_logf(lt)) * kLn2 : -INFINITY;
+}
+
+}  // namespace
+
+int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout& w, char* workspace,
+                  hipStream_t stream) {
+    int32_t* chunk_start = reinterpret_cast<int32_t*>(workspace + w.off_chunk_start);
+    int2* items = reinterpret_cast<int2*>(workspace + w.off_items);
+    float* part_ml = reinterpret_cast<float*>(workspace + w.off_part_ml);
+    float* part_o = reinterpret_cast<float*>(workspace + w.off_part_o);
+    const int32_t per_prog = w.max_chunks / a.batch;
+
+    hipLaunchKernelGGL(plan_chunks_kernel, dim3(1), dim3(1024), 0, stream, a.context_lens, a.batch,
+                       w.chunk_pages * kPageSize, per_prog, chunk_start, items);
+    TA_HIP_TRY(hipGetLastError());
+
+    if (w.max_chunks > 0) {
+        ChunkParams cp{};
+        cp.q = a.q;
+        cp.k_pool = reinterpret_cast<const char*>(a.k_pool);
+        cp.v_pool = reinterpret_cast<const char*>(a.v_pool);
+        cp.block_table = a.block_table;
+        cp.context_lens = a.context_lens;
+        cp.chunk_start = chunk_start;
+        cp.items = items;
+        cp.part_ml = part_ml;
+        cp.part_o = part_o;
+        cp.stride_page_bytes = g.stride_page_bytes;
+        cp.stride_head_bytes = g.stride_head_bytes;
+        cp.block_table_stride = a.block_table_stride;
+        cp.batch = a.batch;
+        cp.num_q_heads = g.num_q_heads;
+        cp.num_kv_heads = g.num_kv_heads;
+        cp.chunk_pages = w.chunk_pages;
+        cp.scale_log2 = g.scale_log2;
+        const int64_t blocks = int64_t(w.max_chunks) * g.num_kv_heads;
+        if (blocks > 0x7fffffff) return TA_ERR_INVALID_ARG;
+        const dim3 grid(static_cast<unsigned>(blocks)), block(kChunkThreads);
+        switch (g.group) {
+            case 1: hipLaunchKernelGGL(decode_chunk_kernel<1>, grid, block, 0, stream, cp); break;
+            case 2: hipLaunchKernelGGL(decode_chunk_kernel<2>, grid, block, 0, stream, cp); break;
+            case 4: hipLaunchKernelGGL(decode_chunk_kernel<4>, grid, block, 0, stream, cp); break;
+            case 8: hipLaunchKernelGGL(decode_chunk_kernel<8>, grid, block, 0, stream, cp); break;
+            default: return TA_ERR_UNSUPPORTED;
+        }
+        TA_HIP_TRY(hipGetLastError());
+    }
+
+    MergeParams mp{};
+    mp.chunk_start = chunk_start;
+    mp.part_ml = part_ml;
+    mp.part_o = part_o;
+    mp.out = a.out;
+    mp.lse = a.lse;
+    mp.batch = a.batch;
+    mp.num_q_heads = g.num_q_heads;
+    const int64_t rows = int64_t(a.batch) * g.num_q_heads;
+    hipLaunchKernelGGL(decode_merge_kernel, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0,
+                       stream, mp);
+    TA_HIP_TRY(hipGetLastError());
+    return TA_OK;
+}
+
+}  // namespace ta

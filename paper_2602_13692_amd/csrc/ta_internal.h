@@ -1,0 +1,101 @@
+// Internal declarations shared by the HIP sources of the library (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ta.h"
+
+namespace ta {
+
+constexpr int kHeadDim = 128;
+constexpr int kPageSize = 16;
+constexpr int kWaveSize = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+// Finite stand-in for "no key seen yet": keeps (m_old - m_new) free of inf - inf.
+constexpr float kNegBig = -1.0e30f;
+
+// Records a failed HIP call for ta_last_hip_error(); returns TA_ERR_HIP.
+int note_hip_error(hipError_t e);
+
+#define TA_HIP_TRY(expr)                                   \
+    do {                                                   \
+        hipError_t _e = (expr);                            \
+        if (_e != hipSuccess) return ::ta::note_hip_error(_e); \
+    } while (0)
+
+// Resolved geometry: strides in bytes, scale folded with log2(e).
+struct Geometry {
+    int32_t num_q_heads;
+    int32_t num_kv_heads;
+    int32_t group;            // Hq / Hkv
+    float scale;              // multiplies q.k
+    float scale_log2;         // scale * log2(e)
+    int64_t stride_page_bytes;
+    int64_t stride_head_bytes;
+};
+
+// Validates the descriptor; on TA_OK fills g.
+int resolve_geometry(const ta_attn_desc* desc, Geometry* g);
+
+// Layout of the caller's workspace for one call.  All offsets are multiples of 256 bytes.
+struct WorkspaceLayout {
+    int32_t chunk_pages;       // pages per split-K chunk
+    int32_t max_chunks;        // upper bound on the number of (program, chunk) items
+    int32_t max_tiles;         // upper bound on prefill query tiles (0 for decode)
+    size_t off_chunk_start;    // int32 [batch + 1]
+    size_t off_items;          // int2  [max_chunks]
+    size_t off_part_ml;        // float [max_chunks][Hq][2]
+    size_t off_part_o;         // float [max_chunks][Hq][128]
+    size_t off_tile_start;     // int32 [batch + 1]      (prefill)
+    size_t off_tiles;          // int2  [max_tiles]      (prefill)
+    size_t total_bytes;
+};
+
+WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_len,
+                               int32_t max_context_len);
+
+// ---- launchers (each validates nothing; callers have done that) ----
+
+struct DecodeArgs {
+    const uint16_t* q;
+    const uint16_t* k_pool;
+    const uint16_t* v_pool;
+    const int32_t* block_table;
+    const int32_t* context_lens;
+    uint16_t* out;
+    float* lse;
+    int32_t block_table_stride;
+    int32_t batch;
+    int32_t max_context_len;
+};
+
+int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout& w, char* workspace,
+                  hipStream_t stream);
+
+struct PrefillArgs {
+    const uint16_t* q;
+    const int32_t* cu_q_lens;
+    const uint16_t* k_pool;
+    const uint16_t* v_pool;
+    const int32_t* block_table;
+    const int32_t* context_lens;
+    uint16_t* out;
+    float* lse;
+    int32_t block_table_stride;
+    int32_t batch;
+    int32_t total_q;
+    int32_t max_q_len;
+    int32_t max_context_len;
+};
+
+int launch_prefill(const Geometry& g, const PrefillArgs& a, const WorkspaceLayout& w, char* workspace,
+                   hipStream_t stream);
+
+int launch_restore(void* k_pool, void* v_pool, size_t page_bytes, const void* host_k,
+                   const void* host_v, const int32_t* dst_slots, int32_t n_pages, void* staging,
+                   size_t staging_bytes, hipStream_t stream);
+
+}  // namespace ta

@@ -1,0 +1,434 @@
+// Append-prefill attention for gfx950: the n new tokens of a program attend
+// causally to the retained prefix plus themselves (ThunderAgent Sec. 4.2, the
+// incremental-prefill term of Eq. 3; Sec. 2.1, c_{t+1} extends c_t).
+//
+// Here q.K^T and p.V are dense contractions, so both run on the matrix cores
+// (v_mfma_f32_32x32x16_bf16).  One workgroup of four waves owns 256 score rows
+// = (256 / G) consecutive new tokens x the G query heads that share a kv head,
+// and walks the program's keys in tiles of 64 (four pages):
+//
+//   * K and V tiles go HBM -> registers -> LDS once per workgroup, double
+//     buffered, and serve all 256 rows;
+//   * every wave owns 64 rows and computes the TRANSPOSED scores S^T = K Q^T,
+//     so that each lane holds one query row's scores in its accumulator
+//     registers: the softmax needs one cross-lane exchange per tile, and the
+//     exponentiated scores are already laid out as the B operand of
+//     O^T = V^T P^T;
+//   * V is written to LDS as [4-key group][dim][4 keys], which makes the A
+//     operand of O^T = V^T P^T two 8-byte LDS reads per lane;
+//   * the running maximum is only raised (and O rescaled) when it grows by more
+//     than 2^8, a wave-uniform and rare event after the first tile.
+#include "ta_internal.h"
+
+namespace ta {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kThreads = 256;
+constexpr int kRowsPerBlock = 256;  // score rows per workgroup
+constexpr int kTileKeys = 64;       // keys per LDS tile (4 pages)
+constexpr int kKTileBytes = kTileKeys * kHeadDim * 2;  // 16 KiB
+constexpr int kVTileBytes = kTileKeys * kHeadDim * 2;  // 16 KiB
+constexpr float kRescaleThreshold = 8.0f;  // log2 units
+
+struct PrefillParams {
+    const uint16_t* q;
+    const char* k_pool;
+    const char* v_pool;
+    const int32_t* block_table;
+    const int32_t* context_lens;
+    const int32_t* cu_q_lens;
+    const int32_t* tile_start;  // [batch + 1]
+    const int2* tiles;          // (program, query tile)
+    uint16_t* out;
+    float* lse;
+    int64_t stride_page_bytes;
+    int64_t stride_head_bytes;
+    int32_t block_table_stride;
+    int32_t batch;
+    int32_t num_q_heads;
+    int32_t num_kv_heads;
+    float scale_log2;
+};
+
+// plan: query tiles of tile_tokens tokens per program, listed flat
+__global__ __launch_bounds__(1024) void plan_tiles_kernel(const int32_t* __restrict__ cu_q_lens,
+                                                          int32_t batch, int32_t tile_tokens,
+                                                          int32_t max_per_program,
+                                                          int32_t* __restrict__ tile_start,
+                                                          int2* __restrict__ tiles) {
+    __shared__ int32_t scan[1024];
+    __shared__ int32_t carry;
+    const int tid = threadIdx.x;
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < batch; base += 1024) {
+        const int b = base + tid;
+        int n = 0;
+        if (b < batch) {
+            const int nq = cu_q_lens[b + 1] - cu_q_lens[b];
+            n = nq > 0 ? (nq + tile_tokens - 1) / tile_tokens : 0;
+            n = n > max_per_program ? max_per_program : n;
+        }
+        scan[tid] = n;
+        __syncthreads();
+        for (int off = 1; off < 1024; off <<= 1) {
+            const int v = tid >= off ? scan[tid - off] : 0;
+            __syncthreads();
+            scan[tid] += v;
+            __syncthreads();
+        }
+        const int first = carry + scan[tid] - n;
+        if (b < batch) {
+            tile_start[b] = first;
+            for (int c = 0; c < n; ++c) tiles[first + c] = make_int2(b, c);
+        }
+        __syncthreads();
+        if (tid == 1023) carry += scan[1023];
+        __syncthreads();
+    }
+    if (tid == 0) tile_start[batch] = carry;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    // round to nearest even; inputs are finite non-negative weights
+    typedef __attribute__((ext_vector_type(2))) float f32x2;
+    const f32x2 v = {lo, hi};
+    const bf16x2 r = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+__device__ __forceinline__ uint16_t to_bf16_rne(float f) {
+    uint32_t u = __builtin_bit_cast(uint32_t, f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+}
+
+// Staging registers of one thread for one 64-key tile: four 16-byte pieces of K
+// (keys r16 + 16 i, chunk c) and four of V (keys 4 r16 + j, chunk c).
+struct Stage {
+    u32x4 k[4];
+    u32x4 v[4];
+};
+
+// LDS byte offset of the 8-byte entry (4-key group q, dim) in a V tile.
+__device__ __forceinline__ int v_entry_offset(int quad, int dim) {
+    const int chunk = dim >> 3;              // 64-byte run of 8 dims
+    const int piece = (dim >> 1) & 3;        // 16-byte piece inside the run
+    return quad * 1024 + chunk * 64 + ((piece ^ ((chunk >> 2) & 3)) << 4) + ((dim & 1) << 3);
+}
+
+template <int G>
+__global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
+    constexpr int kTileTokens = kRowsPerBlock / G;
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    char* k_lds = lds;                       // [2][kKTileBytes]
+    char* v_lds = lds + 2 * kKTileBytes;     // [2][kVTileBytes]
+
+    const int n_tiles_total = p.tile_start[p.batch];
+    const int tile_id = blockIdx.x / p.num_kv_heads;
+    if (tile_id >= n_tiles_total) return;
+    const int g = blockIdx.x - tile_id * p.num_kv_heads;
+    const int2 tl = p.tiles[tile_id];
+    const int b = tl.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hl = lane >> 5;                // which half of the wave
+    const int l32 = lane & 31;
+
+    const int q0 = p.cu_q_lens[b];
+    const int nq = p.cu_q_lens[b + 1] - q0;
+    const int L = p.context_lens[b];
+    const int prefix = L - nq;
+    const int t0 = tl.y * kTileTokens;                   // first new token of this tile
+    int t_end = t0 + kTileTokens;
+    t_end = t_end > nq ? nq : t_end;
+    const int keys_needed = prefix + t_end;              // largest visible count in the tile
+    const int n_tiles = (keys_needed + kTileKeys - 1) / kTileKeys;
+    const int n_unmasked = (prefix + t0 + 1) / kTileKeys;  // tiles every row sees completely
+    const int n_pages_b = (L + kPageSize - 1) / kPageSize;
+
+    // ---- per-lane rows: two blocks of 32 rows per wave ----
+    // row -> (token, head): row = token_local * G + head
+    int vis[2];            // visible keys of this lane's row in row block rb (0 = row does not exist)
+    bf16x8 qf[2][8];       // B operands: q[row][16 ks + 8 hl .. + 7]
+    int64_t out_row[2];    // element offset of the row in out, or -1
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        const int row = wave * 64 + rb * 32 + l32;
+        const int tok = t0 + row / G;
+        const int head = g * G + row % G;
+        const bool ok = tok < nq;
+        vis[rb] = ok ? prefix + tok + 1 : 0;
+        out_row[rb] = ok ? (int64_t(q0 + tok) * p.num_q_heads + head) * kHeadDim : int64_t(-1);
+        const uint16_t* qrow = p.q + (ok ? out_row[rb] : 0) + hl * 8;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            u32x4 t = {0u, 0u, 0u, 0u};
+            if (ok) t = *reinterpret_cast<const u32x4*>(qrow + ks * 16);
+            qf[rb][ks] = __builtin_bit_cast(bf16x8, t);
+        }
+    }
+
+    // ---- staging addresses ----
+    const int c16 = tid & 15;   // 16-byte chunk of a 256-byte row
+    const int r16 = tid >> 4;   // 0..15
+    const char* k_base = p.k_pool + int64_t(g) * p.stride_head_bytes + r16 * 256 + c16 * 16;
+    const char* v_base = p.v_pool + int64_t(g) * p.stride_head_bytes + (r16 & 3) * 1024 + c16 * 16;
+    const int32_t* table = p.block_table + int64_t(b) * p.block_table_stride;
+    const int k_lds_off = r16 * 256 + ((c16 ^ r16) << 4);           // + i * 4096 for key r16 + 16 i
+    const int v_lds_off = r16 * 1024 + c16 * 64;                    // pieces at ((j ^ (c16 >> 2)) << 4)
+
+    auto load_tile = [&](Stage& st, int t) {
+        // page ids of the tile's four pages, clamped to the program's last page
+        int id[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int pg = t * 4 + i;
+            pg = pg < n_pages_b ? pg : n_pages_b - 1;
+            id[i] = table[pg];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            st.k[i] = *reinterpret_cast<const u32x4*>(k_base + int64_t(id[i]) * p.stride_page_bytes);
+        // V: this thread's 4-key group r16 lies in page r16 / 4 of the tile (uniform per wave)
+        int vid = id[0];
+        vid = (r16 >> 2) == 1 ? id[1] : vid;
+        vid = (r16 >> 2) == 2 ? id[2] : vid;
+        vid = (r16 >> 2) == 3 ? id[3] : vid;
+        const char* vp = v_base + int64_t(vid) * p.stride_page_bytes;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) st.v[j] = *reinterpret_cast<const u32x4*>(vp + j * 256);
+    };
+
+    auto store_tile = [&](const Stage& st, int t, int buf) {
+        char* kd = k_lds + buf * kKTileBytes + k_lds_off;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(kd + i * 4096) = st.k[i];
+        // keys at or beyond the context length may hold anything (even NaN): V rows there
+        // are zeroed, because 0 * NaN inside the matrix core would poison the output
+        u32x4 vr[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool live = t * kTileKeys + r16 * 4 + j < L;
+            vr[j] = live ? st.v[j] : u32x4{0u, 0u, 0u, 0u};
+        }
+        // transpose 4 keys x 8 dims into 8 entries of (4 keys) and write 4 pieces of 16 bytes
+        char* vd = v_lds + buf * kVTileBytes + v_lds_off;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {  // dims 2w, 2w+1 of this chunk -> piece w
+            const uint32_t a0 = vr[0][w], a1 = vr[1][w], a2 = vr[2][w], a3 = vr[3][w];
+            u32x4 piece;
+            piece.x = __builtin_amdgcn_perm(a1, a0, 0x05040100u);  // dim 2w:   keys 0,1
+            piece.y = __builtin_amdgcn_perm(a3, a2, 0x05040100u);  //           keys 2,3
+            piece.z = __builtin_amdgcn_perm(a1, a0, 0x07060302u);  // dim 2w+1: keys 0,1
+            piece.w = __builtin_amdgcn_perm(a3, a2, 0x07060302u);  //           keys 2,3
+            *reinterpret_cast<u32x4*>(vd + ((w ^ (c16 >> 2)) << 4)) = piece;
+        }
+    };
+
+    // ---- accumulators ----
+    f32x16 o[4][2];        // O^T blocks: [dim block][row block]
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[db][rb][r] = 0.0f;
+    float m[2] = {kNegBig, kNegBig};   // running maximum (log2 domain, scaled)
+    float lsum[2] = {0.0f, 0.0f};      // this lane's share of the row sum
+
+    // LDS read offsets
+    int k_rd[2];   // K operand: key l32 + 32 kb, chunk (2 ks + hl) ^ (key & 15)
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) k_rd[kb] = (kb * 32 + l32) * 256;
+    const int k_swz = l32 & 15;
+    int v_rd[4];   // V operand: dim l32 + 32 db of 4-key group (2 x + hl)
+#pragma unroll
+    for (int db = 0; db < 4; ++db) v_rd[db] = v_entry_offset(hl, db * 32 + l32);
+
+    Stage st;
+    if (n_tiles > 0) {
+        load_tile(st, 0);
+        store_tile(st, 0, 0);
+    }
+    __syncthreads();
+
+    for (int t = 0; t < n_tiles; ++t) {
+        const int buf = t & 1;
+        const bool more = t + 1 < n_tiles;
+        if (more) load_tile(st, t + 1);
+        __builtin_amdgcn_sched_barrier(0);  // keep the next tile's loads ahead of this tile's arithmetic
+        const char* kt = k_lds + buf * kKTileBytes;
+        const char* vt = v_lds + buf * kVTileBytes;
+        const bool masked = t >= n_unmasked;
+
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            // S^T block: 32 keys x (2 x 32 rows)
+            f32x16 s[2];
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[rb][r] = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8*>(
+                    kt + k_rd[kb] + (((2 * ks + hl) ^ k_swz) << 4));
+                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][ks], s[0], 0, 0, 0);
+                s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][ks], s[1], 0, 0, 0);
+            }
+            // register r of lane (l32, hl) holds key 8 (r / 4) + 4 hl + r % 4 of this block
+            bf16x8 pf[2][2];   // B operands of the two k = 16 steps
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                if (masked) {
+                    const int key0 = t * kTileKeys + kb * 32 + 4 * hl;
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = key0 + 8 * (r >> 2) + (r & 3);
+                        s[rb][r] = key < vis[rb] ? s[rb][r] : -INFINITY;
+                    }
+                }
+                float mx = s[rb][0];
+#pragma unroll
+                for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[rb][r]);
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float cand = mx * p.scale_log2;
+                // raise the reference only when it would grow by more than the threshold
+                const bool grow = cand > m[rb] + kRescaleThreshold;
+                if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                    const float m_new = fmaxf(m[rb], cand);
+                    const float alpha = __builtin_amdgcn_exp2f(m[rb] - m_new);
+                    m[rb] = m_new;
+                    lsum[rb] *= alpha;
+#pragma unroll
+                    for (int db = 0; db < 4; ++db)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) o[db][rb][r] *= alpha;
+                }
+                const float bias = -m[rb];
+                float pr[16];
+                float acc = 0.0f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    pr[r] = __builtin_amdgcn_exp2f(fmaf(s[rb][r], p.scale_log2, bias));
+                    acc += pr[r];
+                }
+                lsum[rb] += acc;
+#pragma unroll
+                for (int step = 0; step < 2; ++step) {
+                    u32x4 w;
+                    w.x = pack_bf16(pr[8 * step + 0], pr[8 * step + 1]);
+                    w.y = pack_bf16(pr[8 * step + 2], pr[8 * step + 3]);
+                    w.z = pack_bf16(pr[8 * step + 4], pr[8 * step + 5]);
+                    w.w = pack_bf16(pr[8 * step + 6], pr[8 * step + 7]);
+                    pf[rb][step] = __builtin_bit_cast(bf16x8, w);
+                }
+            }
+            // O^T += V^T P^T : step 0 uses key groups (hl, 2 + hl), step 1 uses (4 + hl, 6 + hl)
+#pragma unroll
+            for (int step = 0; step < 2; ++step) {
+                const char* vq = vt + (kb * 8 + step * 4) * 1024;
+#pragma unroll
+                for (int db = 0; db < 4; ++db) {
+                    const u32x2 lo = *reinterpret_cast<const u32x2*>(vq + v_rd[db]);
+                    const u32x2 hi = *reinterpret_cast<const u32x2*>(vq + v_rd[db] + 2 * 1024);
+                    const u32x4 av = {lo.x, lo.y, hi.x, hi.y};
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+                    o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[0][step], o[db][0], 0, 0, 0);
+                    o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[1][step], o[db][1], 0, 0, 0);
+                }
+            }
+        }
+
+        if (more) store_tile(st, t + 1, buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: normalise and write ----
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+        const float total = lsum[rb] + __shfl_xor(lsum[rb], 32);
+        const float inv = total > 0.0f ? 1.0f / total : 0.0f;
+        if (out_row[rb] >= 0) {
+            uint16_t* orow = p.out + out_row[rb];
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    // registers 4 q4 .. 4 q4 + 3 are dims db 32 + 8 q4 + 4 hl + 0..3
+                    const int dim = db * 32 + 8 * q4 + 4 * hl;
+                    u32x2 w;
+                    w.x = uint32_t(to_bf16_rne(o[db][rb][4 * q4 + 0] * inv)) |
+                          (uint32_t(to_bf16_rne(o[db][rb][4 * q4 + 1] * inv)) << 16);
+                    w.y = uint32_t(to_bf16_rne(o[db][rb][4 * q4 + 2] * inv)) |
+                          (uint32_t(to_bf16_rne(o[db][rb][4 * q4 + 3] * inv)) << 16);
+                    *reinterpret_cast<u32x2*>(orow + dim) = w;
+                }
+            }
+            if (p.lse != nullptr && hl == 0)
+                p.lse[out_row[rb] / kHeadDim] =
+                    total > 0.0f ? (m[rb] + __builtin_amdgcn_logf(total)) * kLn2 : -INFINITY;
+        }
+    }
+}
+
+}  // namespace
+
+int launch_prefill(const Geometry& g, const PrefillArgs& a, const WorkspaceLayout& w, char* workspace,
+                   hipStream_t stream) {
+    int32_t* tile_start = reinterpret_cast<int32_t*>(workspace + w.off_tile_start);
+    int2* tiles = reinterpret_cast<int2*>(workspace + w.off_tiles);
+    const int tile_tokens = kRowsPerBlock / g.group;
+    const int32_t per_prog = (a.max_q_len + tile_tokens - 1) / tile_tokens;
+    const int64_t max_tiles = int64_t(per_prog) * a.batch;
+    if (max_tiles > w.max_tiles) return TA_ERR_INVALID_ARG;
+
+    hipLaunchKernelGGL(plan_tiles_kernel, dim3(1), dim3(1024), 0, stream, a.cu_q_lens, a.batch,
+                       tile_tokens, per_prog, tile_start, tiles);
+    TA_HIP_TRY(hipGetLastError());
+
+    PrefillParams pp{};
+    pp.q = a.q;
+    pp.k_pool = reinterpret_cast<const char*>(a.k_pool);
+    pp.v_pool = reinterpret_cast<const char*>(a.v_pool);
+    pp.block_table = a.block_table;
+    pp.context_lens = a.context_lens;
+    pp.cu_q_lens = a.cu_q_lens;
+    pp.tile_start = tile_start;
+    pp.tiles = tiles;
+    pp.out = a.out;
+    pp.lse = a.lse;
+    pp.stride_page_bytes = g.stride_page_bytes;
+    pp.stride_head_bytes = g.stride_head_bytes;
+    pp.block_table_stride = a.block_table_stride;
+    pp.batch = a.batch;
+    pp.num_q_heads = g.num_q_heads;
+    pp.num_kv_heads = g.num_kv_heads;
+    pp.scale_log2 = g.scale_log2;
+
+    const int64_t blocks = max_tiles * g.num_kv_heads;
+    if (blocks > 0x7fffffff) return TA_ERR_INVALID_ARG;
+    const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
+    const size_t lds_bytes = 2 * kKTileBytes + 2 * kVTileBytes;
+    switch (g.group) {
+        case 1: hipLaunchKernelGGL(prefill_kernel<1>, grid, block, lds_bytes, stream, pp); break;
+        case 2: hipLaunchKernelGGL(prefill_kernel<2>, grid, block, lds_bytes, stream, pp); break;
+        case 4: hipLaunchKernelGGL(prefill_kernel<4>, grid, block, lds_bytes, stream, pp); break;
+        case 8: hipLaunchKernelGGL(prefill_kernel<8>, grid, block, lds_bytes, stream, pp); break;
+        default: return TA_ERR_UNSUPPORTED;
+    }
+    TA_HIP_TRY(hipGetLastError());
+    return TA_OK;
+}
+
+}  // namespace ta

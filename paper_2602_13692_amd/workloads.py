@@ -197,10 +197,14 @@ def tiny_decode(device="cpu", seed: int = SEED_BASE + 1) -> PagedBatch:
 
 def llama8b_decode(device="cpu", seed: int = SEED_BASE + 2, batch: int = 64,
                    len_lo: int = 4096, len_hi: int = 32768,
-                   num_q_heads: int = 32, num_kv_heads: int = 8) -> PagedBatch:
-    """Decode layer, lengths uniform in [len_lo, len_hi], pool sized to fit all pages."""
+                   num_q_heads: int = 32, num_kv_heads: int = 8, first_lens=()) -> PagedBatch:
+    """Decode layer, lengths uniform in [len_lo, len_hi], pool sized to fit all pages.
+
+    first_lens overrides the lengths of the first programs (edge cases in tests).
+    """
     rng = np.random.default_rng(seed)
     lens = rng.integers(len_lo, len_hi + 1, size=batch).astype(np.int32)
+    lens[:len(first_lens)] = np.asarray(first_lens, dtype=np.int32)
     n_pages = pages_of(lens)
     pool_pages = int(n_pages.sum())
     slots = rng.permutation(pool_pages).astype(np.int32)

@@ -1,0 +1,84 @@
+"""Shared helpers of the GPU parity tests: call the C ABI, call the oracle, compare."""
+import numpy as np
+import torch
+
+import oracle
+from paper_2602_13692_amd import binding as ta
+from paper_2602_13692_amd import workloads as wl
+
+ABS_TOL = 2e-2      # contract: |gpu - oracle| <= 2e-2 + 1e-2 * |oracle| (bf16 in, fp32 accumulate)
+REL_TOL = 1e-2
+ROW_L2_TOL = 1e-2   # tighter gates of our own: relative L2 error per output row ...
+LSE_TOL = 2e-3      # ... and the log-sum-exp, which a zero output could not fake
+
+
+def widen_bf16(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def desc_of(wb) -> ta.Desc:
+    return ta.Desc(wb.num_q_heads, wb.num_kv_heads)
+
+
+def geom_of(wb) -> oracle.Geometry:
+    return oracle.Geometry(wb.num_q_heads, wb.num_kv_heads)
+
+
+def gpu_decode(wb, stream=None):
+    dev = wb.q.device
+    desc = desc_of(wb)
+    bt = torch.from_numpy(wb.block_table).to(dev)
+    cl = torch.from_numpy(wb.context_lens).to(dev)
+    out = torch.full_like(wb.q, float("nan"))
+    lse = torch.full((wb.batch, wb.num_q_heads), float("nan"), dtype=torch.float32, device=dev)
+    ws = ta.alloc_workspace(desc, wb.batch, 1, wb.max_context_len, dev)
+    ta.ta_paged_decode(desc, wb.q, wb.k_pool, wb.v_pool, bt, cl, wb.max_context_len, out, lse, ws, stream)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def gpu_prefill(wb, stream=None):
+    dev = wb.q.device
+    desc = desc_of(wb)
+    bt = torch.from_numpy(wb.block_table).to(dev)
+    cl = torch.from_numpy(wb.context_lens).to(dev)
+    cu = torch.from_numpy(wb.cu_q_lens).to(dev)
+    out = torch.full_like(wb.q, float("nan"))
+    lse = torch.full((wb.total_q, wb.num_q_heads), float("nan"), dtype=torch.float32, device=dev)
+    ws = ta.alloc_workspace(desc, wb.batch, max(wb.max_q_len, 2), wb.max_context_len, dev)
+    ta.ta_append_prefill(desc, wb.q, cu, wb.k_pool, wb.v_pool, bt, cl, wb.total_q, wb.max_q_len,
+                         wb.max_context_len, out, lse, ws, stream)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def oracle_decode(wb):
+    return oracle.paged_decode(geom_of(wb), wl.as_u16(wb.q), wl.as_u16(wb.k_pool), wl.as_u16(wb.v_pool),
+                               wb.block_table, wb.context_lens)
+
+
+def oracle_prefill(wb):
+    return oracle.append_prefill(geom_of(wb), wl.as_u16(wb.q), wb.cu_q_lens, wl.as_u16(wb.k_pool),
+                                 wl.as_u16(wb.v_pool), wb.block_table, wb.context_lens)
+
+
+def assert_close(gpu_out, gpu_lse, ref_out, ref_lse, what=""):
+    """Element-wise contract tolerance plus the tighter per-row gates."""
+    got = widen_bf16(gpu_out).reshape(ref_out.shape)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite output"
+    err = np.abs(got - ref_out)
+    bound = ABS_TOL + REL_TOL * np.abs(ref_out)
+    worst = np.unravel_index(np.argmax(err - bound), err.shape)
+    assert np.all(err <= bound), f"{what}: |err|={err[worst]:.4g} at {worst}, ref={ref_out[worst]:.4g}"
+    num = np.sqrt((err ** 2).sum(axis=-1))
+    den = np.sqrt((ref_out ** 2).sum(axis=-1))
+    ok_rows = den > 0
+    rel = np.where(ok_rows, num / np.where(ok_rows, den, 1.0), num)
+    assert rel.max() <= ROW_L2_TOL, f"{what}: row relative L2 error {rel.max():.4g}"
+    if gpu_lse is not None:
+        gl = gpu_lse.detach().cpu().numpy().astype(np.float64).reshape(ref_lse.shape)
+        finite = np.isfinite(ref_lse)
+        assert np.array_equal(np.isneginf(gl), np.isneginf(ref_lse)), f"{what}: -inf lse mismatch"
+        assert np.max(np.abs(gl[finite] - ref_lse[finite]), initial=0.0) <= LSE_TOL, \
+            f"{what}: lse error {np.max(np.abs(gl[finite] - ref_lse[finite])):.4g}"
+    return float(err.max()), float(rel.max())

@@ -1,0 +1,118 @@
+"""GPU parity: ta_paged_decode through the C ABI against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_13692_amd import binding as ta
+from paper_2602_13692_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def test_config1_tiny_decode():
+    wb = wl.tiny_decode(DEV)
+    out, lse = gu.gpu_decode(wb)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, "config 1")
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (8, 4), (8, 2), (8, 1), (32, 8), (64, 8)])
+def test_ragged_lengths_all_group_sizes(Hq, Hkv):
+    """Lengths that end inside a page, span several chunks and leave some waves without pages."""
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 100 + Hq + Hkv, batch=13, len_lo=1, len_hi=2500,
+                           num_q_heads=Hq, num_kv_heads=Hkv, first_lens=[1, 15, 16, 17, 1024, 1025])
+    out, lse = gu.gpu_decode(wb)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, f"ragged Hq={Hq} Hkv={Hkv}")
+
+
+@pytest.mark.parametrize("chunk_pages", [8, 16, 32, 64])
+def test_every_chunk_length(chunk_pages, monkeypatch):
+    monkeypatch.setenv("TA_DECODE_CHUNK_PAGES", str(chunk_pages))
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 200, batch=9, len_lo=100, len_hi=5000)
+    out, lse = gu.gpu_decode(wb)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, f"chunk_pages={chunk_pages}")
+
+
+def test_padding_poison_is_never_read():
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 300, batch=16, len_lo=1, len_hi=700)
+    ref, ref_lse = gu.oracle_decode(wb)
+    wl.poison_padding(wb)
+    out, lse = gu.gpu_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, "poisoned padding")
+
+
+def test_needle_key_dominates():
+    """One key per (program, kv head) gets weight ~1: outputs are O(1) and the relative term bites."""
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 400, batch=8, len_lo=3000, len_hi=9000)
+    pos = wl.plant_needles(wb, seed=7)
+    out, lse = gu.gpu_decode(wb)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, "needle")
+    G = wb.num_q_heads // wb.num_kv_heads
+    assert np.abs(ref[:, ::G]).max() > 0.5 and (pos >= 0).all()
+
+
+def test_sharpened_queries():
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 500, batch=8, len_lo=500, len_hi=6000)
+    wl.sharpen(wb, 4.0)
+    out, lse = gu.gpu_decode(wb)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, "sharp")
+
+
+def test_empty_program_and_empty_batch():
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 600, batch=4, len_lo=20, len_hi=90)
+    wb.context_lens[2] = 0
+    out, lse = gu.gpu_decode(wb)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, "empty program")
+    assert torch.all(out[2] == 0) and torch.all(torch.isneginf(lse[2]))
+    desc = gu.desc_of(wb)
+    assert ta.ta_paged_decode(desc, None, None, None, None, torch.empty(0, dtype=torch.int32, device=DEV),
+                              0, None, None, None, check=False) == ta.TA_OK
+
+
+def test_forked_programs_shared_prefix_config4_shape():
+    wb = wl.forked_decode(DEV, seed=wl.SEED_BASE + 700, batch=32, group=16, prefix_len=2048,
+                          suffix_lo=100, suffix_hi=600)
+    out, lse = gu.gpu_decode(wb)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, "forked")
+
+
+def test_runs_are_deterministic():
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 800, batch=12, len_lo=100, len_hi=4000)
+    a, la = gu.gpu_decode(wb)
+    b, lb = gu.gpu_decode(wb)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16)) and torch.equal(la, lb)
+
+
+def test_scale_override_and_strided_pool():
+    """A non-default scale, and a pool whose page stride is larger than the packed tile size."""
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 900, batch=5, len_lo=50, len_hi=900,
+                           num_q_heads=8, num_kv_heads=2)
+    import oracle
+    dev = wb.q.device
+    pad = 256
+    tile = 2 * 16 * 128
+    k_wide = torch.randn(wb.pool_pages, tile + pad, device=dev).to(torch.bfloat16)
+    v_wide = torch.randn(wb.pool_pages, tile + pad, device=dev).to(torch.bfloat16)
+    k_wide[:, :tile] = wb.k_pool.view(wb.pool_pages, tile)
+    v_wide[:, :tile] = wb.v_pool.view(wb.pool_pages, tile)
+    desc = ta.Desc(8, 2, scale=0.05, pool_stride_page=tile + pad)
+    bt = torch.from_numpy(wb.block_table).to(dev)
+    cl = torch.from_numpy(wb.context_lens).to(dev)
+    out = torch.empty_like(wb.q)
+    lse = torch.empty((wb.batch, 8), dtype=torch.float32, device=dev)
+    ws = ta.alloc_workspace(desc, wb.batch, 1, wb.max_context_len, dev)
+    ta.ta_paged_decode(desc, wb.q, k_wide, v_wide, bt, cl, wb.max_context_len, out, lse, ws)
+    torch.cuda.synchronize()
+    geom = oracle.Geometry(8, 2, scale=float(np.float32(0.05)))
+    ref, ref_lse = oracle.paged_decode(geom, wl.as_u16(wb.q), wl.as_u16(wb.k_pool), wl.as_u16(wb.v_pool),
+                                       wb.block_table, wb.context_lens)
+    gu.assert_close(out, lse, ref, ref_lse, "scale/stride")

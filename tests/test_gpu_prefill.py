@@ -1,0 +1,90 @@
+"""GPU parity: ta_append_prefill through the C ABI against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_13692_amd import binding as ta
+from paper_2602_13692_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _check(wb, what):
+    out, lse = gu.gpu_prefill(wb)
+    ref, ref_lse = gu.oracle_prefill(wb)
+    return gu.assert_close(out, lse, ref, ref_lse, what)
+
+
+def test_config3_shape_small():
+    """Same structure as the append-prefill configuration, shrunk so the oracle takes seconds."""
+    wb = wl.append_prefill(DEV, batch=6, new_lo=16, new_hi=300, prefix_lo=500, prefix_hi=2500)
+    _check(wb, "config 3 (small)")
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (8, 4), (8, 2), (8, 1)])
+def test_all_group_sizes(Hq, Hkv):
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 30 + Hkv, batch=4, new_lo=1, new_hi=150,
+                           prefix_lo=0, prefix_hi=700, num_q_heads=Hq, num_kv_heads=Hkv)
+    _check(wb, f"groups Hq={Hq} Hkv={Hkv}")
+
+
+@pytest.mark.parametrize("n,prefix", [(1, 0), (1, 77), (63, 1), (64, 0), (65, 63), (128, 64), (200, 0),
+                                      (17, 1000), (257, 31)])
+def test_tile_and_page_boundaries(n, prefix):
+    """Query-tile (64 tokens), key-tile (64 keys) and page (16) boundaries, empty prefixes."""
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 31, batch=3, new_lo=n, new_hi=n, prefix_lo=prefix,
+                           prefix_hi=prefix, num_q_heads=8, num_kv_heads=2)
+    _check(wb, f"n={n} prefix={prefix}")
+
+
+def test_padding_poison_is_never_read():
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 32, batch=5, new_lo=3, new_hi=120, prefix_lo=5,
+                           prefix_hi=900, num_q_heads=8, num_kv_heads=2)
+    ref, ref_lse = gu.oracle_prefill(wb)
+    wl.poison_padding(wb)
+    out, lse = gu.gpu_prefill(wb)
+    gu.assert_close(out, lse, ref, ref_lse, "poisoned padding")
+
+
+def test_sharpened_queries():
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 33, batch=3, new_lo=40, new_hi=200, prefix_lo=300,
+                           prefix_hi=1500, num_q_heads=8, num_kv_heads=2)
+    wl.sharpen(wb, 4.0)
+    _check(wb, "sharp")
+
+
+def test_program_without_new_tokens_and_empty_call():
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 34, batch=4, new_lo=5, new_hi=90, prefix_lo=20,
+                           prefix_hi=400, num_q_heads=8, num_kv_heads=2)
+    # program 1 contributes no rows: drop its queries from the packed array
+    cu = wb.cu_q_lens
+    keep = np.ones(wb.total_q, dtype=bool)
+    keep[cu[1]:cu[2]] = False
+    wb.context_lens[1] -= wb.q_lens[1]
+    wb.q_lens[1] = 0
+    wb.q = wb.q[torch.from_numpy(keep).to(DEV)].contiguous()
+    _check(wb, "n_b = 0")
+    desc = gu.desc_of(wb)
+    assert ta.ta_append_prefill(desc, None, None, None, None, None,
+                                torch.empty(0, dtype=torch.int32, device=DEV), 0, 0, 0, None, None, None,
+                                check=False) == ta.TA_OK
+
+
+def test_single_new_token_agrees_with_decode():
+    """Append-prefill with one new token per program is the decode step."""
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 35, batch=7, len_lo=1, len_hi=1500, num_q_heads=8,
+                           num_kv_heads=2)
+    out_p, lse_p = gu.gpu_prefill(wb)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out_p, lse_p, ref, ref_lse, "prefill n=1")
+
+
+def test_runs_are_deterministic():
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 36, batch=4, new_lo=30, new_hi=200, prefix_lo=100,
+                           prefix_hi=1200)
+    a, la = gu.gpu_prefill(wb)
+    b, lb = gu.gpu_prefill(wb)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16)) and torch.equal(la, lb)
