@@ -1,0 +1,315 @@
+#!/usr/bin/env python3
+"""One-GPU benchmark of the paged-KV attention hot path on MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--only decode|all] [--calibrate-copy]
+
+A step is one ta_paged_decode call (work plan, split-K chunk kernel, merge) on
+the Llama-3-8B-shaped decode batch: 64 programs, 32 q / 8 kv heads, context
+lengths uniform in 4k..32k, 16-token pages scattered over the pool by a seeded
+permutation.  All inputs are resident in HBM before the timed region.  The
+headline value is KV bytes read per second (K and V of every cached token once).
+
+The same JSON line carries
+  roofline      the chunk kernel's own duration (HIP events recorded inside the
+                library around that kernel) against the 8 TB/s HBM peak;
+  cpu_baseline  the fp64 oracle timed on this host's cores on the same batch;
+  extra         append-prefill (MFMA, TFLOP/s), forked-prefix decode and
+                restore-then-decode on the other workload shapes.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
+
+# HBM bytes per decode-chunk launch from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by
+# the same counter on a 1 GiB device copy), keyed by the hash of the kernel source they were
+# taken with.  A changed kernel source gives null until the counters are taken again.
+TRAFFIC_BYTES = {}
+
+
+def source_hash(name: str) -> str:
+    path = os.path.join(ROOT, "paper_2602_13692_amd", "csrc", name)
+    return hashlib.sha256(open(path, "rb").read()).hexdigest()[:16]
+
+
+def time_steps(fn, steps: int, warmup: int, torch):
+    """W untimed steps, then exactly K steps between synchronisations; returns ms per step."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+class KernelTimer:
+    """Per-step HIP event pairs recorded by the library around its dominant kernel."""
+
+    def __init__(self, steps: int, torch, ta):
+        self.torch, self.ta = torch, ta
+        self.pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                      for _ in range(steps)]
+        for a, b in self.pairs:      # the first record creates the underlying hipEvent_t
+            a.record()
+            b.record()
+        torch.cuda.synchronize()
+        self.i = 0
+
+    def arm(self):
+        a, b = self.pairs[self.i]
+        self.ta.ta_profile_events(a.cuda_event, b.cuda_event)
+        self.i += 1
+
+    def disarm(self):
+        self.ta.ta_profile_events(None, None)
+
+    def mean_ms(self) -> float:
+        self.torch.cuda.synchronize()
+        used = self.pairs[: self.i]
+        return sum(a.elapsed_time(b) for a, b in used) / max(len(used), 1)
+
+
+def run_decode(wb, steps, warmup, torch, ta):
+    dev = wb.q.device
+    desc = ta.Desc(wb.num_q_heads, wb.num_kv_heads)
+    bt = torch.from_numpy(wb.block_table).to(dev)
+    cl = torch.from_numpy(wb.context_lens).to(dev)
+    out = torch.empty_like(wb.q)
+    lse = torch.empty((wb.batch, wb.num_q_heads), dtype=torch.float32, device=dev)
+    ws = ta.alloc_workspace(desc, wb.batch, 1, wb.max_context_len, dev)
+    timer = KernelTimer(steps, torch, ta)
+
+    def step():
+        ta.ta_paged_decode(desc, wb.q, wb.k_pool, wb.v_pool, bt, cl, wb.max_context_len, out, lse, ws)
+
+    def timed_step():
+        timer.arm()
+        step()
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        timed_step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    timer.disarm()
+    return ms, timer.mean_ms(), out, lse
+
+
+def run_prefill(wb, steps, warmup, torch, ta):
+    dev = wb.q.device
+    desc = ta.Desc(wb.num_q_heads, wb.num_kv_heads)
+    bt = torch.from_numpy(wb.block_table).to(dev)
+    cl = torch.from_numpy(wb.context_lens).to(dev)
+    cu = torch.from_numpy(wb.cu_q_lens).to(dev)
+    out = torch.empty_like(wb.q)
+    lse = torch.empty((wb.total_q, wb.num_q_heads), dtype=torch.float32, device=dev)
+    ws = ta.alloc_workspace(desc, wb.batch, max(wb.max_q_len, 2), wb.max_context_len, dev)
+    timer = KernelTimer(steps, torch, ta)
+
+    def step():
+        ta.ta_append_prefill(desc, wb.q, cu, wb.k_pool, wb.v_pool, bt, cl, wb.total_q, wb.max_q_len,
+                             wb.max_context_len, out, lse, ws)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        timer.arm()
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    timer.disarm()
+    return ms, timer.mean_ms(), out, lse
+
+
+def oracle_baseline(wb, wl):
+    """The fp64 oracle as it stands, on this host's cores, on the whole decode batch."""
+    import oracle
+
+    q, kp, vp = wl.as_u16(wb.q), wl.as_u16(wb.k_pool), wl.as_u16(wb.v_pool)
+    geom = oracle.Geometry(wb.num_q_heads, wb.num_kv_heads)
+    t0 = time.perf_counter()
+    out, lse = oracle.paged_decode(geom, q, kp, vp, wb.block_table, wb.context_lens)
+    dt = time.perf_counter() - t0
+    kv_bytes = int(wb.context_lens.astype("int64").sum()) * wb.kv_bytes_per_token
+    return {
+        "value": kv_bytes / dt / 1e9, "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": f"all {wb.batch} programs x {wb.num_q_heads} query heads of the same batch, "
+                  f"{dt:.2f} s wall",
+    }, out, lse
+
+
+def spot_check(out, lse, ref_out, ref_lse, torch):
+    import numpy as np
+
+    got = out.float().cpu().numpy().astype("float64").reshape(ref_out.shape)
+    err = np.abs(got - ref_out)
+    ok = bool(np.all(err <= 2e-2 + 1e-2 * np.abs(ref_out)))
+    lse_err = float(np.max(np.abs(lse.cpu().numpy().reshape(ref_lse.shape) - ref_lse)))
+    return {"within_tolerance": ok, "max_abs_err": float(err.max()), "max_lse_err": lse_err}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--only", choices=["decode", "all"], default="all")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the hot path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    from paper_2602_13692_amd import binding as ta
+    from paper_2602_13692_amd import workloads as wl
+
+    if not os.path.exists(ta.LIB_PATH):
+        import __graft_entry__
+
+        __graft_entry__.build()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # ---------------- headline: decode on the Llama-3-8B-shaped batch ----------------
+    wb = wl.llama8b_decode(dev)
+    kv_bytes = int(wb.context_lens.astype("int64").sum()) * wb.kv_bytes_per_token
+    ms, kernel_ms, out, lse = run_decode(wb, args.steps, args.warmup, torch, ta)
+    value = kv_bytes / ms / 1e6
+    achieved = kv_bytes / kernel_ms / 1e6
+    traffic = TRAFFIC_BYTES.get(source_hash("ta_decode.hip"))
+    result = {
+        "metric": "paged_decode_kv_gbps", "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": "config 2: Llama-3-8B-shaped decode layer, 64 programs, 32 q / 8 kv heads, "
+                        "d=128, page 16, context lengths uniform 4k-32k, seeded page permutation",
+            "batch": wb.batch, "cached_tokens": int(wb.context_lens.sum()),
+            "kv_bytes_per_step": kv_bytes, "layer_tokens_per_s": round(wb.batch / ms * 1e3, 1),
+        },
+        "roofline": {
+            "bound": "hbm", "kernel": "decode_chunk_kernel<4>", "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+            "kernel_ms": round(kernel_ms, 4), "traffic": traffic,
+        },
+    }
+    if not args.no_cpu_baseline:
+        base, ref_out, ref_lse = oracle_baseline(wb, wl)
+        base["value"] = round(base["value"], 3)
+        result["cpu_baseline"] = base
+        result["config"]["parity_vs_oracle"] = spot_check(out, lse, ref_out, ref_lse, torch)
+        del ref_out, ref_lse
+    if args.calibrate_copy:
+        x = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        y = torch.empty_like(x)
+        y.copy_(x)
+        torch.cuda.synchronize()
+        del x, y
+    del wb, out, lse
+    torch.cuda.empty_cache()
+
+    extra = {}
+    if args.only == "all":
+        # ---------------- append-prefill (MFMA) ----------------
+        wb = wl.append_prefill(dev)
+        flops = 4.0 * wb.head_dim * wb.num_q_heads * wb.unmasked_pairs()
+        p_steps = max(2, min(args.steps, 5))
+        ms, kernel_ms, out, lse = run_prefill(wb, p_steps, 1, torch, ta)
+        extra["append_prefill"] = {
+            "workload": "config 3: 64 programs append 256-2048 new tokens onto 8k-32k prefixes",
+            "metric": "append_prefill_tflops", "value": round(flops / ms / 1e9, 1), "unit": "TFLOP/s",
+            "ms_per_step": round(ms, 3), "steps": p_steps, "new_tokens": wb.total_q,
+            "new_tokens_per_s": round(wb.total_q / ms * 1e3, 1), "flops_per_step": flops,
+            "roofline": {"bound": "mfma", "kernel": "prefill_kernel<4>",
+                         "achieved": round(flops / kernel_ms / 1e9, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": round(flops / kernel_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
+                         "kernel_ms": round(kernel_ms, 3), "traffic": None},
+        }
+        del wb, out, lse
+        torch.cuda.empty_cache()
+
+        # ---------------- forked programs with shared prefixes ----------------
+        wb = wl.forked_decode(dev)
+        logical = int(wb.context_lens.astype("int64").sum()) * wb.kv_bytes_per_token
+        unique = wb.unique_tokens() * wb.kv_bytes_per_token
+        ms, kernel_ms, out, lse = run_decode(wb, max(2, min(args.steps, 20)), 2, torch, ta)
+        extra["forked_decode"] = {
+            "workload": "config 4: 256 programs, 64 q / 8 kv heads, groups of 16 share a 16k prefix",
+            "ms_per_step": round(ms, 4), "logical_kv_gbps": round(logical / ms / 1e6, 1),
+            "unique_kv_gbps": round(unique / ms / 1e6, 1),
+            "frac_of_unique_bytes_roofline": round(unique / kernel_ms / 1e6 / HBM_PEAK_GBPS, 4),
+            "kernel_ms": round(kernel_ms, 4),
+        }
+        del wb, out, lse
+        torch.cuda.empty_cache()
+
+        # ---------------- restore from pinned host memory, then decode ----------------
+        wb = wl.long_horizon_restore(dev)
+        rs = wb.restore
+        page_bytes = wb.num_kv_heads * wb.page_size * wb.head_dim * 2
+        n = int(rs.dst_slots.shape[0])
+        slots = torch.from_numpy(rs.dst_slots.copy())
+        res = {}
+        for mode, nbytes in (("zero_copy", ta.ta_restore_staging_min_bytes(n)),
+                             ("staged", ta.ta_restore_staging_min_bytes(n) + 2 * (256 << 20))):
+            staging = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+            def step():
+                ta.ta_kv_page_restore(wb.k_pool, wb.v_pool, page_bytes, rs.host_k, rs.host_v, slots,
+                                      wb.pool_pages, staging)
+
+            r_ms = time_steps(step, 3, 1, torch)
+            res[mode] = {"ms": round(r_ms, 2), "gbps": round(2.0 * n * page_bytes / r_ms / 1e6, 2)}
+            del staging
+        # the link roofline: one large pinned host-to-device copy of the same bytes
+        big = torch.empty_like(rs.host_k, device=dev)
+        link_ms = time_steps(lambda: big.copy_(rs.host_k, non_blocking=True), 3, 1, torch)
+        link_gbps = n * page_bytes / link_ms / 1e6
+        del big
+        kv5 = int(wb.context_lens.astype("int64").sum()) * wb.kv_bytes_per_token
+        ms, kernel_ms, out, lse = run_decode(wb, max(2, min(args.steps, 10)), 2, torch, ta)
+        best = min(res.values(), key=lambda r: r["ms"])
+        extra["restore_then_decode"] = {
+            "workload": "config 5: 128 programs, lognormal lengths (median 24k, cap 128k), 30% restored "
+                        "from pinned host memory into random free slots, then one decode",
+            "restored_pages": n, "restored_bytes": 2 * n * page_bytes, "restore": res,
+            "host_link_h2d_gbps": round(link_gbps, 2),
+            "restore_frac_of_link": round(best["gbps"] / link_gbps, 3),
+            "decode_ms": round(ms, 4), "decode_kv_gbps": round(kv5 / ms / 1e6, 1),
+            "decode_kernel_frac_of_hbm_peak": round(kv5 / kernel_ms / 1e6 / HBM_PEAK_GBPS, 4),
+            "restore_to_decode_time_ratio": round(best["ms"] / ms, 1),
+        }
+        del wb, out, lse
+        torch.cuda.empty_cache()
+    result["extra"] = extra
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -173,6 +173,18 @@ TA_API int ta_kv_page_restore(void *k_pool, void *v_pool, size_t page_bytes, con
                        const void *host_v, const int32_t *dst_slots, int32_t n_pages,
                        int32_t pool_pages, void *staging, size_t staging_bytes, void *hip_stream);
 
+/*
+ * Instrumentation for benchmarks (no paper passage: it measures, it computes
+ * nothing).  While both events are non-NULL, ta_paged_decode and
+ * ta_append_prefill record start_event immediately before and stop_event
+ * immediately after their dominant kernel (the split-K chunk kernel, the MFMA
+ * tile kernel) on the call's stream, so that hipEventElapsedTime(start, stop)
+ * is that kernel's duration.  The events are hipEvent_t passed as void*, owned
+ * by the caller, and apply to the calling thread's next calls until replaced;
+ * NULLs switch the recording off.
+ */
+TA_API void ta_profile_events(void *start_event, void *stop_event);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ TA_ERR_HIP = -3
 EXPORTS = (
     "ta_version", "ta_strerror", "ta_last_hip_error", "ta_workspace_bytes", "ta_paged_decode",
     "ta_append_prefill", "ta_restore_staging_min_bytes", "ta_restore_staging_full_bytes",
-    "ta_kv_page_restore",
+    "ta_kv_page_restore", "ta_profile_events",
 )
 
 
@@ -95,6 +95,8 @@ def _lib():
         lib.ta_restore_staging_full_bytes.argtypes = [i32, sz]
         lib.ta_kv_page_restore.restype = ctypes.c_int
         lib.ta_kv_page_restore.argtypes = [vp, vp, sz, vp, vp, vp, i32, i32, vp, sz, vp]
+        lib.ta_profile_events.restype = None
+        lib.ta_profile_events.argtypes = [vp, vp]
         _LIB = lib
     return _LIB
 
@@ -182,6 +184,11 @@ def ta_kv_page_restore(k_pool, v_pool, page_bytes: int, host_k, host_v, dst_slot
     if check:
         _check(rc, "ta_kv_page_restore")
     return rc
+
+
+def ta_profile_events(start_event, stop_event) -> None:
+    """start/stop: raw hipEvent_t handles (ints) or None to switch recording off."""
+    _lib().ta_profile_events(ctypes.c_void_p(start_event), ctypes.c_void_p(stop_event))
 
 
 def alloc_workspace(desc: Desc, batch: int, max_q_len: int, max_context_len: int, device="cuda"):

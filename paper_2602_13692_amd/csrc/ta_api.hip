@@ -16,6 +16,10 @@ int note_hip_error(hipError_t e) {
     return TA_ERR_HIP;
 }
 
+static thread_local ProfileEvents g_profile_events = {nullptr, nullptr};
+
+ProfileEvents profile_events() { return g_profile_events; }
+
 static size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 
 int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
@@ -114,6 +118,12 @@ const char* ta_strerror(int status) {
 }
 
 int ta_last_hip_error(void) { return g_last_hip_error; }
+
+void ta_profile_events(void* start_event, void* stop_event) {
+    const bool on = start_event != nullptr && stop_event != nullptr;
+    g_profile_events.start = on ? static_cast<hipEvent_t>(start_event) : nullptr;
+    g_profile_events.stop = on ? static_cast<hipEvent_t>(stop_event) : nullptr;
+}
 
 size_t ta_workspace_bytes(const ta_attn_desc* desc, int32_t batch, int32_t max_q_len,
                           int32_t max_context_len) {

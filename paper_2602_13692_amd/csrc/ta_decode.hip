@@ -435,6 +435,8 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
         const int64_t blocks = int64_t(w.max_chunks) * g.num_kv_heads;
         if (blocks > 0x7fffffff) return TA_ERR_INVALID_ARG;
         const dim3 grid(static_cast<unsigned>(blocks)), block(kChunkThreads);
+        const ProfileEvents ev = profile_events();
+        if (ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
         switch (g.group) {
             case 1: hipLaunchKernelGGL(decode_chunk_kernel<1>, grid, block, 0, stream, cp); break;
             case 2: hipLaunchKernelGGL(decode_chunk_kernel<2>, grid, block, 0, stream, cp); break;
@@ -443,6 +445,7 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
             default: return TA_ERR_UNSUPPORTED;
         }
         TA_HIP_TRY(hipGetLastError());
+        if (ev.stop != nullptr) TA_HIP_TRY(hipEventRecord(ev.stop, stream));
     }
 
     MergeParams mp{};

@@ -26,6 +26,13 @@ int note_hip_error(hipError_t e);
         if (_e != hipSuccess) return ::ta::note_hip_error(_e); \
     } while (0)
 
+// Benchmark instrumentation: events recorded around the dominant kernel (may be null).
+struct ProfileEvents {
+    hipEvent_t start;
+    hipEvent_t stop;
+};
+ProfileEvents profile_events();
+
 // Resolved geometry: strides in bytes, scale folded with log2(e).
 struct Geometry {
     int32_t num_q_heads;

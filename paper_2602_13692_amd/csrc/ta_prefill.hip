@@ -420,6 +420,8 @@ int launch_prefill(const Geometry& g, const PrefillArgs& a, const WorkspaceLayou
     if (blocks > 0x7fffffff) return TA_ERR_INVALID_ARG;
     const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
     const size_t lds_bytes = 2 * kKTileBytes + 2 * kVTileBytes;
+    const ProfileEvents ev = profile_events();
+    if (ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
     switch (g.group) {
         case 1: hipLaunchKernelGGL(prefill_kernel<1>, grid, block, lds_bytes, stream, pp); break;
         case 2: hipLaunchKernelGGL(prefill_kernel<2>, grid, block, lds_bytes, stream, pp); break;
@@ -428,6 +430,7 @@ int launch_prefill(const Geometry& g, const PrefillArgs& a, const WorkspaceLayou
         default: return TA_ERR_UNSUPPORTED;
     }
     TA_HIP_TRY(hipGetLastError());
+    if (ev.stop != nullptr) TA_HIP_TRY(hipEventRecord(ev.stop, stream));
     return TA_OK;
 }
 
