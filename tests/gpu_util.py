@@ -82,3 +82,58 @@ def assert_close(gpu_out, gpu_lse, ref_out, ref_lse, what=""):
         assert np.max(np.abs(gl[finite] - ref_lse[finite]), initial=0.0) <= LSE_TOL, \
             f"{what}: lse error {np.max(np.abs(gl[finite] - ref_lse[finite])):.4g}"
     return float(err.max()), float(rel.max())
+
+
+def compact_programs(wb, programs):
+    """Host copy of just the pages the given programs name, with block tables remapped.
+
+    Input plumbing only: lets the oracle check sampled rows of a workload whose whole
+    pool would be many GiB.  Returns (k_pool_u16, v_pool_u16, table[int32, len(programs) x stride]).
+    """
+    ps = wb.page_size
+    remap = {}
+    rows = []
+    for b in programs:
+        npg = (int(wb.context_lens[b]) + ps - 1) // ps
+        row = np.full(wb.block_table.shape[1], -1, dtype=np.int32)
+        for i in range(npg):
+            page = int(wb.block_table[b, i])
+            row[i] = remap.setdefault(page, len(remap))
+        rows.append(row)
+    order = np.array(list(remap.keys()), dtype=np.int64)     # insertion order == new index
+    idx = torch.from_numpy(order).to(wb.k_pool.device)
+    k_small = wl.as_u16(wb.k_pool.index_select(0, idx))
+    v_small = wl.as_u16(wb.v_pool.index_select(0, idx))
+    return k_small, v_small, np.stack(rows)
+
+
+def check_sampled_rows(wb, gpu_out, gpu_lse, rng, n_programs=6, rows_per_program=8, what=""):
+    """Compare sampled (program, new token, head) rows of a full-size run with the oracle."""
+    programs = sorted(rng.choice(wb.batch, size=min(n_programs, wb.batch), replace=False).tolist())
+    # always include the longest context: it crosses the most chunks / tiles
+    longest = int(np.argmax(wb.context_lens))
+    if longest not in programs:
+        programs[0] = longest
+        programs.sort()
+    k_small, v_small, table = compact_programs(wb, programs)
+    cu = wb.cu_q_lens
+    row_b, row_t, row_h, row_vis = [], [], [], []
+    for local, b in enumerate(programs):
+        n = int(wb.q_lens[b])
+        L = int(wb.context_lens[b])
+        for _ in range(rows_per_program):
+            i = int(rng.integers(0, n))
+            row_b.append(local)
+            row_t.append(int(cu[b]) + i)
+            row_h.append(int(rng.integers(0, wb.num_q_heads)))
+            row_vis.append(L - n + i + 1)
+        # the last new token sees everything, the first sees only the prefix and itself
+        for i in (0, n - 1):
+            row_b.append(local); row_t.append(int(cu[b]) + i); row_h.append(0); row_vis.append(L - n + i + 1)
+    ref, ref_lse = oracle.attend_rows(geom_of(wb), wl.as_u16(wb.q), k_small, v_small, table,
+                                      row_b, row_t, row_h, row_vis)
+    t = torch.tensor(row_t, device=gpu_out.device)
+    h = torch.tensor(row_h, device=gpu_out.device)
+    got = gpu_out[t, h]
+    got_lse = gpu_lse[t, h]
+    return assert_close(got, got_lse, ref, ref_lse, what)
