@@ -271,17 +271,17 @@ __global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams
     const int n_mine = n_full > wave ? (n_full - wave + kChunkWaves - 1) / kChunkWaves : 0;
     if (n_mine > 0) {
         auto tile_of = [&](int j) -> int64_t {
-            const int jj = j < n_mine ? j : n_mine - 1;  // past the end: re-read the last page
-            const int id = __builtin_amdgcn_readlane(my_id, wave + kChunkWaves * jj);
+            const int id = __builtin_amdgcn_readlane(my_id, wave + kChunkWaves * j);
             return int64_t(id) * p.stride_page_bytes;
         };
         PageRegs bufA, bufB;
         int64_t off = tile_of(0);
         load_page(bufA, k_head + off, v_head + off, lane);
         int j = 0;
-        // two pages per trip, one basic block: each buffer is refilled right after
-        // its page has been consumed and is consumed one page later
-        for (; j + 2 <= n_mine; j += 2) {
+        // two pages per trip, one basic block: each buffer is refilled right after its
+        // page has been consumed and is consumed one page later.  The loop runs while a
+        // third page exists, so no load is ever issued for a page that is not used.
+        for (; j + 2 < n_mine; j += 2) {
             off = tile_of(j + 1);
             load_page(bufB, k_head + off, v_head + off, lane);
             __builtin_amdgcn_sched_barrier(0);
@@ -291,7 +291,16 @@ __global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams
             __builtin_amdgcn_sched_barrier(0);
             process_page<G, false>(bufB, qreg, m, l, o, p.scale_log2, row, kPageSize);
         }
-        if (j < n_mine) process_page<G, false>(bufA, qreg, m, l, o, p.scale_log2, row, kPageSize);
+        // one or two pages are left; bufA holds page j
+        if (j + 1 < n_mine) {
+            off = tile_of(j + 1);
+            load_page(bufB, k_head + off, v_head + off, lane);
+            __builtin_amdgcn_sched_barrier(0);
+            process_page<G, false>(bufA, qreg, m, l, o, p.scale_log2, row, kPageSize);
+            process_page<G, false>(bufB, qreg, m, l, o, p.scale_log2, row, kPageSize);
+        } else {
+            process_page<G, false>(bufA, qreg, m, l, o, p.scale_log2, row, kPageSize);
+        }
     }
     if (has_tail && ((n_here - 1) & (kChunkWaves - 1)) == wave) {
         PageRegs t;

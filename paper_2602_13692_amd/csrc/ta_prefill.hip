@@ -7,8 +7,8 @@
 // = (256 / G) consecutive new tokens x the G query heads that share a kv head,
 // and walks the program's keys in tiles of 64 (four pages):
 //
-//   * K and V tiles go HBM -> registers -> LDS once per workgroup, double
-//     buffered, and serve all 256 rows;
+//   * K and V tiles go HBM -> registers -> LDS once per workgroup, through a
+//     ring of three tiles with one barrier per tile, and serve all 256 rows;
 //   * every wave owns 64 rows and computes the TRANSPOSED scores S^T = K Q^T,
 //     so that each lane holds one query row's scores in its accumulator
 //     registers: the softmax needs one cross-lane exchange per tile, and the
@@ -36,6 +36,7 @@ constexpr int kTileKeys = 64;       // keys per LDS tile (4 pages)
 constexpr int kKTileBytes = kTileKeys * kHeadDim * 2;  // 16 KiB
 constexpr int kVTileBytes = kTileKeys * kHeadDim * 2;  // 16 KiB
 constexpr float kRescaleThreshold = 8.0f;  // log2 units
+constexpr int kRing = 3;                   // LDS tiles in flight
 
 struct PrefillParams {
     const uint16_t* q;
@@ -104,6 +105,11 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, r);
 }
 
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b),
+                                           acc, false);
+}
+
 __device__ __forceinline__ uint16_t to_bf16_rne(float f) {
     uint32_t u = __builtin_bit_cast(uint32_t, f);
     if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40);
@@ -129,8 +135,8 @@ template <int G>
 __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
     constexpr int kTileTokens = kRowsPerBlock / G;
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    char* k_lds = lds;                       // [2][kKTileBytes]
-    char* v_lds = lds + 2 * kKTileBytes;     // [2][kVTileBytes]
+    char* k_lds = lds;                           // [kRing][kKTileBytes]
+    char* v_lds = lds + kRing * kKTileBytes;     // [kRing][kVTileBytes]
 
     const int n_tiles_total = p.tile_start[p.batch];
     const int tile_id = blockIdx.x / p.num_kv_heads;
@@ -194,7 +200,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
         for (int i = 0; i < 4; ++i) {
             int pg = t * 4 + i;
             pg = pg < n_pages_b ? pg : n_pages_b - 1;
-            id[i] = table[pg];
+            id[i] = __builtin_amdgcn_readfirstlane(table[pg]);
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -209,8 +215,8 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
         for (int j = 0; j < 4; ++j) st.v[j] = *reinterpret_cast<const u32x4*>(vp + j * 256);
     };
 
-    auto store_tile = [&](const Stage& st, int t, int buf) {
-        char* kd = k_lds + buf * kKTileBytes + k_lds_off;
+    auto store_tile = [&](const Stage& st, int t, int slot) {
+        char* kd = k_lds + slot * kKTileBytes + k_lds_off;
 #pragma unroll
         for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(kd + i * 4096) = st.k[i];
         // keys at or beyond the context length may hold anything (even NaN): V rows there
@@ -222,7 +228,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
             vr[j] = live ? st.v[j] : u32x4{0u, 0u, 0u, 0u};
         }
         // transpose 4 keys x 8 dims into 8 entries of (4 keys) and write 4 pieces of 16 bytes
-        char* vd = v_lds + buf * kVTileBytes + v_lds_off;
+        char* vd = v_lds + slot * kVTileBytes + v_lds_off;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {  // dims 2w, 2w+1 of this chunk -> piece w
             const uint32_t a0 = vr[0][w], a1 = vr[1][w], a2 = vr[2][w], a3 = vr[3][w];
@@ -243,7 +249,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[db][rb][r] = 0.0f;
-    float m[2] = {kNegBig, kNegBig};   // running maximum (log2 domain, scaled)
+    float m[2] = {kNegBig, kNegBig};   // reference maximum (log2 domain, scaled)
     float lsum[2] = {0.0f, 0.0f};      // this lane's share of the row sum
 
     // LDS read offsets
@@ -255,103 +261,183 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
 #pragma unroll
     for (int db = 0; db < 4; ++db) v_rd[db] = v_entry_offset(hl, db * 32 + l32);
 
+    // ---- the four steps of one 32-key block ----
+    // A: S^T block = K Q^T, 32 keys x (2 x 32 rows); register r of lane (l32, hl) holds
+    //    key 8 (r / 4) + 4 hl + r % 4 of the block
+    auto scores = [&](const char* kt, int kb, f32x16 (&s)[2]) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[rb][r] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(kt + k_rd[kb] + (((2 * ks + hl) ^ k_swz) << 4));
+            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][ks], s[0], 0, 0, 0);
+            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][ks], s[1], 0, 0, 0);
+        }
+    };
+    // causal mask of a block that straddles the diagonal
+    auto mask_scores = [&](int key_base, f32x16 (&s)[2]) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = key_base + 4 * hl + 8 * (r >> 2) + (r & 3);
+                s[rb][r] = key < vis[rb] ? s[rb][r] : -INFINITY;
+            }
+    };
+    // B1: row maxima; the reference is raised (and O, l rescaled) only when it would grow
+    //     by more than the threshold, a wave-uniform and rare event
+    auto raise_reference = [&](const f32x16 (&s)[2]) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            float mx = fmaxf(fmaxf(s[rb][0], s[rb][1]), s[rb][2]);
+#pragma unroll
+            for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[rb][r]), s[rb][r + 1]);
+            mx = fmaxf(mx, s[rb][15]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float cand = mx * p.scale_log2;
+            const bool grow = cand > m[rb] + kRescaleThreshold;
+            if (__builtin_expect(__builtin_amdgcn_ballot_w64(grow) != 0, 0)) {
+                const float m_new = fmaxf(m[rb], cand);
+                const float alpha = __builtin_amdgcn_exp2f(m[rb] - m_new);
+                m[rb] = m_new;
+                lsum[rb] *= alpha;
+                // O lives in the accumulation registers the matrix core writes; scaling it there
+                // (read, multiply, write back) keeps this rare path from forcing copies of O
+                // into vector registers on the common path
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        float x = o[db][rb][r];
+                        float tmp;
+                        asm volatile(
+                            "v_accvgpr_read_b32 %1, %0\n\t"
+                            "s_nop 1\n\t"
+                            "v_mul_f32 %1, %1, %2\n\t"
+                            "s_nop 1\n\t"
+                            "v_accvgpr_write_b32 %0, %1"
+                            : "+a"(x), "=&v"(tmp)
+                            : "v"(alpha));
+                        o[db][rb][r] = x;
+                    }
+            }
+        }
+    };
+    // B2: weights 2^(s c - m), row-sum share, packing into the B operands of the two k = 16 steps
+    auto weights = [&](const f32x16 (&s)[2], bf16x8 (&pf)[2][2]) {
+        const uint32_t ones = 0x3f803f80u;   // (1.0, 1.0) in bf16
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            const float bias = -m[rb];
+            float pr[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) pr[r] = __builtin_amdgcn_exp2f(fmaf(s[rb][r], p.scale_log2, bias));
+            // the row sum adds up the ROUNDED weights (the ones the matrix core multiplies),
+            // two per instruction
+            float acc = lsum[rb];
+#pragma unroll
+            for (int step = 0; step < 2; ++step) {
+                u32x4 w;
+                w.x = pack_bf16(pr[8 * step + 0], pr[8 * step + 1]);
+                w.y = pack_bf16(pr[8 * step + 2], pr[8 * step + 3]);
+                w.z = pack_bf16(pr[8 * step + 4], pr[8 * step + 5]);
+                w.w = pack_bf16(pr[8 * step + 6], pr[8 * step + 7]);
+                acc = dot2_bf16(w.x, ones, acc);
+                acc = dot2_bf16(w.y, ones, acc);
+                acc = dot2_bf16(w.z, ones, acc);
+                acc = dot2_bf16(w.w, ones, acc);
+                pf[rb][step] = __builtin_bit_cast(bf16x8, w);
+            }
+            lsum[rb] = acc;
+        }
+    };
+    // C: O^T += V^T P^T; step 0 uses key groups (hl, 2 + hl), step 1 uses (4 + hl, 6 + hl)
+    auto accumulate = [&](const char* vt, int kb, const bf16x8 (&pf)[2][2]) {
+#pragma unroll
+        for (int step = 0; step < 2; ++step) {
+            const char* vq = vt + (kb * 8 + step * 4) * 1024;
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                const u32x2 lo = *reinterpret_cast<const u32x2*>(vq + v_rd[db]);
+                const u32x2 hi = *reinterpret_cast<const u32x2*>(vq + v_rd[db] + 2 * 1024);
+                const u32x4 av = {lo.x, lo.y, hi.x, hi.y};
+                const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+                o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[0][step], o[db][0], 0, 0, 0);
+                o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[1][step], o[db][1], 0, 0, 0);
+            }
+        }
+    };
+
+    // ---- LDS ring of three tiles; tile t lives in slot t % 3 ----
+    // Every iteration t: compute on tile t (the pipelined body also reads K of tile t + 1),
+    // write tile t + 2 into the slot tile t - 1 left, start the loads of tile t + 3, barrier.
+    // Tile t - 1 was last read before the previous barrier and tile t + 2 is first read after
+    // this one, so one barrier per tile is enough.
     Stage st;
     if (n_tiles > 0) {
         load_tile(st, 0);
         store_tile(st, 0, 0);
+        load_tile(st, 1);
+        store_tile(st, 1, 1);
+        load_tile(st, 2);
     }
     __syncthreads();
 
-    for (int t = 0; t < n_tiles; ++t) {
-        const int buf = t & 1;
-        const bool more = t + 1 < n_tiles;
-        if (more) load_tile(st, t + 1);
-        __builtin_amdgcn_sched_barrier(0);  // keep the next tile's loads ahead of this tile's arithmetic
-        const char* kt = k_lds + buf * kKTileBytes;
-        const char* vt = v_lds + buf * kVTileBytes;
-        const bool masked = t >= n_unmasked;
+    int slot = 0;                                // slot of tile t
+    auto next_slot = [](int s) { return s == kRing - 1 ? 0 : s + 1; };
+    auto end_of_tile = [&](int t) {
+        const int s2 = slot == 0 ? 2 : slot - 1;  // slot of tile t + 2 == slot of tile t - 1
+        store_tile(st, t + 2, s2);
+        load_tile(st, t + 3);
+        __syncthreads();
+        slot = next_slot(slot);
+    };
 
+    int t = 0;
+    // ---- pipelined body for tiles whose successor is also unmasked ----
+    const int n_pipe = n_unmasked - 1;
+    if (n_pipe > 0) {
+        f32x16 sa[2], sb[2];
+        bf16x8 pf[2][2];
+        scores(k_lds + slot * kKTileBytes, 0, sa);
+        raise_reference(sa);
+        for (; t < n_pipe; ++t) {
+            const char* kt = k_lds + slot * kKTileBytes;
+            const char* vt = v_lds + slot * kVTileBytes;
+            const char* kt_next = k_lds + next_slot(slot) * kKTileBytes;
+            // scores of the next block run on the matrix core while the vector ALU turns the
+            // current block's scores into weights; then the weights feed the matrix core while
+            // the vector ALU reduces the next block's row maxima
+            scores(kt, 1, sb);
+            weights(sa, pf);
+            accumulate(vt, 0, pf);
+            raise_reference(sb);
+            scores(kt_next, 0, sa);
+            weights(sb, pf);
+            accumulate(vt, 1, pf);
+            raise_reference(sa);
+            end_of_tile(t);
+        }
+        // sa holds the first block of tile t, which the plain body below computes again
+    }
+    // ---- plain body: the last unmasked tile and the tiles that straddle the diagonal ----
+    for (; t < n_tiles; ++t) {
+        const char* kt = k_lds + slot * kKTileBytes;
+        const char* vt = v_lds + slot * kVTileBytes;
+        const bool masked = t >= n_unmasked;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
-            // S^T block: 32 keys x (2 x 32 rows)
             f32x16 s[2];
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[rb][r] = 0.0f;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8*>(
-                    kt + k_rd[kb] + (((2 * ks + hl) ^ k_swz) << 4));
-                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][ks], s[0], 0, 0, 0);
-                s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][ks], s[1], 0, 0, 0);
-            }
-            // register r of lane (l32, hl) holds key 8 (r / 4) + 4 hl + r % 4 of this block
-            bf16x8 pf[2][2];   // B operands of the two k = 16 steps
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
-                if (masked) {
-                    const int key0 = t * kTileKeys + kb * 32 + 4 * hl;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int key = key0 + 8 * (r >> 2) + (r & 3);
-                        s[rb][r] = key < vis[rb] ? s[rb][r] : -INFINITY;
-                    }
-                }
-                float mx = s[rb][0];
-#pragma unroll
-                for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[rb][r]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float cand = mx * p.scale_log2;
-                // raise the reference only when it would grow by more than the threshold
-                const bool grow = cand > m[rb] + kRescaleThreshold;
-                if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-                    const float m_new = fmaxf(m[rb], cand);
-                    const float alpha = __builtin_amdgcn_exp2f(m[rb] - m_new);
-                    m[rb] = m_new;
-                    lsum[rb] *= alpha;
-#pragma unroll
-                    for (int db = 0; db < 4; ++db)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) o[db][rb][r] *= alpha;
-                }
-                const float bias = -m[rb];
-                float pr[16];
-                float acc = 0.0f;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    pr[r] = __builtin_amdgcn_exp2f(fmaf(s[rb][r], p.scale_log2, bias));
-                    acc += pr[r];
-                }
-                lsum[rb] += acc;
-#pragma unroll
-                for (int step = 0; step < 2; ++step) {
-                    u32x4 w;
-                    w.x = pack_bf16(pr[8 * step + 0], pr[8 * step + 1]);
-                    w.y = pack_bf16(pr[8 * step + 2], pr[8 * step + 3]);
-                    w.z = pack_bf16(pr[8 * step + 4], pr[8 * step + 5]);
-                    w.w = pack_bf16(pr[8 * step + 6], pr[8 * step + 7]);
-                    pf[rb][step] = __builtin_bit_cast(bf16x8, w);
-                }
-            }
-            // O^T += V^T P^T : step 0 uses key groups (hl, 2 + hl), step 1 uses (4 + hl, 6 + hl)
-#pragma unroll
-            for (int step = 0; step < 2; ++step) {
-                const char* vq = vt + (kb * 8 + step * 4) * 1024;
-#pragma unroll
-                for (int db = 0; db < 4; ++db) {
-                    const u32x2 lo = *reinterpret_cast<const u32x2*>(vq + v_rd[db]);
-                    const u32x2 hi = *reinterpret_cast<const u32x2*>(vq + v_rd[db] + 2 * 1024);
-                    const u32x4 av = {lo.x, lo.y, hi.x, hi.y};
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, av);
-                    o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[0][step], o[db][0], 0, 0, 0);
-                    o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[1][step], o[db][1], 0, 0, 0);
-                }
-            }
+            bf16x8 pf[2][2];
+            scores(kt, kb, s);
+            if (masked) mask_scores(t * kTileKeys + kb * 32, s);
+            raise_reference(s);
+            weights(s, pf);
+            accumulate(vt, kb, pf);
         }
-
-        if (more) store_tile(st, t + 1, buf ^ 1);
-        __syncthreads();
+        end_of_tile(t);
     }
 
     // ---- epilogue: normalise and write ----
@@ -419,7 +505,18 @@ int launch_prefill(const Geometry& g, const PrefillArgs& a, const WorkspaceLayou
     const int64_t blocks = max_tiles * g.num_kv_heads;
     if (blocks > 0x7fffffff) return TA_ERR_INVALID_ARG;
     const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
-    const size_t lds_bytes = 2 * kKTileBytes + 2 * kVTileBytes;
+    const size_t lds_bytes = kRing * (kKTileBytes + kVTileBytes);
+    // 96 KiB of dynamic LDS is above the default 64 KiB limit: raise it once per kernel
+    static const hipError_t lds_rc[4] = {
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<1>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes)),
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<2>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes)),
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<4>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes)),
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<8>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes))};
+    for (hipError_t e : lds_rc) TA_HIP_TRY(e);
     const ProfileEvents ev = profile_events();
     if (ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
     switch (g.group) {

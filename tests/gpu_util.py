@@ -10,6 +10,9 @@ ABS_TOL = 2e-2      # contract: |gpu - oracle| <= 2e-2 + 1e-2 * |oracle| (bf16 i
 REL_TOL = 1e-2
 ROW_L2_TOL = 1e-2   # tighter gates of our own: relative L2 error per output row ...
 LSE_TOL = 2e-3      # ... and the log-sum-exp, which a zero output could not fake
+# Append-prefill sums the bf16-ROUNDED weights (the ones the matrix core multiplies), so when one
+# key dominates a row the sum carries that weight's rounding error, at most 2^-8 relative.
+LSE_TOL_PREFILL = 5e-3
 
 
 def widen_bf16(t: torch.Tensor) -> np.ndarray:
@@ -62,7 +65,7 @@ def oracle_prefill(wb):
                                  wl.as_u16(wb.v_pool), wb.block_table, wb.context_lens)
 
 
-def assert_close(gpu_out, gpu_lse, ref_out, ref_lse, what=""):
+def assert_close(gpu_out, gpu_lse, ref_out, ref_lse, what="", lse_tol=LSE_TOL):
     """Element-wise contract tolerance plus the tighter per-row gates."""
     got = widen_bf16(gpu_out).reshape(ref_out.shape)
     assert np.all(np.isfinite(got)), f"{what}: non-finite output"
@@ -79,7 +82,7 @@ def assert_close(gpu_out, gpu_lse, ref_out, ref_lse, what=""):
         gl = gpu_lse.detach().cpu().numpy().astype(np.float64).reshape(ref_lse.shape)
         finite = np.isfinite(ref_lse)
         assert np.array_equal(np.isneginf(gl), np.isneginf(ref_lse)), f"{what}: -inf lse mismatch"
-        assert np.max(np.abs(gl[finite] - ref_lse[finite]), initial=0.0) <= LSE_TOL, \
+        assert np.max(np.abs(gl[finite] - ref_lse[finite]), initial=0.0) <= lse_tol, \
             f"{what}: lse error {np.max(np.abs(gl[finite] - ref_lse[finite])):.4g}"
     return float(err.max()), float(rel.max())
 
@@ -107,7 +110,8 @@ def compact_programs(wb, programs):
     return k_small, v_small, np.stack(rows)
 
 
-def check_sampled_rows(wb, gpu_out, gpu_lse, rng, n_programs=6, rows_per_program=8, what=""):
+def check_sampled_rows(wb, gpu_out, gpu_lse, rng, n_programs=6, rows_per_program=8, what="",
+                       lse_tol=LSE_TOL):
     """Compare sampled (program, new token, head) rows of a full-size run with the oracle."""
     programs = sorted(rng.choice(wb.batch, size=min(n_programs, wb.batch), replace=False).tolist())
     # always include the longest context: it crosses the most chunks / tiles
@@ -136,4 +140,4 @@ def check_sampled_rows(wb, gpu_out, gpu_lse, rng, n_programs=6, rows_per_program
     h = torch.tensor(row_h, device=gpu_out.device)
     got = gpu_out[t, h]
     got_lse = gpu_lse[t, h]
-    return assert_close(got, got_lse, ref, ref_lse, what)
+    return assert_close(got, got_lse, ref, ref_lse, what, lse_tol=lse_tol)
