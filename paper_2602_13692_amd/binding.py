@@ -13,7 +13,8 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libta_hip.so")
+# TA_LIB_PATH selects another build of the same library (kernel experiments); default: in-tree
+LIB_PATH = os.environ.get("TA_LIB_PATH", os.path.join(_HERE, "libta_hip.so"))
 
 TA_OK = 0
 TA_ERR_INVALID_ARG = -1

@@ -180,6 +180,9 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
         for (int ks = 0; ks < 8; ++ks) {
             u32x4 t = {0u, 0u, 0u, 0u};
             if (ok) t = *reinterpret_cast<const u32x4*>(qrow + ks * 16);
+            // Q is only ever a matrix-instruction operand: parking it in accumulation registers
+            // leaves the vector registers to the softmax and the operand prefetch
+            asm volatile("" : "+a"(t));
             qf[rb][ks] = __builtin_bit_cast(bf16x8, t);
         }
     }
@@ -193,23 +196,32 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
     const int k_lds_off = r16 * 256 + ((c16 ^ r16) << 4);           // + i * 4096 for key r16 + 16 i
     const int v_lds_off = r16 * 1024 + c16 * 64;                    // pieces at ((j ^ (c16 >> 2)) << 4)
 
+    // Page ids: lane l of every wave holds the id of page (64 g + l) of the current group of 64
+    // pages (16 tiles), clamped to the program's last page; the next group is fetched one
+    // group ahead, so no tile waits for a dependent id load.
+    auto fetch_ids = [&](int group) -> int {
+        int pg = group * 64 + lane;
+        pg = pg < n_pages_b ? pg : n_pages_b - 1;
+        return table[pg];
+    };
+    int ids_group = 0;
+    int ids_cur = fetch_ids(0);
+    int ids_next = fetch_ids(1);
+
     auto load_tile = [&](Stage& st, int t) {
-        // page ids of the tile's four pages, clamped to the program's last page
+        if ((t >> 4) != ids_group) {      // tiles are visited in order, so this is group + 1
+            ids_group = t >> 4;
+            ids_cur = ids_next;
+            ids_next = fetch_ids(ids_group + 1);
+        }
         int id[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            int pg = t * 4 + i;
-            pg = pg < n_pages_b ? pg : n_pages_b - 1;
-            id[i] = __builtin_amdgcn_readfirstlane(table[pg]);
-        }
+        for (int i = 0; i < 4; ++i) id[i] = __builtin_amdgcn_readlane(ids_cur, (t & 15) * 4 + i);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             st.k[i] = *reinterpret_cast<const u32x4*>(k_base + int64_t(id[i]) * p.stride_page_bytes);
         // V: this thread's 4-key group r16 lies in page r16 / 4 of the tile (uniform per wave)
-        int vid = id[0];
-        vid = (r16 >> 2) == 1 ? id[1] : vid;
-        vid = (r16 >> 2) == 2 ? id[2] : vid;
-        vid = (r16 >> 2) == 3 ? id[3] : vid;
+        const int vid = __builtin_amdgcn_readlane(ids_cur, (t & 15) * 4 + wave);
         const char* vp = v_base + int64_t(vid) * p.stride_page_bytes;
 #pragma unroll
         for (int j = 0; j < 4; ++j) st.v[j] = *reinterpret_cast<const u32x4*>(vp + j * 256);
@@ -288,18 +300,12 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
     };
     // B1: row maxima; the reference is raised (and O, l rescaled) only when it would grow
     //     by more than the threshold, a wave-uniform and rare event
-    auto raise_reference = [&](const f32x16 (&s)[2]) {
+    auto rescale_if_needed = [&](const float (&cand)[2]) {
+        const bool grow = cand[0] > m[0] + kRescaleThreshold || cand[1] > m[1] + kRescaleThreshold;
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(grow) != 0, 0)) {
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            float mx = fmaxf(fmaxf(s[rb][0], s[rb][1]), s[rb][2]);
-#pragma unroll
-            for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[rb][r]), s[rb][r + 1]);
-            mx = fmaxf(mx, s[rb][15]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float cand = mx * p.scale_log2;
-            const bool grow = cand > m[rb] + kRescaleThreshold;
-            if (__builtin_expect(__builtin_amdgcn_ballot_w64(grow) != 0, 0)) {
-                const float m_new = fmaxf(m[rb], cand);
+            for (int rb = 0; rb < 2; ++rb) {
+                const float m_new = fmaxf(m[rb], cand[rb]);
                 const float alpha = __builtin_amdgcn_exp2f(m[rb] - m_new);
                 m[rb] = m_new;
                 lsum[rb] *= alpha;
@@ -324,6 +330,19 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
                     }
             }
         }
+    };
+    auto raise_reference = [&](const f32x16 (&s)[2]) {
+        float cand[2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            float mx = fmaxf(fmaxf(s[rb][0], s[rb][1]), s[rb][2]);
+#pragma unroll
+            for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[rb][r]), s[rb][r + 1]);
+            mx = fmaxf(mx, s[rb][15]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            cand[rb] = mx * p.scale_log2;
+        }
+        rescale_if_needed(cand);
     };
     // B2: weights 2^(s c - m), row-sum share, packing into the B operands of the two k = 16 steps
     auto weights = [&](const f32x16 (&s)[2], bf16x8 (&pf)[2][2]) {
@@ -370,6 +389,95 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
         }
     };
 
+    // ---- the pipelined body's two regions, written slice by slice ----
+    // With one wave per SIMD nothing hides latency except the order of this wave's own
+    // instructions, so the order is written out: every slice issues two matrix instructions,
+    // the LDS read of the operand needed two slices later, and a fixed share of the vector
+    // work; a scheduling barrier closes the slice so the compiler keeps the interleaving.
+    //
+    // Region X: scores of the next block (matrix core) with the weights of the current block
+    // (vector ALU).  Slice ks turns scores 2 ks and 2 ks + 1 of both row blocks into weights.
+    auto region_scores_weights = [&](const char* kt, int kb, f32x16 (&s_new)[2],
+                                     const f32x16 (&s_old)[2], bf16x8 (&pf)[2][2]) {
+        const uint32_t ones = 0x3f803f80u;   // (1.0, 1.0) in bf16
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        bf16x8 a[8];
+        uint32_t pw[2][8];
+        float acc[2] = {lsum[0], lsum[1]};
+        const float bias[2] = {-m[0], -m[1]};
+        auto k_operand = [&](int ks) {
+            return *reinterpret_cast<const bf16x8*>(kt + k_rd[kb] + (((2 * ks + hl) ^ k_swz) << 4));
+        };
+        a[0] = k_operand(0);
+        a[1] = k_operand(1);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            s_new[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], qf[0][ks], ks == 0 ? zero : s_new[0], 0, 0, 0);
+            s_new[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], qf[1][ks], ks == 0 ? zero : s_new[1], 0, 0, 0);
+            if (ks + 2 < 8) a[ks + 2] = k_operand(ks + 2);
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(s_old[rb][2 * ks], p.scale_log2, bias[rb]));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(s_old[rb][2 * ks + 1], p.scale_log2, bias[rb]));
+                pw[rb][ks] = pack_bf16(p0, p1);
+                acc[rb] = dot2_bf16(pw[rb][ks], ones, acc[rb]);   // row sum of the ROUNDED weights
+            }
+            // the slice's vector results are "used" here, so instruction selection cannot let
+            // them drift past the barrier to the end of the region
+            asm volatile("" ::"v"(pw[0][ks]), "v"(pw[1][ks]), "v"(acc[0]), "v"(acc[1]));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        lsum[0] = acc[0];
+        lsum[1] = acc[1];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int step = 0; step < 2; ++step) {
+                const u32x4 w = {pw[rb][4 * step], pw[rb][4 * step + 1], pw[rb][4 * step + 2], pw[rb][4 * step + 3]};
+                pf[rb][step] = __builtin_bit_cast(bf16x8, w);
+            }
+    };
+    // Region Y: O^T += V^T P^T (matrix core) with the row maxima of the next block's scores
+    // (vector ALU).  The maxima start two slices in, when the scores have left the matrix core.
+    auto region_accumulate_maxima = [&](const char* vt, int kb, const bf16x8 (&pf)[2][2],
+                                        const f32x16 (&s_new)[2]) {
+        bf16x8 av[8];
+        auto v_operand = [&](int idx) {   // idx = 4 step + dim block
+            const char* vq = vt + (kb * 8 + (idx >> 2) * 4) * 1024 + v_rd[idx & 3];
+            const u32x2 lo = *reinterpret_cast<const u32x2*>(vq);
+            const u32x2 hi = *reinterpret_cast<const u32x2*>(vq + 2 * 1024);
+            const u32x4 w = {lo.x, lo.y, hi.x, hi.y};
+            return __builtin_bit_cast(bf16x8, w);
+        };
+        float mx[2] = {-INFINITY, -INFINITY};
+        av[0] = v_operand(0);
+        av[1] = v_operand(1);
+#pragma unroll
+        for (int idx = 0; idx < 8; ++idx) {
+            const int step = idx >> 2, db = idx & 3;
+            o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[idx], pf[0][step], o[db][0], 0, 0, 0);
+            o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[idx], pf[1][step], o[db][1], 0, 0, 0);
+            if (idx + 2 < 8) av[idx + 2] = v_operand(idx + 2);
+            if (idx >= 4) {   // four slices, four scores of each row block per slice
+                const int r0 = (idx - 4) * 4;
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb) {
+                    mx[rb] = fmaxf(fmaxf(mx[rb], s_new[rb][r0]), s_new[rb][r0 + 1]);
+                    mx[rb] = fmaxf(fmaxf(mx[rb], s_new[rb][r0 + 2]), s_new[rb][r0 + 3]);
+                }
+                asm volatile("" ::"v"(mx[0]), "v"(mx[1]));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        float cand[2];
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            mx[rb] = fmaxf(mx[rb], __shfl_xor(mx[rb], 32));
+            cand[rb] = mx[rb] * p.scale_log2;
+        }
+        rescale_if_needed(cand);
+    };
+
     // ---- LDS ring of three tiles; tile t lives in slot t % 3 ----
     // Every iteration t: compute on tile t (the pipelined body also reads K of tile t + 1),
     // write tile t + 2 into the slot tile t - 1 left, start the loads of tile t + 3, barrier.
@@ -407,17 +515,10 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
             const char* kt = k_lds + slot * kKTileBytes;
             const char* vt = v_lds + slot * kVTileBytes;
             const char* kt_next = k_lds + next_slot(slot) * kKTileBytes;
-            // scores of the next block run on the matrix core while the vector ALU turns the
-            // current block's scores into weights; then the weights feed the matrix core while
-            // the vector ALU reduces the next block's row maxima
-            scores(kt, 1, sb);
-            weights(sa, pf);
-            accumulate(vt, 0, pf);
-            raise_reference(sb);
-            scores(kt_next, 0, sa);
-            weights(sb, pf);
-            accumulate(vt, 1, pf);
-            raise_reference(sa);
+            region_scores_weights(kt, 1, sb, sa, pf);
+            region_accumulate_maxima(vt, 0, pf, sb);
+            region_scores_weights(kt_next, 0, sa, sb, pf);
+            region_accumulate_maxima(vt, 1, pf, sa);
             end_of_tile(t);
         }
         // sa holds the first block of tile t, which the plain body below computes again
