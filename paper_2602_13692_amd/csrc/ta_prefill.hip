@@ -37,6 +37,8 @@ constexpr int kKTileBytes = kTileKeys * kHeadDim * 2;  // 16 KiB
 constexpr int kVTileBytes = kTileKeys * kHeadDim * 2;  // 16 KiB
 constexpr float kRescaleThreshold = 8.0f;  // log2 units
 constexpr int kRing = 3;                   // LDS tiles in flight
+constexpr int kKAhead = 3;                 // LDS operand reads in flight ahead of their matrix instruction
+constexpr int kVAhead = 4;
 
 struct PrefillParams {
     const uint16_t* q;
@@ -208,49 +210,58 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
     int ids_cur = fetch_ids(0);
     int ids_next = fetch_ids(1);
 
-    auto load_tile = [&](Stage& st, int t) {
+    // Loading one tile = planning (page ids -> byte offsets, scalar) + 8 loads of 16 bytes;
+    // storing it to LDS = 4 K writes + 4 V pieces (mask, 4x8 transpose, write).  Both are cut
+    // into eight steps so that the pipelined body can spread them over its slices.
+    struct LoadPlan {
+        int64_t k_off[4];
+        int64_t v_off;
+    };
+    auto plan_load = [&](int t) -> LoadPlan {
         if ((t >> 4) != ids_group) {      // tiles are visited in order, so this is group + 1
             ids_group = t >> 4;
             ids_cur = ids_next;
             ids_next = fetch_ids(ids_group + 1);
         }
-        int id[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) id[i] = __builtin_amdgcn_readlane(ids_cur, (t & 15) * 4 + i);
+        LoadPlan lp;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            st.k[i] = *reinterpret_cast<const u32x4*>(k_base + int64_t(id[i]) * p.stride_page_bytes);
+            lp.k_off[i] = int64_t(__builtin_amdgcn_readlane(ids_cur, (t & 15) * 4 + i)) * p.stride_page_bytes;
         // V: this thread's 4-key group r16 lies in page r16 / 4 of the tile (uniform per wave)
-        const int vid = __builtin_amdgcn_readlane(ids_cur, (t & 15) * 4 + wave);
-        const char* vp = v_base + int64_t(vid) * p.stride_page_bytes;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) st.v[j] = *reinterpret_cast<const u32x4*>(vp + j * 256);
+        lp.v_off = int64_t(__builtin_amdgcn_readlane(ids_cur, (t & 15) * 4 + wave)) * p.stride_page_bytes;
+        return lp;
     };
-
-    auto store_tile = [&](const Stage& st, int t, int slot) {
-        char* kd = k_lds + slot * kKTileBytes + k_lds_off;
+    auto load_step = [&](Stage& st, const LoadPlan& lp, int i) {
+        if (i < 4) st.k[i] = *reinterpret_cast<const u32x4*>(k_base + lp.k_off[i]);
+        else st.v[i - 4] = *reinterpret_cast<const u32x4*>(v_base + lp.v_off + (i - 4) * 256);
+    };
+    auto load_tile = [&](Stage& st, int t) {
+        const LoadPlan lp = plan_load(t);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(kd + i * 4096) = st.k[i];
-        // keys at or beyond the context length may hold anything (even NaN): V rows there
-        // are zeroed, because 0 * NaN inside the matrix core would poison the output
-        u32x4 vr[4];
+        for (int i = 0; i < 8; ++i) load_step(st, lp, i);
+    };
+    auto store_step = [&](const Stage& st, int t, int slot, int i) {
+        if (i < 4) {
+            *reinterpret_cast<u32x4*>(k_lds + slot * kKTileBytes + k_lds_off + i * 4096) = st.k[i];
+        } else {
+            // piece w holds dims 2w, 2w+1 of this thread's chunk for its four keys: a 4x2
+            // transpose.  Keys at or beyond the context length may hold anything (even NaN):
+            // their V rows are zeroed, because 0 * NaN inside the matrix core would poison O.
+            const int w = i - 4;
+            uint32_t a[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bool live = t * kTileKeys + r16 * 4 + j < L;
-            vr[j] = live ? st.v[j] : u32x4{0u, 0u, 0u, 0u};
-        }
-        // transpose 4 keys x 8 dims into 8 entries of (4 keys) and write 4 pieces of 16 bytes
-        char* vd = v_lds + slot * kVTileBytes + v_lds_off;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {  // dims 2w, 2w+1 of this chunk -> piece w
-            const uint32_t a0 = vr[0][w], a1 = vr[1][w], a2 = vr[2][w], a3 = vr[3][w];
+            for (int j = 0; j < 4; ++j) a[j] = (t * kTileKeys + r16 * 4 + j < L) ? st.v[j][w] : 0u;
             u32x4 piece;
-            piece.x = __builtin_amdgcn_perm(a1, a0, 0x05040100u);  // dim 2w:   keys 0,1
-            piece.y = __builtin_amdgcn_perm(a3, a2, 0x05040100u);  //           keys 2,3
-            piece.z = __builtin_amdgcn_perm(a1, a0, 0x07060302u);  // dim 2w+1: keys 0,1
-            piece.w = __builtin_amdgcn_perm(a3, a2, 0x07060302u);  //           keys 2,3
-            *reinterpret_cast<u32x4*>(vd + ((w ^ (c16 >> 2)) << 4)) = piece;
+            piece.x = __builtin_amdgcn_perm(a[1], a[0], 0x05040100u);  // dim 2w:   keys 0,1
+            piece.y = __builtin_amdgcn_perm(a[3], a[2], 0x05040100u);  //           keys 2,3
+            piece.z = __builtin_amdgcn_perm(a[1], a[0], 0x07060302u);  // dim 2w+1: keys 0,1
+            piece.w = __builtin_amdgcn_perm(a[3], a[2], 0x07060302u);  //           keys 2,3
+            *reinterpret_cast<u32x4*>(v_lds + slot * kVTileBytes + v_lds_off + ((w ^ (c16 >> 2)) << 4)) = piece;
         }
+    };
+    auto store_tile = [&](const Stage& st, int t, int slot) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) store_step(st, t, slot, i);
     };
 
     // ---- accumulators ----
@@ -300,9 +311,14 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
     };
     // B1: row maxima; the reference is raised (and O, l rescaled) only when it would grow
     //     by more than the threshold, a wave-uniform and rare event
+    // The hand-written matrix instructions are invisible to the compiler's hazard checks:
+    // before anything else reads O, let the matrix core finish (32 wait states cover the
+    // 16-pass write-back latency).
+    auto mfma_drain = [&]() { asm volatile("s_nop 15\n\ts_nop 15"); };
     auto rescale_if_needed = [&](const float (&cand)[2]) {
         const bool grow = cand[0] > m[0] + kRescaleThreshold || cand[1] > m[1] + kRescaleThreshold;
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(grow) != 0, 0)) {
+            mfma_drain();
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb) {
                 const float m_new = fmaxf(m[rb], cand[rb]);
@@ -408,13 +424,13 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
         auto k_operand = [&](int ks) {
             return *reinterpret_cast<const bf16x8*>(kt + k_rd[kb] + (((2 * ks + hl) ^ k_swz) << 4));
         };
-        a[0] = k_operand(0);
-        a[1] = k_operand(1);
+#pragma unroll
+        for (int i = 0; i < kKAhead; ++i) a[i] = k_operand(i);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             s_new[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], qf[0][ks], ks == 0 ? zero : s_new[0], 0, 0, 0);
             s_new[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], qf[1][ks], ks == 0 ? zero : s_new[1], 0, 0, 0);
-            if (ks + 2 < 8) a[ks + 2] = k_operand(ks + 2);
+            if (ks + kKAhead < 8) a[ks + kKAhead] = k_operand(ks + kKAhead);
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb) {
                 const float p0 = __builtin_amdgcn_exp2f(fmaf(s_old[rb][2 * ks], p.scale_log2, bias[rb]));
@@ -440,7 +456,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
     // Region Y: O^T += V^T P^T (matrix core) with the row maxima of the next block's scores
     // (vector ALU).  The maxima start two slices in, when the scores have left the matrix core.
     auto region_accumulate_maxima = [&](const char* vt, int kb, const bf16x8 (&pf)[2][2],
-                                        const f32x16 (&s_new)[2]) {
+                                        const f32x16 (&s_new)[2], auto&& staging_step) {
         bf16x8 av[8];
         auto v_operand = [&](int idx) {   // idx = 4 step + dim block
             const char* vq = vt + (kb * 8 + (idx >> 2) * 4) * 1024 + v_rd[idx & 3];
@@ -450,14 +466,17 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
             return __builtin_bit_cast(bf16x8, w);
         };
         float mx[2] = {-INFINITY, -INFINITY};
-        av[0] = v_operand(0);
-        av[1] = v_operand(1);
+#pragma unroll
+        for (int i = 0; i < kVAhead; ++i) av[i] = v_operand(i);
 #pragma unroll
         for (int idx = 0; idx < 8; ++idx) {
             const int step = idx >> 2, db = idx & 3;
-            o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[idx], pf[0][step], o[db][0], 0, 0, 0);
-            o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[idx], pf[1][step], o[db][1], 0, 0, 0);
-            if (idx + 2 < 8) av[idx + 2] = v_operand(idx + 2);
+            // written as assembly so that O is pinned to accumulation registers ("+a") while the
+            // scores, which the vector ALU reads, stay in vector registers; nothing reads O
+            // again before mfma_drain()
+            asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(o[db][0]) : "v"(av[idx]), "v"(pf[0][step]));
+            asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(o[db][1]) : "v"(av[idx]), "v"(pf[1][step]));
+            if (idx + kVAhead < 8) av[idx + kVAhead] = v_operand(idx + kVAhead);
             if (idx >= 4) {   // four slices, four scores of each row block per slice
                 const int r0 = (idx - 4) * 4;
 #pragma unroll
@@ -467,6 +486,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
                 }
                 asm volatile("" ::"v"(mx[0]), "v"(mx[1]));
             }
+            staging_step(idx);   // one eighth of the next tiles' HBM -> LDS traffic
             __builtin_amdgcn_sched_barrier(0);
         }
         float cand[2];
@@ -480,50 +500,54 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
 
     // ---- LDS ring of three tiles; tile t lives in slot t % 3 ----
     // Every iteration t: compute on tile t (the pipelined body also reads K of tile t + 1),
-    // write tile t + 2 into the slot tile t - 1 left, start the loads of tile t + 3, barrier.
-    // Tile t - 1 was last read before the previous barrier and tile t + 2 is first read after
-    // this one, so one barrier per tile is enough.
-    Stage st;
-    if (n_tiles > 0) {
-        load_tile(st, 0);
-        store_tile(st, 0, 0);
-        load_tile(st, 1);
-        store_tile(st, 1, 1);
-        load_tile(st, 2);
-    }
+    // write tile t + 2 (loaded two iterations ago) into the slot tile t - 1 left, start the
+    // loads of tile t + 4 into the registers just freed, barrier.  Tile t - 1 was last read
+    // before the previous barrier and tile t + 2 is first read after this one, so one barrier
+    // per tile is enough.  Two register sets alternate: st0 holds tile t + 2, st1 tile t + 3.
+    Stage st0, st1;
+    load_tile(st0, 0);
+    store_tile(st0, 0, 0);
+    load_tile(st0, 1);
+    store_tile(st0, 1, 1);
+    load_tile(st0, 2);
+    load_tile(st1, 3);
     __syncthreads();
 
     int slot = 0;                                // slot of tile t
     auto next_slot = [](int s) { return s == kRing - 1 ? 0 : s + 1; };
-    auto end_of_tile = [&](int t) {
-        const int s2 = slot == 0 ? 2 : slot - 1;  // slot of tile t + 2 == slot of tile t - 1
-        store_tile(st, t + 2, s2);
-        load_tile(st, t + 3);
+    auto prev_slot = [](int s) { return s == 0 ? kRing - 1 : s - 1; };
+
+    // one pipelined iteration; st holds tile t + 2 on entry and tile t + 4 (in flight) on exit
+    f32x16 sa[2], sb[2];
+    bf16x8 pf[2][2];
+    auto pipelined_tile = [&](int t, Stage& st) {
+        const char* kt = k_lds + slot * kKTileBytes;
+        const char* vt = v_lds + slot * kVTileBytes;
+        const char* kt_next = k_lds + next_slot(slot) * kKTileBytes;
+        const int s2 = prev_slot(slot);          // slot of tile t + 2 == slot of tile t - 1
+        region_scores_weights(kt, 1, sb, sa, pf);
+        region_accumulate_maxima(vt, 0, pf, sb, [&](int i) { store_step(st, t + 2, s2, i); });
+        region_scores_weights(kt_next, 0, sa, sb, pf);
+        const LoadPlan lp = plan_load(t + 4);
+        region_accumulate_maxima(vt, 1, pf, sa, [&](int i) { load_step(st, lp, i); });
         __syncthreads();
         slot = next_slot(slot);
     };
 
     int t = 0;
-    // ---- pipelined body for tiles whose successor is also unmasked ----
-    const int n_pipe = n_unmasked - 1;
+    // ---- pipelined body for tiles whose successor is also unmasked, two tiles per trip ----
+    const int n_pipe = (n_unmasked - 1) & ~1;
     if (n_pipe > 0) {
-        f32x16 sa[2], sb[2];
-        bf16x8 pf[2][2];
         scores(k_lds + slot * kKTileBytes, 0, sa);
         raise_reference(sa);
-        for (; t < n_pipe; ++t) {
-            const char* kt = k_lds + slot * kKTileBytes;
-            const char* vt = v_lds + slot * kVTileBytes;
-            const char* kt_next = k_lds + next_slot(slot) * kKTileBytes;
-            region_scores_weights(kt, 1, sb, sa, pf);
-            region_accumulate_maxima(vt, 0, pf, sb);
-            region_scores_weights(kt_next, 0, sa, sb, pf);
-            region_accumulate_maxima(vt, 1, pf, sa);
-            end_of_tile(t);
+        for (; t < n_pipe; t += 2) {
+            pipelined_tile(t, st0);
+            pipelined_tile(t + 1, st1);
         }
         // sa holds the first block of tile t, which the plain body below computes again
+        mfma_drain();
     }
-    // ---- plain body: the last unmasked tile and the tiles that straddle the diagonal ----
+    // ---- plain body: the last unmasked tiles and the tiles that straddle the diagonal ----
     for (; t < n_tiles; ++t) {
         const char* kt = k_lds + slot * kKTileBytes;
         const char* vt = v_lds + slot * kVTileBytes;
@@ -531,14 +555,19 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             f32x16 s[2];
-            bf16x8 pf[2][2];
             scores(kt, kb, s);
             if (masked) mask_scores(t * kTileKeys + kb * 32, s);
             raise_reference(s);
             weights(s, pf);
             accumulate(vt, kb, pf);
         }
-        end_of_tile(t);
+        store_tile(st0, t + 2, prev_slot(slot));
+        load_tile(st0, t + 4);
+        const Stage tmp = st0;                   // st0 must hold tile t + 3 next time round
+        st0 = st1;
+        st1 = tmp;
+        __syncthreads();
+        slot = next_slot(slot);
     }
 
     // ---- epilogue: normalise and write ----
