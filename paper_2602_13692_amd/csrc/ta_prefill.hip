@@ -14,8 +14,11 @@
 //     registers: the softmax needs one cross-lane exchange per tile, and the
 //     exponentiated scores are already laid out as the B operand of
 //     O^T = V^T P^T;
-//   * V is written to LDS as [4-key group][dim][4 keys], which makes the A
-//     operand of O^T = V^T P^T two 8-byte LDS reads per lane;
+//   * V is written to LDS as [8-key octet][dim][8 keys] (an in-register
+//     transpose at staging time), which makes the A operand of O^T = V^T P^T
+//     one 16-byte LDS read per lane; LDS moves a fixed 64 bytes per cycle and CU
+//     for 16-byte accesses and half that for 8-byte ones, and this kernel is
+//     bound by exactly that, so every operand is read 16 bytes wide;
 //   * the running maximum is only raised (and O rescaled) when it grows by more
 //     than 2^8, a wave-uniform and rare event after the first tile.
 #include "ta_internal.h"
@@ -119,18 +122,30 @@ __device__ __forceinline__ uint16_t to_bf16_rne(float f) {
     return static_cast<uint16_t>(u >> 16);
 }
 
+// Maximum of a value over lanes l and l ^ 32 (the two lanes that hold one score row), on the
+// vector ALU: v_permlane32_swap returns {old[0..31], src[0..31]} and {old[32..63], src[32..63]}.
+__device__ __forceinline__ float max_across_halves(float x) {
+    const uint32_t u = __builtin_bit_cast(uint32_t, x);
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__builtin_bit_cast(float, r.x), __builtin_bit_cast(float, r.y));
+}
+
 // Staging registers of one thread for one 64-key tile: four 16-byte pieces of K
-// (keys r16 + 16 i, chunk c) and four of V (keys 4 r16 + j, chunk c).
+// (keys r16 + 16 i, chunk c16) and eight 8-byte pieces of V (the eight keys of one
+// "octet", 4 dims).
 struct Stage {
     u32x4 k[4];
-    u32x4 v[4];
+    u32x2 v[8];
 };
 
-// LDS byte offset of the 8-byte entry (4-key group q, dim) in a V tile.
-__device__ __forceinline__ int v_entry_offset(int quad, int dim) {
-    const int chunk = dim >> 3;              // 64-byte run of 8 dims
-    const int piece = (dim >> 1) & 3;        // 16-byte piece inside the run
-    return quad * 1024 + chunk * 64 + ((piece ^ ((chunk >> 2) & 3)) << 4) + ((dim & 1) << 3);
+// V lives in LDS as [octet][dim][8 keys]: one 16-byte entry is exactly the A operand of one
+// lane for O^T += V^T P^T.  Octet (kb, step, hl) of a 64-key tile holds the keys that lane half
+// hl contracts in k = 16 step `step` of 32-key block kb: kb 32 + step 16 + hl 4 + {0..3, 8..11}.
+// Byte offset of the entry of `dim` inside its octet (the 16-byte entries of a 64-byte run of
+// four dims are XOR-swizzled so that the staging writes are bank-conflict free):
+__device__ __forceinline__ int v_entry_offset(int dim) {
+    const int chunk = dim >> 2;
+    return chunk * 64 + (((dim & 3) ^ ((chunk >> 2) & 3)) << 4);
 }
 
 template <int G>
@@ -193,10 +208,15 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
     const int c16 = tid & 15;   // 16-byte chunk of a 256-byte row
     const int r16 = tid >> 4;   // 0..15
     const char* k_base = p.k_pool + int64_t(g) * p.stride_head_bytes + r16 * 256 + c16 * 16;
-    const char* v_base = p.v_pool + int64_t(g) * p.stride_head_bytes + (r16 & 3) * 1024 + c16 * 16;
+    // V: thread -> (octet oc = tid / 32, 8-byte chunk c32 of 4 dims); the octet's keys all lie in
+    // page oc / 2 = wave of the tile, rows 4 hl + {0..3} and 8 + 4 hl + {0..3}
+    const int c32 = tid & 31;
+    const int oc = tid >> 5;
+    const char* v_base = p.v_pool + int64_t(g) * p.stride_head_bytes + ((oc & 1) * 4) * 256 + c32 * 8;
+    const int v_key0 = (oc >> 1) * 16 + (oc & 1) * 4;                // first key of the octet in the tile
     const int32_t* table = p.block_table + int64_t(b) * p.block_table_stride;
     const int k_lds_off = r16 * 256 + ((c16 ^ r16) << 4);           // + i * 4096 for key r16 + 16 i
-    const int v_lds_off = r16 * 1024 + c16 * 64;                    // pieces at ((j ^ (c16 >> 2)) << 4)
+    const int v_lds_off = oc * 2048 + c32 * 64;                     // entries at ((e ^ (c32 >> 2)) << 4)
 
     // Page ids: lane l of every wave holds the id of page (64 g + l) of the current group of 64
     // pages (16 tiles), clamped to the program's last page; the next group is fetched one
@@ -227,13 +247,19 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             lp.k_off[i] = int64_t(__builtin_amdgcn_readlane(ids_cur, (t & 15) * 4 + i)) * p.stride_page_bytes;
-        // V: this thread's 4-key group r16 lies in page r16 / 4 of the tile (uniform per wave)
+        // V: this thread's octet lies in page `wave` of the tile
         lp.v_off = int64_t(__builtin_amdgcn_readlane(ids_cur, (t & 15) * 4 + wave)) * p.stride_page_bytes;
         return lp;
     };
     auto load_step = [&](Stage& st, const LoadPlan& lp, int i) {
-        if (i < 4) st.k[i] = *reinterpret_cast<const u32x4*>(k_base + lp.k_off[i]);
-        else st.v[i - 4] = *reinterpret_cast<const u32x4*>(v_base + lp.v_off + (i - 4) * 256);
+        if (i < 4) {
+            st.k[i] = *reinterpret_cast<const u32x4*>(k_base + lp.k_off[i]);
+        } else {   // octet rows 2 (i - 4) and 2 (i - 4) + 1; rows 4..7 sit 8 keys further
+            const int j = 2 * (i - 4);
+            const int row = (j & 3) + (j >> 2) * 8;
+            st.v[j] = *reinterpret_cast<const u32x2*>(v_base + lp.v_off + row * 256);
+            st.v[j + 1] = *reinterpret_cast<const u32x2*>(v_base + lp.v_off + (row + 1) * 256);
+        }
     };
     auto load_tile = [&](Stage& st, int t) {
         const LoadPlan lp = plan_load(t);
@@ -244,19 +270,23 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
         if (i < 4) {
             *reinterpret_cast<u32x4*>(k_lds + slot * kKTileBytes + k_lds_off + i * 4096) = st.k[i];
         } else {
-            // piece w holds dims 2w, 2w+1 of this thread's chunk for its four keys: a 4x2
-            // transpose.  Keys at or beyond the context length may hold anything (even NaN):
-            // their V rows are zeroed, because 0 * NaN inside the matrix core would poison O.
-            const int w = i - 4;
-            uint32_t a[4];
+            // entry e = the octet's eight keys at dim 4 c32 + e: an 8x1 column of the 8x4 block
+            // this thread loaded.  Keys at or beyond the context length may hold anything (even
+            // NaN): their V rows are zeroed, because 0 * NaN inside the matrix core would poison O.
+            const int e = i - 4;
+            uint32_t a[8];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) a[j] = (t * kTileKeys + r16 * 4 + j < L) ? st.v[j][w] : 0u;
-            u32x4 piece;
-            piece.x = __builtin_amdgcn_perm(a[1], a[0], 0x05040100u);  // dim 2w:   keys 0,1
-            piece.y = __builtin_amdgcn_perm(a[3], a[2], 0x05040100u);  //           keys 2,3
-            piece.z = __builtin_amdgcn_perm(a[1], a[0], 0x07060302u);  // dim 2w+1: keys 0,1
-            piece.w = __builtin_amdgcn_perm(a[3], a[2], 0x07060302u);  //           keys 2,3
-            *reinterpret_cast<u32x4*>(v_lds + slot * kVTileBytes + v_lds_off + ((w ^ (c16 >> 2)) << 4)) = piece;
+            for (int j = 0; j < 8; ++j) {
+                const int key = t * kTileKeys + v_key0 + (j & 3) + (j >> 2) * 8;
+                a[j] = key < L ? st.v[j][e >> 1] : 0u;
+            }
+            const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;   // high or low halves
+            u32x4 entry;
+            entry.x = __builtin_amdgcn_perm(a[1], a[0], sel);
+            entry.y = __builtin_amdgcn_perm(a[3], a[2], sel);
+            entry.z = __builtin_amdgcn_perm(a[5], a[4], sel);
+            entry.w = __builtin_amdgcn_perm(a[7], a[6], sel);
+            *reinterpret_cast<u32x4*>(v_lds + slot * kVTileBytes + v_lds_off + ((e ^ ((c32 >> 2) & 3)) << 4)) = entry;
         }
     };
     auto store_tile = [&](const Stage& st, int t, int slot) {
@@ -280,9 +310,9 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) k_rd[kb] = (kb * 32 + l32) * 256;
     const int k_swz = l32 & 15;
-    int v_rd[4];   // V operand: dim l32 + 32 db of 4-key group (2 x + hl)
+    int v_rd[4];   // V operand: entry of dim l32 + 32 db in octet (.., hl)
 #pragma unroll
-    for (int db = 0; db < 4; ++db) v_rd[db] = v_entry_offset(hl, db * 32 + l32);
+    for (int db = 0; db < 4; ++db) v_rd[db] = hl * 2048 + v_entry_offset(db * 32 + l32);
 
     // ---- the four steps of one 32-key block ----
     // A: S^T block = K Q^T, 32 keys x (2 x 32 rows); register r of lane (l32, hl) holds
@@ -355,7 +385,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
 #pragma unroll
             for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[rb][r]), s[rb][r + 1]);
             mx = fmaxf(mx, s[rb][15]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            mx = max_across_halves(mx);
             cand[rb] = mx * p.scale_log2;
         }
         rescale_if_needed(cand);
@@ -388,17 +418,14 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
             lsum[rb] = acc;
         }
     };
-    // C: O^T += V^T P^T; step 0 uses key groups (hl, 2 + hl), step 1 uses (4 + hl, 6 + hl)
+    // C: O^T += V^T P^T; the A operand of (block kb, step, lane half hl) is octet 4 kb + 2 step + hl
     auto accumulate = [&](const char* vt, int kb, const bf16x8 (&pf)[2][2]) {
 #pragma unroll
         for (int step = 0; step < 2; ++step) {
-            const char* vq = vt + (kb * 8 + step * 4) * 1024;
+            const char* vq = vt + (kb * 4 + step * 2) * 2048;
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
-                const u32x2 lo = *reinterpret_cast<const u32x2*>(vq + v_rd[db]);
-                const u32x2 hi = *reinterpret_cast<const u32x2*>(vq + v_rd[db] + 2 * 1024);
-                const u32x4 av = {lo.x, lo.y, hi.x, hi.y};
-                const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+                const bf16x8 a = *reinterpret_cast<const bf16x8*>(vq + v_rd[db]);
                 o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[0][step], o[db][0], 0, 0, 0);
                 o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[1][step], o[db][1], 0, 0, 0);
             }
@@ -459,11 +486,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
                                         const f32x16 (&s_new)[2], auto&& staging_step) {
         bf16x8 av[8];
         auto v_operand = [&](int idx) {   // idx = 4 step + dim block
-            const char* vq = vt + (kb * 8 + (idx >> 2) * 4) * 1024 + v_rd[idx & 3];
-            const u32x2 lo = *reinterpret_cast<const u32x2*>(vq);
-            const u32x2 hi = *reinterpret_cast<const u32x2*>(vq + 2 * 1024);
-            const u32x4 w = {lo.x, lo.y, hi.x, hi.y};
-            return __builtin_bit_cast(bf16x8, w);
+            return *reinterpret_cast<const bf16x8*>(vt + (kb * 4 + (idx >> 2) * 2) * 2048 + v_rd[idx & 3]);
         };
         float mx[2] = {-INFINITY, -INFINITY};
 #pragma unroll
@@ -492,7 +515,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
         float cand[2];
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
-            mx[rb] = fmaxf(mx[rb], __shfl_xor(mx[rb], 32));
+            mx[rb] = max_across_halves(mx[rb]);
             cand[rb] = mx[rb] * p.scale_log2;
         }
         rescale_if_needed(cand);
