@@ -2,9 +2,12 @@
 // program's whole cached context (ThunderAgent Sec. 2.1; the decode term of the
 // cost decomposition, Sec. 4.2, Eq. 3).
 //
-// Three kernels per call:
+// Kernels per call:
+//   prefix  finds the leading pages consecutive programs have in common;
 //   plan    cuts every program's pages into fixed-length chunks of the key axis
-//           and lists them flat, so ragged batches keep all CUs busy;
+//           and lists them flat, so ragged batches keep all CUs busy; chunks that a
+//           group of programs shares go to the matrix-core tile kernel instead
+//           (one pass over the shared pages for all members);
 //   chunk   one workgroup per (chunk, kv head): streams the chunk's K and V
 //           pages from HBM once, serves all Hq/Hkv query heads of the group
 //           from the same registers, keeps an online softmax per 16-lane row,
@@ -55,27 +58,73 @@ __device__ __forceinline__ uint16_t to_bf16_rne(float f) {
 }
 
 // ---------------------------------------------------------------------------
-// plan: exclusive scan of ceil(L_b / chunk_tokens) and the flat item list
+// shared-prefix detection: leading pages that program b's block table has in common
+// with program b - 1 (forked agent branches list the same prefix pages), counted only
+// as far as both programs fill the pages completely
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void plan_chunks_kernel(const int32_t* __restrict__ context_lens,
-                                                           int32_t batch, int32_t chunk_tokens,
-                                                           int32_t max_per_program,
-                                                           int32_t* __restrict__ chunk_start,
-                                                           int2* __restrict__ items) {
-    __shared__ int32_t scan[1024];
-    __shared__ int32_t carry;
-    const int tid = threadIdx.x;
-    if (tid == 0) carry = 0;
+__global__ __launch_bounds__(256) void common_prefix_kernel(const int32_t* __restrict__ block_table,
+                                                            int32_t block_table_stride,
+                                                            const int32_t* __restrict__ context_lens,
+                                                            int32_t* __restrict__ lcp) {
+    __shared__ int first_diff;
+    const int b = blockIdx.x;
+    if (b == 0) {
+        if (threadIdx.x == 0) lcp[0] = 0;
+        return;
+    }
+    const int la = context_lens[b - 1], lb = context_lens[b];
+    int n = (la < lb ? la : lb) / kPageSize;          // pages both programs fill completely
+    n = n < 0 ? 0 : n;
+    const int32_t* ta = block_table + int64_t(b - 1) * block_table_stride;
+    const int32_t* tb = block_table + int64_t(b) * block_table_stride;
+    if (n == 0 || ta[0] != tb[0]) {                    // the common case: nothing shared
+        if (threadIdx.x == 0) lcp[b] = 0;
+        return;
+    }
+    if (threadIdx.x == 0) first_diff = n;
     __syncthreads();
-    for (int base = 0; base < batch; base += 1024) {
-        const int b = base + tid;
-        int n = 0;
-        if (b < batch) {
-            const int L = context_lens[b];
-            n = L > 0 ? (L + chunk_tokens - 1) / chunk_tokens : 0;
-            n = n > max_per_program ? max_per_program : n;  // lengths above the host bound are clipped
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+        if (ta[i] != tb[i]) {
+            atomicMin(&first_diff, i);
+            break;
         }
-        scan[tid] = n;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) lcp[b] = first_diff;
+}
+
+// ---------------------------------------------------------------------------
+// plan: cuts every program's pages into chunks, gives each chunk a slot for its partial
+// result (chunk_start[b] + chunk index), finds groups of consecutive programs that share
+// leading chunks, and lists the work flat:
+//   shared_items  (first program, members, chunk)   -> matrix-core kernel, all members at once
+//   items         (program, chunk) for every chunk that is not shared -> vector-ALU kernel
+// counts[0] = number of items, counts[1] = number of shared items.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __restrict__ context_lens,
+                                                           const int32_t* __restrict__ lcp,
+                                                           int32_t batch, int32_t chunk_pages,
+                                                           int32_t max_per_program, int32_t max_members,
+                                                           int32_t max_shared_items,
+                                                           int32_t* __restrict__ chunk_start,
+                                                           int2* __restrict__ items,
+                                                           int4* __restrict__ shared_items,
+                                                           int32_t* __restrict__ counts) {
+    __shared__ int32_t scan[1024];
+    __shared__ int32_t shared_chunks[1024];   // leading chunks of program b computed by its group
+    __shared__ int4 groups[512];
+    __shared__ int32_t carry, n_groups, n_shared;
+    const int tid = threadIdx.x;
+    const int chunk_tokens = chunk_pages * kPageSize;
+
+    auto chunks_of = [&](int b) {
+        const int L = context_lens[b];
+        int n = L > 0 ? (L + chunk_tokens - 1) / chunk_tokens : 0;
+        return n > max_per_program ? max_per_program : n;   // lengths above the host bound are clipped
+    };
+    // exclusive scan of `value` over one pass of up to 1024 programs; returns this thread's offset
+    auto block_scan = [&](int value) {
+        scan[tid] = value;
         __syncthreads();
         for (int off = 1; off < 1024; off <<= 1) {
             const int v = tid >= off ? scan[tid - off] : 0;
@@ -83,16 +132,70 @@ __global__ __launch_bounds__(1024) void plan_chunks_kernel(const int32_t* __rest
             scan[tid] += v;
             __syncthreads();
         }
-        const int first = carry + scan[tid] - n;
-        if (b < batch) {
-            chunk_start[b] = first;
-            for (int c = 0; c < n; ++c) items[first + c] = make_int2(b, c);
-        }
+        const int first = carry + scan[tid] - value;
         __syncthreads();
         if (tid == 1023) carry += scan[1023];
         __syncthreads();
+        return first;
+    };
+
+    // 1. partial slots
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < batch; base += 1024) {
+        const int b = base + tid;
+        const int first = block_scan(b < batch ? chunks_of(b) : 0);
+        if (b < batch) chunk_start[b] = first;
     }
     if (tid == 0) chunk_start[batch] = carry;
+
+    // 2. groups of programs with common leading chunks (batches of up to 1024 programs)
+    shared_chunks[tid] = 0;
+    if (tid == 0) { n_groups = 0; n_shared = 0; }
+    __syncthreads();
+    if (lcp != nullptr && batch <= 1024 && batch >= 2) {
+        scan[tid] = (tid > 0 && tid < batch) ? lcp[tid] / chunk_pages : 0;   // chunks shared with b - 1
+        __syncthreads();
+        if (tid == 0) {
+            int ng = 0, off = 0, b = 0;
+            while (b < batch) {
+                int e = b + 1, common = 0x7fffffff;
+                while (e < batch && e - b < max_members && scan[e] > 0) {
+                    common = scan[e] < common ? scan[e] : common;
+                    ++e;
+                }
+                if (e - b >= 2 && ng < 512 && off + common <= max_shared_items) {
+                    groups[ng++] = make_int4(b, e - b, common, off);
+                    off += common;
+                    for (int i = b; i < e; ++i) shared_chunks[i] = common;
+                }
+                b = e;
+            }
+            n_groups = ng;
+            n_shared = off;
+        }
+        __syncthreads();
+        if (tid < n_groups) {
+            const int4 gr = groups[tid];
+            for (int c = 0; c < gr.z; ++c) shared_items[gr.w + c] = make_int4(gr.x, gr.y, c, 0);
+        }
+    }
+    __syncthreads();
+
+    // 3. the remaining chunks, one item each
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < batch; base += 1024) {
+        const int b = base + tid;
+        const int n = b < batch ? chunks_of(b) : 0;
+        const int sc = (b < batch && batch <= 1024) ? shared_chunks[b] : 0;
+        const int first = block_scan(n - sc);
+        for (int c = sc; c < n; ++c) items[first + c - sc] = make_int2(b, c);
+    }
+    if (tid == 0) {
+        counts[0] = carry;
+        counts[1] = n_shared;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -104,7 +207,8 @@ struct ChunkParams {
     const char* v_pool;
     const int32_t* block_table;
     const int32_t* context_lens;
-    const int32_t* chunk_start;  // [batch + 1]
+    const int32_t* chunk_start;  // [batch + 1] first partial slot of each program
+    const int32_t* counts;       // counts[0] = number of items
     const int2* items;
     float* part_ml;
     float* part_o;
@@ -220,7 +324,7 @@ __device__ __forceinline__ void process_page(const PageRegs& pg, const uint32_t 
 
 template <int G>
 __global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams p) {
-    const int n_items = p.chunk_start[p.batch];
+    const int n_items = p.counts[0];
     const int item = blockIdx.x / p.num_kv_heads;
     if (item >= n_items) return;
     const int g = blockIdx.x - item * p.num_kv_heads;
@@ -355,7 +459,7 @@ __global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams
             lt = fmaf(sm_l[w][h], wt, lt);
             acc = fmaf(sm_o[w][h][c], wt, acc);
         }
-        const int64_t rowid = int64_t(item) * p.num_q_heads + g * G + h;
+        const int64_t rowid = int64_t(p.chunk_start[b] + it.y) * p.num_q_heads + g * G + h;
         p.part_o[rowid * kHeadDim + c] = acc;
         if (c == 0) {
             p.part_ml[rowid * 2 + 0] = mt * p.scale_log2;  // max in the log2 domain
@@ -416,11 +520,43 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     int2* items = reinterpret_cast<int2*>(workspace + w.off_items);
     float* part_ml = reinterpret_cast<float*>(workspace + w.off_part_ml);
     float* part_o = reinterpret_cast<float*>(workspace + w.off_part_o);
+    int32_t* counts = reinterpret_cast<int32_t*>(workspace + w.off_counts);
+    int32_t* lcp = reinterpret_cast<int32_t*>(workspace + w.off_lcp);
+    int4* shared_items = reinterpret_cast<int4*>(workspace + w.off_shared_items);
     const int32_t per_prog = w.max_chunks / a.batch;
+    // sharing needs at least two programs and a non-empty block table
+    const bool look_for_sharing = a.batch >= 2 && a.batch <= 1024 && w.max_shared_items > 0 &&
+                                  a.block_table_stride > 0;
 
-    hipLaunchKernelGGL(plan_chunks_kernel, dim3(1), dim3(1024), 0, stream, a.context_lens, a.batch,
-                       w.chunk_pages * kPageSize, per_prog, chunk_start, items);
+    if (look_for_sharing) {
+        hipLaunchKernelGGL(common_prefix_kernel, dim3(a.batch), dim3(256), 0, stream, a.block_table,
+                           a.block_table_stride, a.context_lens, lcp);
+        TA_HIP_TRY(hipGetLastError());
+    }
+    hipLaunchKernelGGL(plan_decode_kernel, dim3(1), dim3(1024), 0, stream, a.context_lens,
+                       look_for_sharing ? lcp : nullptr, a.batch, w.chunk_pages, per_prog,
+                       256 / g.group, w.max_shared_items, chunk_start, items, shared_items, counts);
     TA_HIP_TRY(hipGetLastError());
+
+    if (look_for_sharing) {
+        SharedPrefixArgs sa{};
+        sa.q = a.q;
+        sa.k_pool = a.k_pool;
+        sa.v_pool = a.v_pool;
+        sa.block_table = a.block_table;
+        sa.context_lens = a.context_lens;
+        sa.shared_items = reinterpret_cast<const int32_t*>(shared_items);
+        sa.counts = counts;
+        sa.chunk_start = chunk_start;
+        sa.part_ml = part_ml;
+        sa.part_o = part_o;
+        sa.block_table_stride = a.block_table_stride;
+        sa.batch = a.batch;
+        sa.tiles_per_chunk = w.chunk_pages / 4;
+        sa.max_items = w.max_shared_items;
+        const int rc = launch_shared_prefix(g, sa, stream);
+        if (rc != TA_OK) return rc;
+    }
 
     if (w.max_chunks > 0) {
         ChunkParams cp{};
@@ -430,6 +566,7 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
         cp.block_table = a.block_table;
         cp.context_lens = a.context_lens;
         cp.chunk_start = chunk_start;
+        cp.counts = counts;
         cp.items = items;
         cp.part_ml = part_ml;
         cp.part_o = part_o;

@@ -56,6 +56,10 @@ struct WorkspaceLayout {
     size_t off_items;          // int2  [max_chunks]
     size_t off_part_ml;        // float [max_chunks][Hq][2]
     size_t off_part_o;         // float [max_chunks][Hq][128]
+    int32_t max_shared_items;  // upper bound on (group, shared chunk) items
+    size_t off_counts;         // int32 [4]: private items, shared items
+    size_t off_lcp;            // int32 [batch] leading pages shared with the previous program
+    size_t off_shared_items;   // int4  [max_shared_items]
     size_t off_tile_start;     // int32 [batch + 1]      (prefill)
     size_t off_tiles;          // int2  [max_tiles]      (prefill)
     size_t total_bytes;
@@ -100,6 +104,27 @@ struct PrefillArgs {
 
 int launch_prefill(const Geometry& g, const PrefillArgs& a, const WorkspaceLayout& w, char* workspace,
                    hipStream_t stream);
+
+// Decode of the chunks that a group of programs shares (block tables with a common head):
+// the matrix-core tile kernel computes the split-K partials of all members at once.
+struct SharedPrefixArgs {
+    const uint16_t* q;
+    const uint16_t* k_pool;
+    const uint16_t* v_pool;
+    const int32_t* block_table;
+    const int32_t* context_lens;
+    const int32_t* shared_items;   // int4 per item: first program, members, chunk, unused
+    const int32_t* counts;         // counts[1] = number of shared items
+    const int32_t* chunk_start;
+    float* part_ml;
+    float* part_o;
+    int32_t block_table_stride;
+    int32_t batch;
+    int32_t tiles_per_chunk;
+    int32_t max_items;
+};
+
+int launch_shared_prefix(const Geometry& g, const SharedPrefixArgs& a, hipStream_t stream);
 
 int launch_restore(void* k_pool, void* v_pool, size_t page_bytes, const void* host_k,
                    const void* host_v, const int32_t* dst_slots, int32_t n_pages, void* staging,

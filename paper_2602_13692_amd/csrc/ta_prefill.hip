@@ -54,6 +54,13 @@ struct PrefillParams {
     const int2* tiles;          // (program, query tile)
     uint16_t* out;
     float* lse;
+    // shared-prefix decode only: one item = (first program of the group, members, chunk)
+    const int4* shared_items;
+    const int32_t* counts;       // counts[1] = number of shared items
+    const int32_t* chunk_start;  // [batch + 1] first partial slot of each program
+    float* part_ml;              // [slot][Hq][2]  reference maximum (log2 domain), sum
+    float* part_o;               // [slot][Hq][128] unnormalised output
+    int32_t tiles_per_chunk;
     int64_t stride_page_bytes;
     int64_t stride_head_bytes;
     int32_t block_table_stride;
@@ -148,50 +155,68 @@ __device__ __forceinline__ int v_entry_offset(int dim) {
     return chunk * 64 + (((dim & 3) ^ ((chunk >> 2) & 3)) << 4);
 }
 
-template <int G>
-__global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
-    constexpr int kTileTokens = kRowsPerBlock / G;
+// SHARED = false: append-prefill, rows = (new token, head), causal, writes bf16 output.
+// SHARED = true:  decode of a group of programs whose block tables begin with the same pages
+//                 (forked agent branches): rows = (member program, head), keys = one chunk of
+//                 the shared prefix, no mask, writes split-K partials for the decode merge.
+template <int G, bool SHARED>
+__global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillParams p) {
+    constexpr int kTileTokens = kRowsPerBlock / G;   // programs per item when SHARED
     extern __shared__ __attribute__((aligned(16))) char lds[];
     char* k_lds = lds;                           // [kRing][kKTileBytes]
     char* v_lds = lds + kRing * kKTileBytes;     // [kRing][kVTileBytes]
 
-    const int n_tiles_total = p.tile_start[p.batch];
+    const int n_items = SHARED ? p.counts[1] : p.tile_start[p.batch];
     const int tile_id = blockIdx.x / p.num_kv_heads;
-    if (tile_id >= n_tiles_total) return;
+    if (tile_id >= n_items) return;
     const int g = blockIdx.x - tile_id * p.num_kv_heads;
-    const int2 tl = p.tiles[tile_id];
-    const int b = tl.x;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hl = lane >> 5;                // which half of the wave
     const int l32 = lane & 31;
 
-    const int q0 = p.cu_q_lens[b];
-    const int nq = p.cu_q_lens[b + 1] - q0;
-    const int L = p.context_lens[b];
-    const int prefix = L - nq;
-    const int t0 = tl.y * kTileTokens;                   // first new token of this tile
-    int t_end = t0 + kTileTokens;
-    t_end = t_end > nq ? nq : t_end;
-    const int keys_needed = prefix + t_end;              // largest visible count in the tile
-    const int n_tiles = (keys_needed + kTileKeys - 1) / kTileKeys;
-    const int n_unmasked = (prefix + t0 + 1) / kTileKeys;  // tiles every row sees completely
-    const int n_pages_b = (L + kPageSize - 1) / kPageSize;
+    int b, q0, nq, L, prefix, t0, t_begin, n_tiles, n_unmasked, members = 0, chunk = 0;
+    if (SHARED) {
+        const int4 it = p.shared_items[tile_id];
+        b = it.x;                      // the group's first program: its block table names the pages
+        members = it.y;
+        chunk = it.z;
+        q0 = 0; nq = 0; prefix = 0; t0 = 0;
+        L = 0x7fffffff;                // every key of a shared chunk exists
+        t_begin = chunk * p.tiles_per_chunk;
+        n_tiles = t_begin + p.tiles_per_chunk;
+        n_unmasked = n_tiles;
+    } else {
+        const int2 tl = p.tiles[tile_id];
+        b = tl.x;
+        q0 = p.cu_q_lens[b];
+        nq = p.cu_q_lens[b + 1] - q0;
+        L = p.context_lens[b];
+        prefix = L - nq;
+        t0 = tl.y * kTileTokens;                         // first new token of this tile
+        int t_end = t0 + kTileTokens;
+        t_end = t_end > nq ? nq : t_end;
+        const int keys_needed = prefix + t_end;          // largest visible count in the tile
+        t_begin = 0;
+        n_tiles = (keys_needed + kTileKeys - 1) / kTileKeys;
+        n_unmasked = (prefix + t0 + 1) / kTileKeys;      // tiles every row sees completely
+    }
+    const int n_pages_b = (p.context_lens[b] + kPageSize - 1) / kPageSize;
 
     // ---- per-lane rows: two blocks of 32 rows per wave ----
-    // row -> (token, head): row = token_local * G + head
+    // row -> (token or member program, head): row = index * G + head
     int vis[2];            // visible keys of this lane's row in row block rb (0 = row does not exist)
     bf16x8 qf[2][8];       // B operands: q[row][16 ks + 8 hl .. + 7]
-    int64_t out_row[2];    // element offset of the row in out, or -1
+    int64_t out_row[2];    // element offset of the row in q / out, or -1
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
         const int row = wave * 64 + rb * 32 + l32;
-        const int tok = t0 + row / G;
+        const int idx = t0 + row / G;
         const int head = g * G + row % G;
-        const bool ok = tok < nq;
-        vis[rb] = ok ? prefix + tok + 1 : 0;
-        out_row[rb] = ok ? (int64_t(q0 + tok) * p.num_q_heads + head) * kHeadDim : int64_t(-1);
+        const bool ok = SHARED ? (row / G < members) : (idx < nq);
+        vis[rb] = ok ? prefix + idx + 1 : 0;
+        out_row[rb] = ok ? (int64_t(SHARED ? b + row / G : q0 + idx) * p.num_q_heads + head) * kHeadDim : int64_t(-1);
         const uint16_t* qrow = p.q + (ok ? out_row[rb] : 0) + hl * 8;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
@@ -226,9 +251,9 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
         pg = pg < n_pages_b ? pg : n_pages_b - 1;
         return table[pg];
     };
-    int ids_group = 0;
-    int ids_cur = fetch_ids(0);
-    int ids_next = fetch_ids(1);
+    int ids_group = t_begin >> 4;
+    int ids_cur = fetch_ids(ids_group);
+    int ids_next = fetch_ids(ids_group + 1);
 
     // Loading one tile = planning (page ids -> byte offsets, scalar) + 8 loads of 16 bytes;
     // storing it to LDS = 4 K writes + 4 V pieces (mask, 4x8 transpose, write).  Both are cut
@@ -483,7 +508,7 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
     // Region Y: O^T += V^T P^T (matrix core) with the row maxima of the next block's scores
     // (vector ALU).  The maxima start two slices in, when the scores have left the matrix core.
     auto region_accumulate_maxima = [&](const char* vt, int kb, const bf16x8 (&pf)[2][2],
-                                        const f32x16 (&s_new)[2], auto&& staging_step) {
+                                        const f32x16 (&s_new)[2], bool use_new, auto&& staging_step) {
         bf16x8 av[8];
         auto v_operand = [&](int idx) {   // idx = 4 step + dim block
             return *reinterpret_cast<const bf16x8*>(vt + (kb * 4 + (idx >> 2) * 2) * 2048 + v_rd[idx & 3]);
@@ -516,7 +541,8 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) {
             mx[rb] = max_across_halves(mx[rb]);
-            cand[rb] = mx[rb] * p.scale_log2;
+            // a look-ahead block that will be thrown away must not move the reference
+            cand[rb] = use_new ? mx[rb] * p.scale_log2 : kNegBig;
         }
         rescale_if_needed(cand);
     };
@@ -528,12 +554,12 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
     // before the previous barrier and tile t + 2 is first read after this one, so one barrier
     // per tile is enough.  Two register sets alternate: st0 holds tile t + 2, st1 tile t + 3.
     Stage st0, st1;
-    load_tile(st0, 0);
-    store_tile(st0, 0, 0);
-    load_tile(st0, 1);
-    store_tile(st0, 1, 1);
-    load_tile(st0, 2);
-    load_tile(st1, 3);
+    load_tile(st0, t_begin);
+    store_tile(st0, t_begin, 0);
+    load_tile(st0, t_begin + 1);
+    store_tile(st0, t_begin + 1, 1);
+    load_tile(st0, t_begin + 2);
+    load_tile(st1, t_begin + 3);
     __syncthreads();
 
     int slot = 0;                                // slot of tile t
@@ -549,21 +575,23 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
         const char* kt_next = k_lds + next_slot(slot) * kKTileBytes;
         const int s2 = prev_slot(slot);          // slot of tile t + 2 == slot of tile t - 1
         region_scores_weights(kt, 1, sb, sa, pf);
-        region_accumulate_maxima(vt, 0, pf, sb, [&](int i) { store_step(st, t + 2, s2, i); });
+        region_accumulate_maxima(vt, 0, pf, sb, true, [&](int i) { store_step(st, t + 2, s2, i); });
         region_scores_weights(kt_next, 0, sa, sb, pf);
         const LoadPlan lp = plan_load(t + 4);
-        region_accumulate_maxima(vt, 1, pf, sa, [&](int i) { load_step(st, lp, i); });
+        region_accumulate_maxima(vt, 1, pf, sa, t + 1 < n_unmasked, [&](int i) { load_step(st, lp, i); });
         __syncthreads();
         slot = next_slot(slot);
     };
 
-    int t = 0;
-    // ---- pipelined body for tiles whose successor is also unmasked, two tiles per trip ----
-    const int n_pipe = (n_unmasked - 1) & ~1;
-    if (n_pipe > 0) {
+    int t = t_begin;
+    // ---- pipelined body, two tiles per trip.  Append-prefill pipelines the tiles whose
+    // successor is also unmasked; a shared chunk has no masked tile and is pipelined to its end
+    // (the scores of the block after its last one are computed and thrown away). ----
+    const int pipe_end = SHARED ? n_tiles : t_begin + ((n_unmasked - 1 - t_begin) & ~1);
+    if (pipe_end > t_begin) {
         scores(k_lds + slot * kKTileBytes, 0, sa);
         raise_reference(sa);
-        for (; t < n_pipe; t += 2) {
+        for (; t < pipe_end; t += 2) {
             pipelined_tile(t, st0);
             pipelined_tile(t + 1, st1);
         }
@@ -593,12 +621,32 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
         slot = next_slot(slot);
     }
 
-    // ---- epilogue: normalise and write ----
+    // ---- epilogue ----
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
         const float total = lsum[rb] + __shfl_xor(lsum[rb], 32);
-        const float inv = total > 0.0f ? 1.0f / total : 0.0f;
-        if (out_row[rb] >= 0) {
+        if (out_row[rb] < 0) continue;
+        if (SHARED) {
+            // split-K partial of (member program, head) for this chunk: unnormalised O, the
+            // reference maximum it is relative to, and the sum of weights
+            const int member = (wave * 64 + rb * 32 + l32) / G;
+            const int head = g * G + (wave * 64 + rb * 32 + l32) % G;
+            const int64_t rowid = int64_t(p.chunk_start[b + member] + chunk) * p.num_q_heads + head;
+            float* orow = p.part_o + rowid * kHeadDim;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const int dim = db * 32 + 8 * q4 + 4 * hl;
+                    *reinterpret_cast<float4*>(orow + dim) = make_float4(o[db][rb][4 * q4], o[db][rb][4 * q4 + 1],
+                                                                           o[db][rb][4 * q4 + 2], o[db][rb][4 * q4 + 3]);
+                }
+            if (hl == 0) {
+                p.part_ml[rowid * 2 + 0] = m[rb];
+                p.part_ml[rowid * 2 + 1] = total;
+            }
+        } else {
+            const float inv = total > 0.0f ? 1.0f / total : 0.0f;
             uint16_t* orow = p.out + out_row[rb];
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
@@ -618,6 +666,30 @@ __global__ __launch_bounds__(kThreads, 1) void prefill_kernel(PrefillParams p) {
                 p.lse[out_row[rb] / kHeadDim] =
                     total > 0.0f ? (m[rb] + __builtin_amdgcn_logf(total)) * kLn2 : -INFINITY;
         }
+    }
+}
+
+// 96 KiB of dynamic LDS is above the default 64 KiB limit: raised once per kernel instance.
+template <int G, bool SHARED>
+int launch_instance(unsigned blocks, const PrefillParams& pp, hipStream_t stream) {
+    const size_t lds_bytes = kRing * (kKTileBytes + kVTileBytes);
+    static const hipError_t lds_rc =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_tile_kernel<G, SHARED>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));
+    TA_HIP_TRY(lds_rc);
+    hipLaunchKernelGGL((attention_tile_kernel<G, SHARED>), dim3(blocks), dim3(kThreads), lds_bytes, stream, pp);
+    TA_HIP_TRY(hipGetLastError());
+    return TA_OK;
+}
+
+template <bool SHARED>
+int launch_tile_kernel(int group, unsigned blocks, const PrefillParams& pp, hipStream_t stream) {
+    switch (group) {
+        case 1: return launch_instance<1, SHARED>(blocks, pp, stream);
+        case 2: return launch_instance<2, SHARED>(blocks, pp, stream);
+        case 4: return launch_instance<4, SHARED>(blocks, pp, stream);
+        case 8: return launch_instance<8, SHARED>(blocks, pp, stream);
+        default: return TA_ERR_UNSUPPORTED;
     }
 }
 
@@ -657,31 +729,38 @@ int launch_prefill(const Geometry& g, const PrefillArgs& a, const WorkspaceLayou
 
     const int64_t blocks = max_tiles * g.num_kv_heads;
     if (blocks > 0x7fffffff) return TA_ERR_INVALID_ARG;
-    const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
-    const size_t lds_bytes = kRing * (kKTileBytes + kVTileBytes);
-    // 96 KiB of dynamic LDS is above the default 64 KiB limit: raise it once per kernel
-    static const hipError_t lds_rc[4] = {
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<1>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes)),
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<2>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes)),
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<4>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes)),
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&prefill_kernel<8>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes))};
-    for (hipError_t e : lds_rc) TA_HIP_TRY(e);
     const ProfileEvents ev = profile_events();
     if (ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
-    switch (g.group) {
-        case 1: hipLaunchKernelGGL(prefill_kernel<1>, grid, block, lds_bytes, stream, pp); break;
-        case 2: hipLaunchKernelGGL(prefill_kernel<2>, grid, block, lds_bytes, stream, pp); break;
-        case 4: hipLaunchKernelGGL(prefill_kernel<4>, grid, block, lds_bytes, stream, pp); break;
-        case 8: hipLaunchKernelGGL(prefill_kernel<8>, grid, block, lds_bytes, stream, pp); break;
-        default: return TA_ERR_UNSUPPORTED;
-    }
-    TA_HIP_TRY(hipGetLastError());
+    const int rc = launch_tile_kernel<false>(g.group, static_cast<unsigned>(blocks), pp, stream);
+    if (rc != TA_OK) return rc;
     if (ev.stop != nullptr) TA_HIP_TRY(hipEventRecord(ev.stop, stream));
     return TA_OK;
+}
+
+int launch_shared_prefix(const Geometry& g, const SharedPrefixArgs& a, hipStream_t stream) {
+    PrefillParams pp{};
+    pp.q = a.q;
+    pp.k_pool = reinterpret_cast<const char*>(a.k_pool);
+    pp.v_pool = reinterpret_cast<const char*>(a.v_pool);
+    pp.block_table = a.block_table;
+    pp.context_lens = a.context_lens;
+    pp.shared_items = reinterpret_cast<const int4*>(a.shared_items);
+    pp.counts = a.counts;
+    pp.chunk_start = a.chunk_start;
+    pp.part_ml = a.part_ml;
+    pp.part_o = a.part_o;
+    pp.tiles_per_chunk = a.tiles_per_chunk;
+    pp.stride_page_bytes = g.stride_page_bytes;
+    pp.stride_head_bytes = g.stride_head_bytes;
+    pp.block_table_stride = a.block_table_stride;
+    pp.batch = a.batch;
+    pp.num_q_heads = g.num_q_heads;
+    pp.num_kv_heads = g.num_kv_heads;
+    pp.scale_log2 = g.scale_log2;
+    const int64_t blocks = int64_t(a.max_items) * g.num_kv_heads;
+    if (blocks <= 0) return TA_OK;
+    if (blocks > 0x7fffffff) return TA_ERR_INVALID_ARG;
+    return launch_tile_kernel<true>(g.group, static_cast<unsigned>(blocks), pp, stream);
 }
 
 }  // namespace ta

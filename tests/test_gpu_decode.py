@@ -116,3 +116,35 @@ def test_scale_override_and_strided_pool():
     ref, ref_lse = oracle.paged_decode(geom, wl.as_u16(wb.q), wl.as_u16(wb.k_pool), wl.as_u16(wb.v_pool),
                                        wb.block_table, wb.context_lens)
     gu.assert_close(out, lse, ref, ref_lse, "scale/stride")
+
+
+@pytest.mark.parametrize("chunk_pages", [8, 64])
+@pytest.mark.parametrize("Hq,Hkv,group", [(64, 8, 16), (32, 8, 5), (8, 8, 40), (16, 2, 40)])
+def test_shared_prefix_groups_take_the_matrix_core_path(Hq, Hkv, group, chunk_pages, monkeypatch):
+    """Forked programs: whole shared chunks are computed once per group by the tile kernel.
+
+    Groups larger than one tile of rows are split, the shared length is not a multiple of the
+    chunk, and one member is cut short inside the shared region.
+    """
+    monkeypatch.setenv("TA_DECODE_CHUNK_PAGES", str(chunk_pages))
+    wb = wl.forked_decode(DEV, seed=wl.SEED_BASE + 710 + group, batch=2 * group, group=group,
+                          prefix_len=2048 + 16 * 37, suffix_lo=1, suffix_hi=700, num_q_heads=Hq,
+                          num_kv_heads=Hkv)
+    wb.context_lens[3] = 1500          # ends inside the shared prefix
+    wb.context_lens[group + 1] = 16    # shares a single page
+    wl.poison_padding(wb)
+    out, lse = gu.gpu_decode(wb)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, f"shared prefix Hq={Hq} Hkv={Hkv} group={group}",
+                    lse_tol=gu.LSE_TOL_PREFILL)
+
+
+def test_tables_that_only_start_alike_are_not_grouped():
+    """Two programs whose tables agree on the first page only: nothing may be shared."""
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 720, batch=6, len_lo=1200, len_hi=3000,
+                           num_q_heads=8, num_kv_heads=2)
+    wb.block_table[1, 0] = wb.block_table[0, 0]
+    wb.block_table[3, :5] = wb.block_table[2, :5]
+    out, lse = gu.gpu_decode(wb)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, "partly aliased tables")
