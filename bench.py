@@ -34,7 +34,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # HBM bytes per decode-chunk launch from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by
 # the same counter on a 1 GiB device copy), keyed by the hash of the kernel source they were
 # taken with.  A changed kernel source gives null until the counters are taken again.
-TRAFFIC_BYTES = {}
+TRAFFIC_BYTES = {"f5c541ccf892deb4": 5089000000}
 
 
 def source_hash(name: str) -> str:
@@ -246,7 +246,7 @@ def main():
             "metric": "append_prefill_tflops", "value": round(flops / ms / 1e9, 1), "unit": "TFLOP/s",
             "ms_per_step": round(ms, 3), "steps": p_steps, "new_tokens": wb.total_q,
             "new_tokens_per_s": round(wb.total_q / ms * 1e3, 1), "flops_per_step": flops,
-            "roofline": {"bound": "mfma", "kernel": "prefill_kernel<4>",
+            "roofline": {"bound": "mfma", "kernel": "attention_tile_kernel<4, false>",
                          "achieved": round(flops / kernel_ms / 1e9, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                          "unit": "TFLOP/s", "frac": round(flops / kernel_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
                          "kernel_ms": round(kernel_ms, 3), "traffic": None},
@@ -263,8 +263,8 @@ def main():
             "workload": "config 4: 256 programs, 64 q / 8 kv heads, groups of 16 share a 16k prefix",
             "ms_per_step": round(ms, 4), "logical_kv_gbps": round(logical / ms / 1e6, 1),
             "unique_kv_gbps": round(unique / ms / 1e6, 1),
-            "frac_of_unique_bytes_roofline": round(unique / kernel_ms / 1e6 / HBM_PEAK_GBPS, 4),
-            "kernel_ms": round(kernel_ms, 4),
+            "frac_of_unique_bytes_roofline": round(unique / ms / 1e6 / HBM_PEAK_GBPS, 4),
+            "private_chunk_kernel_ms": round(kernel_ms, 4),
         }
         del wb, out, lse
         torch.cuda.empty_cache()
