@@ -122,21 +122,25 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
         int n = L > 0 ? (L + chunk_tokens - 1) / chunk_tokens : 0;
         return n > max_per_program ? max_per_program : n;   // lengths above the host bound are clipped
     };
-    // exclusive scan of `value` over one pass of up to 1024 programs; returns this thread's offset
+    // exclusive scan of `value` over one pass of up to 1024 programs (wave-level shuffles, then
+    // the sixteen wave totals); returns this thread's offset including earlier passes
+    __shared__ int32_t wave_total[16];
     auto block_scan = [&](int value) {
-        scan[tid] = value;
-        __syncthreads();
-        for (int off = 1; off < 1024; off <<= 1) {
-            const int v = tid >= off ? scan[tid - off] : 0;
-            __syncthreads();
-            scan[tid] += v;
-            __syncthreads();
+        const int lane = tid & 63, wv = tid >> 6;
+        int x = value;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int y = __shfl_up(x, off);
+            if (lane >= off) x += y;
         }
-        const int first = carry + scan[tid] - value;
+        if (lane == 63) wave_total[wv] = x;
         __syncthreads();
-        if (tid == 1023) carry += scan[1023];
+        int before = carry;
+        for (int w = 0; w < wv; ++w) before += wave_total[w];
         __syncthreads();
-        return first;
+        if (tid == 1023) carry = before + x;
+        __syncthreads();
+        return before + x - value;
     };
 
     // 1. partial slots
@@ -497,6 +501,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(MergeParams p) {
     for (int s = 32; s >= 1; s >>= 1) mt = fmaxf(mt, __shfl_xor(mt, s));
 
     float lt = 0.0f, o0 = 0.0f, o1 = 0.0f;
+#pragma unroll 8
     for (int c = c0; c < c1; ++c) {
         const int64_t r = int64_t(c) * p.num_q_heads + h;
         const float wt = fast_exp2(p.part_ml[r * 2] - mt);

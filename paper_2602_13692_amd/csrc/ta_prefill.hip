@@ -166,10 +166,13 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     char* k_lds = lds;                           // [kRing][kKTileBytes]
     char* v_lds = lds + kRing * kKTileBytes;     // [kRing][kVTileBytes]
 
+    // Workgroups stride over the (item, kv head) pairs: append-prefill is launched with one
+    // workgroup per pair, the shared-prefix decode with a small resident grid (its item count is
+    // only known on the device and is usually zero).
     const int n_items = SHARED ? p.counts[1] : p.tile_start[p.batch];
-    const int tile_id = blockIdx.x / p.num_kv_heads;
-    if (tile_id >= n_items) return;
-    const int g = blockIdx.x - tile_id * p.num_kv_heads;
+    for (int blk = blockIdx.x; blk < n_items * p.num_kv_heads; blk += gridDim.x) {
+    const int tile_id = blk / p.num_kv_heads;
+    const int g = blk - tile_id * p.num_kv_heads;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -667,6 +670,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
                     total > 0.0f ? (m[rb] + __builtin_amdgcn_logf(total)) * kLn2 : -INFINITY;
         }
     }
+    __syncthreads();   // the next item reuses the LDS ring
+    }
 }
 
 // 96 KiB of dynamic LDS is above the default 64 KiB limit: raised once per kernel instance.
@@ -757,9 +762,9 @@ int launch_shared_prefix(const Geometry& g, const SharedPrefixArgs& a, hipStream
     pp.num_q_heads = g.num_q_heads;
     pp.num_kv_heads = g.num_kv_heads;
     pp.scale_log2 = g.scale_log2;
-    const int64_t blocks = int64_t(a.max_items) * g.num_kv_heads;
+    int64_t blocks = int64_t(a.max_items) * g.num_kv_heads;
     if (blocks <= 0) return TA_OK;
-    if (blocks > 0x7fffffff) return TA_ERR_INVALID_ARG;
+    if (blocks > 512) blocks = 512;   // one workgroup fits per CU; they stride over the items
     return launch_tile_kernel<true>(g.group, static_cast<unsigned>(blocks), pp, stream);
 }
 
