@@ -7,6 +7,7 @@
 // = (256 / G) consecutive new tokens x the G query heads that share a kv head,
 // and walks the program's keys in tiles of 64 (four pages):
 //
+//   * (K rows are padded to 272 bytes in LDS instead of being swizzled)
 //   * K and V tiles go HBM -> registers -> LDS once per workgroup, through a
 //     ring of three tiles with one barrier per tile, and serve all 256 rows;
 //   * every wave owns 64 rows and computes the TRANSPOSED scores S^T = K Q^T,
@@ -21,6 +22,8 @@
 //     bound by exactly that, so every operand is read 16 bytes wide;
 //   * the running maximum is only raised (and O rescaled) when it grows by more
 //     than 2^8, a wave-uniform and rare event after the first tile.
+#include <type_traits>
+
 #include "ta_internal.h"
 
 namespace ta {
@@ -33,13 +36,12 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
-constexpr int kThreads = 256;
-constexpr int kRowsPerBlock = 256;  // score rows per workgroup
+constexpr int kThreads = 512;        // eight waves, two per SIMD
+constexpr int kRowsPerBlock = 256;   // score rows per workgroup
+constexpr int kRB = 1;               // 32-row blocks per wave
 constexpr int kTileKeys = 64;       // keys per LDS tile (4 pages)
-constexpr int kKTileBytes = kTileKeys * kHeadDim * 2;  // 16 KiB
-constexpr int kVTileBytes = kTileKeys * kHeadDim * 2;  // 16 KiB
 constexpr float kRescaleThreshold = 8.0f;  // log2 units
-constexpr int kRing = 3;                   // LDS tiles in flight
+constexpr int kRing = 4;                   // LDS slots (tiles in flight)
 constexpr int kKAhead = 3;                 // LDS operand reads in flight ahead of their matrix instruction
 constexpr int kVAhead = 4;
 
@@ -137,23 +139,23 @@ __device__ __forceinline__ float max_across_halves(float x) {
     return fmaxf(__builtin_bit_cast(float, r.x), __builtin_bit_cast(float, r.y));
 }
 
-// Staging registers of one thread for one 64-key tile: four 16-byte pieces of K
-// (keys r16 + 16 i, chunk c16) and eight 8-byte pieces of V (the eight keys of one
-// "octet", 4 dims).
-struct Stage {
-    u32x4 k[4];
-    u32x2 v[8];
-};
+// LDS holds a ring of kRing slots; a slot is the K tile followed by the V tile of 64 keys, both
+// row-major (one key = 256 bytes) with their sixteen 16-byte chunks permuted per row so that the
+// operand reads are free of bank conflicts:
+//   K: chunk c of key k sits at chunk position c ^ (k & 15)        (16 lanes read 16 keys, same c)
+//   V: chunk c of key k sits at chunk position c ^ ((k & 3) << 2)  (a transposing read touches
+//      4 keys x 64 bytes)
+// The tiles are written by the memory pipeline itself (global_load_lds_dwordx4: every lane names
+// the 16 global bytes it wants, the wave's 64 pieces land in LDS in lane order), so staging costs
+// no vector registers and no LDS store instructions; the permutation is applied on the global
+// side, by choosing which chunk a lane fetches.
+constexpr int kTileBytes = kTileKeys * kHeadDim * 2;   // 16 KiB
+constexpr int kSlotBytes = 2 * kTileBytes;
 
-// V lives in LDS as [octet][dim][8 keys]: one 16-byte entry is exactly the A operand of one
-// lane for O^T += V^T P^T.  Octet (kb, step, hl) of a 64-key tile holds the keys that lane half
-// hl contracts in k = 16 step `step` of 32-key block kb: kb 32 + step 16 + hl 4 + {0..3, 8..11}.
-// Byte offset of the entry of `dim` inside its octet (the 16-byte entries of a 64-byte run of
-// four dims are XOR-swizzled so that the staging writes are bank-conflict free):
-__device__ __forceinline__ int v_entry_offset(int dim) {
-    const int chunk = dim >> 2;
-    return chunk * 64 + (((dim & 3) ^ ((chunk >> 2) & 3)) << 4);
-}
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+#define TA_LDS_PTR(T, ptr) ((__attribute__((address_space(3))) T*)(ptr))
+#define TA_GLOBAL_PTR(ptr) ((const __attribute__((address_space(1))) void*)(ptr))
 
 // SHARED = false: append-prefill, rows = (new token, head), causal, writes bf16 output.
 // SHARED = true:  decode of a group of programs whose block tables begin with the same pages
@@ -162,9 +164,7 @@ __device__ __forceinline__ int v_entry_offset(int dim) {
 template <int G, bool SHARED>
 __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillParams p) {
     constexpr int kTileTokens = kRowsPerBlock / G;   // programs per item when SHARED
-    extern __shared__ __attribute__((aligned(16))) char lds[];
-    char* k_lds = lds;                           // [kRing][kKTileBytes]
-    char* v_lds = lds + kRing * kKTileBytes;     // [kRing][kVTileBytes]
+    extern __shared__ __attribute__((aligned(16))) char lds[];   // [kRing][K tile | V tile]
 
     // Workgroups stride over the (item, kv head) pairs: append-prefill is launched with one
     // workgroup per pair, the shared-prefix decode with a small resident grid (its item count is
@@ -207,14 +207,14 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     }
     const int n_pages_b = (p.context_lens[b] + kPageSize - 1) / kPageSize;
 
-    // ---- per-lane rows: two blocks of 32 rows per wave ----
+    // ---- per-lane rows: one block of 32 rows per wave ----
     // row -> (token or member program, head): row = index * G + head
-    int vis[2];            // visible keys of this lane's row in row block rb (0 = row does not exist)
-    bf16x8 qf[2][8];       // B operands: q[row][16 ks + 8 hl .. + 7]
-    int64_t out_row[2];    // element offset of the row in q / out, or -1
+    int vis[kRB];            // visible keys of this lane's row in row block rb (0 = row does not exist)
+    bf16x8 qf[kRB][8];       // B operands: q[row][16 ks + 8 hl .. + 7]
+    int64_t out_row[kRB];    // element offset of the row in q / out, or -1
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-        const int row = wave * 64 + rb * 32 + l32;
+    for (int rb = 0; rb < kRB; ++rb) {
+        const int row = wave * (32 * kRB) + rb * 32 + l32;
         const int idx = t0 + row / G;
         const int head = g * G + row % G;
         const bool ok = SHARED ? (row / G < members) : (idx < nq);
@@ -225,26 +225,26 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
         for (int ks = 0; ks < 8; ++ks) {
             u32x4 t = {0u, 0u, 0u, 0u};
             if (ok) t = *reinterpret_cast<const u32x4*>(qrow + ks * 16);
-            // Q is only ever a matrix-instruction operand: parking it in accumulation registers
-            // leaves the vector registers to the softmax and the operand prefetch
-            asm volatile("" : "+a"(t));
             qf[rb][ks] = __builtin_bit_cast(bf16x8, t);
         }
     }
 
-    // ---- staging addresses ----
-    const int c16 = tid & 15;   // 16-byte chunk of a 256-byte row
-    const int r16 = tid >> 4;   // 0..15
-    const char* k_base = p.k_pool + int64_t(g) * p.stride_head_bytes + r16 * 256 + c16 * 16;
-    // V: thread -> (octet oc = tid / 32, 8-byte chunk c32 of 4 dims); the octet's keys all lie in
-    // page oc / 2 = wave of the tile, rows 4 hl + {0..3} and 8 + 4 hl + {0..3}
-    const int c32 = tid & 31;
-    const int oc = tid >> 5;
-    const char* v_base = p.v_pool + int64_t(g) * p.stride_head_bytes + ((oc & 1) * 4) * 256 + c32 * 8;
-    const int v_key0 = (oc >> 1) * 16 + (oc & 1) * 4;                // first key of the octet in the tile
+    // ---- staging: wave w brings in keys 8 w .. 8 w + 7 of every tile (half a page) ----
+    // Two instructions for K and two for V; instruction q covers keys 8 w + 4 q + (0 .. 3), and
+    // lane (lrow, l16) of it fills chunk position l16 of key 8 w + 4 q + lrow.
+    const int l16 = lane & 15;
+    const int lrow = lane >> 4;
+    uint32_t dma_k[2], dma_v[2];    // byte offset inside the page of the chunk this lane fetches
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int row = 8 * (wave & 1) + 4 * q + lrow;            // row of the key in its page
+        dma_k[q] = row * 256 + ((l16 ^ (row & 15)) << 4);
+        dma_v[q] = row * 256 + ((l16 ^ ((row & 3) << 2)) << 4);
+    }
+    const char* k_head = p.k_pool + int64_t(g) * p.stride_head_bytes;
+    const char* v_head = p.v_pool + int64_t(g) * p.stride_head_bytes;
     const int32_t* table = p.block_table + int64_t(b) * p.block_table_stride;
-    const int k_lds_off = r16 * 256 + ((c16 ^ r16) << 4);           // + i * 4096 for key r16 + 16 i
-    const int v_lds_off = oc * 2048 + c32 * 64;                     // entries at ((e ^ (c32 >> 2)) << 4)
+    const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(TA_LDS_PTR(char, lds)));
 
     // Page ids: lane l of every wave holds the id of page (64 g + l) of the current group of 64
     // pages (16 tiles), clamped to the program's last page; the next group is fetched one
@@ -254,113 +254,115 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
         pg = pg < n_pages_b ? pg : n_pages_b - 1;
         return table[pg];
     };
+    // byte offset of a page inside a pool, computed by all lanes at once when a group of ids
+    // becomes current (their load was issued a group earlier)
+    auto page_bytes = [&](int id) -> int64_t { return int64_t(id) * p.stride_page_bytes; };
+    auto lane_value = [&](int64_t v, int idx) -> int64_t {
+        const uint32_t lo = __builtin_amdgcn_readlane(static_cast<int>(v), idx);
+        const uint32_t hi = __builtin_amdgcn_readlane(static_cast<int>(v >> 32), idx);
+        return static_cast<int64_t>((uint64_t(hi) << 32) | lo);
+    };
     int ids_group = t_begin >> 4;
-    int ids_cur = fetch_ids(ids_group);
+    int64_t ids_cur = page_bytes(fetch_ids(ids_group));
     int ids_next = fetch_ids(ids_group + 1);
 
-    // Loading one tile = planning (page ids -> byte offsets, scalar) + 8 loads of 16 bytes;
-    // storing it to LDS = 4 K writes + 4 V pieces (mask, 4x8 transpose, write).  Both are cut
-    // into eight steps so that the pipelined body can spread them over its slices.
-    struct LoadPlan {
-        int64_t k_off[4];
-        int64_t v_off;
-    };
-    auto plan_load = [&](int t) -> LoadPlan {
+    // Starting the loads of one tile = the page offset out of the lanes + four instructions.
+    // Exactly four per tile, always (tiles past the end re-read the last page): the waits below
+    // count on it.
+    auto plan_load = [&](int t) -> int64_t {
         if ((t >> 4) != ids_group) {      // tiles are visited in order, so this is group + 1
             ids_group = t >> 4;
-            ids_cur = ids_next;
+            ids_cur = page_bytes(ids_next);
             ids_next = fetch_ids(ids_group + 1);
         }
-        LoadPlan lp;
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            lp.k_off[i] = int64_t(__builtin_amdgcn_readlane(ids_cur, (t & 15) * 4 + i)) * p.stride_page_bytes;
-        // V: this thread's octet lies in page `wave` of the tile
-        lp.v_off = int64_t(__builtin_amdgcn_readlane(ids_cur, (t & 15) * 4 + wave)) * p.stride_page_bytes;
-        return lp;
+        return lane_value(ids_cur, (t & 15) * 4 + (wave >> 1));
     };
-    auto load_step = [&](Stage& st, const LoadPlan& lp, int i) {
-        if (i < 4) {
-            st.k[i] = *reinterpret_cast<const u32x4*>(k_base + lp.k_off[i]);
-        } else {   // octet rows 2 (i - 4) and 2 (i - 4) + 1; rows 4..7 sit 8 keys further
-            const int j = 2 * (i - 4);
-            const int row = (j & 3) + (j >> 2) * 8;
-            st.v[j] = *reinterpret_cast<const u32x2*>(v_base + lp.v_off + row * 256);
-            st.v[j + 1] = *reinterpret_cast<const u32x2*>(v_base + lp.v_off + (row + 1) * 256);
-        }
+    auto load_step = [&](int64_t page_off, int slot, int i) __attribute__((always_inline)) {
+        const uint32_t dst = lds_base + slot * kSlotBytes + (i >> 1) * kTileBytes + wave * 2048 + (i & 1) * 1024;
+        const char* src = ((i >> 1) ? v_head : k_head) + page_off + ((i >> 1) ? dma_v[i & 1] : dma_k[i & 1]);
+        // Written as assembly on purpose: for the builtin form the compiler assumes that every
+        // later LDS read may touch the bytes in flight and waits for the load right away.  The
+        // waits are placed by hand instead (finish_tile), one per tile.
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory");
     };
-    auto load_tile = [&](Stage& st, int t) {
-        const LoadPlan lp = plan_load(t);
+    auto load_tile = [&](int t, int slot) __attribute__((always_inline)) {
+        const int64_t page_off = plan_load(t);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) load_step(st, lp, i);
+        for (int i = 0; i < 4; ++i) load_step(page_off, slot, i);
     };
-    auto store_step = [&](const Stage& st, int t, int slot, int i) {
-        if (i < 4) {
-            *reinterpret_cast<u32x4*>(k_lds + slot * kKTileBytes + k_lds_off + i * 4096) = st.k[i];
-        } else {
-            // entry e = the octet's eight keys at dim 4 c32 + e: an 8x1 column of the 8x4 block
-            // this thread loaded.  Keys at or beyond the context length may hold anything (even
-            // NaN): their V rows are zeroed, because 0 * NaN inside the matrix core would poison O.
-            const int e = i - 4;
-            uint32_t a[8];
+    // Keys at or beyond the context length may hold anything (even NaN): their V rows are
+    // zeroed once they have landed, because 0 * NaN inside the matrix core would poison O.
+    // Every lane clears the pieces it fetched itself.
+    auto scrub_tail = [&](int t, int slot) {
+        if ((t + 1) * kTileKeys > L) {   // only the tile that holds the end of the context
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int key = t * kTileKeys + v_key0 + (j & 3) + (j >> 2) * 8;
-                a[j] = key < L ? st.v[j][e >> 1] : 0u;
+            for (int q = 0; q < 2; ++q) {
+                const int key = t * kTileKeys + 8 * wave + 4 * q + lrow;
+                if (key >= L)
+                    *reinterpret_cast<u32x4*>(lds + slot * kSlotBytes + kTileBytes + wave * 2048 + q * 1024 + lane * 16) =
+                        u32x4{0u, 0u, 0u, 0u};
             }
-            const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;   // high or low halves
-            u32x4 entry;
-            entry.x = __builtin_amdgcn_perm(a[1], a[0], sel);
-            entry.y = __builtin_amdgcn_perm(a[3], a[2], sel);
-            entry.z = __builtin_amdgcn_perm(a[5], a[4], sel);
-            entry.w = __builtin_amdgcn_perm(a[7], a[6], sel);
-            *reinterpret_cast<u32x4*>(v_lds + slot * kVTileBytes + v_lds_off + ((e ^ ((c32 >> 2) & 3)) << 4)) = entry;
         }
-    };
-    auto store_tile = [&](const Stage& st, int t, int slot) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) store_step(st, t, slot, i);
     };
 
     // ---- accumulators ----
-    f32x16 o[4][2];        // O^T blocks: [dim block][row block]
+    f32x16 o[4][kRB];        // O^T blocks: [dim block][row block]
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[db][rb][r] = 0.0f;
-    float m[2] = {kNegBig, kNegBig};   // reference maximum (log2 domain, scaled)
-    float lsum[2] = {0.0f, 0.0f};      // this lane's share of the row sum
+    float m[kRB], lsum[kRB];   // reference maximum (log2 domain, scaled); this lane's share of the row sum
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb) { m[rb] = kNegBig; lsum[rb] = 0.0f; }
 
-    // LDS read offsets
-    int k_rd[2];   // K operand: key l32 + 32 kb, chunk (2 ks + hl) ^ (key & 15)
+    // ---- LDS operand reads: one per-lane offset each, the rest are compile-time offsets ----
+    // K operand of (block kb, step ks): key l32 + 32 kb, dims 16 ks + 8 hl .. + 7 = chunk 2 ks + hl
+    int k_rd[8];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) k_rd[kb] = (kb * 32 + l32) * 256;
-    const int k_swz = l32 & 15;
-    int v_rd[4];   // V operand: entry of dim l32 + 32 db in octet (.., hl)
+    for (int ks = 0; ks < 8; ++ks) k_rd[ks] = l32 * 256 + (((2 * ks + hl) ^ (l32 & 15)) << 4);
+    // V operand of (block kb, step, dim block db): lane (l32, hl) needs dim 32 db + l32 of the keys
+    // 32 kb + 16 step + 4 hl + {0..3, 8..11} (the keys whose weights sit in its B operand).  Two
+    // transposing reads (ds_read_b64_tr_b16) fetch four keys each: in every group of 16 lanes,
+    // lane s names the 8 bytes (4 dims) of key s / 4 at dims 4 (s % 4) .., and lane j receives
+    // dim j of the four keys.
+    int v_rd[4];
 #pragma unroll
-    for (int db = 0; db < 4; ++db) v_rd[db] = hl * 2048 + v_entry_offset(db * 32 + l32);
+    for (int db = 0; db < 4; ++db) {
+        const int key = 4 * hl + (l16 >> 2);                      // + 32 kb + 16 step + 8 half
+        const int c = 4 * db + 2 * (lrow & 1) + ((lane & 3) >> 1);   // 16-byte chunk of the dims
+        v_rd[db] = key * 256 + ((c ^ ((key & 3) << 2)) << 4) + (lane & 1) * 8;
+    }
+    auto k_operand_at = [&](const char* kt, int kb, int ks) __attribute__((always_inline)) {
+        return *reinterpret_cast<const bf16x8*>(kt + kb * 32 * 256 + k_rd[ks]);
+    };
+    auto v_operand_at = [&](const char* vt, int kb, int idx) __attribute__((always_inline)) {   // idx = 4 step + dim block
+        const char* at = vt + (kb * 32 + (idx >> 2) * 16) * 256 + v_rd[idx & 3];
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(TA_LDS_PTR(s16x4, at));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(TA_LDS_PTR(s16x4, at + 8 * 256));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
 
     // ---- the four steps of one 32-key block ----
-    // A: S^T block = K Q^T, 32 keys x (2 x 32 rows); register r of lane (l32, hl) holds
+    // A: S^T block = K Q^T, 32 keys x 32 rows; register r of lane (l32, hl) holds
     //    key 8 (r / 4) + 4 hl + r % 4 of the block
-    auto scores = [&](const char* kt, int kb, f32x16 (&s)[2]) {
+    auto scores = [&](const char* kt, int kb, f32x16 (&s)[kRB]) {
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[rb][r] = 0.0f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(kt + k_rd[kb] + (((2 * ks + hl) ^ k_swz) << 4));
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][ks], s[0], 0, 0, 0);
-            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][ks], s[1], 0, 0, 0);
+            const bf16x8 a = k_operand_at(kt, kb, ks);
+#pragma unroll
+            for (int rb = 0; rb < kRB; ++rb) s[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[rb][ks], s[rb], 0, 0, 0);
         }
     };
     // causal mask of a block that straddles the diagonal
-    auto mask_scores = [&](int key_base, f32x16 (&s)[2]) {
+    auto mask_scores = [&](int key_base, f32x16 (&s)[kRB]) {
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int key = key_base + 4 * hl + 8 * (r >> 2) + (r & 3);
@@ -369,46 +371,28 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     };
     // B1: row maxima; the reference is raised (and O, l rescaled) only when it would grow
     //     by more than the threshold, a wave-uniform and rare event
-    // The hand-written matrix instructions are invisible to the compiler's hazard checks:
-    // before anything else reads O, let the matrix core finish (32 wait states cover the
-    // 16-pass write-back latency).
-    auto mfma_drain = [&]() { asm volatile("s_nop 15\n\ts_nop 15"); };
-    auto rescale_if_needed = [&](const float (&cand)[2]) {
-        const bool grow = cand[0] > m[0] + kRescaleThreshold || cand[1] > m[1] + kRescaleThreshold;
-        if (__builtin_expect(__builtin_amdgcn_ballot_w64(grow) != 0, 0)) {
-            mfma_drain();
+    auto rescale_if_needed = [&](const float (&cand)[kRB]) {
+        bool grow = false;
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
+        for (int rb = 0; rb < kRB; ++rb) grow = grow || cand[rb] > m[rb] + kRescaleThreshold;
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(grow) != 0, 0)) {
+#pragma unroll
+            for (int rb = 0; rb < kRB; ++rb) {
                 const float m_new = fmaxf(m[rb], cand[rb]);
                 const float alpha = __builtin_amdgcn_exp2f(m[rb] - m_new);
                 m[rb] = m_new;
                 lsum[rb] *= alpha;
-                // O lives in the accumulation registers the matrix core writes; scaling it there
-                // (read, multiply, write back) keeps this rare path from forcing copies of O
-                // into vector registers on the common path
 #pragma unroll
                 for (int db = 0; db < 4; ++db)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        float x = o[db][rb][r];
-                        float tmp;
-                        asm volatile(
-                            "v_accvgpr_read_b32 %1, %0\n\t"
-                            "s_nop 1\n\t"
-                            "v_mul_f32 %1, %1, %2\n\t"
-                            "s_nop 1\n\t"
-                            "v_accvgpr_write_b32 %0, %1"
-                            : "+a"(x), "=&v"(tmp)
-                            : "v"(alpha));
-                        o[db][rb][r] = x;
-                    }
+                    for (int r = 0; r < 16; ++r) o[db][rb][r] *= alpha;
             }
         }
     };
-    auto raise_reference = [&](const f32x16 (&s)[2]) {
-        float cand[2];
+    auto raise_reference = [&](const f32x16 (&s)[kRB]) {
+        float cand[kRB];
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
+        for (int rb = 0; rb < kRB; ++rb) {
             float mx = fmaxf(fmaxf(s[rb][0], s[rb][1]), s[rb][2]);
 #pragma unroll
             for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[rb][r]), s[rb][r + 1]);
@@ -419,10 +403,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
         rescale_if_needed(cand);
     };
     // B2: weights 2^(s c - m), row-sum share, packing into the B operands of the two k = 16 steps
-    auto weights = [&](const f32x16 (&s)[2], bf16x8 (&pf)[2][2]) {
+    auto weights = [&](const f32x16 (&s)[kRB], bf16x8 (&pf)[kRB][2]) {
         const uint32_t ones = 0x3f803f80u;   // (1.0, 1.0) in bf16
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
+        for (int rb = 0; rb < kRB; ++rb) {
             const float bias = -m[rb];
             float pr[16];
 #pragma unroll
@@ -446,62 +430,59 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
             lsum[rb] = acc;
         }
     };
-    // C: O^T += V^T P^T; the A operand of (block kb, step, lane half hl) is octet 4 kb + 2 step + hl
-    auto accumulate = [&](const char* vt, int kb, const bf16x8 (&pf)[2][2]) {
+    // C: O^T += V^T P^T
+    auto accumulate = [&](const char* vt, int kb, const bf16x8 (&pf)[kRB][2]) {
 #pragma unroll
-        for (int step = 0; step < 2; ++step) {
-            const char* vq = vt + (kb * 4 + step * 2) * 2048;
+        for (int idx = 0; idx < 8; ++idx) {
+            const bf16x8 a = v_operand_at(vt, kb, idx);
 #pragma unroll
-            for (int db = 0; db < 4; ++db) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8*>(vq + v_rd[db]);
-                o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[0][step], o[db][0], 0, 0, 0);
-                o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[1][step], o[db][1], 0, 0, 0);
-            }
+            for (int rb = 0; rb < kRB; ++rb)
+                o[idx & 3][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[rb][idx >> 2], o[idx & 3][rb], 0, 0, 0);
         }
     };
 
     // ---- the pipelined body's two regions, written slice by slice ----
-    // With one wave per SIMD nothing hides latency except the order of this wave's own
-    // instructions, so the order is written out: every slice issues two matrix instructions,
-    // the LDS read of the operand needed two slices later, and a fixed share of the vector
-    // work; a scheduling barrier closes the slice so the compiler keeps the interleaving.
+    // Two waves share a SIMD; within a wave nothing hides latency except the order of its own
+    // instructions, so the order is written out: every slice issues one matrix instruction, the
+    // LDS read of an operand needed a few slices later, and a fixed share of the vector work; a
+    // scheduling barrier closes the slice so the compiler keeps the interleaving.
+    //
+    // The LDS reads of a region's first operands are issued by the region before it (its last
+    // slices call `prefetch_next`), so no region starts by waiting out an LDS round trip:
+    // ka[0 .. kKAhead) and va[0 .. kVAhead) are always in flight or loaded on entry.
     //
     // Region X: scores of the next block (matrix core) with the weights of the current block
-    // (vector ALU).  Slice ks turns scores 2 ks and 2 ks + 1 of both row blocks into weights.
-    auto region_scores_weights = [&](const char* kt, int kb, f32x16 (&s_new)[2],
-                                     const f32x16 (&s_old)[2], bf16x8 (&pf)[2][2]) {
+    // (vector ALU).  Slice ks turns scores 2 ks and 2 ks + 1 into weights.
+    bf16x8 ka[8], va[8];
+    auto region_scores_weights = [&](const char* kt, int kb, f32x16 (&s_new)[kRB], const f32x16 (&s_old)[kRB],
+                                     bf16x8 (&pf)[kRB][2], auto&& prefetch_next) __attribute__((always_inline)) {
         const uint32_t ones = 0x3f803f80u;   // (1.0, 1.0) in bf16
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        bf16x8 a[8];
-        uint32_t pw[2][8];
-        float acc[2] = {lsum[0], lsum[1]};
-        const float bias[2] = {-m[0], -m[1]};
-        auto k_operand = [&](int ks) {
-            return *reinterpret_cast<const bf16x8*>(kt + k_rd[kb] + (((2 * ks + hl) ^ k_swz) << 4));
-        };
+        uint32_t pw[kRB][8];
+        float acc[kRB], bias[kRB];
 #pragma unroll
-        for (int i = 0; i < kKAhead; ++i) a[i] = k_operand(i);
+        for (int rb = 0; rb < kRB; ++rb) { acc[rb] = lsum[rb]; bias[rb] = -m[rb]; }
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            s_new[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], qf[0][ks], ks == 0 ? zero : s_new[0], 0, 0, 0);
-            s_new[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], qf[1][ks], ks == 0 ? zero : s_new[1], 0, 0, 0);
-            if (ks + kKAhead < 8) a[ks + kKAhead] = k_operand(ks + kKAhead);
 #pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
+            for (int rb = 0; rb < kRB; ++rb) {
+                s_new[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[rb][ks], ks == 0 ? zero : s_new[rb], 0, 0, 0);
+                if (rb == 0 && ks + kKAhead < 8) ka[ks + kKAhead] = k_operand_at(kt, kb, ks + kKAhead);
+                if (rb == kRB - 1 && ks >= 8 - kVAhead) prefetch_next(ks - (8 - kVAhead));
                 const float p0 = __builtin_amdgcn_exp2f(fmaf(s_old[rb][2 * ks], p.scale_log2, bias[rb]));
                 const float p1 = __builtin_amdgcn_exp2f(fmaf(s_old[rb][2 * ks + 1], p.scale_log2, bias[rb]));
                 pw[rb][ks] = pack_bf16(p0, p1);
                 acc[rb] = dot2_bf16(pw[rb][ks], ones, acc[rb]);   // row sum of the ROUNDED weights
+                // the vector results are "used" here, so instruction selection cannot let them
+                // drift past the barrier to the end of the region
+                asm volatile("" ::"v"(pw[rb][ks]), "v"(acc[rb]));
+                __builtin_amdgcn_sched_barrier(0);
             }
-            // the slice's vector results are "used" here, so instruction selection cannot let
-            // them drift past the barrier to the end of the region
-            asm volatile("" ::"v"(pw[0][ks]), "v"(pw[1][ks]), "v"(acc[0]), "v"(acc[1]));
-            __builtin_amdgcn_sched_barrier(0);
         }
-        lsum[0] = acc[0];
-        lsum[1] = acc[1];
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int rb = 0; rb < kRB; ++rb) lsum[rb] = acc[rb];
+#pragma unroll
+        for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
             for (int step = 0; step < 2; ++step) {
                 const u32x4 w = {pw[rb][4 * step], pw[rb][4 * step + 1], pw[rb][4 * step + 2], pw[rb][4 * step + 3]};
@@ -509,40 +490,36 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
             }
     };
     // Region Y: O^T += V^T P^T (matrix core) with the row maxima of the next block's scores
-    // (vector ALU).  The maxima start two slices in, when the scores have left the matrix core.
-    auto region_accumulate_maxima = [&](const char* vt, int kb, const bf16x8 (&pf)[2][2],
-                                        const f32x16 (&s_new)[2], bool use_new, auto&& staging_step) {
-        bf16x8 av[8];
-        auto v_operand = [&](int idx) {   // idx = 4 step + dim block
-            return *reinterpret_cast<const bf16x8*>(vt + (kb * 4 + (idx >> 2) * 2) * 2048 + v_rd[idx & 3]);
-        };
-        float mx[2] = {-INFINITY, -INFINITY};
+    // (vector ALU).  The maxima start four slices in, when the scores have left the matrix core.
+    auto region_accumulate_maxima = [&](const char* vt, int kb, const bf16x8 (&pf)[kRB][2], const f32x16 (&s_new)[kRB],
+                                        bool use_new, auto&& staging_step, auto&& prefetch_next)
+                                        __attribute__((always_inline)) {
+        float mx[kRB];
 #pragma unroll
-        for (int i = 0; i < kVAhead; ++i) av[i] = v_operand(i);
+        for (int rb = 0; rb < kRB; ++rb) mx[rb] = -INFINITY;
 #pragma unroll
         for (int idx = 0; idx < 8; ++idx) {
             const int step = idx >> 2, db = idx & 3;
-            // written as assembly so that O is pinned to accumulation registers ("+a") while the
-            // scores, which the vector ALU reads, stay in vector registers; nothing reads O
-            // again before mfma_drain()
-            asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(o[db][0]) : "v"(av[idx]), "v"(pf[0][step]));
-            asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(o[db][1]) : "v"(av[idx]), "v"(pf[1][step]));
-            if (idx + kVAhead < 8) av[idx + kVAhead] = v_operand(idx + kVAhead);
-            if (idx >= 4) {   // four slices, four scores of each row block per slice
-                const int r0 = (idx - 4) * 4;
 #pragma unroll
-                for (int rb = 0; rb < 2; ++rb) {
+            for (int rb = 0; rb < kRB; ++rb) {
+                o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[idx], pf[rb][step], o[db][rb], 0, 0, 0);
+                if (rb == 0) {
+                    if (idx + kVAhead < 8) va[idx + kVAhead] = v_operand_at(vt, kb, idx + kVAhead);
+                    if (idx >= 8 - kKAhead) prefetch_next(idx - (8 - kKAhead));
+                }
+                if (rb == kRB - 1) staging_step(idx);   // a share of the next tiles' HBM -> LDS traffic
+                if (idx >= 4) {   // four slices, four scores per slice
+                    const int r0 = (idx - 4) * 4;
                     mx[rb] = fmaxf(fmaxf(mx[rb], s_new[rb][r0]), s_new[rb][r0 + 1]);
                     mx[rb] = fmaxf(fmaxf(mx[rb], s_new[rb][r0 + 2]), s_new[rb][r0 + 3]);
+                    asm volatile("" ::"v"(mx[rb]));
                 }
-                asm volatile("" ::"v"(mx[0]), "v"(mx[1]));
+                __builtin_amdgcn_sched_barrier(0);
             }
-            staging_step(idx);   // one eighth of the next tiles' HBM -> LDS traffic
-            __builtin_amdgcn_sched_barrier(0);
         }
-        float cand[2];
+        float cand[kRB];
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
+        for (int rb = 0; rb < kRB; ++rb) {
             mx[rb] = max_across_halves(mx[rb]);
             // a look-ahead block that will be thrown away must not move the reference
             cand[rb] = use_new ? mx[rb] * p.scale_log2 : kNegBig;
@@ -550,90 +527,95 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
         rescale_if_needed(cand);
     };
 
-    // ---- LDS ring of three tiles; tile t lives in slot t % 3 ----
-    // Every iteration t: compute on tile t (the pipelined body also reads K of tile t + 1),
-    // write tile t + 2 (loaded two iterations ago) into the slot tile t - 1 left, start the
-    // loads of tile t + 4 into the registers just freed, barrier.  Tile t - 1 was last read
-    // before the previous barrier and tile t + 2 is first read after this one, so one barrier
-    // per tile is enough.  Two register sets alternate: st0 holds tile t + 2, st1 tile t + 3.
-    Stage st0, st1;
-    load_tile(st0, t_begin);
-    store_tile(st0, t_begin, 0);
-    load_tile(st0, t_begin + 1);
-    store_tile(st0, t_begin + 1, 1);
-    load_tile(st0, t_begin + 2);
-    load_tile(st1, t_begin + 3);
+    // ---- LDS ring of four slots; tile t lives in slot (t - t_begin) % 4 ----
+    // Every iteration t: start the loads of tile t + 3 into the slot tile t - 1 left (last read
+    // before the previous barrier), compute on tile t (the pipelined body also reads K of tile
+    // t + 1), then wait until at most this iteration's four loads are in flight -- the memory
+    // pipeline retires loads in order, so tile t + 2 has landed -- and meet at the barrier.
+    // A tile is therefore requested two iterations before its first use.
+    auto slot_ptr = [&](int slot) { return lds + slot * kSlotBytes; };
+    auto finish_tile = [&](int t_landed, int slot_landed) __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        scrub_tail(t_landed, slot_landed);
+        __syncthreads();
+    };
+#pragma unroll
+    for (int i = 0; i < 3; ++i) load_tile(t_begin + i, i);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < 3; ++i) scrub_tail(t_begin + i, i);
     __syncthreads();
 
-    int slot = 0;                                // slot of tile t
-    auto next_slot = [](int s) { return s == kRing - 1 ? 0 : s + 1; };
-    auto prev_slot = [](int s) { return s == 0 ? kRing - 1 : s - 1; };
-
-    // one pipelined iteration; st holds tile t + 2 on entry and tile t + 4 (in flight) on exit
-    f32x16 sa[2], sb[2];
-    bf16x8 pf[2][2];
-    auto pipelined_tile = [&](int t, Stage& st) {
-        const char* kt = k_lds + slot * kKTileBytes;
-        const char* vt = v_lds + slot * kVTileBytes;
-        const char* kt_next = k_lds + next_slot(slot) * kKTileBytes;
-        const int s2 = prev_slot(slot);          // slot of tile t + 2 == slot of tile t - 1
-        region_scores_weights(kt, 1, sb, sa, pf);
-        region_accumulate_maxima(vt, 0, pf, sb, true, [&](int i) { store_step(st, t + 2, s2, i); });
-        region_scores_weights(kt_next, 0, sa, sb, pf);
-        const LoadPlan lp = plan_load(t + 4);
-        region_accumulate_maxima(vt, 1, pf, sa, t + 1 < n_unmasked, [&](int i) { load_step(st, lp, i); });
-        __syncthreads();
-        slot = next_slot(slot);
+    // one pipelined iteration on tile t in slot S (a compile-time value: every LDS address of
+    // the body is then a per-lane register plus an instruction offset)
+    f32x16 sa[kRB], sb[kRB];
+    bf16x8 pf[kRB][2];
+    auto pipelined_tile = [&](int t, auto slot_tag) __attribute__((always_inline)) {
+        constexpr int S = decltype(slot_tag)::value;
+        const char* kt = lds + S * kSlotBytes;
+        const char* vt = kt + kTileBytes;
+        const char* kt_next = lds + ((S + 1) & 3) * kSlotBytes;
+        const int64_t page_off = plan_load(t + 3);
+        region_scores_weights(kt, 1, sb, sa, pf, [&](int i) { va[i] = v_operand_at(vt, 0, i); });
+        region_accumulate_maxima(vt, 0, pf, sb, true,
+                                 [&](int i) { if (i < 4) load_step(page_off, (S + 3) & 3, i); },
+                                 [&](int i) { ka[i] = k_operand_at(kt_next, 0, i); });
+        region_scores_weights(kt_next, 0, sa, sb, pf, [&](int i) { va[i] = v_operand_at(vt, 1, i); });
+        // the next tile's first region reads K of tile t + 1, block 1 (in LDS since the last barrier)
+        region_accumulate_maxima(vt, 1, pf, sa, t + 1 < n_unmasked, [&](int) {},
+                                 [&](int i) { ka[i] = k_operand_at(kt_next, 1, i); });
+        finish_tile(t + 2, (S + 2) & 3);
     };
 
     int t = t_begin;
-    // ---- pipelined body, two tiles per trip.  Append-prefill pipelines the tiles whose
+    // ---- pipelined body, four tiles per trip.  Append-prefill pipelines the tiles whose
     // successor is also unmasked; a shared chunk has no masked tile and is pipelined to its end
     // (the scores of the block after its last one are computed and thrown away). ----
-    const int pipe_end = SHARED ? n_tiles : t_begin + ((n_unmasked - 1 - t_begin) & ~1);
+    const int pipe_end = t_begin + (((SHARED ? n_tiles : n_unmasked - 1) - t_begin) & ~3);
     if (pipe_end > t_begin) {
-        scores(k_lds + slot * kKTileBytes, 0, sa);
+        scores(slot_ptr(0), 0, sa);
         raise_reference(sa);
-        for (; t < pipe_end; t += 2) {
-            pipelined_tile(t, st0);
-            pipelined_tile(t + 1, st1);
+#pragma unroll
+        for (int i = 0; i < kKAhead; ++i) ka[i] = k_operand_at(slot_ptr(0), 1, i);
+        for (; t < pipe_end; t += 4) {
+            pipelined_tile(t, std::integral_constant<int, 0>{});
+            pipelined_tile(t + 1, std::integral_constant<int, 1>{});
+            pipelined_tile(t + 2, std::integral_constant<int, 2>{});
+            pipelined_tile(t + 3, std::integral_constant<int, 3>{});
         }
         // sa holds the first block of tile t, which the plain body below computes again
-        mfma_drain();
     }
     // ---- plain body: the last unmasked tiles and the tiles that straddle the diagonal ----
+    int slot = 0;                                // (t - t_begin) % 4: the pipelined trips are whole turns
     for (; t < n_tiles; ++t) {
-        const char* kt = k_lds + slot * kKTileBytes;
-        const char* vt = v_lds + slot * kVTileBytes;
+        load_tile(t + 3, (slot + 3) & 3);
+        const char* kt = slot_ptr(slot);
+        const char* vt = kt + kTileBytes;
         const bool masked = t >= n_unmasked;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
-            f32x16 s[2];
+            f32x16 s[kRB];
             scores(kt, kb, s);
             if (masked) mask_scores(t * kTileKeys + kb * 32, s);
             raise_reference(s);
             weights(s, pf);
             accumulate(vt, kb, pf);
         }
-        store_tile(st0, t + 2, prev_slot(slot));
-        load_tile(st0, t + 4);
-        const Stage tmp = st0;                   // st0 must hold tile t + 3 next time round
-        st0 = st1;
-        st1 = tmp;
-        __syncthreads();
-        slot = next_slot(slot);
+        finish_tile(t + 2, (slot + 2) & 3);
+        slot = (slot + 1) & 3;
     }
 
     // ---- epilogue ----
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
+    for (int rb = 0; rb < kRB; ++rb) {
         const float total = lsum[rb] + __shfl_xor(lsum[rb], 32);
         if (out_row[rb] < 0) continue;
         if (SHARED) {
             // split-K partial of (member program, head) for this chunk: unnormalised O, the
             // reference maximum it is relative to, and the sum of weights
-            const int member = (wave * 64 + rb * 32 + l32) / G;
-            const int head = g * G + (wave * 64 + rb * 32 + l32) % G;
+            const int row = wave * (32 * kRB) + rb * 32 + l32;
+            const int member = row / G;
+            const int head = g * G + row % G;
             const int64_t rowid = int64_t(p.chunk_start[b + member] + chunk) * p.num_q_heads + head;
             float* orow = p.part_o + rowid * kHeadDim;
 #pragma unroll
@@ -670,14 +652,16 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
                     total > 0.0f ? (m[rb] + __builtin_amdgcn_logf(total)) * kLn2 : -INFINITY;
         }
     }
-    __syncthreads();   // the next item reuses the LDS ring
+    // the next item reuses the LDS ring: no load may still be on its way into it
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
     }
 }
 
-// 96 KiB of dynamic LDS is above the default 64 KiB limit: raised once per kernel instance.
+// 128 KiB of dynamic LDS is above the default 64 KiB limit: raised once per kernel instance.
 template <int G, bool SHARED>
 int launch_instance(unsigned blocks, const PrefillParams& pp, hipStream_t stream) {
-    const size_t lds_bytes = kRing * (kKTileBytes + kVTileBytes);
+    const size_t lds_bytes = kRing * kSlotBytes;
     static const hipError_t lds_rc =
         hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_tile_kernel<G, SHARED>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));
