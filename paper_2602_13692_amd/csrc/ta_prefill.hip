@@ -3,25 +3,30 @@
 // incremental-prefill term of Eq. 3; Sec. 2.1, c_{t+1} extends c_t).
 //
 // Here q.K^T and p.V are dense contractions, so both run on the matrix cores
-// (v_mfma_f32_32x32x16_bf16).  One workgroup of four waves owns 256 score rows
-// = (256 / G) consecutive new tokens x the G query heads that share a kv head,
-// and walks the program's keys in tiles of 64 (four pages):
+// (v_mfma_f32_32x32x16_bf16).  One workgroup of eight waves (two per SIMD, so
+// that one wave's vector work fills the issue slots the other leaves) owns 256
+// score rows = (256 / G) consecutive new tokens x the G query heads that share
+// a kv head, and walks the program's keys in tiles of 64 (four pages):
 //
-//   * (K rows are padded to 272 bytes in LDS instead of being swizzled)
-//   * K and V tiles go HBM -> registers -> LDS once per workgroup, through a
-//     ring of three tiles with one barrier per tile, and serve all 256 rows;
-//   * every wave owns 64 rows and computes the TRANSPOSED scores S^T = K Q^T,
+//   * K and V tiles go HBM -> LDS once per workgroup and serve all 256 rows.
+//     The memory pipeline writes them into LDS itself (global_load_lds_dwordx4),
+//     so staging takes no vector registers, no LDS store instructions and no
+//     vector ALU work; a ring of four slots keeps a tile in flight for two
+//     iterations, with one barrier per tile;
+//   * every wave owns 32 rows and computes the TRANSPOSED scores S^T = K Q^T,
 //     so that each lane holds one query row's scores in its accumulator
 //     registers: the softmax needs one cross-lane exchange per tile, and the
 //     exponentiated scores are already laid out as the B operand of
 //     O^T = V^T P^T;
-//   * V is written to LDS as [8-key octet][dim][8 keys] (an in-register
-//     transpose at staging time), which makes the A operand of O^T = V^T P^T
-//     one 16-byte LDS read per lane; LDS moves a fixed 64 bytes per cycle and CU
-//     for 16-byte accesses and half that for 8-byte ones, and this kernel is
-//     bound by exactly that, so every operand is read 16 bytes wide;
+//   * V stays row-major in LDS; the A operand of O^T = V^T P^T (eight keys of one
+//     dim per lane) is fetched by the transposing LDS read ds_read_b64_tr_b16;
 //   * the running maximum is only raised (and O rescaled) when it grows by more
 //     than 2^8, a wave-uniform and rare event after the first tile.
+//
+// With random operands the chip's power management, not the instruction mix,
+// sets the pace of this kernel: the shader clock settles well below its
+// nominal value as soon as the matrix cores are busy most of the time, and
+// every byte fetched through the fabric costs clock as well.
 #include <type_traits>
 
 #include "ta_internal.h"
@@ -39,7 +44,7 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 constexpr int kThreads = 512;        // eight waves, two per SIMD
 constexpr int kRowsPerBlock = 256;   // score rows per workgroup
 constexpr int kRB = 1;               // 32-row blocks per wave
-constexpr int kTileKeys = 64;       // keys per LDS tile (4 pages)
+constexpr int kTileKeys = 64;        // keys per LDS tile (4 pages)
 constexpr float kRescaleThreshold = 8.0f;  // log2 units
 constexpr int kRing = 4;                   // LDS slots (tiles in flight)
 constexpr int kKAhead = 3;                 // LDS operand reads in flight ahead of their matrix instruction
