@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """One-GPU benchmark of the paged-KV attention hot path on MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--only decode|all] [--calibrate-copy]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--only decode|prefill|all] [--calibrate-copy]
 
 A step is one ta_paged_decode call (work plan, split-K chunk kernel, merge) on
 the Llama-3-8B-shaped decode batch: 64 programs, 32 q / 8 kv heads, context
@@ -34,7 +34,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # HBM bytes per decode-chunk launch from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by
 # the same counter on a 1 GiB device copy), keyed by the hash of the kernel source they were
 # taken with.  A changed kernel source gives null until the counters are taken again.
-TRAFFIC_BYTES = {"f5c541ccf892deb4": 5089000000}
+TRAFFIC_BYTES = {"2b19ef91a58a12f8": 5089000000}
 
 
 def source_hash(name: str) -> str:
@@ -165,12 +165,28 @@ def spot_check(out, lse, ref_out, ref_lse, torch):
     return {"within_tolerance": ok, "max_abs_err": float(err.max()), "max_lse_err": lse_err}
 
 
+def matrix_core_sustained_tflops(torch, ta, dev, iters: int = 60000) -> float:
+    """Rate of ta_matrix_core_probe on N(0,1) bf16 operands over roughly 20 ms."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(260213692)
+    ops = torch.randn(8 * 64 * 8, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    sink = torch.empty(ta.PROBE_SINK_BYTES, dtype=torch.uint8, device=dev)
+    ta.ta_matrix_core_probe(ops, 1000, sink)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    ta.ta_matrix_core_probe(ops, iters, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    return ta.PROBE_FLOP_PER_ITER * iters / e0.elapsed_time(e1) / 1e9
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--only", choices=["decode", "all"], default="all")
+    ap.add_argument("--only", choices=["decode", "prefill", "all"], default="all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
@@ -235,7 +251,7 @@ def main():
     torch.cuda.empty_cache()
 
     extra = {}
-    if args.only == "all":
+    if args.only in ("all", "prefill"):
         # ---------------- append-prefill (MFMA) ----------------
         wb = wl.append_prefill(dev)
         flops = 4.0 * wb.head_dim * wb.num_q_heads * wb.unmasked_pairs()
@@ -251,9 +267,15 @@ def main():
                          "unit": "TFLOP/s", "frac": round(flops / kernel_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
                          "kernel_ms": round(kernel_ms, 3), "traffic": None},
         }
+        # What the matrix cores sustain on operands of the same kind (N(0,1) in bf16) when they do
+        # nothing else: under such a load the power management, not the nominal clock, sets the rate.
+        sustained = matrix_core_sustained_tflops(torch, ta, dev)
+        extra["append_prefill"]["matrix_cores_alone_same_operand_kind_tflops"] = round(sustained, 1)
+        extra["append_prefill"]["frac_of_matrix_cores_alone"] = round(flops / kernel_ms / 1e9 / sustained, 4)
         del wb, out, lse
         torch.cuda.empty_cache()
 
+    if args.only == "all":
         # ---------------- forked programs with shared prefixes ----------------
         wb = wl.forked_decode(dev)
         logical = int(wb.context_lens.astype("int64").sum()) * wb.kv_bytes_per_token

@@ -185,6 +185,28 @@ TA_API int ta_kv_page_restore(void *k_pool, void *v_pool, size_t page_bytes, con
  */
 TA_API void ta_profile_events(void *start_event, void *stop_event);
 
+/*
+ * Measurement aid (no paper passage: it measures, it computes nothing useful).
+ * Runs iters x 16 independent v_mfma_f32_32x32x16_bf16 per wave, one wave per
+ * SIMD on 256 workgroups, on the caller's operand values, so that the caller
+ * can time the rate the matrix cores sustain on data of that kind: the shader
+ * clock under such a load is set by power management and depends on how many
+ * operand bits toggle.  Floating-point operations enqueued:
+ *   TA_PROBE_FLOP_PER_ITER * iters.
+ *
+ *   operands  DEVICE, 8192 bytes, 16-byte aligned: eight operand registers
+ *             (A0, B0, A1, B1, ...) x 64 lanes x 8 bf16, any finite values
+ *   iters     >= 1
+ *   sink      DEVICE, TA_PROBE_SINK_BYTES, written (keeps the work alive)
+ *   hip_stream  hipStream_t as void*, may be NULL
+ *
+ * Returns TA_ERR_INVALID_ARG for NULL or misaligned pointers or iters < 1.
+ * Nothing is allocated; the work is enqueued, not awaited.
+ */
+#define TA_PROBE_FLOP_PER_ITER (256.0 * 4.0 * 16.0 * 2.0 * 32.0 * 32.0 * 16.0)
+#define TA_PROBE_SINK_BYTES (256 * 256 * 4)
+TA_API int ta_matrix_core_probe(const void *operands, int32_t iters, void *sink, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

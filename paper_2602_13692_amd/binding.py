@@ -24,7 +24,7 @@ TA_ERR_HIP = -3
 EXPORTS = (
     "ta_version", "ta_strerror", "ta_last_hip_error", "ta_workspace_bytes", "ta_paged_decode",
     "ta_append_prefill", "ta_restore_staging_min_bytes", "ta_restore_staging_full_bytes",
-    "ta_kv_page_restore", "ta_profile_events",
+    "ta_kv_page_restore", "ta_profile_events", "ta_matrix_core_probe",
 )
 
 
@@ -98,6 +98,8 @@ def _lib():
         lib.ta_kv_page_restore.argtypes = [vp, vp, sz, vp, vp, vp, i32, i32, vp, sz, vp]
         lib.ta_profile_events.restype = None
         lib.ta_profile_events.argtypes = [vp, vp]
+        lib.ta_matrix_core_probe.restype = ctypes.c_int
+        lib.ta_matrix_core_probe.argtypes = [vp, i32, vp, vp]
         _LIB = lib
     return _LIB
 
@@ -190,6 +192,18 @@ def ta_kv_page_restore(k_pool, v_pool, page_bytes: int, host_k, host_v, dst_slot
 def ta_profile_events(start_event, stop_event) -> None:
     """start/stop: raw hipEvent_t handles (ints) or None to switch recording off."""
     _lib().ta_profile_events(ctypes.c_void_p(start_event), ctypes.c_void_p(stop_event))
+
+
+PROBE_FLOP_PER_ITER = 256.0 * 4.0 * 16.0 * 2.0 * 32.0 * 32.0 * 16.0
+PROBE_SINK_BYTES = 256 * 256 * 4
+
+
+def ta_matrix_core_probe(operands, iters: int, sink, stream=None, check: bool = True) -> int:
+    """operands: 8192-byte device tensor of bf16 operand values; sink: PROBE_SINK_BYTES device bytes."""
+    rc = _lib().ta_matrix_core_probe(_ptr(operands), int(iters), _ptr(sink), _stream(stream))
+    if check:
+        _check(rc, "ta_matrix_core_probe")
+    return rc
 
 
 def alloc_workspace(desc: Desc, batch: int, max_q_len: int, max_context_len: int, device="cuda"):

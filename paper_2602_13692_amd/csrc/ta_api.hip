@@ -124,6 +124,13 @@ const char* ta_strerror(int status) {
 
 int ta_last_hip_error(void) { return g_last_hip_error; }
 
+int ta_matrix_core_probe(const void* operands, int32_t iters, void* sink, void* hip_stream) {
+    if (operands == nullptr || sink == nullptr || iters < 1) return TA_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(operands) & 15) != 0 || (reinterpret_cast<uintptr_t>(sink) & 3) != 0)
+        return TA_ERR_INVALID_ARG;
+    return ta::launch_matrix_core_probe(operands, iters, sink, static_cast<hipStream_t>(hip_stream));
+}
+
 void ta_profile_events(void* start_event, void* stop_event) {
     const bool on = start_event != nullptr && stop_event != nullptr;
     g_profile_events.start = on ? static_cast<hipEvent_t>(start_event) : nullptr;

@@ -130,4 +130,7 @@ int launch_restore(void* k_pool, void* v_pool, size_t page_bytes, const void* ho
                    const void* host_v, const int32_t* dst_slots, int32_t n_pages, void* staging,
                    size_t staging_bytes, hipStream_t stream);
 
+// Measurement aid: 256 workgroups x 4 waves x iters x 16 matrix instructions on the given operands.
+int launch_matrix_core_probe(const void* operands, int32_t iters, void* sink, hipStream_t stream);
+
 }  // namespace ta

@@ -68,3 +68,7 @@ def test_host_side_rejections_need_no_device():
     assert lib.ta_kv_page_restore(null, null, 32768, null, null, null, -1, 10, null, 0, null) == ta.TA_ERR_INVALID_ARG
     assert lib.ta_restore_staging_min_bytes(1000) == 4096
     assert lib.ta_restore_staging_full_bytes(1000, 32768) == 4096 + 2 * 32768
+    # the matrix-core probe rejects missing or misaligned buffers and a non-positive count
+    assert lib.ta_matrix_core_probe(null, 10, null, null) == ta.TA_ERR_INVALID_ARG
+    assert lib.ta_matrix_core_probe(ctypes.c_void_p(4096), 0, ctypes.c_void_p(8192), null) == ta.TA_ERR_INVALID_ARG
+    assert lib.ta_matrix_core_probe(ctypes.c_void_p(4100), 10, ctypes.c_void_p(8192), null) == ta.TA_ERR_INVALID_ARG
