@@ -75,10 +75,13 @@ class KernelTimer:
     def disarm(self):
         self.ta.ta_profile_events(None, None)
 
-    def mean_ms(self) -> float:
+    def times_ms(self):
         self.torch.cuda.synchronize()
-        used = self.pairs[: self.i]
-        return sum(a.elapsed_time(b) for a, b in used) / max(len(used), 1)
+        return [a.elapsed_time(b) for a, b in self.pairs[: self.i]]
+
+    def mean_ms(self) -> float:
+        t = self.times_ms()
+        return sum(t) / max(len(t), 1)
 
 
 def run_decode(wb, steps, warmup, torch, ta):
@@ -107,6 +110,7 @@ def run_decode(wb, steps, warmup, torch, ta):
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
     timer.disarm()
+    run_decode.last_kernel_times = sorted(timer.times_ms())
     return ms, timer.mean_ms(), out, lse
 
 
@@ -165,6 +169,23 @@ def spot_check(out, lse, ref_out, ref_lse, torch):
     return {"within_tolerance": ok, "max_abs_err": float(err.max()), "max_lse_err": lse_err}
 
 
+def stream_read_gbps(torch, ta, buf, reps: int = 5) -> float:
+    """Best of a few timed ta_stream_read_probe passes over `buf` (GB/s)."""
+    sink = torch.empty(ta.STREAM_SINK_BYTES, dtype=torch.uint8, device=buf.device)
+    ta.ta_stream_read_probe(buf, sink)
+    torch.cuda.synchronize()
+    best = 0.0
+    nbytes = buf.numel() * buf.element_size()
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ta.ta_stream_read_probe(buf, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, nbytes / e0.elapsed_time(e1) / 1e6)
+    return best
+
+
 def matrix_core_sustained_tflops(torch, ta, dev, iters: int = 60000) -> float:
     """Rate of ta_matrix_core_probe on N(0,1) bf16 operands over roughly 20 ms."""
     gen = torch.Generator(device=dev)
@@ -215,6 +236,8 @@ def main():
     wb = wl.llama8b_decode(dev)
     kv_bytes = int(wb.context_lens.astype("int64").sum()) * wb.kv_bytes_per_token
     ms, kernel_ms, out, lse = run_decode(wb, args.steps, args.warmup, torch, ta)
+    ktimes = run_decode.last_kernel_times
+    stream_gbps = stream_read_gbps(torch, ta, wb.k_pool)
     value = kv_bytes / ms / 1e6
     achieved = kv_bytes / kernel_ms / 1e6
     traffic = TRAFFIC_BYTES.get(source_hash("ta_decode.hip"))
@@ -232,7 +255,11 @@ def main():
         "roofline": {
             "bound": "hbm", "kernel": "decode_chunk_kernel<4>", "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-            "kernel_ms": round(kernel_ms, 4), "traffic": traffic,
+            "kernel_ms": round(kernel_ms, 4), "kernel_ms_median": round(ktimes[len(ktimes) // 2], 4),
+            "kernel_ms_min": round(ktimes[0], 4), "traffic": traffic,
+            # what a kernel with the same load shape and no arithmetic reads per second in this run
+            "stream_read_same_run_gbps": round(stream_gbps, 1),
+            "frac_of_stream_read": round(achieved / stream_gbps, 4),
         },
     }
     if not args.no_cpu_baseline:

@@ -207,6 +207,21 @@ TA_API void ta_profile_events(void *start_event, void *stop_event);
 #define TA_PROBE_SINK_BYTES (256 * 256 * 4)
 TA_API int ta_matrix_core_probe(const void *operands, int32_t iters, void *sink, void *hip_stream);
 
+/*
+ * Measurement aid (no paper passage).  Reads the buffer once with the load shape
+ * of the decode kernel (16 bytes per lane, non-temporal, four loads in flight)
+ * and no arithmetic, so that the caller can time the read bandwidth the memory
+ * system delivers to such a kernel.
+ *
+ *   src     DEVICE, `bytes` bytes, 16-byte aligned, only read
+ *   bytes   a positive multiple of 16
+ *   sink    DEVICE, TA_STREAM_SINK_BYTES, written
+ *
+ * Returns TA_ERR_INVALID_ARG for NULL or misaligned pointers or a bad size.
+ */
+#define TA_STREAM_SINK_BYTES (8192 * 256 * 4)
+TA_API int ta_stream_read_probe(const void *src, size_t bytes, void *sink, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

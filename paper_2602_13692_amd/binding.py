@@ -24,7 +24,7 @@ TA_ERR_HIP = -3
 EXPORTS = (
     "ta_version", "ta_strerror", "ta_last_hip_error", "ta_workspace_bytes", "ta_paged_decode",
     "ta_append_prefill", "ta_restore_staging_min_bytes", "ta_restore_staging_full_bytes",
-    "ta_kv_page_restore", "ta_profile_events", "ta_matrix_core_probe",
+    "ta_kv_page_restore", "ta_profile_events", "ta_matrix_core_probe", "ta_stream_read_probe",
 )
 
 
@@ -100,6 +100,8 @@ def _lib():
         lib.ta_profile_events.argtypes = [vp, vp]
         lib.ta_matrix_core_probe.restype = ctypes.c_int
         lib.ta_matrix_core_probe.argtypes = [vp, i32, vp, vp]
+        lib.ta_stream_read_probe.restype = ctypes.c_int
+        lib.ta_stream_read_probe.argtypes = [vp, sz, vp, vp]
         _LIB = lib
     return _LIB
 
@@ -203,6 +205,18 @@ def ta_matrix_core_probe(operands, iters: int, sink, stream=None, check: bool = 
     rc = _lib().ta_matrix_core_probe(_ptr(operands), int(iters), _ptr(sink), _stream(stream))
     if check:
         _check(rc, "ta_matrix_core_probe")
+    return rc
+
+
+STREAM_SINK_BYTES = 8192 * 256 * 4
+
+
+def ta_stream_read_probe(src, sink, stream=None, check: bool = True) -> int:
+    """src: device tensor whose bytes (a multiple of 16) are read once; sink: STREAM_SINK_BYTES."""
+    rc = _lib().ta_stream_read_probe(_ptr(src), int(src.numel() * src.element_size()), _ptr(sink),
+                                     _stream(stream))
+    if check:
+        _check(rc, "ta_stream_read_probe")
     return rc
 
 

@@ -131,6 +131,13 @@ int ta_matrix_core_probe(const void* operands, int32_t iters, void* sink, void* 
     return ta::launch_matrix_core_probe(operands, iters, sink, static_cast<hipStream_t>(hip_stream));
 }
 
+int ta_stream_read_probe(const void* src, size_t bytes, void* sink, void* hip_stream) {
+    if (src == nullptr || sink == nullptr || bytes == 0 || (bytes & 15) != 0) return TA_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(src) & 15) != 0 || (reinterpret_cast<uintptr_t>(sink) & 3) != 0)
+        return TA_ERR_INVALID_ARG;
+    return ta::launch_stream_read_probe(src, bytes, sink, static_cast<hipStream_t>(hip_stream));
+}
+
 void ta_profile_events(void* start_event, void* stop_event) {
     const bool on = start_event != nullptr && stop_event != nullptr;
     g_profile_events.start = on ? static_cast<hipEvent_t>(start_event) : nullptr;

@@ -132,5 +132,7 @@ int launch_restore(void* k_pool, void* v_pool, size_t page_bytes, const void* ho
 
 // Measurement aid: 256 workgroups x 4 waves x iters x 16 matrix instructions on the given operands.
 int launch_matrix_core_probe(const void* operands, int32_t iters, void* sink, hipStream_t stream);
+// Measurement aid: reads `bytes` (a multiple of 16) once with the decode kernel's load shape.
+int launch_stream_read_probe(const void* src, size_t bytes, void* sink, hipStream_t stream);
 
 }  // namespace ta

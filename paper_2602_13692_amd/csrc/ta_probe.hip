@@ -17,6 +17,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int kProbeBlocks = 256;    // one per CU
 constexpr int kProbeThreads = 256;   // one wave per SIMD
+constexpr int kStreamBlocks = 8192;  // grid-stride; 32 workgroups per CU
 
 __global__ __launch_bounds__(kProbeThreads) void matrix_core_probe_kernel(const u32x4* __restrict__ operands,
                                                                           int32_t iters, float* __restrict__ sink) {
@@ -47,7 +48,33 @@ __global__ __launch_bounds__(kProbeThreads) void matrix_core_probe_kernel(const 
     sink[blockIdx.x * kProbeThreads + threadIdx.x] = s;
 }
 
+// Streaming read: every byte of the buffer once, 16 bytes per lane, non-temporal, the access
+// pattern of the decode kernel without its arithmetic.  Its rate is the read bandwidth the
+// memory system delivers to a kernel of that shape.
+__global__ __launch_bounds__(256) void stream_read_probe_kernel(const u32x4* __restrict__ src, size_t n_vec,
+                                                                uint32_t* __restrict__ sink) {
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    const size_t stride = size_t(gridDim.x) * blockDim.x * 4;
+    size_t i = size_t(blockIdx.x) * blockDim.x * 4 + threadIdx.x;
+    for (; i + 3 * 256 < n_vec; i += stride) {      // four independent loads in flight per lane
+        const u32x4 a = __builtin_nontemporal_load(src + i);
+        const u32x4 b = __builtin_nontemporal_load(src + i + 256);
+        const u32x4 c = __builtin_nontemporal_load(src + i + 512);
+        const u32x4 d = __builtin_nontemporal_load(src + i + 768);
+        acc ^= a ^ b ^ c ^ d;
+    }
+    for (; i < n_vec; i += 256) acc ^= __builtin_nontemporal_load(src + i);   // ragged tail of the last block
+    sink[blockIdx.x * blockDim.x + threadIdx.x] = acc.x ^ acc.y ^ acc.z ^ acc.w;
+}
+
 }  // namespace
+
+int launch_stream_read_probe(const void* src, size_t bytes, void* sink, hipStream_t stream) {
+    hipLaunchKernelGGL(stream_read_probe_kernel, dim3(kStreamBlocks), dim3(256), 0, stream,
+                       static_cast<const u32x4*>(src), bytes / 16, static_cast<uint32_t*>(sink));
+    TA_HIP_TRY(hipGetLastError());
+    return TA_OK;
+}
 
 int launch_matrix_core_probe(const void* operands, int32_t iters, void* sink, hipStream_t stream) {
     hipLaunchKernelGGL(matrix_core_probe_kernel, dim3(kProbeBlocks), dim3(kProbeThreads), 0, stream,

@@ -72,3 +72,5 @@ def test_host_side_rejections_need_no_device():
     assert lib.ta_matrix_core_probe(null, 10, null, null) == ta.TA_ERR_INVALID_ARG
     assert lib.ta_matrix_core_probe(ctypes.c_void_p(4096), 0, ctypes.c_void_p(8192), null) == ta.TA_ERR_INVALID_ARG
     assert lib.ta_matrix_core_probe(ctypes.c_void_p(4100), 10, ctypes.c_void_p(8192), null) == ta.TA_ERR_INVALID_ARG
+    assert lib.ta_stream_read_probe(null, 4096, null, null) == ta.TA_ERR_INVALID_ARG
+    assert lib.ta_stream_read_probe(ctypes.c_void_p(4096), 24, ctypes.c_void_p(8192), null) == ta.TA_ERR_INVALID_ARG
