@@ -313,7 +313,7 @@ def main():
             "ms_per_step": round(ms, 4), "logical_kv_gbps": round(logical / ms / 1e6, 1),
             "unique_kv_gbps": round(unique / ms / 1e6, 1),
             "frac_of_unique_bytes_roofline": round(unique / ms / 1e6 / HBM_PEAK_GBPS, 4),
-            "private_chunk_kernel_ms": round(kernel_ms, 4),
+            "dominant_kernel_ms": round(kernel_ms, 4),
         }
         del wb, out, lse
         torch.cuda.empty_cache()

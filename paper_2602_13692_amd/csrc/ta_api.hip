@@ -84,8 +84,10 @@ WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_l
         w.off_items = off;       off = align256(off + sizeof(int32_t) * 2 * size_t(w.max_chunks));
         w.off_part_ml = off;     off = align256(off + sizeof(float) * 2 * size_t(w.max_chunks) * g.num_q_heads);
         w.off_part_o = off;      off = align256(off + sizeof(float) * kHeadDim * size_t(w.max_chunks) * g.num_q_heads);
-        // a shared chunk serves at least two programs
-        w.max_shared_items = static_cast<int32_t>((int64_t(batch) / 2) * per_prog);
+        // a shared chunk serves at least two programs; with eight heads per kv head every chunk
+        // goes to the matrix-core kernel, one item each at most
+        w.max_shared_items = g.group == 8 ? w.max_chunks
+                                          : static_cast<int32_t>((int64_t(batch) / 2) * per_prog);
         w.off_counts = off;      off = align256(off + sizeof(int32_t) * 4);
         w.off_lcp = off;         off = align256(off + sizeof(int32_t) * size_t(batch));
         w.off_shared_items = off; off = align256(off + sizeof(int32_t) * 4 * size_t(w.max_shared_items));

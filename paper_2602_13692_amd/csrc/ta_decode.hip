@@ -100,12 +100,14 @@ __global__ __launch_bounds__(256) void common_prefix_kernel(const int32_t* __res
 //   shared_items  (first program, members, chunk)   -> matrix-core kernel, all members at once
 //   items         (program, chunk) for every chunk that is not shared -> vector-ALU kernel
 // counts[0] = number of items, counts[1] = number of shared items.
+// With private_on_tiles every remaining chunk is listed as a group of one program in
+// shared_items instead, and `items` stays empty.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __restrict__ context_lens,
                                                            const int32_t* __restrict__ lcp,
                                                            int32_t batch, int32_t chunk_pages,
                                                            int32_t max_per_program, int32_t max_members,
-                                                           int32_t max_shared_items,
+                                                           int32_t max_shared_items, int32_t private_on_tiles,
                                                            int32_t* __restrict__ chunk_start,
                                                            int2* __restrict__ items,
                                                            int4* __restrict__ shared_items,
@@ -194,11 +196,15 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
         const int n = b < batch ? chunks_of(b) : 0;
         const int sc = (b < batch && batch <= 1024) ? shared_chunks[b] : 0;
         const int first = block_scan(n - sc);
-        for (int c = sc; c < n; ++c) items[first + c - sc] = make_int2(b, c);
+        if (private_on_tiles) {
+            for (int c = sc; c < n; ++c) shared_items[n_shared + first + c - sc] = make_int4(b, 1, c, 0);
+        } else {
+            for (int c = sc; c < n; ++c) items[first + c - sc] = make_int2(b, c);
+        }
     }
     if (tid == 0) {
-        counts[0] = carry;
-        counts[1] = n_shared;
+        counts[0] = private_on_tiles ? 0 : carry;
+        counts[1] = private_on_tiles ? n_shared + carry : n_shared;
     }
 }
 
@@ -532,6 +538,10 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     // sharing needs at least two programs and a non-empty block table
     const bool look_for_sharing = a.batch >= 2 && a.batch <= 1024 && w.max_shared_items > 0 &&
                                   a.block_table_stride > 0;
+    // Eight query heads per kv head leave the vector-ALU kernel one wave per SIMD (its per-head
+    // state fills the register file) and make it compute-bound; the matrix-core kernel takes
+    // the private chunks too, as groups of one program.
+    const bool private_on_tiles = g.group == 8 && w.max_shared_items >= w.max_chunks;
 
     if (look_for_sharing) {
         hipLaunchKernelGGL(common_prefix_kernel, dim3(a.batch), dim3(256), 0, stream, a.block_table,
@@ -540,10 +550,12 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     }
     hipLaunchKernelGGL(plan_decode_kernel, dim3(1), dim3(1024), 0, stream, a.context_lens,
                        look_for_sharing ? lcp : nullptr, a.batch, w.chunk_pages, per_prog,
-                       256 / g.group, w.max_shared_items, chunk_start, items, shared_items, counts);
+                       256 / g.group, w.max_shared_items, private_on_tiles ? 1 : 0, chunk_start, items,
+                       shared_items, counts);
     TA_HIP_TRY(hipGetLastError());
 
-    if (look_for_sharing) {
+    const ProfileEvents ev = profile_events();
+    if (look_for_sharing || private_on_tiles) {
         SharedPrefixArgs sa{};
         sa.q = a.q;
         sa.k_pool = a.k_pool;
@@ -559,11 +571,13 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
         sa.batch = a.batch;
         sa.tiles_per_chunk = w.chunk_pages / 4;
         sa.max_items = w.max_shared_items;
+        if (private_on_tiles && ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
         const int rc = launch_shared_prefix(g, sa, stream);
         if (rc != TA_OK) return rc;
+        if (private_on_tiles && ev.stop != nullptr) TA_HIP_TRY(hipEventRecord(ev.stop, stream));
     }
 
-    if (w.max_chunks > 0) {
+    if (w.max_chunks > 0 && !private_on_tiles) {
         ChunkParams cp{};
         cp.q = a.q;
         cp.k_pool = reinterpret_cast<const char*>(a.k_pool);
@@ -586,7 +600,6 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
         const int64_t blocks = int64_t(w.max_chunks) * g.num_kv_heads;
         if (blocks > 0x7fffffff) return TA_ERR_INVALID_ARG;
         const dim3 grid(static_cast<unsigned>(blocks)), block(kChunkThreads);
-        const ProfileEvents ev = profile_events();
         if (ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
         switch (g.group) {
             case 1: hipLaunchKernelGGL(decode_chunk_kernel<1>, grid, block, 0, stream, cp); break;

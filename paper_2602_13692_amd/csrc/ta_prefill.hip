@@ -166,6 +166,10 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 // SHARED = true:  decode of a group of programs whose block tables begin with the same pages
 //                 (forked agent branches): rows = (member program, head), keys = one chunk of
 //                 the shared prefix, no mask, writes split-K partials for the decode merge.
+//                 A group of one program is a private chunk (used when G = 8, where the
+//                 vector-ALU decode kernel runs out of registers): it may hold the end of the
+//                 program's context, so its last tile is masked like a causal one.
+// Waves none of whose 32 rows exist take part in the loads and barriers only.
 template <int G, bool SHARED>
 __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillParams p) {
     constexpr int kTileTokens = kRowsPerBlock / G;   // programs per item when SHARED
@@ -191,10 +195,16 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
         members = it.y;
         chunk = it.z;
         q0 = 0; nq = 0; prefix = 0; t0 = 0;
-        L = 0x7fffffff;                // every key of a shared chunk exists
         t_begin = chunk * p.tiles_per_chunk;
         n_tiles = t_begin + p.tiles_per_chunk;
         n_unmasked = n_tiles;
+        L = 0x7fffffff;                // every key of a shared chunk exists
+        if (members == 1) {            // a private chunk ends where its program's context ends
+            L = p.context_lens[b];
+            const int last = (L + kTileKeys - 1) / kTileKeys;
+            n_tiles = n_tiles < last ? n_tiles : last;
+            n_unmasked = L / kTileKeys < n_tiles ? L / kTileKeys : n_tiles;
+        }
     } else {
         const int2 tl = p.tiles[tile_id];
         b = tl.x;
@@ -223,7 +233,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
         const int idx = t0 + row / G;
         const int head = g * G + row % G;
         const bool ok = SHARED ? (row / G < members) : (idx < nq);
-        vis[rb] = ok ? prefix + idx + 1 : 0;
+        vis[rb] = ok ? (SHARED ? L : prefix + idx + 1) : 0;
         out_row[rb] = ok ? (int64_t(SHARED ? b + row / G : q0 + idx) * p.num_q_heads + head) * kHeadDim : int64_t(-1);
         const uint16_t* qrow = p.q + (ok ? out_row[rb] : 0) + hl * 8;
 #pragma unroll
@@ -233,6 +243,11 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
             qf[rb][ks] = __builtin_bit_cast(bf16x8, t);
         }
     }
+
+    bool any_row = false;
+#pragma unroll
+    for (int rb = 0; rb < kRB; ++rb) any_row = any_row || vis[rb] > 0;
+    const bool wave_active = __builtin_amdgcn_ballot_w64(any_row) != 0;   // wave-uniform
 
     // ---- staging: wave w brings in keys 8 w .. 8 w + 7 of every tile (half a page) ----
     // Two instructions for K and two for V; instruction q covers keys 8 w + 4 q + (0 .. 3), and
@@ -574,10 +589,18 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
 
     int t = t_begin;
     // ---- pipelined body, four tiles per trip.  Append-prefill pipelines the tiles whose
-    // successor is also unmasked; a shared chunk has no masked tile and is pipelined to its end
+    // successor is also unmasked; a shared chunk without a masked tile is pipelined to its end
     // (the scores of the block after its last one are computed and thrown away). ----
-    const int pipe_end = t_begin + (((SHARED ? n_tiles : n_unmasked - 1) - t_begin) & ~3);
-    if (pipe_end > t_begin) {
+    const int pipe_limit = (SHARED && n_unmasked == n_tiles) ? n_tiles : n_unmasked - 1;
+    const int pipe_end = t_begin + ((pipe_limit - t_begin) & ~3);
+    if (!wave_active) {
+        // nothing to compute: keep the workgroup's loads and barriers going
+        for (; t < n_tiles; ++t) {
+            const int s = (t - t_begin) & 3;
+            load_tile(t + 3, (s + 3) & 3);
+            finish_tile(t + 2, (s + 2) & 3);
+        }
+    } else if (pipe_end > t_begin) {
         scores(slot_ptr(0), 0, sa);
         raise_reference(sa);
 #pragma unroll
