@@ -8,6 +8,8 @@ from .ta_oracle import (  # noqa: F401
     append_prefill,
     attend_rows,
     build,
+    kv_append,
+    kv_page_evict,
     kv_page_restore,
     num_threads,
     paged_decode,

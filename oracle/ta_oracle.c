@@ -277,3 +277,59 @@ int ta_oracle_kv_page_restore(uint8_t *k_pool, uint8_t *v_pool, int64_t page_byt
     }
     return 0;
 }
+
+/*
+ * KV page evict (the device-side consequence of the paper's Pause, Sec. 4.3:
+ * a paused program's KV cache leaves the pool; App. A.2 and A.4 keep it in host
+ * memory): host[i] = pool[src_slots[i]] for K and for V, bytes only.  The pool
+ * is not modified.  A slot may be named more than once.  Returns 0, or -1 when
+ * a slot is out of range (nothing is written in that case).
+ */
+int ta_oracle_kv_page_evict(const uint8_t *k_pool, const uint8_t *v_pool, int64_t page_bytes,
+                            uint8_t *host_k, uint8_t *host_v,
+                            const int32_t *src_slots, int32_t n_pages, int32_t pool_pages)
+{
+    if (n_pages < 0 || pool_pages < 0 || page_bytes < 0) return -1;
+    for (int32_t i = 0; i < n_pages; ++i)
+        if (src_slots[i] < 0 || src_slots[i] >= pool_pages) return -1;
+    for (int32_t i = 0; i < n_pages; ++i) {
+        memcpy(host_k + (int64_t)i * page_bytes, k_pool + (int64_t)src_slots[i] * page_bytes, (size_t)page_bytes);
+        memcpy(host_v + (int64_t)i * page_bytes, v_pool + (int64_t)src_slots[i] * page_bytes, (size_t)page_bytes);
+    }
+    return 0;
+}
+
+/*
+ * KV append (Sec. 2.1: the context c_{t+1} extends c_t, so the cache of a
+ * program grows at its tail; Sec. 4.2: the new tokens are the ones an
+ * incremental prefill or a decode step attends from).  Program b's n_b new
+ * tokens, n_b = cu_new[b + 1] - cu_new[b], become its tokens
+ * context_lens[b] - n_b ... context_lens[b] - 1 (context_lens counts them
+ * already): row (cu_new[b] + i) of new_k / new_v, laid out [token][Hkv][d], is
+ * written to the pool at the place the block table gives token
+ * context_lens[b] - n_b + i.  Bit patterns are copied; nothing else changes.
+ */
+void ta_oracle_kv_append(const oracle_geom *ge, const uint16_t *new_k, const uint16_t *new_v,
+                         const int32_t *cu_new, uint16_t *k_pool, uint16_t *v_pool,
+                         const int32_t *block_table, int64_t table_stride,
+                         const int32_t *context_lens, int32_t batch)
+{
+    const int64_t d = ge->head_dim, Hkv = ge->num_kv_heads, S = ge->page_size;
+    for (int32_t b = 0; b < batch; ++b) {
+        const int64_t n = cu_new[b + 1] - cu_new[b];
+        const int64_t first = (int64_t)context_lens[b] - n;
+        for (int64_t i = 0; i < n; ++i) {
+            const int64_t token = first + i;
+            const int64_t page = block_table[(int64_t)b * table_stride + token / S];
+            const int64_t row = token % S;
+            for (int64_t g = 0; g < Hkv; ++g) {
+                const int64_t dst = page * ge->stride_page + g * ge->stride_head + row * ge->stride_token;
+                const int64_t src = ((int64_t)(cu_new[b] + i) * Hkv + g) * d;
+                for (int64_t c = 0; c < d; ++c) {
+                    k_pool[dst + c] = new_k[src + c];
+                    v_pool[dst + c] = new_v[src + c];
+                }
+            }
+        }
+    }
+}

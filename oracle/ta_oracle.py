@@ -76,6 +76,8 @@ def _load():
         _lib = ctypes.CDLL(_LIB)
         _lib.ta_oracle_num_threads.restype = ctypes.c_int
         _lib.ta_oracle_kv_page_restore.restype = ctypes.c_int
+        _lib.ta_oracle_kv_page_evict.restype = ctypes.c_int
+        _lib.ta_oracle_kv_append.restype = None
     return _lib
 
 
@@ -186,4 +188,36 @@ def kv_page_restore(k_pool, v_pool, page_bytes, host_k, host_v, dst_slots, pool_
             _p(k_pool), _p(v_pool), ctypes.c_int64(int(page_bytes)), _p(host_k), _p(host_v),
             _p(dst_slots), ctypes.c_int32(int(dst_slots.shape[0])), ctypes.c_int32(int(pool_pages)),
         )
+    )
+
+
+def kv_page_evict(k_pool, v_pool, page_bytes, host_k, host_v, src_slots, pool_pages) -> int:
+    """Gather pages out of the uint8 pools into host_k / host_v in place; returns 0 or -1."""
+    lib = _load()
+    for a in (k_pool, v_pool, host_k, host_v):
+        assert a.dtype == np.uint8 and a.flags["C_CONTIGUOUS"]
+    src_slots = _i32(src_slots)
+    return int(
+        lib.ta_oracle_kv_page_evict(
+            _p(k_pool), _p(v_pool), ctypes.c_int64(int(page_bytes)), _p(host_k), _p(host_v),
+            _p(src_slots), ctypes.c_int32(int(src_slots.shape[0])), ctypes.c_int32(int(pool_pages)),
+        )
+    )
+
+
+def kv_append(geom: Geometry, new_k, new_v, cu_new_lens, k_pool, v_pool, block_table, context_lens) -> None:
+    """Write the new tokens' rows (uint16 [total_new,Hkv,d]) into the uint16 pools in place."""
+    lib = _load()
+    new_k, new_v = _u16(new_k), _u16(new_v)
+    for a in (k_pool, v_pool):
+        assert a.dtype == np.uint16 and a.flags["C_CONTIGUOUS"]
+    cu_new_lens = _i32(cu_new_lens)
+    block_table = _i32(block_table)
+    context_lens = _i32(context_lens)
+    B = int(context_lens.shape[0])
+    stride = int(block_table.shape[1]) if block_table.ndim == 2 else 0
+    g = geom.c_struct()
+    lib.ta_oracle_kv_append(
+        ctypes.byref(g), _p(new_k), _p(new_v), _p(cu_new_lens), _p(k_pool), _p(v_pool),
+        _p(block_table), ctypes.c_int64(stride), _p(context_lens), ctypes.c_int32(B),
     )

@@ -15,7 +15,9 @@
 //   merge   combines the partials of a (program, query head) and writes bf16.
 //
 // The work is HBM-bound (4 flop per KV byte at group size 4), so it runs on the
-// vector ALUs: packed bf16 dot products for q.k, fp32 FMAs for p.v.
+// vector ALUs: packed bf16 dot products for q.k, fp32 FMAs for p.v.  With eight query
+// heads per kv head the per-head state of this kernel would fill the register file (one
+// wave per SIMD, compute-bound), so there every chunk goes to the matrix-core tile kernel.
 #include "ta_internal.h"
 
 namespace ta {
@@ -541,7 +543,7 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     // Eight query heads per kv head leave the vector-ALU kernel one wave per SIMD (its per-head
     // state fills the register file) and make it compute-bound; the matrix-core kernel takes
     // the private chunks too, as groups of one program.
-    const bool private_on_tiles = g.group == 8 && w.max_shared_items >= w.max_chunks;
+    const bool private_on_tiles = g.group == 8;   // the workspace plan sizes shared_items for it
 
     if (look_for_sharing) {
         hipLaunchKernelGGL(common_prefix_kernel, dim3(a.batch), dim3(256), 0, stream, a.block_table,
@@ -605,7 +607,6 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
             case 1: hipLaunchKernelGGL(decode_chunk_kernel<1>, grid, block, 0, stream, cp); break;
             case 2: hipLaunchKernelGGL(decode_chunk_kernel<2>, grid, block, 0, stream, cp); break;
             case 4: hipLaunchKernelGGL(decode_chunk_kernel<4>, grid, block, 0, stream, cp); break;
-            case 8: hipLaunchKernelGGL(decode_chunk_kernel<8>, grid, block, 0, stream, cp); break;
             default: return TA_ERR_UNSUPPORTED;
         }
         TA_HIP_TRY(hipGetLastError());

@@ -483,6 +483,96 @@ def test_evict_restore_round_trip_keeps_decode_result():
 
 
 # ---------------------------------------------------------------------------
+# evict (the inverse of restore) and append (the cache grows at its tail)
+# ---------------------------------------------------------------------------
+
+def test_evict_gathers_exact_bytes_and_leaves_the_pool_alone():
+    rng = np.random.default_rng(43)
+    P, page_bytes, n = 19, 2 * PS * D * 2, 11
+    k_pool = rng.integers(0, 256, size=(P, page_bytes), dtype=np.uint8)
+    v_pool = rng.integers(0, 256, size=(P, page_bytes), dtype=np.uint8)
+    k0, v0 = k_pool.copy(), v_pool.copy()
+    src = rng.integers(0, P, size=n).astype(np.int32)          # repeats allowed
+    host_k = np.zeros((n, page_bytes), np.uint8)
+    host_v = np.zeros((n, page_bytes), np.uint8)
+    assert oracle.kv_page_evict(k_pool, v_pool, page_bytes, host_k, host_v, src, P) == 0
+    assert np.array_equal(host_k, k0[src]) and np.array_equal(host_v, v0[src])     # numpy fancy indexing
+    assert np.array_equal(k_pool, k0) and np.array_equal(v_pool, v0)
+    for bad in ([0, P], [-1, 2]):
+        hk = np.zeros((2, page_bytes), np.uint8)
+        assert oracle.kv_page_evict(k_pool, v_pool, page_bytes, hk, hk.copy(), np.array(bad, np.int32), P) == -1
+        assert not hk.any()
+
+
+def test_evict_then_restore_elsewhere_is_the_identity_on_contents():
+    rng = np.random.default_rng(44)
+    P, page_bytes, n = 16, 256, 6
+    k_pool = rng.integers(0, 256, size=(P, page_bytes), dtype=np.uint8)
+    v_pool = rng.integers(0, 256, size=(P, page_bytes), dtype=np.uint8)
+    src = rng.choice(P, size=n, replace=False).astype(np.int32)
+    host_k = np.zeros((n, page_bytes), np.uint8)
+    host_v = np.zeros((n, page_bytes), np.uint8)
+    assert oracle.kv_page_evict(k_pool, v_pool, page_bytes, host_k, host_v, src, P) == 0
+    k2, v2 = np.zeros_like(k_pool), np.zeros_like(v_pool)
+    dst = rng.choice(P, size=n, replace=False).astype(np.int32)
+    assert oracle.kv_page_restore(k2, v2, page_bytes, host_k, host_v, dst, P) == 0
+    assert np.array_equal(k2[dst], k_pool[src]) and np.array_equal(v2[dst], v_pool[src])
+
+
+@pytest.mark.parametrize("Hkv", [1, 2])
+def test_append_writes_the_tail_rows_and_nothing_else(Hkv):
+    """Checked against direct numpy indexing of the [P][Hkv][16][d] pool."""
+    rng = np.random.default_rng(45 + Hkv)
+    lens = np.array([1, 16, 17, 40, 33], np.int32)            # after the append
+    n_new = np.array([1, 3, 17, 0, 20], np.int32)             # one token, a page boundary, a whole context, none
+    c = random_case(rng, 5, 2 * Hkv, Hkv, lens)
+    total = int(n_new.sum())
+    new_k = rng.integers(0, 65536, size=(total, Hkv, D)).astype(np.uint16)
+    new_v = rng.integers(0, 65536, size=(total, Hkv, D)).astype(np.uint16)
+    kp, vp = c["k_pool"].copy(), c["v_pool"].copy()
+    oracle.kv_append(c["geom"], new_k, new_v, cu(n_new), kp, vp, c["table"], lens)
+    want_k, want_v = c["k_pool"].copy(), c["v_pool"].copy()
+    row = 0
+    for b in range(5):
+        for i in range(int(n_new[b])):
+            tok = int(lens[b] - n_new[b] + i)
+            page = int(c["table"][b, tok // PS])
+            want_k[page, :, tok % PS, :] = new_k[row]
+            want_v[page, :, tok % PS, :] = new_v[row]
+            row += 1
+    assert np.array_equal(kp, want_k) and np.array_equal(vp, want_v)
+    assert not np.array_equal(kp, c["k_pool"])
+
+
+def test_append_then_attend_equals_attending_a_pool_filled_directly():
+    """The precondition of append-prefill (new K/V already in their pages) is what append produces."""
+    rng = np.random.default_rng(47)
+    lens = np.array([37, 20, 64], np.int32)
+    n_new = np.array([5, 20, 1], np.int32)
+    c = random_case(rng, 3, 4, 2, lens, q_lens=n_new)
+    geom = c["geom"]
+    ref_out, ref_lse = oracle.append_prefill(geom, c["q"], cu(n_new), c["k_pool"], c["v_pool"], c["table"], lens)
+    # pull the new tokens' rows out of the full pool, blank them, append them again
+    kp, vp = c["k_pool"].copy(), c["v_pool"].copy()
+    new_k = np.zeros((int(n_new.sum()), 2, D), np.uint16)
+    new_v = np.zeros_like(new_k)
+    row = 0
+    for b in range(3):
+        for i in range(int(n_new[b])):
+            tok = int(lens[b] - n_new[b] + i)
+            page = int(c["table"][b, tok // PS])
+            new_k[row] = kp[page, :, tok % PS, :]
+            new_v[row] = vp[page, :, tok % PS, :]
+            kp[page, :, tok % PS, :] = 0x7FC0     # NaN until appended
+            vp[page, :, tok % PS, :] = 0x7FC0
+            row += 1
+    oracle.kv_append(geom, new_k, new_v, cu(n_new), kp, vp, c["table"], lens)
+    assert np.array_equal(kp, c["k_pool"]) and np.array_equal(vp, c["v_pool"])
+    out, lse = oracle.append_prefill(geom, c["q"], cu(n_new), kp, vp, c["table"], lens)
+    assert np.array_equal(out, ref_out) and np.array_equal(lse, ref_lse)
+
+
+# ---------------------------------------------------------------------------
 # workload generators: structure only
 # ---------------------------------------------------------------------------
 
