@@ -294,6 +294,19 @@ def main():
                          "unit": "TFLOP/s", "frac": round(flops / kernel_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
                          "kernel_ms": round(kernel_ms, 3), "traffic": None},
         }
+        # writing the new tokens' K/V into their pages first (what a serving step does before this call)
+        new_k = torch.empty((wb.total_q, wb.num_kv_heads, wb.head_dim), dtype=torch.bfloat16, device=dev).normal_()
+        new_v = torch.empty_like(new_k).normal_()
+        a_bt = torch.from_numpy(wb.block_table).to(dev)
+        a_cl = torch.from_numpy(wb.context_lens).to(dev)
+        a_cu = torch.from_numpy(wb.cu_q_lens).to(dev)
+        a_desc = ta.Desc(wb.num_q_heads, wb.num_kv_heads)
+        a_ms = time_steps(lambda: ta.ta_kv_append(a_desc, new_k, new_v, a_cu, wb.k_pool, wb.v_pool, a_bt, a_cl,
+                                                  wb.total_q), 5, 1, torch)
+        moved = 2.0 * 2.0 * new_k.numel() * 2      # K and V, read once and written once
+        extra["append_prefill"]["kv_append"] = {"ms": round(a_ms, 4), "bytes_read_plus_written": moved,
+                                                "gbps": round(moved / a_ms / 1e6, 1)}
+        del new_k, new_v
         # What the matrix cores sustain on operands of the same kind (N(0,1) in bf16) when they do
         # nothing else: under such a load the power management, not the nominal clock, sets the rate.
         sustained = matrix_core_sustained_tflops(torch, ta, dev)
@@ -340,7 +353,23 @@ def main():
         big = torch.empty_like(rs.host_k, device=dev)
         link_ms = time_steps(lambda: big.copy_(rs.host_k, non_blocking=True), 3, 1, torch)
         link_gbps = n * page_bytes / link_ms / 1e6
-        del big
+        # the Pause side: the same pages leave the pool for pinned host memory
+        back_k, back_v = torch.empty_like(rs.host_k).pin_memory(), torch.empty_like(rs.host_v).pin_memory()
+        ev = {}
+        for mode, nbytes in (("zero_copy", ta.ta_restore_staging_min_bytes(n)),
+                             ("staged", ta.ta_restore_staging_min_bytes(n) + 2 * (256 << 20))):
+            staging = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+            def evict_step():
+                ta.ta_kv_page_evict(wb.k_pool, wb.v_pool, page_bytes, back_k, back_v, slots,
+                                    wb.pool_pages, staging)
+
+            e_ms = time_steps(evict_step, 3, 1, torch)
+            ev[mode] = {"ms": round(e_ms, 2), "gbps": round(2.0 * n * page_bytes / e_ms / 1e6, 2)}
+            del staging
+        d2h_ms = time_steps(lambda: back_k.copy_(big, non_blocking=True), 3, 1, torch)
+        d2h_gbps = n * page_bytes / d2h_ms / 1e6
+        del big, back_k, back_v
         kv5 = int(wb.context_lens.astype("int64").sum()) * wb.kv_bytes_per_token
         ms, kernel_ms, out, lse = run_decode(wb, max(2, min(args.steps, 10)), 2, torch, ta)
         best = min(res.values(), key=lambda r: r["ms"])
@@ -350,6 +379,8 @@ def main():
             "restored_pages": n, "restored_bytes": 2 * n * page_bytes, "restore": res,
             "host_link_h2d_gbps": round(link_gbps, 2),
             "restore_frac_of_link": round(best["gbps"] / link_gbps, 3),
+            "evict": ev, "host_link_d2h_gbps": round(d2h_gbps, 2),
+            "evict_frac_of_link": round(max(r["gbps"] for r in ev.values()) / d2h_gbps, 3),
             "decode_ms": round(ms, 4), "decode_kv_gbps": round(kv5 / ms / 1e6, 1),
             "decode_kernel_frac_of_hbm_peak": round(kv5 / kernel_ms / 1e6 / HBM_PEAK_GBPS, 4),
             "restore_to_decode_time_ratio": round(best["ms"] / ms, 1),

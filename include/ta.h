@@ -14,6 +14,9 @@
  *                        whole cached context;
  *   ta_append_prefill    n new tokens per program attend causally to prefix +
  *                        themselves;
+ *   ta_kv_page_evict     pool pages are copied out to pinned host memory (Pause);
+ *   ta_kv_append         the new tokens' keys and values are written to the tail
+ *                        of their programs' pages;
  *   ta_kv_page_restore   pages held in pinned host memory are written back
  *                        into free slots of the device page pool.
  *
@@ -172,6 +175,53 @@ TA_API size_t ta_restore_staging_full_bytes(int32_t n_pages, size_t page_bytes);
 TA_API int ta_kv_page_restore(void *k_pool, void *v_pool, size_t page_bytes, const void *host_k,
                        const void *host_v, const int32_t *dst_slots, int32_t n_pages,
                        int32_t pool_pages, void *staging, size_t staging_bytes, void *hip_stream);
+
+/*
+ * KV page evict, the inverse of ta_kv_page_restore (Sec. 4.3: Pause releases a
+ * program's KV cache; App. A.2/A.4: the pages are kept in host memory instead
+ * of being recomputed later).  Bytes only, bit-exact:
+ *     host_k[i] = k_pool[src_slots[i]],  host_v[i] = v_pool[src_slots[i]],  i < n_pages
+ * The pools are only read; the caller frees the slots by forgetting them.
+ *
+ *   k_pool,v_pool DEVICE, pool_pages pages of page_bytes each, contiguous, only read
+ *   host_k,host_v HOST, PINNED (hipHostMalloc), written: [n_pages][page_bytes], 16-byte aligned
+ *   src_slots     HOST int32 [n_pages], each in [0, pool_pages); a slot may repeat.
+ *                 Read before the call returns.
+ *   staging       DEVICE, 256-byte aligned, at least ta_restore_staging_min_bytes(n_pages);
+ *                 from ta_restore_staging_full_bytes on the pages are gathered into it and
+ *                 leave through large device-to-host copies, below that the gather kernel
+ *                 writes the pinned host pages itself
+ * The copies are enqueued on hip_stream; host_k / host_v hold the pages once
+ * the stream has reached the end of the call.
+ * Errors as for ta_kv_page_restore (nothing is enqueued when the slot list is bad).
+ */
+TA_API int ta_kv_page_evict(const void *k_pool, const void *v_pool, size_t page_bytes, void *host_k,
+                     void *host_v, const int32_t *src_slots, int32_t n_pages, int32_t pool_pages,
+                     void *staging, size_t staging_bytes, void *hip_stream);
+
+/*
+ * KV append (Sec. 2.1: the context c_{t+1} extends c_t, so a program's cache
+ * grows at its tail; it is what makes the precondition of ta_append_prefill and
+ * ta_paged_decode true: the new tokens' keys and values are in their pages).
+ * Program b's n_b = cu_new_lens[b+1] - cu_new_lens[b] new tokens become its
+ * tokens context_lens[b] - n_b .. context_lens[b] - 1 (context_lens counts them
+ * already); bit patterns are copied:
+ *     pool[block_table[b][t / 16]][g][t % 16][:] = new[cu_new_lens[b] + i][g][:],
+ *     t = context_lens[b] - n_b + i,  for K and for V, every kv head g
+ * The pages named by the block table must exist; no other byte changes.
+ *
+ *   new_k,new_v   DEVICE bf16 [total_new][Hkv][128], programs packed back to back
+ *   cu_new_lens   DEVICE int32 [batch+1], non-decreasing, cu_new_lens[0] = 0
+ *   k_pool,v_pool DEVICE, written; layout per desc
+ *   total_new     HOST, equals cu_new_lens[batch]
+ * Other arguments as for ta_paged_decode.  Two programs that share a tail page
+ * and both write it race (forked programs share full prefix pages only).
+ * Returns TA_ERR_INVALID_ARG for NULL or misaligned pointers or negative sizes.
+ */
+TA_API int ta_kv_append(const ta_attn_desc *desc, const void *new_k, const void *new_v,
+                 const int32_t *cu_new_lens, void *k_pool, void *v_pool,
+                 const int32_t *block_table, int32_t block_table_stride,
+                 const int32_t *context_lens, int32_t batch, int32_t total_new, void *hip_stream);
 
 /*
  * Instrumentation for benchmarks (no paper passage: it measures, it computes

@@ -24,7 +24,8 @@ TA_ERR_HIP = -3
 EXPORTS = (
     "ta_version", "ta_strerror", "ta_last_hip_error", "ta_workspace_bytes", "ta_paged_decode",
     "ta_append_prefill", "ta_restore_staging_min_bytes", "ta_restore_staging_full_bytes",
-    "ta_kv_page_restore", "ta_profile_events", "ta_matrix_core_probe", "ta_stream_read_probe",
+    "ta_kv_page_restore", "ta_kv_page_evict", "ta_kv_append", "ta_profile_events",
+    "ta_matrix_core_probe", "ta_stream_read_probe",
 )
 
 
@@ -96,6 +97,10 @@ def _lib():
         lib.ta_restore_staging_full_bytes.argtypes = [i32, sz]
         lib.ta_kv_page_restore.restype = ctypes.c_int
         lib.ta_kv_page_restore.argtypes = [vp, vp, sz, vp, vp, vp, i32, i32, vp, sz, vp]
+        lib.ta_kv_page_evict.restype = ctypes.c_int
+        lib.ta_kv_page_evict.argtypes = [vp, vp, sz, vp, vp, vp, i32, i32, vp, sz, vp]
+        lib.ta_kv_append.restype = ctypes.c_int
+        lib.ta_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, i32, i32, vp]
         lib.ta_profile_events.restype = None
         lib.ta_profile_events.argtypes = [vp, vp]
         lib.ta_matrix_core_probe.restype = ctypes.c_int
@@ -188,6 +193,32 @@ def ta_kv_page_restore(k_pool, v_pool, page_bytes: int, host_k, host_v, dst_slot
         int(staging.numel() * staging.element_size()) if staging is not None else 0, _stream(stream))
     if check:
         _check(rc, "ta_kv_page_restore")
+    return rc
+
+
+def ta_kv_page_evict(k_pool, v_pool, page_bytes, host_k, host_v, src_slots, pool_pages, staging,
+                     stream=None, check: bool = True) -> int:
+    """src_slots: CPU int32 tensor; host_k / host_v: pinned CPU tensors that receive the pages."""
+    n = int(src_slots.shape[0]) if src_slots is not None else 0
+    rc = _lib().ta_kv_page_evict(
+        _ptr(k_pool), _ptr(v_pool), int(page_bytes), _ptr(host_k), _ptr(host_v), _ptr(src_slots), n,
+        int(pool_pages), _ptr(staging),
+        int(staging.numel() * staging.element_size()) if staging is not None else 0, _stream(stream))
+    if check:
+        _check(rc, "ta_kv_page_evict")
+    return rc
+
+
+def ta_kv_append(desc: Desc, new_k, new_v, cu_new_lens, k_pool, v_pool, block_table, context_lens,
+                 total_new: int, stream=None, check: bool = True) -> int:
+    d = desc.c()
+    batch = int(context_lens.shape[0])
+    stride = int(block_table.shape[1]) if block_table.dim() == 2 else 0
+    rc = _lib().ta_kv_append(ctypes.byref(d), _ptr(new_k), _ptr(new_v), _ptr(cu_new_lens), _ptr(k_pool),
+                             _ptr(v_pool), _ptr(block_table), stride, _ptr(context_lens), batch,
+                             int(total_new), _stream(stream))
+    if check:
+        _check(rc, "ta_kv_append")
     return rc
 
 

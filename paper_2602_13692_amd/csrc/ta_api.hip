@@ -263,4 +263,40 @@ int ta_kv_page_restore(void* k_pool, void* v_pool, size_t page_bytes, const void
                           staging_bytes, static_cast<hipStream_t>(hip_stream));
 }
 
+int ta_kv_page_evict(const void* k_pool, const void* v_pool, size_t page_bytes, void* host_k,
+                     void* host_v, const int32_t* src_slots, int32_t n_pages, int32_t pool_pages,
+                     void* staging, size_t staging_bytes, void* hip_stream) {
+    if (n_pages < 0 || pool_pages < 0) return TA_ERR_INVALID_ARG;
+    if (n_pages == 0) return TA_OK;
+    if (!k_pool || !v_pool || !host_k || !host_v || !src_slots || !staging) return TA_ERR_INVALID_ARG;
+    if (page_bytes == 0 || page_bytes % 16 != 0) return TA_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(v_pool) |
+         reinterpret_cast<uintptr_t>(host_k) | reinterpret_cast<uintptr_t>(host_v)) & 15)
+        return TA_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(staging) & 255) return TA_ERR_INVALID_ARG;
+    if (staging_bytes < ta_restore_staging_min_bytes(n_pages)) return TA_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n_pages; ++i)
+        if (src_slots[i] < 0 || src_slots[i] >= pool_pages) return TA_ERR_INVALID_ARG;
+    return launch_evict(k_pool, v_pool, page_bytes, host_k, host_v, src_slots, n_pages, staging,
+                        staging_bytes, static_cast<hipStream_t>(hip_stream));
+}
+
+int ta_kv_append(const ta_attn_desc* desc, const void* new_k, const void* new_v,
+                 const int32_t* cu_new_lens, void* k_pool, void* v_pool, const int32_t* block_table,
+                 int32_t block_table_stride, const int32_t* context_lens, int32_t batch,
+                 int32_t total_new, void* hip_stream) {
+    Geometry g{};
+    const int rc = resolve_geometry(desc, &g);
+    if (rc != TA_OK) return rc;
+    if (batch < 0 || total_new < 0 || block_table_stride < 0) return TA_ERR_INVALID_ARG;
+    if (batch == 0 || total_new == 0) return TA_OK;
+    if (!new_k || !new_v || !cu_new_lens || !k_pool || !v_pool || !block_table || !context_lens)
+        return TA_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(new_k) | reinterpret_cast<uintptr_t>(new_v) |
+         reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(v_pool)) & 15)
+        return TA_ERR_INVALID_ARG;
+    return launch_append(g, new_k, new_v, cu_new_lens, k_pool, v_pool, block_table, block_table_stride,
+                         context_lens, batch, total_new, static_cast<hipStream_t>(hip_stream));
+}
+
 }  // extern "C"

@@ -130,6 +130,14 @@ int launch_restore(void* k_pool, void* v_pool, size_t page_bytes, const void* ho
                    const void* host_v, const int32_t* dst_slots, int32_t n_pages, void* staging,
                    size_t staging_bytes, hipStream_t stream);
 
+int launch_evict(const void* k_pool, const void* v_pool, size_t page_bytes, void* host_k, void* host_v,
+                 const int32_t* src_slots, int32_t n_pages, void* staging, size_t staging_bytes,
+                 hipStream_t stream);
+
+int launch_append(const Geometry& g, const void* new_k, const void* new_v, const int32_t* cu_new_lens,
+                  void* k_pool, void* v_pool, const int32_t* block_table, int32_t block_table_stride,
+                  const int32_t* context_lens, int32_t batch, int32_t total_new, hipStream_t stream);
+
 // Measurement aid: 256 workgroups x 4 waves x iters x 16 matrix instructions on the given operands.
 int launch_matrix_core_probe(const void* operands, int32_t iters, void* sink, hipStream_t stream);
 // Measurement aid: reads `bytes` (a multiple of 16) once with the decode kernel's load shape.

@@ -42,7 +42,113 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_pages_kernel(
     for (; t < n16; t += kScatterThreads) dst[t] = src[t];
 }
 
+// The inverse: one workgroup per (page, K-or-V) copies a pool page to its place in the
+// contiguous destination (pinned host memory or device staging).
+__global__ __launch_bounds__(kScatterThreads) void gather_pages_kernel(
+    const char* __restrict__ k_pool, const char* __restrict__ v_pool, char* __restrict__ dst_k,
+    char* __restrict__ dst_v, const int32_t* __restrict__ slots, int32_t first_page, int32_t n_pages,
+    int64_t page_bytes) {
+    const int i = blockIdx.x >> 1;
+    if (i >= n_pages) return;
+    const bool is_v = (blockIdx.x & 1) != 0;
+    const int64_t slot = slots[first_page + i];
+    const uint4* src = reinterpret_cast<const uint4*>((is_v ? v_pool : k_pool) + slot * page_bytes);
+    uint4* dst = reinterpret_cast<uint4*>((is_v ? dst_v : dst_k) + int64_t(i) * page_bytes);
+    const int64_t n16 = page_bytes / 16;
+    int64_t t = threadIdx.x;
+    for (; t + 3 * kScatterThreads < n16; t += 4 * kScatterThreads) {
+        const uint4 a = src[t];
+        const uint4 b = src[t + kScatterThreads];
+        const uint4 c = src[t + 2 * kScatterThreads];
+        const uint4 d = src[t + 3 * kScatterThreads];
+        dst[t] = a;
+        dst[t + kScatterThreads] = b;
+        dst[t + 2 * kScatterThreads] = c;
+        dst[t + 3 * kScatterThreads] = d;
+    }
+    for (; t < n16; t += kScatterThreads) dst[t] = src[t];
+}
+
+// KV append: one workgroup per new token copies its K row and its V row of every kv head
+// (16-byte lanes) to the place the block table gives the token.
+__global__ __launch_bounds__(256) void append_tokens_kernel(
+    const char* __restrict__ new_k, const char* __restrict__ new_v, const int32_t* __restrict__ cu_new,
+    char* __restrict__ k_pool, char* __restrict__ v_pool, const int32_t* __restrict__ block_table,
+    int32_t block_table_stride, const int32_t* __restrict__ context_lens, int32_t batch, int32_t num_kv_heads,
+    int64_t stride_page_bytes, int64_t stride_head_bytes) {
+    const int row = blockIdx.x;                       // index into new_k / new_v
+    if (row >= cu_new[batch]) return;
+    // the program that owns the row: last b with cu_new[b] <= row
+    int lo = 0, hi = batch - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (cu_new[mid] <= row) lo = mid; else hi = mid - 1;
+    }
+    const int b = lo;
+    const int n = cu_new[b + 1] - cu_new[b];
+    const int token = context_lens[b] - n + (row - cu_new[b]);
+    const int64_t page = block_table[int64_t(b) * block_table_stride + token / kPageSize];
+    const int64_t dst_row = page * stride_page_bytes + int64_t(token % kPageSize) * (kHeadDim * 2);
+    const int64_t src_row = int64_t(row) * num_kv_heads * (kHeadDim * 2);
+    // 16 lanes cover one 256-byte row
+    for (int piece = threadIdx.x; piece < num_kv_heads * 16 * 2; piece += blockDim.x) {
+        const int is_v = piece / (num_kv_heads * 16);
+        const int rest = piece - is_v * num_kv_heads * 16;
+        const int g = rest >> 4, c = rest & 15;
+        const uint4 x = *reinterpret_cast<const uint4*>((is_v ? new_v : new_k) + src_row + g * (kHeadDim * 2) + c * 16);
+        *reinterpret_cast<uint4*>((is_v ? v_pool : k_pool) + dst_row + g * stride_head_bytes + c * 16) = x;
+    }
+}
+
 }  // namespace
+
+int launch_evict(const void* k_pool, const void* v_pool, size_t page_bytes, void* host_k, void* host_v,
+                 const int32_t* src_slots, int32_t n_pages, void* staging, size_t staging_bytes,
+                 hipStream_t stream) {
+    const size_t slot_bytes = ta_restore_staging_min_bytes(n_pages);
+    int32_t* slots_dev = static_cast<int32_t*>(staging);
+    TA_HIP_TRY(hipMemcpyAsync(slots_dev, src_slots, sizeof(int32_t) * size_t(n_pages),
+                              hipMemcpyHostToDevice, stream));
+    const char* kp = static_cast<const char*>(k_pool);
+    const char* vp = static_cast<const char*>(v_pool);
+    char* hk = static_cast<char*>(host_k);
+    char* hv = static_cast<char*>(host_v);
+    const size_t room = staging_bytes - slot_bytes;
+    const size_t half = (room / 2) & ~size_t(255);
+    const int64_t per_round = static_cast<int64_t>(half / page_bytes);
+    if (per_round < 1) {
+        // zero-copy: the kernel writes the pinned host pages itself
+        hipLaunchKernelGGL(gather_pages_kernel, dim3(2u * unsigned(n_pages)), dim3(kScatterThreads), 0,
+                           stream, kp, vp, hk, hv, slots_dev, 0, n_pages, int64_t(page_bytes));
+        TA_HIP_TRY(hipGetLastError());
+        return TA_OK;
+    }
+    char* stage_k = static_cast<char*>(staging) + slot_bytes;
+    char* stage_v = stage_k + half;
+    for (int64_t first = 0; first < n_pages; first += per_round) {
+        const int64_t n = (n_pages - first) < per_round ? (n_pages - first) : per_round;
+        const size_t bytes = size_t(n) * page_bytes;
+        hipLaunchKernelGGL(gather_pages_kernel, dim3(2u * unsigned(n)), dim3(kScatterThreads), 0, stream,
+                           kp, vp, stage_k, stage_v, slots_dev, int32_t(first), int32_t(n),
+                           int64_t(page_bytes));
+        TA_HIP_TRY(hipGetLastError());
+        TA_HIP_TRY(hipMemcpyAsync(hk + size_t(first) * page_bytes, stage_k, bytes, hipMemcpyDeviceToHost, stream));
+        TA_HIP_TRY(hipMemcpyAsync(hv + size_t(first) * page_bytes, stage_v, bytes, hipMemcpyDeviceToHost, stream));
+    }
+    return TA_OK;
+}
+
+int launch_append(const Geometry& g, const void* new_k, const void* new_v, const int32_t* cu_new_lens,
+                  void* k_pool, void* v_pool, const int32_t* block_table, int32_t block_table_stride,
+                  const int32_t* context_lens, int32_t batch, int32_t total_new, hipStream_t stream) {
+    hipLaunchKernelGGL(append_tokens_kernel, dim3(unsigned(total_new)), dim3(256), 0, stream,
+                       static_cast<const char*>(new_k), static_cast<const char*>(new_v), cu_new_lens,
+                       static_cast<char*>(k_pool), static_cast<char*>(v_pool), block_table,
+                       block_table_stride, context_lens, batch, g.num_kv_heads, g.stride_page_bytes,
+                       g.stride_head_bytes);
+    TA_HIP_TRY(hipGetLastError());
+    return TA_OK;
+}
 
 int launch_restore(void* k_pool, void* v_pool, size_t page_bytes, const void* host_k,
                    const void* host_v, const int32_t* dst_slots, int32_t n_pages, void* staging,

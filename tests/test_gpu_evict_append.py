@@ -1,0 +1,139 @@
+"""GPU parity: ta_kv_page_evict and ta_kv_append through the C ABI, bit-exact against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_13692_amd import binding as ta
+from paper_2602_13692_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _page_bytes(wb):
+    return wb.num_kv_heads * 16 * 128 * 2
+
+
+@pytest.mark.parametrize("mode", ["zero_copy", "staged_small", "staged_all"])
+def test_evict_is_bit_exact_and_leaves_the_pool_alone(mode):
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 1100, batch=12, len_lo=100, len_hi=3000)
+    page_bytes = _page_bytes(wb)
+    rng = np.random.default_rng(wl.SEED_BASE + 1101)
+    n = 301
+    src = rng.integers(0, wb.pool_pages, size=n).astype(np.int32)      # repeats allowed
+    kp = wl.as_u16(wb.k_pool).copy().view(np.uint8).reshape(wb.pool_pages, page_bytes)
+    vp = wl.as_u16(wb.v_pool).copy().view(np.uint8).reshape(wb.pool_pages, page_bytes)
+    want_k = np.zeros((n, page_bytes), np.uint8)
+    want_v = np.zeros((n, page_bytes), np.uint8)
+    assert oracle.kv_page_evict(kp, vp, page_bytes, want_k, want_v, src, wb.pool_pages) == 0
+    if mode == "zero_copy":
+        nbytes = ta.ta_restore_staging_min_bytes(n)
+    elif mode == "staged_small":
+        nbytes = ta.ta_restore_staging_full_bytes(n, page_bytes) + 7 * 2 * page_bytes
+    else:
+        nbytes = ta.ta_restore_staging_min_bytes(n) + 2 * n * page_bytes + 512
+    staging = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    host_k = torch.zeros((n, page_bytes), dtype=torch.uint8).pin_memory()
+    host_v = torch.zeros((n, page_bytes), dtype=torch.uint8).pin_memory()
+    ta.ta_kv_page_evict(wb.k_pool, wb.v_pool, page_bytes, host_k, host_v, torch.from_numpy(src.copy()),
+                        wb.pool_pages, staging)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_k.numpy(), want_k) and np.array_equal(host_v.numpy(), want_v)
+    got_k = wl.as_u16(wb.k_pool).view(np.uint8).reshape(wb.pool_pages, page_bytes)
+    got_v = wl.as_u16(wb.v_pool).view(np.uint8).reshape(wb.pool_pages, page_bytes)
+    assert np.array_equal(got_k, kp) and np.array_equal(got_v, vp)
+
+
+def test_evict_then_restore_elsewhere_then_decode_is_bit_identical():
+    """Pause then Restore of some programs into other slots: the decode result does not change."""
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 1102, batch=10, len_lo=200, len_hi=2500)
+    page_bytes = _page_bytes(wb)
+    out0, lse0 = gu.gpu_decode(wb)
+    # programs 1, 4 and 7 leave and come back into the slots of a larger pool's free tail
+    moved = [1, 4, 7]
+    pages = np.concatenate([wb.block_table[b][wb.block_table[b] >= 0] for b in moved]).astype(np.int32)
+    n = int(pages.shape[0])
+    extra = n + 5
+    P2 = wb.pool_pages + extra
+    k2 = torch.zeros((P2,) + tuple(wb.k_pool.shape[1:]), dtype=wb.k_pool.dtype, device=DEV)
+    v2 = torch.zeros_like(k2)
+    k2[: wb.pool_pages] = wb.k_pool
+    v2[: wb.pool_pages] = wb.v_pool
+    staging = torch.empty(ta.ta_restore_staging_min_bytes(n) + 32 * 2 * page_bytes, dtype=torch.uint8, device=DEV)
+    host_k = torch.zeros((n, page_bytes), dtype=torch.uint8).pin_memory()
+    host_v = torch.zeros((n, page_bytes), dtype=torch.uint8).pin_memory()
+    ta.ta_kv_page_evict(k2, v2, page_bytes, host_k, host_v, torch.from_numpy(pages.copy()), P2, staging)
+    torch.cuda.synchronize()
+    # the old slots now hold garbage; the pages return to fresh slots
+    k2.view(torch.int16)[torch.from_numpy(pages.astype(np.int64)).to(DEV)] = 0x7FC0
+    v2.view(torch.int16)[torch.from_numpy(pages.astype(np.int64)).to(DEV)] = 0x7FC0
+    rng = np.random.default_rng(wl.SEED_BASE + 1103)
+    dst = (wb.pool_pages + rng.permutation(extra)[:n]).astype(np.int32)
+    ta.ta_kv_page_restore(k2, v2, page_bytes, host_k, host_v, torch.from_numpy(dst.copy()), P2, staging)
+    table = wb.block_table.copy()
+    off = 0
+    for b in moved:
+        k = int((wb.block_table[b] >= 0).sum())
+        table[b, :k] = dst[off:off + k]
+        off += k
+    wb2 = wl.PagedBatch(**{**wb.__dict__, "k_pool": k2, "v_pool": v2, "block_table": table, "pool_pages": P2})
+    out1, lse1 = gu.gpu_decode(wb2)
+    assert torch.equal(out0, out1) and torch.equal(lse0, lse1)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(32, 8), (8, 2), (4, 1)])
+def test_append_is_bit_exact_and_touches_nothing_else(Hq, Hkv):
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 1110 + Hkv, batch=9, new_lo=1, new_hi=70, prefix_lo=0,
+                           prefix_hi=300, num_q_heads=Hq, num_kv_heads=Hkv)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(wl.SEED_BASE + 1111)
+    new_k = torch.randn((wb.total_q, Hkv, 128), generator=gen, device=DEV).to(torch.bfloat16)
+    new_v = torch.randn((wb.total_q, Hkv, 128), generator=gen, device=DEV).to(torch.bfloat16)
+    geom = oracle.Geometry(Hq, Hkv)
+    kp, vp = wl.as_u16(wb.k_pool).copy(), wl.as_u16(wb.v_pool).copy()
+    oracle.kv_append(geom, wl.as_u16(new_k), wl.as_u16(new_v), wb.cu_q_lens, kp, vp, wb.block_table,
+                     wb.context_lens)
+    bt = torch.from_numpy(wb.block_table).to(DEV)
+    cl = torch.from_numpy(wb.context_lens).to(DEV)
+    cu = torch.from_numpy(wb.cu_q_lens).to(DEV)
+    ta.ta_kv_append(ta.Desc(Hq, Hkv), new_k, new_v, cu, wb.k_pool, wb.v_pool, bt, cl, wb.total_q)
+    torch.cuda.synchronize()
+    assert np.array_equal(wl.as_u16(wb.k_pool), kp) and np.array_equal(wl.as_u16(wb.v_pool), vp)
+
+
+def test_append_one_token_per_program_then_decode_matches_oracle():
+    """The decode step of a turn: the newest token's K/V is appended, then it attends to everything."""
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 1120, batch=16, len_lo=1, len_hi=1200)
+    B, Hkv = wb.batch, wb.num_kv_heads
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(wl.SEED_BASE + 1121)
+    new_k = torch.randn((B, Hkv, 128), generator=gen, device=DEV).to(torch.bfloat16)
+    new_v = torch.randn((B, Hkv, 128), generator=gen, device=DEV).to(torch.bfloat16)
+    cu = torch.arange(B + 1, dtype=torch.int32, device=DEV)
+    bt = torch.from_numpy(wb.block_table).to(DEV)
+    cl = torch.from_numpy(wb.context_lens).to(DEV)
+    ta.ta_kv_append(ta.Desc(wb.num_q_heads, Hkv), new_k, new_v, cu, wb.k_pool, wb.v_pool, bt, cl, B)
+    out, lse = gu.gpu_decode(wb)
+    ref_out, ref_lse = gu.oracle_decode(wb)       # reads the pools the append has just written
+    gu.assert_close(out, lse, ref_out, ref_lse, "append then decode")
+
+
+def test_append_and_evict_reject_bad_arguments():
+    wb = wl.tiny_decode(DEV)
+    d = ta.Desc(wb.num_q_heads, wb.num_kv_heads)
+    bt = torch.from_numpy(wb.block_table).to(DEV)
+    cl = torch.from_numpy(wb.context_lens).to(DEV)
+    cu = torch.arange(wb.batch + 1, dtype=torch.int32, device=DEV)
+    nk = torch.zeros((wb.batch, wb.num_kv_heads, 128), dtype=torch.bfloat16, device=DEV)
+    assert ta.ta_kv_append(d, None, nk, cu, wb.k_pool, wb.v_pool, bt, cl, wb.batch, check=False) == ta.TA_ERR_INVALID_ARG
+    assert ta.ta_kv_append(d, nk, nk, cu, wb.k_pool, wb.v_pool, bt, cl, 0) == ta.TA_OK
+    page_bytes = _page_bytes(wb)
+    staging = torch.empty(4096, dtype=torch.uint8, device=DEV)
+    host = torch.zeros((2, page_bytes), dtype=torch.uint8).pin_memory()
+    bad = torch.tensor([0, wb.pool_pages], dtype=torch.int32)
+    assert ta.ta_kv_page_evict(wb.k_pool, wb.v_pool, page_bytes, host, host.clone().pin_memory(), bad,
+                               wb.pool_pages, staging, check=False) == ta.TA_ERR_INVALID_ARG
+    assert not host.any()
