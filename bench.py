@@ -202,6 +202,41 @@ def matrix_core_sustained_tflops(torch, ta, dev, iters: int = 60000) -> float:
     return ta.PROBE_FLOP_PER_ITER * iters / e0.elapsed_time(e1) / 1e9
 
 
+def crossover(torch, ta, wl, dev):
+    """Restore against recompute for one program and one layer, context c = 1k .. 128k.
+
+    Recompute is ta_append_prefill with an empty prefix (the attention part of re-prefilling the
+    whole context, quadratic in c: a lower bound, the linear layers of a model come on top);
+    restore is ta_kv_page_restore of the same c tokens from pinned host memory (linear in c).
+    Small contexts are batched so the GPU is full; times are per program.
+    """
+    rows = []
+    for c in (1024, 2048, 4096, 8192, 16384, 32768, 65536, 131072):
+        batch = max(1, 16384 // c)
+        wb = wl.append_prefill(dev, seed=wl.SEED_BASE + 60, batch=batch, new_lo=c, new_hi=c,
+                               prefix_lo=0, prefix_hi=0)
+        flops = 4.0 * wb.head_dim * wb.num_q_heads * wb.unmasked_pairs()
+        ms, kernel_ms, out, lse = run_prefill(wb, 2 if c >= 65536 else 3, 1, torch, ta)
+        del out, lse
+        page_bytes = wb.num_kv_heads * wb.page_size * wb.head_dim * 2
+        n = wb.pool_pages
+        host_k = torch.empty((n, page_bytes), dtype=torch.uint8).pin_memory()
+        host_v = torch.empty((n, page_bytes), dtype=torch.uint8).pin_memory()
+        slots = torch.arange(n, dtype=torch.int32)
+        staging = torch.empty(ta.ta_restore_staging_min_bytes(n) + 2 * (64 << 20), dtype=torch.uint8, device=dev)
+        r_ms = time_steps(lambda: ta.ta_kv_page_restore(wb.k_pool, wb.v_pool, page_bytes, host_k, host_v, slots,
+                                                        wb.pool_pages, staging), 3, 1, torch)
+        rows.append({"context": c, "programs": batch,
+                     "recompute_attention_ms_per_program": round(ms / batch, 4),
+                     "recompute_tflops": round(flops / ms / 1e9, 1),
+                     "restore_ms_per_program": round(r_ms / batch, 4),
+                     "restore_gbps": round(2.0 * n * page_bytes / r_ms / 1e6, 2),
+                     "restore_over_recompute": round(r_ms / ms, 3)})
+        del wb, host_k, host_v, staging
+        torch.cuda.empty_cache()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -209,6 +244,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--only", choices=["decode", "prefill", "all"], default="all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--crossover", action="store_true",
+                    help="print the restore-versus-recompute table (one JSON line) instead of the benchmark")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -231,6 +268,10 @@ def main():
         __graft_entry__.build()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.crossover:
+        print(json.dumps({"metric": "restore_vs_recompute_one_layer", "data": "synthetic",
+                          "rows": crossover(torch, ta, wl, dev)}), flush=True)
+        return
 
     # ---------------- headline: decode on the Llama-3-8B-shaped batch ----------------
     wb = wl.llama8b_decode(dev)
