@@ -10,6 +10,7 @@ import ctypes
 import os
 from dataclasses import dataclass
 
+import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -25,7 +26,7 @@ EXPORTS = (
     "ta_version", "ta_strerror", "ta_last_hip_error", "ta_workspace_bytes", "ta_paged_decode",
     "ta_append_prefill", "ta_restore_staging_min_bytes", "ta_restore_staging_full_bytes",
     "ta_kv_page_restore", "ta_kv_page_evict", "ta_kv_append", "ta_profile_events",
-    "ta_matrix_core_probe", "ta_stream_read_probe",
+    "ta_matrix_core_probe", "ta_stream_read_probe", "ta_sched_tick",
 )
 
 
@@ -101,6 +102,8 @@ def _lib():
         lib.ta_kv_page_evict.argtypes = [vp, vp, sz, vp, vp, vp, i32, i32, vp, sz, vp]
         lib.ta_kv_append.restype = ctypes.c_int
         lib.ta_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, i32, i32, vp]
+        lib.ta_sched_tick.restype = ctypes.c_int
+        lib.ta_sched_tick.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp]
         lib.ta_profile_events.restype = None
         lib.ta_profile_events.argtypes = [vp, vp]
         lib.ta_matrix_core_probe.restype = ctypes.c_int
@@ -249,6 +252,39 @@ def ta_stream_read_probe(src, sink, stream=None, check: bool = True) -> int:
     if check:
         _check(rc, "ta_stream_read_probe")
     return rc
+
+
+# ---- program-aware scheduling tick (host code) ----
+PHASE_REASONING, PHASE_ACTING = 0, 1
+STATUS_ACTIVE, STATUS_PAUSED, STATUS_TERMINATED = 0, 1, 2
+# numpy layout of ta_program
+PROGRAM_DTYPE = np.dtype([("id", "<i4"), ("context", "<i4"), ("backend", "<i4"), ("phase", "<i4"),
+                          ("status", "<i4"), ("acting_time", "<f4")])
+
+
+class SchedConfig(ctypes.Structure):
+    _fields_ = [("capacity_tokens", ctypes.c_double), ("lambda_max", ctypes.c_double),
+                ("lambda_min", ctypes.c_double), ("decay_base", ctypes.c_double)]
+
+
+def ta_sched_tick(programs: np.ndarray, n_backends: int, capacity_tokens: float, lambda_max: float = 1.0,
+                  lambda_min: float = 1.0, decay_base: float = 2.0, check: bool = True):
+    """programs: C-contiguous array of PROGRAM_DTYPE, updated in place.
+    Returns (status, paused ids, restored ids, restored backends) as numpy int32 arrays."""
+    assert programs.dtype == PROGRAM_DTYPE and programs.flags["C_CONTIGUOUS"]
+    n = int(programs.shape[0])
+    cfg = SchedConfig(capacity_tokens, lambda_max, lambda_min, decay_base)
+    paused = np.zeros(max(n, 1), np.int32)
+    restored = np.zeros(max(n, 1), np.int32)
+    backends = np.zeros(max(n, 1), np.int32)
+    n_p, n_r = ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = _lib().ta_sched_tick(ctypes.byref(cfg), programs.ctypes.data_as(ctypes.c_void_p), n, int(n_backends),
+                              paused.ctypes.data_as(ctypes.c_void_p), ctypes.byref(n_p),
+                              restored.ctypes.data_as(ctypes.c_void_p),
+                              backends.ctypes.data_as(ctypes.c_void_p), ctypes.byref(n_r))
+    if check:
+        _check(rc, "ta_sched_tick")
+    return rc, paused[: n_p.value], restored[: n_r.value], backends[: n_r.value]
 
 
 def alloc_workspace(desc: Desc, batch: int, max_q_len: int, max_context_len: int, device="cuda"):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libta_hip.so")
-SOURCES = ["ta_api.hip", "ta_decode.hip", "ta_prefill.hip", "ta_restore.hip", "ta_probe.hip"]
+SOURCES = ["ta_api.hip", "ta_decode.hip", "ta_prefill.hip", "ta_restore.hip", "ta_probe.hip", "ta_sched.cpp"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
     # packed fp32 VALU forms stay off for every kernel in this library
