@@ -59,8 +59,17 @@ static int32_t choose_chunk_pages(const Geometry& g, int32_t batch, int32_t max_
     if (env != nullptr) {
         const int v = std::atoi(env);
         if (v == 8 || v == 16 || v == 32 || v == 64) return v;
+        if ((v == 128 || v == 256) && g.group == 8) return v;   // the tile kernel only
     }
     const int64_t pages = (int64_t(max_context_len) + kPageSize - 1) / kPageSize;
+    if (g.group == 8) {
+        // every chunk runs on the matrix-core tile kernel, whose per-item cost (filling the LDS
+        // ring, writing 32 to 128 rows of partials) wants long items: up to 4096 tokens
+        for (int32_t c : {256, 128}) {
+            const int64_t items = int64_t(batch) * g.num_kv_heads * ((pages + c - 1) / c);
+            if (items >= 2048) return c;
+        }
+    }
     for (int32_t c : {64, 32, 16}) {
         const int64_t items = int64_t(batch) * g.num_kv_heads * ((pages + c - 1) / c);
         if (items >= 4096) return c;

@@ -29,13 +29,17 @@ def test_ragged_lengths_all_group_sizes(Hq, Hkv):
     gu.assert_close(out, lse, ref, ref_lse, f"ragged Hq={Hq} Hkv={Hkv}")
 
 
-@pytest.mark.parametrize("chunk_pages", [8, 16, 32, 64])
-def test_every_chunk_length(chunk_pages, monkeypatch):
+@pytest.mark.parametrize("Hq,chunk_pages", [(32, 8), (32, 16), (32, 32), (32, 64),
+                                             (64, 8), (64, 16), (64, 32), (64, 64), (64, 128), (64, 256)])
+def test_every_chunk_length(chunk_pages, Hq, monkeypatch):
+    """Four heads per kv head run on the vector-ALU kernel (chunks of up to 64 pages), eight on
+    the matrix-core tile kernel (up to 256)."""
     monkeypatch.setenv("TA_DECODE_CHUNK_PAGES", str(chunk_pages))
-    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 200, batch=9, len_lo=100, len_hi=5000)
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 200, batch=9, len_lo=100, len_hi=9000, num_q_heads=Hq)
     out, lse = gu.gpu_decode(wb)
     ref, ref_lse = gu.oracle_decode(wb)
-    gu.assert_close(out, lse, ref, ref_lse, f"chunk_pages={chunk_pages}")
+    gu.assert_close(out, lse, ref, ref_lse, f"chunk_pages={chunk_pages} Hq={Hq}",
+                    lse_tol=gu.LSE_TOL if Hq == 32 else gu.LSE_TOL_PREFILL)
 
 
 def test_padding_poison_is_never_read():
@@ -118,7 +122,7 @@ def test_scale_override_and_strided_pool():
     gu.assert_close(out, lse, ref, ref_lse, "scale/stride")
 
 
-@pytest.mark.parametrize("chunk_pages", [8, 64])
+@pytest.mark.parametrize("chunk_pages", [8, 64, 128])
 @pytest.mark.parametrize("Hq,Hkv,group", [(64, 8, 16), (32, 8, 5), (8, 8, 40), (16, 2, 40)])
 def test_shared_prefix_groups_take_the_matrix_core_path(Hq, Hkv, group, chunk_pages, monkeypatch):
     """Forked programs: whole shared chunks are computed once per group by the tile kernel.
