@@ -290,6 +290,9 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     // Exactly four per tile, always (tiles past the end re-read the last page): the waits below
     // count on it.
     auto plan_load = [&](int t) -> int64_t {
+        // the ring runs three tiles ahead: past the item's last tile it re-reads that tile
+        // (still in L2) instead of pulling pages nobody will use through the fabric
+        t = t < n_tiles ? t : n_tiles - 1;
         if ((t >> 4) != ids_group) {      // tiles are visited in order, so this is group + 1
             ids_group = t >> 4;
             ids_cur = page_bytes(ids_next);
