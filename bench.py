@@ -34,7 +34,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # HBM bytes per decode-chunk launch from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by
 # the same counter on a 1 GiB device copy), keyed by the hash of the kernel source they were
 # taken with.  A changed kernel source gives null until the counters are taken again.
-TRAFFIC_BYTES = {"2b19ef91a58a12f8": 5089000000}
+TRAFFIC_BYTES = {"488fa22392bb3122": 5089000000}
+# The same for the append-prefill tile kernel: bytes that left the L2 per launch (FETCH_SIZE scaled).
+PREFILL_TRAFFIC_BYTES = {"0f0bc10172bf0c8e": 31191000000}
 
 
 def source_hash(name: str) -> str:
@@ -505,7 +507,8 @@ def main():
             "roofline": {"bound": "mfma", "kernel": "attention_tile_kernel<4, false>",
                          "achieved": round(flops / kernel_ms / 1e9, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                          "unit": "TFLOP/s", "frac": round(flops / kernel_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4),
-                         "kernel_ms": round(kernel_ms, 3), "traffic": None},
+                         "kernel_ms": round(kernel_ms, 3),
+                         "traffic": PREFILL_TRAFFIC_BYTES.get(source_hash("ta_prefill.hip"))},
         }
         # writing the new tokens' K/V into their pages first (what a serving step does before this call)
         new_k = torch.empty((wb.total_q, wb.num_kv_heads, wb.head_dim), dtype=torch.bfloat16, device=dev).normal_()
