@@ -419,7 +419,7 @@ def main():
                     help="also run one 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+        print("bench.py: the library runs on ONE GPU only (no sharding, no collectives); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 

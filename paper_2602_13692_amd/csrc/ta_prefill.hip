@@ -35,7 +35,6 @@ namespace ta {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
@@ -46,7 +45,8 @@ constexpr int kRowsPerBlock = 256;   // score rows per workgroup
 constexpr int kRB = 1;               // 32-row blocks per wave
 constexpr int kTileKeys = 64;        // keys per LDS tile (4 pages)
 constexpr float kRescaleThreshold = 8.0f;  // log2 units
-constexpr int kRing = 4;                   // LDS slots (tiles in flight)
+constexpr int kRing = 4;                   // LDS slots (tiles in flight); the slot arithmetic below is "& 3"
+static_assert(kRing == 4, "slot indices are computed modulo four");
 constexpr int kKAhead = 3;                 // LDS operand reads in flight ahead of their matrix instruction
 constexpr int kVAhead = 4;
 
@@ -158,7 +158,6 @@ constexpr int kTileBytes = kTileKeys * kHeadDim * 2;   // 16 KiB
 constexpr int kSlotBytes = 2 * kTileBytes;
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
 #define TA_LDS_PTR(T, ptr) ((__attribute__((address_space(3))) T*)(ptr))
 #define TA_GLOBAL_PTR(ptr) ((const __attribute__((address_space(1))) void*)(ptr))
 
@@ -176,8 +175,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     extern __shared__ __attribute__((aligned(16))) char lds[];   // [kRing][K tile | V tile]
 
     // Workgroups stride over the (item, kv head) pairs: append-prefill is launched with one
-    // workgroup per pair, the shared-prefix decode with a small resident grid (its item count is
-    // only known on the device and is usually zero).
+    // workgroup per pair, the decode side with a small resident grid (its item count is only
+    // known on the device, and is zero unless programs share pages or G = 8).
     const int n_items = SHARED ? p.counts[1] : p.tile_start[p.batch];
     for (int blk = blockIdx.x; blk < n_items * p.num_kv_heads; blk += gridDim.x) {
     const int tile_id = blk / p.num_kv_heads;
