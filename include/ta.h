@@ -37,6 +37,15 @@
  *   - Device-resident metadata is not validated: a block-table entry outside
  *     the pool or a context length beyond stride*page_size is undefined
  *     behaviour.  Everything the host can see is validated before any launch.
+ *     With the environment variable TA_DEBUG=1, ta_paged_decode and
+ *     ta_append_prefill first run a checking kernel and wait for it (the call
+ *     then synchronises the stream and cannot be captured in a graph): context
+ *     lengths outside [0, max_context_len], negative block-table entries among
+ *     the pages in use, and a cu_q_lens that does not start at 0, decreases,
+ *     does not end at total_q, or gives a program more new tokens than
+ *     max_q_len or than its context holds, make the call return
+ *     TA_ERR_INVALID_ARG before any attention kernel runs.  (The pool size is
+ *     not an argument, so entries beyond the pool cannot be checked.)
  *   - Return value: TA_OK (0) or a negative ta_status.  No exceptions, no
  *     aborts, nothing is printed.  batch == 0, total_q == 0 and n_pages == 0
  *     are valid and do nothing.

@@ -119,6 +119,65 @@ WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_l
 
 using namespace ta;
 
+namespace ta {
+namespace {
+
+// Debug validation of the device-resident metadata (TA_DEBUG=1): what a wrong entry would turn
+// into a wild address inside the attention kernels is caught here instead.  bit 0: a context
+// length outside [0, max_context_len]; bit 1: a block-table entry below zero among the pages a
+// program uses; bit 2: cu_q_lens not starting at zero, decreasing, or not ending at total_q;
+// bit 3: more new tokens than max_q_len or than the program's context holds.
+__global__ void clear_flag_kernel(int32_t* flag) { *flag = 0; }
+
+__global__ __launch_bounds__(256) void check_metadata_kernel(const int32_t* __restrict__ block_table,
+                                                             int32_t block_table_stride,
+                                                             const int32_t* __restrict__ context_lens,
+                                                             const int32_t* __restrict__ cu_q_lens, int32_t batch,
+                                                             int32_t max_context_len, int32_t total_q,
+                                                             int32_t max_q_len, int32_t* __restrict__ flag) {
+    int bad = 0;
+    for (int b = blockIdx.x * blockDim.x + threadIdx.x; b < batch; b += gridDim.x * blockDim.x) {
+        const int L = context_lens[b];
+        if (L < 0 || L > max_context_len) {
+            bad |= 1;
+            continue;
+        }
+        const int pages = (L + kPageSize - 1) / kPageSize;
+        for (int i = 0; i < pages; ++i)
+            if (block_table[int64_t(b) * block_table_stride + i] < 0) bad |= 2;
+        if (cu_q_lens != nullptr) {
+            const int n = cu_q_lens[b + 1] - cu_q_lens[b];
+            if (n < 0 || (b == 0 && cu_q_lens[0] != 0) || (b == batch - 1 && cu_q_lens[batch] != total_q)) bad |= 4;
+            if (n > max_q_len || n > L) bad |= 8;
+        }
+    }
+    if (bad != 0) atomicOr(flag, bad);
+}
+
+bool debug_checks_enabled() {
+    const char* env = std::getenv("TA_DEBUG");
+    return env != nullptr && env[0] == '1';
+}
+
+// Synchronises the stream: debug mode only.  `flag` is the first word of the caller's workspace.
+int check_metadata(const int32_t* block_table, int32_t block_table_stride, const int32_t* context_lens,
+                   const int32_t* cu_q_lens, int32_t batch, int32_t max_context_len, int32_t total_q,
+                   int32_t max_q_len, int32_t* flag, hipStream_t stream) {
+    hipLaunchKernelGGL(clear_flag_kernel, dim3(1), dim3(1), 0, stream, flag);
+    TA_HIP_TRY(hipGetLastError());
+    const unsigned blocks = static_cast<unsigned>((batch + 255) / 256);
+    hipLaunchKernelGGL(check_metadata_kernel, dim3(blocks < 1024 ? blocks : 1024), dim3(256), 0, stream, block_table,
+                       block_table_stride, context_lens, cu_q_lens, batch, max_context_len, total_q, max_q_len, flag);
+    TA_HIP_TRY(hipGetLastError());
+    int32_t host_flag = 0;
+    TA_HIP_TRY(hipMemcpyAsync(&host_flag, flag, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+    TA_HIP_TRY(hipStreamSynchronize(stream));
+    return host_flag == 0 ? TA_OK : TA_ERR_INVALID_ARG;
+}
+
+}  // namespace
+}  // namespace ta
+
 extern "C" {
 
 int32_t ta_version(void) { return 100; }
@@ -183,6 +242,11 @@ int ta_paged_decode(const ta_attn_desc* desc, const void* q, const void* k_pool,
     if (reinterpret_cast<uintptr_t>(workspace) & 255) return TA_ERR_INVALID_ARG;
     const WorkspaceLayout w = plan_workspace(g, batch, 1, max_context_len);
     if (workspace_bytes < w.total_bytes) return TA_ERR_INVALID_ARG;
+    if (ta::debug_checks_enabled()) {
+        rc = ta::check_metadata(block_table, block_table_stride, context_lens, nullptr, batch, max_context_len, 0,
+                                0, static_cast<int32_t*>(workspace), static_cast<hipStream_t>(hip_stream));
+        if (rc != TA_OK) return rc;
+    }
     DecodeArgs a{};
     a.q = static_cast<const uint16_t*>(q);
     a.k_pool = static_cast<const uint16_t*>(k_pool);
@@ -220,6 +284,12 @@ int ta_append_prefill(const ta_attn_desc* desc, const void* q, const int32_t* cu
     // the tile plan always uses the prefill layout, also when max_q_len == 1
     const WorkspaceLayout w = plan_workspace(g, batch, max_q_len < 2 ? 2 : max_q_len, max_context_len);
     if (workspace_bytes < w.total_bytes) return TA_ERR_INVALID_ARG;
+    if (ta::debug_checks_enabled()) {
+        rc = ta::check_metadata(block_table, block_table_stride, context_lens, cu_q_lens, batch, max_context_len,
+                                total_q, max_q_len, static_cast<int32_t*>(workspace),
+                                static_cast<hipStream_t>(hip_stream));
+        if (rc != TA_OK) return rc;
+    }
     PrefillArgs a{};
     a.q = static_cast<const uint16_t*>(q);
     a.cu_q_lens = cu_q_lens;

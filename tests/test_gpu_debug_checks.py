@@ -1,0 +1,66 @@
+"""GPU: with TA_DEBUG=1 bad device-resident metadata is turned into an error by a checking
+kernel before any attention kernel runs (the attention kernels never see it)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_13692_amd import binding as ta
+from paper_2602_13692_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _decode_rc(wb, table, lens):
+    desc = gu.desc_of(wb)
+    bt = torch.from_numpy(np.ascontiguousarray(table)).to(DEV)
+    cl = torch.from_numpy(np.ascontiguousarray(lens)).to(DEV)
+    out = torch.zeros_like(wb.q)
+    ws = ta.alloc_workspace(desc, wb.batch, 1, wb.max_context_len, DEV)
+    rc = ta.ta_paged_decode(desc, wb.q, wb.k_pool, wb.v_pool, bt, cl, wb.max_context_len, out, None, ws, check=False)
+    torch.cuda.synchronize()
+    return rc
+
+
+def test_decode_metadata_is_checked_in_debug_mode(monkeypatch):
+    monkeypatch.setenv("TA_DEBUG", "1")
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 1400, batch=7, len_lo=20, len_hi=900)
+    assert _decode_rc(wb, wb.block_table, wb.context_lens) == ta.TA_OK
+    lens = wb.context_lens.copy()
+    lens[3] = wb.max_context_len + 1                   # longer than the bound the launch was sized for
+    assert _decode_rc(wb, wb.block_table, lens) == ta.TA_ERR_INVALID_ARG
+    lens = wb.context_lens.copy()
+    lens[0] = -5
+    assert _decode_rc(wb, wb.block_table, lens) == ta.TA_ERR_INVALID_ARG
+    table = wb.block_table.copy()
+    table[5, 0] = -1                                   # a page the program uses is missing
+    assert _decode_rc(wb, table, wb.context_lens) == ta.TA_ERR_INVALID_ARG
+
+
+def test_prefill_metadata_is_checked_in_debug_mode(monkeypatch):
+    monkeypatch.setenv("TA_DEBUG", "1")
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 1401, batch=4, new_lo=5, new_hi=60, prefix_lo=30, prefix_hi=500)
+    desc = gu.desc_of(wb)
+    bt = torch.from_numpy(wb.block_table).to(DEV)
+    cl = torch.from_numpy(wb.context_lens).to(DEV)
+    out = torch.zeros_like(wb.q)
+    ws = ta.alloc_workspace(desc, wb.batch, wb.max_q_len, wb.max_context_len, DEV)
+
+    def rc_with(cu_np, max_q_len=wb.max_q_len):
+        cu = torch.from_numpy(np.ascontiguousarray(cu_np, dtype=np.int32)).to(DEV)
+        rc = ta.ta_append_prefill(desc, wb.q, cu, wb.k_pool, wb.v_pool, bt, cl, wb.total_q, max_q_len,
+                                  wb.max_context_len, out, None, ws, check=False)
+        torch.cuda.synchronize()
+        return rc
+
+    good = wb.cu_q_lens
+    assert rc_with(good) == ta.TA_OK
+    bad = good.copy(); bad[0] = 1
+    assert rc_with(bad) == ta.TA_ERR_INVALID_ARG       # does not start at zero
+    bad = good.copy(); bad[2] = bad[1] - 1
+    assert rc_with(bad) == ta.TA_ERR_INVALID_ARG       # decreases
+    bad = good.copy(); bad[-1] += 3
+    assert rc_with(bad) == ta.TA_ERR_INVALID_ARG       # does not end at total_q
+    assert rc_with(good, max_q_len=int(wb.q_lens.max()) - 1) == ta.TA_ERR_INVALID_ARG
