@@ -88,3 +88,15 @@ def test_runs_are_deterministic():
     a, la = gu.gpu_prefill(wb)
     b, lb = gu.gpu_prefill(wb)
     assert torch.equal(a.view(torch.int16), b.view(torch.int16)) and torch.equal(la, lb)
+
+
+def test_long_causal_sequences_without_a_prefix():
+    """Whole-context re-prefill (the recompute side of the paper's trade-off): every query tile walks a
+    different number of key tiles, most of the work lies near the diagonal."""
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 950, batch=3, new_lo=3000, new_hi=9000, prefix_lo=0,
+                           prefix_hi=0)
+    out, lse = gu.gpu_prefill(wb)
+    assert torch.isfinite(out.float()).all()
+    rng = np.random.default_rng(wl.SEED_BASE + 951)
+    gu.check_sampled_rows(wb, out, lse, rng, n_programs=3, rows_per_program=24, what="long causal",
+                          lse_tol=gu.LSE_TOL_PREFILL)
