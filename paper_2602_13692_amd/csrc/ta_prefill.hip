@@ -77,25 +77,54 @@ struct PrefillParams {
     float scale_log2;
 };
 
-// plan: query tiles of tile_tokens tokens per program, listed flat
+// plan: query tiles of tile_tokens tokens per program, listed flat.  Workgroups are dispatched
+// in list order and a tile's run time grows with its program's context, so for batches of up to
+// 1024 programs the list starts with the longest contexts (the short ones fill the tail of the
+// launch); the tiles of one program stay together, they share its K/V stream in L2.
 __global__ __launch_bounds__(1024) void plan_tiles_kernel(const int32_t* __restrict__ cu_q_lens,
+                                                          const int32_t* __restrict__ context_lens,
                                                           int32_t batch, int32_t tile_tokens,
                                                           int32_t max_per_program,
                                                           int32_t* __restrict__ tile_start,
                                                           int2* __restrict__ tiles) {
     __shared__ int32_t scan[1024];
+    __shared__ int32_t order[1024];    // program at each list position
+    __shared__ int32_t length[1024];   // its context length (sort key)
     __shared__ int32_t carry;
     const int tid = threadIdx.x;
+    auto tiles_of = [&](int b) {
+        const int nq = cu_q_lens[b + 1] - cu_q_lens[b];
+        const int n = nq > 0 ? (nq + tile_tokens - 1) / tile_tokens : 0;
+        return n > max_per_program ? max_per_program : n;
+    };
     if (tid == 0) carry = 0;
+    const bool sorted = batch <= 1024;
+    if (sorted) {
+        order[tid] = tid;
+        length[tid] = tid < batch ? context_lens[tid] : -1;
+        __syncthreads();
+        // bitonic sort, descending by length, ties by program index (a total order: deterministic)
+        for (int k = 2; k <= 1024; k <<= 1) {
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                const int other = tid ^ j;
+                if (other > tid) {
+                    const int la = length[tid], lb = length[other], oa = order[tid], ob = order[other];
+                    const bool a_first = la > lb || (la == lb && oa < ob);   // a belongs before b
+                    const bool descending = (tid & k) == 0;
+                    if (a_first != descending) {
+                        length[tid] = lb; length[other] = la;
+                        order[tid] = ob; order[other] = oa;
+                    }
+                }
+                __syncthreads();
+            }
+        }
+    }
     __syncthreads();
     for (int base = 0; base < batch; base += 1024) {
-        const int b = base + tid;
-        int n = 0;
-        if (b < batch) {
-            const int nq = cu_q_lens[b + 1] - cu_q_lens[b];
-            n = nq > 0 ? (nq + tile_tokens - 1) / tile_tokens : 0;
-            n = n > max_per_program ? max_per_program : n;
-        }
+        const int pos = base + tid;
+        const int b = sorted ? order[tid] : pos;
+        const int n = pos < batch ? tiles_of(b) : 0;
         scan[tid] = n;
         __syncthreads();
         for (int off = 1; off < 1024; off <<= 1) {
@@ -105,7 +134,7 @@ __global__ __launch_bounds__(1024) void plan_tiles_kernel(const int32_t* __restr
             __syncthreads();
         }
         const int first = carry + scan[tid] - n;
-        if (b < batch) {
+        if (pos < batch) {
             tile_start[b] = first;
             for (int c = 0; c < n; ++c) tiles[first + c] = make_int2(b, c);
         }
@@ -723,7 +752,7 @@ int launch_prefill(const Geometry& g, const PrefillArgs& a, const WorkspaceLayou
     const int64_t max_tiles = int64_t(per_prog) * a.batch;
     if (max_tiles > w.max_tiles) return TA_ERR_INVALID_ARG;
 
-    hipLaunchKernelGGL(plan_tiles_kernel, dim3(1), dim3(1024), 0, stream, a.cu_q_lens, a.batch,
+    hipLaunchKernelGGL(plan_tiles_kernel, dim3(1), dim3(1024), 0, stream, a.cu_q_lens, a.context_lens, a.batch,
                        tile_tokens, per_prog, tile_start, tiles);
     TA_HIP_TRY(hipGetLastError());
 
