@@ -161,6 +161,47 @@ def oracle_baseline(wb, wl):
     }, out, lse
 
 
+def prefill_sample_check(wb, wl, out, lse, torch, rows_per_program: int = 48, n_programs: int = 6):
+    """The oracle on a seeded sample of (new token, query head) rows of the prefill batch: parity of
+    those rows, and the oracle's own rate on them (the whole batch would take it minutes)."""
+    import numpy as np
+
+    import oracle
+
+    rng = np.random.default_rng(wl.SEED_BASE + 33)
+    programs = sorted(rng.choice(wb.batch, size=n_programs, replace=False).tolist())
+    # host copy of just the pages these programs name, block tables renumbered (input plumbing)
+    remap, tables = {}, []
+    for b in programs:
+        npg = (int(wb.context_lens[b]) + wb.page_size - 1) // wb.page_size
+        row = np.full(wb.block_table.shape[1], -1, dtype=np.int32)
+        for i in range(npg):
+            row[i] = remap.setdefault(int(wb.block_table[b, i]), len(remap))
+        tables.append(row)
+    idx = torch.from_numpy(np.array(list(remap.keys()), dtype=np.int64)).to(wb.k_pool.device)
+    k_small, v_small = wl.as_u16(wb.k_pool.index_select(0, idx)), wl.as_u16(wb.v_pool.index_select(0, idx))
+    cu = wb.cu_q_lens
+    row_b, row_t, row_h, row_vis = [], [], [], []
+    for local, b in enumerate(programs):
+        n, L = int(wb.q_lens[b]), int(wb.context_lens[b])
+        for i in [0, n - 1] + [int(x) for x in rng.integers(0, n, size=rows_per_program - 2)]:
+            row_b.append(local); row_t.append(int(cu[b]) + i)
+            row_h.append(int(rng.integers(0, wb.num_q_heads))); row_vis.append(L - n + i + 1)
+    geom = oracle.Geometry(wb.num_q_heads, wb.num_kv_heads)
+    t0 = time.perf_counter()
+    ref, ref_lse = oracle.attend_rows(geom, wl.as_u16(wb.q), k_small, v_small, np.stack(tables),
+                                      row_b, row_t, row_h, row_vis)
+    dt = time.perf_counter() - t0
+    t = torch.tensor(row_t, device=out.device)
+    h = torch.tensor(row_h, device=out.device)
+    check = spot_check(out[t, h], lse[t, h], ref, ref_lse, torch)
+    check["rows_checked"] = len(row_t)
+    flops = 4.0 * wb.head_dim * float(sum(row_vis))
+    base = {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{len(row_t)} (new token, query head) rows of {n_programs} programs, {dt:.2f} s wall"}
+    return check, base
+
+
 def spot_check(out, lse, ref_out, ref_lse, torch):
     import numpy as np
 
@@ -510,6 +551,10 @@ def main():
                          "kernel_ms": round(kernel_ms, 3),
                          "traffic": PREFILL_TRAFFIC_BYTES.get(source_hash("ta_prefill.hip"))},
         }
+        if not args.no_cpu_baseline:
+            check, base = prefill_sample_check(wb, wl, out, lse, torch)
+            extra["append_prefill"]["parity_vs_oracle"] = check
+            extra["append_prefill"]["cpu_baseline"] = base
         # writing the new tokens' K/V into their pages first (what a serving step does before this call)
         new_k = torch.empty((wb.total_q, wb.num_kv_heads, wb.head_dim), dtype=torch.bfloat16, device=dev).normal_()
         new_v = torch.empty_like(new_k).normal_()
