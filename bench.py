@@ -36,7 +36,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # taken with.  A changed kernel source gives null until the counters are taken again.
 TRAFFIC_BYTES = {"488fa22392bb3122": 5089000000}
 # The same for the append-prefill tile kernel: bytes that left the L2 per launch (FETCH_SIZE scaled).
-PREFILL_TRAFFIC_BYTES = {"890f93fd659d79c0": 16713000000}
+PREFILL_TRAFFIC_BYTES = {"2071752199da3213": 16713000000}
 
 
 def source_hash(name: str) -> str:

@@ -27,6 +27,7 @@
 // sets the pace of this kernel: the shader clock settles well below its
 // nominal value as soon as the matrix cores are busy most of the time, and
 // every byte fetched through the fabric costs clock as well.
+#include <atomic>
 #include <type_traits>
 
 #include "ta_internal.h"
@@ -717,14 +718,21 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     }
 }
 
-// 128 KiB of dynamic LDS is above the default 64 KiB limit: raised once per kernel instance.
+// 128 KiB of dynamic LDS is above the default 64 KiB limit: raised once per kernel instance and
+// device (the attribute belongs to the device's copy of the kernel).
 template <int G, bool SHARED>
 int launch_instance(unsigned blocks, const PrefillParams& pp, hipStream_t stream) {
     const size_t lds_bytes = kRing * kSlotBytes;
-    static const hipError_t lds_rc =
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_tile_kernel<G, SHARED>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));
-    TA_HIP_TRY(lds_rc);
+    constexpr int kMaxDevices = 64;
+    static std::atomic<bool> raised[kMaxDevices];
+    int device = 0;
+    TA_HIP_TRY(hipGetDevice(&device));
+    if (device < 0 || device >= kMaxDevices) return TA_ERR_UNSUPPORTED;
+    if (!raised[device].load(std::memory_order_acquire)) {
+        TA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&attention_tile_kernel<G, SHARED>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes)));
+        raised[device].store(true, std::memory_order_release);
+    }
     hipLaunchKernelGGL((attention_tile_kernel<G, SHARED>), dim3(blocks), dim3(kThreads), lds_bytes, stream, pp);
     TA_HIP_TRY(hipGetLastError());
     return TA_OK;
