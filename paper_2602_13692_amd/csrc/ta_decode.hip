@@ -101,7 +101,8 @@ __global__ __launch_bounds__(256) void common_prefix_kernel(const int32_t* __res
 // leading chunks, and lists the work flat:
 //   shared_items  (first program, members, chunk)   -> matrix-core kernel, all members at once
 //   items         (program, chunk) for every chunk that is not shared -> vector-ALU kernel
-// counts[0] = number of items, counts[1] = number of shared items.
+// counts[0] = number of items, counts[1] = number of shared items, counts[2] = 0 (the tile
+// kernel's work counter).
 // With private_on_tiles every remaining chunk is listed as a group of one program in
 // shared_items instead, and `items` stays empty.
 // ---------------------------------------------------------------------------
@@ -207,6 +208,7 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
     if (tid == 0) {
         counts[0] = private_on_tiles ? 0 : carry;
         counts[1] = private_on_tiles ? n_shared + carry : n_shared;
+        counts[2] = 0;   // work counter of the tile kernel
     }
 }
 

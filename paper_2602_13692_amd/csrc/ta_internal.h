@@ -57,7 +57,7 @@ struct WorkspaceLayout {
     size_t off_part_ml;        // float [max_chunks][Hq][2]
     size_t off_part_o;         // float [max_chunks][Hq][128]
     int32_t max_shared_items;  // upper bound on (group, shared chunk) items
-    size_t off_counts;         // int32 [4]: private items, shared items
+    size_t off_counts;         // int32 [4]: private items, shared items, tile-kernel work counter
     size_t off_lcp;            // int32 [batch] leading pages shared with the previous program
     size_t off_shared_items;   // int4  [max_shared_items]
     size_t off_tile_start;     // int32 [batch + 1]      (prefill)
@@ -114,7 +114,7 @@ struct SharedPrefixArgs {
     const int32_t* block_table;
     const int32_t* context_lens;
     const int32_t* shared_items;   // int4 per item: first program, members, chunk, unused
-    const int32_t* counts;         // counts[1] = number of shared items
+    int32_t* counts;               // counts[1] = number of shared items, counts[2] = work counter (starts at 0)
     const int32_t* chunk_start;
     float* part_ml;
     float* part_o;

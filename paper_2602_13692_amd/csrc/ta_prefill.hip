@@ -64,7 +64,7 @@ struct PrefillParams {
     float* lse;
     // shared-prefix decode only: one item = (first program of the group, members, chunk)
     const int4* shared_items;
-    const int32_t* counts;       // counts[1] = number of shared items
+    int32_t* counts;             // counts[1] = number of shared items, counts[2] = next (item, kv head) pair to take
     const int32_t* chunk_start;  // [batch + 1] first partial slot of each program
     float* part_ml;              // [slot][Hq][2]  reference maximum (log2 domain), sum
     float* part_o;               // [slot][Hq][128] unnormalised output
@@ -204,11 +204,23 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     constexpr int kTileTokens = kRowsPerBlock / G;   // programs per item when SHARED
     extern __shared__ __attribute__((aligned(16))) char lds[];   // [kRing][K tile | V tile]
 
-    // Workgroups stride over the (item, kv head) pairs: append-prefill is launched with one
-    // workgroup per pair, the decode side with a small resident grid (its item count is only
-    // known on the device, and is zero unless programs share pages or G = 8).
+    // Append-prefill is launched with one workgroup per (item, kv head) pair.  The decode side
+    // is launched with a small resident grid (its item count is only known on the device, and is
+    // zero unless programs share pages or G = 8) whose workgroups take the next pair from a
+    // counter as they finish one: items differ in length by a factor of four, and a fixed
+    // stride left the tail of the launch unbalanced.  Every item writes its own partial slots,
+    // so the result does not depend on which workgroup ran it.
     const int n_items = SHARED ? p.counts[1] : p.tile_start[p.batch];
-    for (int blk = blockIdx.x; blk < n_items * p.num_kv_heads; blk += gridDim.x) {
+    __shared__ int next_pair;
+    auto take_pair = [&]() {
+        if (threadIdx.x == 0) next_pair = atomicAdd(p.counts + 2, 1);
+        __syncthreads();
+        const int v = next_pair;
+        __syncthreads();
+        return v;
+    };
+    for (int blk = SHARED ? take_pair() : int(blockIdx.x); blk < n_items * p.num_kv_heads;
+         blk = SHARED ? take_pair() : blk + int(gridDim.x)) {
     const int tile_id = blk / p.num_kv_heads;
     const int g = blk - tile_id * p.num_kv_heads;
     const int tid = threadIdx.x;
