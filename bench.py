@@ -34,9 +34,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # HBM bytes per decode-chunk launch from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by
 # the same counter on a 1 GiB device copy), keyed by the hash of the kernel source they were
 # taken with.  A changed kernel source gives null until the counters are taken again.
-TRAFFIC_BYTES = {"488fa22392bb3122": 5089000000}
+TRAFFIC_BYTES = {"712500f065c91c3f": 5089000000}
 # The same for the append-prefill tile kernel: bytes that left the L2 per launch (FETCH_SIZE scaled).
-PREFILL_TRAFFIC_BYTES = {"2071752199da3213": 16713000000}
+PREFILL_TRAFFIC_BYTES = {"3683c927a45907fe": 16744000000}
 
 
 def source_hash(name: str) -> str:
