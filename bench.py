@@ -229,6 +229,33 @@ def stream_read_gbps(torch, ta, buf, reps: int = 5) -> float:
     return best
 
 
+def tiny_decode_latency(torch, ta, wl, dev, reps: int = 200):
+    """Config 1 (4 programs, 960 cached tokens) is cache resident and launch bound: microseconds per call."""
+    wb = wl.tiny_decode(dev)
+    desc = ta.Desc(wb.num_q_heads, wb.num_kv_heads)
+    bt = torch.from_numpy(wb.block_table).to(dev)
+    cl = torch.from_numpy(wb.context_lens).to(dev)
+    out = torch.empty_like(wb.q)
+    ws = ta.alloc_workspace(desc, wb.batch, 1, wb.max_context_len, dev)
+
+    def call(stream=None):
+        ta.ta_paged_decode(desc, wb.q, wb.k_pool, wb.v_pool, bt, cl, wb.max_context_len, out, None, ws, stream)
+
+    eager_ms = time_steps(call, reps, 10, torch)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        call(side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            call(side)
+    torch.cuda.synchronize()
+    graph_ms = time_steps(graph.replay, reps, 10, torch)
+    return {"workload": "config 1: 4 programs, 8 q / 2 kv heads, contexts 64-512 (five kernels per call)",
+            "us_per_call_eager": round(eager_ms * 1e3, 1), "us_per_call_hip_graph": round(graph_ms * 1e3, 1)}
+
+
 def matrix_core_sustained_tflops(torch, ta, dev, iters: int = 60000) -> float:
     """Rate of ta_matrix_core_probe on N(0,1) bf16 operands over roughly 20 ms."""
     gen = torch.Generator(device=dev)
@@ -577,6 +604,9 @@ def main():
         torch.cuda.empty_cache()
 
     if args.only == "all":
+        # ---------------- the tiny configuration: latency of one call, eager and from a HIP graph ----------------
+        extra["tiny_decode"] = tiny_decode_latency(torch, ta, wl, dev)
+
         # ---------------- forked programs with shared prefixes ----------------
         wb = wl.forked_decode(dev)
         logical = int(wb.context_lens.astype("int64").sum()) * wb.kv_bytes_per_token
