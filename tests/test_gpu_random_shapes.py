@@ -1,0 +1,66 @@
+"""GPU parity on many small seeded batches of random shape: head counts, group sizes, context and
+query lengths, forked groups, padding poison.  Every case is valid input; each is compared with the
+oracle element by element."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_13692_amd import workloads as wl
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+HEADS = [(1, 1), (2, 1), (4, 1), (8, 1), (4, 2), (8, 2), (16, 2), (8, 8), (32, 8), (64, 8), (12, 3), (24, 3)]
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_decode_random_shapes(seed):
+    rng = np.random.default_rng(wl.SEED_BASE + 5000 + seed)
+    Hq, Hkv = HEADS[seed % len(HEADS)]
+    batch = int(rng.integers(1, 40))
+    hi = int(rng.choice([40, 300, 1500, 6000]))
+    firsts = [int(x) for x in rng.choice([0, 1, 15, 16, 17, 63, 64, 65, 1023, 1024, 1025], size=min(batch, 3))]
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 5100 + seed, batch=batch, len_lo=1, len_hi=hi,
+                           num_q_heads=Hq, num_kv_heads=Hkv, first_lens=firsts)
+    if seed % 2:
+        wl.poison_padding(wb)
+    out, lse = gu.gpu_decode(wb)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, f"decode seed={seed} Hq={Hq} Hkv={Hkv} B={batch}",
+                    lse_tol=gu.LSE_TOL_PREFILL if Hq // Hkv == 8 else gu.LSE_TOL)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_forked_decode_random_shapes(seed):
+    rng = np.random.default_rng(wl.SEED_BASE + 5200 + seed)
+    Hq, Hkv = HEADS[(seed * 5 + 3) % len(HEADS)]
+    group = int(rng.integers(2, 20))
+    n_groups = int(rng.integers(1, 4))
+    prefix = 16 * int(rng.integers(1, 300))
+    wb = wl.forked_decode(DEV, seed=wl.SEED_BASE + 5300 + seed, batch=group * n_groups, group=group,
+                          prefix_len=prefix, suffix_lo=1, suffix_hi=int(rng.choice([5, 200, 900])),
+                          num_q_heads=Hq, num_kv_heads=Hkv)
+    out, lse = gu.gpu_decode(wb)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, f"forked seed={seed} Hq={Hq} Hkv={Hkv} group={group} prefix={prefix}",
+                    lse_tol=gu.LSE_TOL_PREFILL)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_prefill_random_shapes(seed):
+    rng = np.random.default_rng(wl.SEED_BASE + 5400 + seed)
+    Hq, Hkv = HEADS[(seed * 7 + 1) % len(HEADS)]
+    if Hq // Hkv not in (1, 2, 4, 8):
+        Hq, Hkv = 8, 2
+    batch = int(rng.integers(1, 9))
+    new_hi = int(rng.choice([3, 70, 300, 700]))
+    prefix_hi = int(rng.choice([0, 50, 700, 2500]))
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 5500 + seed, batch=batch, new_lo=1, new_hi=new_hi,
+                           prefix_lo=0, prefix_hi=prefix_hi, num_q_heads=Hq, num_kv_heads=Hkv)
+    if seed % 2:
+        wl.poison_padding(wb)
+    out, lse = gu.gpu_prefill(wb)
+    ref, ref_lse = gu.oracle_prefill(wb)
+    gu.assert_close(out, lse, ref, ref_lse, f"prefill seed={seed} Hq={Hq} Hkv={Hkv} B={batch}",
+                    lse_tol=gu.LSE_TOL_PREFILL)
