@@ -144,6 +144,17 @@ def run_prefill(wb, steps, warmup, torch, ta):
     return ms, timer.mean_ms(), out, lse
 
 
+def cpu_model() -> str:
+    """The host CPU's model string (first "model name" line of /proc/cpuinfo)."""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def oracle_baseline(wb, wl):
     """The fp64 oracle as it stands, on this host's cores, on the whole decode batch."""
     import oracle
@@ -155,7 +166,8 @@ def oracle_baseline(wb, wl):
     dt = time.perf_counter() - t0
     kv_bytes = int(wb.context_lens.astype("int64").sum()) * wb.kv_bytes_per_token
     return {
-        "value": kv_bytes / dt / 1e9, "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "value": kv_bytes / dt / 1e9, "unit": "GB/s", "cores": oracle.num_threads(), "cpu": cpu_model(),
+        "kind": "oracle",
         "sample": f"all {wb.batch} programs x {wb.num_q_heads} query heads of the same batch, "
                   f"{dt:.2f} s wall",
     }, out, lse
@@ -197,7 +209,8 @@ def prefill_sample_check(wb, wl, out, lse, torch, rows_per_program: int = 48, n_
     check = spot_check(out[t, h], lse[t, h], ref, ref_lse, torch)
     check["rows_checked"] = len(row_t)
     flops = 4.0 * wb.head_dim * float(sum(row_vis))
-    base = {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+    base = {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "cpu": cpu_model(), "kind": "oracle",
             "sample": f"{len(row_t)} (new token, query head) rows of {n_programs} programs, {dt:.2f} s wall"}
     return check, base
 

@@ -37,15 +37,16 @@
  *   - Device-resident metadata is not validated: a block-table entry outside
  *     the pool or a context length beyond stride*page_size is undefined
  *     behaviour.  Everything the host can see is validated before any launch.
- *     With the environment variable TA_DEBUG=1, ta_paged_decode and
- *     ta_append_prefill first run a checking kernel and wait for it (the call
- *     then synchronises the stream and cannot be captured in a graph): context
- *     lengths outside [0, max_context_len], negative block-table entries among
- *     the pages in use, and a cu_q_lens that does not start at 0, decreases,
- *     does not end at total_q, or gives a program more new tokens than
- *     max_q_len or than its context holds, make the call return
- *     TA_ERR_INVALID_ARG before any attention kernel runs.  (The pool size is
- *     not an argument, so entries beyond the pool cannot be checked.)
+ *     In debug mode (ta_set_debug_checks(1), or the environment variable
+ *     TA_DEBUG=1 when the library makes its first call) ta_paged_decode,
+ *     ta_append_prefill and ta_kv_append first run a checking kernel and wait
+ *     for it (the call then synchronises the stream and cannot be captured in a
+ *     graph): context lengths outside [0, max_context_len], block-table entries
+ *     among the pages in use that are negative or, when the descriptor states
+ *     pool_pages, not below it, and prefix sums (cu_q_lens, cu_new_lens) that do
+ *     not start at 0, decrease, do not end at the stated total, or give a
+ *     program more new tokens than max_q_len or than its context holds, make
+ *     the call return TA_ERR_INVALID_ARG before any other kernel runs.
  *   - Return value: TA_OK (0) or a negative ta_status.  No exceptions, no
  *     aborts, nothing is printed.  batch == 0, total_q == 0 and n_pages == 0
  *     are valid and do nothing.
@@ -78,10 +79,15 @@ typedef struct ta_attn_desc {
     int32_t head_dim;          /* 128 */
     int32_t page_size;         /* 16 tokens */
     float scale;               /* multiplies q.k; 0.0f selects 1/sqrt(head_dim) */
-    int32_t reserved;          /* must be 0 */
+    int32_t pool_pages;        /* pages in each pool, for the debug checks; 0 = not stated */
     int64_t pool_stride_page;  /* elements between pages;       0 selects Hkv*page_size*head_dim */
     int64_t pool_stride_head;  /* elements between kv heads;    0 selects page_size*head_dim */
     int64_t pool_stride_token; /* elements between token rows;  0 selects head_dim (only value supported) */
+    int32_t decode_chunk_pages; /* split-K chunk of ta_paged_decode in pages: 0 lets the library choose
+                                   (by batch and context length), else 8, 16, 32 or 64, and with eight
+                                   query heads per kv head also 128 or 256.  The same value must be
+                                   given to ta_workspace_bytes. */
+    int32_t reserved;          /* must be 0 */
 } ta_attn_desc;
 
 /* Library version, major*10000 + minor*100 + patch. */
@@ -92,6 +98,15 @@ TA_API const char *ta_strerror(int status);
 
 /* The hipError_t (as int) of the last failed HIP call on this thread, 0 if none. */
 TA_API int ta_last_hip_error(void);
+
+/*
+ * Debug mode for the whole process: on != 0 makes the calls listed above check
+ * their device-resident metadata first (and synchronise), 0 switches that off.
+ * Until the first call of this function the mode is what the environment
+ * variable TA_DEBUG said ("1" = on) when the library first looked.
+ * Returns the previous mode (0 or 1).
+ */
+TA_API int ta_set_debug_checks(int on);
 
 /*
  * Bytes of DEVICE workspace that ta_paged_decode (max_q_len <= 1) or
@@ -156,10 +171,10 @@ TA_API int ta_append_prefill(const ta_attn_desc *desc, const void *q, const int3
                       float *lse, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * Bytes of DEVICE staging that ta_kv_page_restore needs at least (the slot
- * list), and the size from which it switches from reading the pinned host
- * pages directly inside the scatter kernel to staging them through large
- * host-to-device copies.
+ * Bytes of DEVICE staging that ta_kv_page_restore / ta_kv_page_evict need at
+ * least (none: 0), and the size from which they switch from touching the
+ * pinned host pages directly inside the scatter / gather kernel to staging
+ * them through large copies over the host link.
  */
 TA_API size_t ta_restore_staging_min_bytes(int32_t n_pages);
 TA_API size_t ta_restore_staging_full_bytes(int32_t n_pages, size_t page_bytes);
@@ -175,8 +190,11 @@ TA_API size_t ta_restore_staging_full_bytes(int32_t n_pages, size_t page_bytes);
  *   page_bytes    bytes of one page of K over all kv heads (Hkv*16*128*2), multiple of 16
  *   host_k,host_v HOST, pinned (hipHostMalloc), [n_pages][page_bytes] contiguous;
  *                 must stay valid until the stream reaches the end of this call
- *   dst_slots     HOST int32 [n_pages], distinct, each in [0, pool_pages); copied before return
- *   staging       DEVICE scratch of staging_bytes >= ta_restore_staging_min_bytes(n_pages).
+ *   dst_slots     HOST int32 [n_pages] (pageable is fine), distinct, each in [0, pool_pages).
+ *                 The list is read completely before the call returns (it travels inside
+ *                 the kernel arguments, 960 slots per launch): the caller may free or reuse
+ *                 it at once, and the call waits for nothing on the stream.
+ *   staging       DEVICE scratch, 256-byte aligned, or NULL with staging_bytes == 0.
  *                 With at least ta_restore_staging_full_bytes() the pages travel as
  *                 large host-to-device copies into staging and a kernel scatters them;
  *                 with less, the scatter kernel reads the pinned host pages directly.
@@ -195,9 +213,9 @@ TA_API int ta_kv_page_restore(void *k_pool, void *v_pool, size_t page_bytes, con
  *   k_pool,v_pool DEVICE, pool_pages pages of page_bytes each, contiguous, only read
  *   host_k,host_v HOST, PINNED (hipHostMalloc), written: [n_pages][page_bytes], 16-byte aligned
  *   src_slots     HOST int32 [n_pages], each in [0, pool_pages); a slot may repeat.
- *                 Read before the call returns.
- *   staging       DEVICE, 256-byte aligned, at least ta_restore_staging_min_bytes(n_pages);
- *                 from ta_restore_staging_full_bytes on the pages are gathered into it and
+ *                 Read completely before the call returns, as for ta_kv_page_restore.
+ *   staging       DEVICE, 256-byte aligned, or NULL with staging_bytes == 0; from
+ *                 ta_restore_staging_full_bytes on the pages are gathered into it and
  *                 leave through large device-to-host copies, below that the gather kernel
  *                 writes the pinned host pages itself
  * The copies are enqueued on hip_stream; host_k / host_v hold the pages once
@@ -243,43 +261,6 @@ TA_API int ta_kv_append(const ta_attn_desc *desc, const void *new_k, const void 
  * NULLs switch the recording off.
  */
 TA_API void ta_profile_events(void *start_event, void *stop_event);
-
-/*
- * Measurement aid (no paper passage: it measures, it computes nothing useful).
- * Runs iters x 16 independent v_mfma_f32_32x32x16_bf16 per wave, one wave per
- * SIMD on 256 workgroups, on the caller's operand values, so that the caller
- * can time the rate the matrix cores sustain on data of that kind: the shader
- * clock under such a load is set by power management and depends on how many
- * operand bits toggle.  Floating-point operations enqueued:
- *   TA_PROBE_FLOP_PER_ITER * iters.
- *
- *   operands  DEVICE, 8192 bytes, 16-byte aligned: eight operand registers
- *             (A0, B0, A1, B1, ...) x 64 lanes x 8 bf16, any finite values
- *   iters     >= 1
- *   sink      DEVICE, TA_PROBE_SINK_BYTES, written (keeps the work alive)
- *   hip_stream  hipStream_t as void*, may be NULL
- *
- * Returns TA_ERR_INVALID_ARG for NULL or misaligned pointers or iters < 1.
- * Nothing is allocated; the work is enqueued, not awaited.
- */
-#define TA_PROBE_FLOP_PER_ITER (256.0 * 4.0 * 16.0 * 2.0 * 32.0 * 32.0 * 16.0)
-#define TA_PROBE_SINK_BYTES (256 * 256 * 4)
-TA_API int ta_matrix_core_probe(const void *operands, int32_t iters, void *sink, void *hip_stream);
-
-/*
- * Measurement aid (no paper passage).  Reads the buffer once with the load shape
- * of the decode kernel (16 bytes per lane, non-temporal, four loads in flight)
- * and no arithmetic, so that the caller can time the read bandwidth the memory
- * system delivers to such a kernel.
- *
- *   src     DEVICE, `bytes` bytes, 16-byte aligned, only read
- *   bytes   a positive multiple of 16
- *   sink    DEVICE, TA_STREAM_SINK_BYTES, written
- *
- * Returns TA_ERR_INVALID_ARG for NULL or misaligned pointers or a bad size.
- */
-#define TA_STREAM_SINK_BYTES (8192 * 256 * 4)
-TA_API int ta_stream_read_probe(const void *src, size_t bytes, void *sink, void *hip_stream);
 
 #ifdef __cplusplus
 }

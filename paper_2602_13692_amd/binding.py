@@ -16,6 +16,8 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 # TA_LIB_PATH selects another build of the same library (kernel experiments); default: in-tree
 LIB_PATH = os.environ.get("TA_LIB_PATH", os.path.join(_HERE, "libta_hip.so"))
+# the benchmark's measurement aids live in a library of their own
+PROBE_LIB_PATH = os.path.join(_HERE, "libta_probe.so")
 
 TA_OK = 0
 TA_ERR_INVALID_ARG = -1
@@ -26,8 +28,9 @@ EXPORTS = (
     "ta_version", "ta_strerror", "ta_last_hip_error", "ta_workspace_bytes", "ta_paged_decode",
     "ta_append_prefill", "ta_restore_staging_min_bytes", "ta_restore_staging_full_bytes",
     "ta_kv_page_restore", "ta_kv_page_evict", "ta_kv_append", "ta_profile_events",
-    "ta_matrix_core_probe", "ta_stream_read_probe", "ta_sched_tick",
+    "ta_set_debug_checks", "ta_sched_tick",
 )
+PROBE_EXPORTS = ("ta_matrix_core_probe", "ta_stream_read_probe")
 
 
 class TaError(RuntimeError):
@@ -45,10 +48,12 @@ class AttnDesc(ctypes.Structure):
         ("head_dim", ctypes.c_int32),
         ("page_size", ctypes.c_int32),
         ("scale", ctypes.c_float),
-        ("reserved", ctypes.c_int32),
+        ("pool_pages", ctypes.c_int32),
         ("pool_stride_page", ctypes.c_int64),
         ("pool_stride_head", ctypes.c_int64),
         ("pool_stride_token", ctypes.c_int64),
+        ("decode_chunk_pages", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
     ]
 
 
@@ -62,11 +67,13 @@ class Desc:
     pool_stride_page: int = 0
     pool_stride_head: int = 0
     pool_stride_token: int = 0
+    pool_pages: int = 0
+    decode_chunk_pages: int = 0
 
     def c(self) -> AttnDesc:
         return AttnDesc(self.num_q_heads, self.num_kv_heads, self.head_dim, self.page_size,
-                        self.scale, 0, self.pool_stride_page, self.pool_stride_head,
-                        self.pool_stride_token)
+                        self.scale, self.pool_pages, self.pool_stride_page, self.pool_stride_head,
+                        self.pool_stride_token, self.decode_chunk_pages, 0)
 
 
 _LIB = None
@@ -106,12 +113,28 @@ def _lib():
         lib.ta_sched_tick.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp]
         lib.ta_profile_events.restype = None
         lib.ta_profile_events.argtypes = [vp, vp]
+        lib.ta_set_debug_checks.restype = ctypes.c_int
+        lib.ta_set_debug_checks.argtypes = [ctypes.c_int]
+        _LIB = lib
+    return _LIB
+
+
+_PROBE_LIB = None
+
+
+def _probe_lib():
+    global _PROBE_LIB
+    if _PROBE_LIB is None:
+        if not os.path.exists(PROBE_LIB_PATH):
+            raise ImportError(f"{PROBE_LIB_PATH} is missing: build it with `python -m paper_2602_13692_amd.build`")
+        lib = ctypes.CDLL(PROBE_LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
         lib.ta_matrix_core_probe.restype = ctypes.c_int
         lib.ta_matrix_core_probe.argtypes = [vp, i32, vp, vp]
         lib.ta_stream_read_probe.restype = ctypes.c_int
         lib.ta_stream_read_probe.argtypes = [vp, sz, vp, vp]
-        _LIB = lib
-    return _LIB
+        _PROBE_LIB = lib
+    return _PROBE_LIB
 
 
 def _ptr(t):
@@ -138,6 +161,11 @@ def ta_strerror(status: int) -> str:
 
 def ta_last_hip_error() -> int:
     return int(_lib().ta_last_hip_error())
+
+
+def ta_set_debug_checks(on: bool) -> bool:
+    """Switches the metadata checks of the whole process on or off; returns the previous mode."""
+    return bool(_lib().ta_set_debug_checks(1 if on else 0))
 
 
 def ta_workspace_bytes(desc: Desc, batch: int, max_q_len: int, max_context_len: int) -> int:
@@ -236,7 +264,7 @@ PROBE_SINK_BYTES = 256 * 256 * 4
 
 def ta_matrix_core_probe(operands, iters: int, sink, stream=None, check: bool = True) -> int:
     """operands: 8192-byte device tensor of bf16 operand values; sink: PROBE_SINK_BYTES device bytes."""
-    rc = _lib().ta_matrix_core_probe(_ptr(operands), int(iters), _ptr(sink), _stream(stream))
+    rc = _probe_lib().ta_matrix_core_probe(_ptr(operands), int(iters), _ptr(sink), _stream(stream))
     if check:
         _check(rc, "ta_matrix_core_probe")
     return rc
@@ -247,7 +275,7 @@ STREAM_SINK_BYTES = 8192 * 256 * 4
 
 def ta_stream_read_probe(src, sink, stream=None, check: bool = True) -> int:
     """src: device tensor whose bytes (a multiple of 16) are read once; sink: STREAM_SINK_BYTES."""
-    rc = _lib().ta_stream_read_probe(_ptr(src), int(src.numel() * src.element_size()), _ptr(sink),
+    rc = _probe_lib().ta_stream_read_probe(_ptr(src), int(src.numel() * src.element_size()), _ptr(sink),
                                      _stream(stream))
     if check:
         _check(rc, "ta_stream_read_probe")

@@ -1,7 +1,10 @@
 // Host side of the C ABI: argument validation, workspace layout, error reporting.
 // Every exported function validates what the host can see, then enqueues kernels
 // on the caller's stream and returns without synchronising.
+#include <algorithm>
+#include <atomic>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -26,7 +29,7 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
     if (d == nullptr) return TA_ERR_INVALID_ARG;
     if (d->num_q_heads <= 0 || d->num_kv_heads <= 0) return TA_ERR_INVALID_ARG;
     if (d->num_q_heads % d->num_kv_heads != 0) return TA_ERR_INVALID_ARG;
-    if (d->reserved != 0) return TA_ERR_INVALID_ARG;
+    if (d->reserved != 0 || d->pool_pages < 0) return TA_ERR_INVALID_ARG;
     if (!(d->scale >= 0.0f) || std::isinf(d->scale)) return TA_ERR_INVALID_ARG;  // also rejects NaN
     if (d->pool_stride_page < 0 || d->pool_stride_head < 0 || d->pool_stride_token < 0)
         return TA_ERR_INVALID_ARG;
@@ -40,9 +43,14 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
     // a (page, head) tile is read with 16-byte accesses
     if (sh % 8 != 0 || sp % 8 != 0) return TA_ERR_UNSUPPORTED;
     if (sh < int64_t(kPageSize) * kHeadDim) return TA_ERR_INVALID_ARG;
+    const int32_t cp = d->decode_chunk_pages;
+    if (cp != 0 && cp != 8 && cp != 16 && cp != 32 && cp != 64 && !((cp == 128 || cp == 256) && group == 8))
+        return TA_ERR_INVALID_ARG;
     g->num_q_heads = d->num_q_heads;
     g->num_kv_heads = d->num_kv_heads;
     g->group = group;
+    g->pool_pages = d->pool_pages;
+    g->decode_chunk_pages = cp;
     g->scale = d->scale > 0.0f ? d->scale : 1.0f / std::sqrt(static_cast<float>(kHeadDim));
     g->scale_log2 = g->scale * kLog2e;
     g->stride_page_bytes = sp * 2;
@@ -55,12 +63,7 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
 // below one percent of the KV bytes, and batches too small to fill the chip
 // with that get shorter chunks.
 static int32_t choose_chunk_pages(const Geometry& g, int32_t batch, int32_t max_context_len) {
-    const char* env = std::getenv("TA_DECODE_CHUNK_PAGES");
-    if (env != nullptr) {
-        const int v = std::atoi(env);
-        if (v == 8 || v == 16 || v == 32 || v == 64) return v;
-        if ((v == 128 || v == 256) && g.group == 8) return v;   // the tile kernel only
-    }
+    if (g.decode_chunk_pages != 0) return g.decode_chunk_pages;   // the caller's choice, validated with the descriptor
     const int64_t pages = (int64_t(max_context_len) + kPageSize - 1) / kPageSize;
     if (g.group == 8) {
         // every chunk runs on the matrix-core tile kernel, whose per-item cost (filling the LDS
@@ -122,11 +125,17 @@ using namespace ta;
 namespace ta {
 namespace {
 
-// Debug validation of the device-resident metadata (TA_DEBUG=1): what a wrong entry would turn
-// into a wild address inside the attention kernels is caught here instead.  bit 0: a context
-// length outside [0, max_context_len]; bit 1: a block-table entry below zero among the pages a
-// program uses; bit 2: cu_q_lens not starting at zero, decreasing, or not ending at total_q;
-// bit 3: more new tokens than max_q_len or than the program's context holds.
+// Debug validation of the device-resident metadata: what a wrong entry would turn into a wild
+// address inside the other kernels is caught here instead.  bit 0: a context length outside
+// [0, max_context_len]; bit 1: a block-table entry below zero, or not below pool_pages when the
+// descriptor states it, among the pages a program uses; bit 2: prefix sums not starting at zero,
+// decreasing, or not ending at the stated total; bit 3: more new tokens than max_q_len or than
+// the program's context holds.
+//
+// The flag word is a device variable of the library (one copy per GPU, found once per device
+// through its symbol), so that the check needs no caller memory.
+__device__ int32_t g_debug_flag;
+
 __global__ void clear_flag_kernel(int32_t* flag) { *flag = 0; }
 
 __global__ __launch_bounds__(256) void check_metadata_kernel(const int32_t* __restrict__ block_table,
@@ -134,7 +143,8 @@ __global__ __launch_bounds__(256) void check_metadata_kernel(const int32_t* __re
                                                              const int32_t* __restrict__ context_lens,
                                                              const int32_t* __restrict__ cu_q_lens, int32_t batch,
                                                              int32_t max_context_len, int32_t total_q,
-                                                             int32_t max_q_len, int32_t* __restrict__ flag) {
+                                                             int32_t max_q_len, int32_t pool_pages,
+                                                             int32_t* __restrict__ flag) {
     int bad = 0;
     for (int b = blockIdx.x * blockDim.x + threadIdx.x; b < batch; b += gridDim.x * blockDim.x) {
         const int L = context_lens[b];
@@ -143,8 +153,10 @@ __global__ __launch_bounds__(256) void check_metadata_kernel(const int32_t* __re
             continue;
         }
         const int pages = (L + kPageSize - 1) / kPageSize;
-        for (int i = 0; i < pages; ++i)
-            if (block_table[int64_t(b) * block_table_stride + i] < 0) bad |= 2;
+        for (int i = 0; i < pages; ++i) {
+            const int32_t e = block_table[int64_t(b) * block_table_stride + i];
+            if (e < 0 || (pool_pages > 0 && e >= pool_pages)) bad |= 2;
+        }
         if (cu_q_lens != nullptr) {
             const int n = cu_q_lens[b + 1] - cu_q_lens[b];
             if (n < 0 || (b == 0 && cu_q_lens[0] != 0) || (b == batch - 1 && cu_q_lens[batch] != total_q)) bad |= 4;
@@ -154,20 +166,49 @@ __global__ __launch_bounds__(256) void check_metadata_kernel(const int32_t* __re
     if (bad != 0) atomicOr(flag, bad);
 }
 
+// -1: not decided yet (the environment is consulted once), 0 / 1: off / on
+std::atomic<int> g_debug_mode{-1};
+
 bool debug_checks_enabled() {
-    const char* env = std::getenv("TA_DEBUG");
-    return env != nullptr && env[0] == '1';
+    int mode = g_debug_mode.load(std::memory_order_acquire);
+    if (mode < 0) {
+        const char* env = std::getenv("TA_DEBUG");
+        int expected = -1;
+        g_debug_mode.compare_exchange_strong(expected, (env != nullptr && env[0] == '1') ? 1 : 0);
+        mode = g_debug_mode.load(std::memory_order_acquire);
+    }
+    return mode == 1;
 }
 
-// Synchronises the stream: debug mode only.  `flag` is the first word of the caller's workspace.
+// Address of this device's copy of the flag word (looked up once per device).
+int debug_flag_address(int32_t** out) {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int32_t*> cached[kMaxDevices];
+    int device = 0;
+    TA_HIP_TRY(hipGetDevice(&device));
+    if (device < 0 || device >= kMaxDevices) return TA_ERR_UNSUPPORTED;
+    int32_t* p = cached[device].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        TA_HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(g_debug_flag)));
+        cached[device].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return TA_OK;
+}
+
+// Synchronises the stream: debug mode only.
 int check_metadata(const int32_t* block_table, int32_t block_table_stride, const int32_t* context_lens,
                    const int32_t* cu_q_lens, int32_t batch, int32_t max_context_len, int32_t total_q,
-                   int32_t max_q_len, int32_t* flag, hipStream_t stream) {
+                   int32_t max_q_len, int32_t pool_pages, hipStream_t stream) {
+    int32_t* flag = nullptr;
+    const int rc = debug_flag_address(&flag);
+    if (rc != TA_OK) return rc;
     hipLaunchKernelGGL(clear_flag_kernel, dim3(1), dim3(1), 0, stream, flag);
     TA_HIP_TRY(hipGetLastError());
     const unsigned blocks = static_cast<unsigned>((batch + 255) / 256);
     hipLaunchKernelGGL(check_metadata_kernel, dim3(blocks < 1024 ? blocks : 1024), dim3(256), 0, stream, block_table,
-                       block_table_stride, context_lens, cu_q_lens, batch, max_context_len, total_q, max_q_len, flag);
+                       block_table_stride, context_lens, cu_q_lens, batch, max_context_len, total_q, max_q_len,
+                       pool_pages, flag);
     TA_HIP_TRY(hipGetLastError());
     int32_t host_flag = 0;
     TA_HIP_TRY(hipMemcpyAsync(&host_flag, flag, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
@@ -194,18 +235,10 @@ const char* ta_strerror(int status) {
 
 int ta_last_hip_error(void) { return g_last_hip_error; }
 
-int ta_matrix_core_probe(const void* operands, int32_t iters, void* sink, void* hip_stream) {
-    if (operands == nullptr || sink == nullptr || iters < 1) return TA_ERR_INVALID_ARG;
-    if ((reinterpret_cast<uintptr_t>(operands) & 15) != 0 || (reinterpret_cast<uintptr_t>(sink) & 3) != 0)
-        return TA_ERR_INVALID_ARG;
-    return ta::launch_matrix_core_probe(operands, iters, sink, static_cast<hipStream_t>(hip_stream));
-}
-
-int ta_stream_read_probe(const void* src, size_t bytes, void* sink, void* hip_stream) {
-    if (src == nullptr || sink == nullptr || bytes == 0 || (bytes & 15) != 0) return TA_ERR_INVALID_ARG;
-    if ((reinterpret_cast<uintptr_t>(src) & 15) != 0 || (reinterpret_cast<uintptr_t>(sink) & 3) != 0)
-        return TA_ERR_INVALID_ARG;
-    return ta::launch_stream_read_probe(src, bytes, sink, static_cast<hipStream_t>(hip_stream));
+int ta_set_debug_checks(int on) {
+    const bool before = ta::debug_checks_enabled();   // settles the environment's say first
+    ta::g_debug_mode.store(on != 0 ? 1 : 0, std::memory_order_release);
+    return before ? 1 : 0;
 }
 
 void ta_profile_events(void* start_event, void* stop_event) {
@@ -244,7 +277,7 @@ int ta_paged_decode(const ta_attn_desc* desc, const void* q, const void* k_pool,
     if (workspace_bytes < w.total_bytes) return TA_ERR_INVALID_ARG;
     if (ta::debug_checks_enabled()) {
         rc = ta::check_metadata(block_table, block_table_stride, context_lens, nullptr, batch, max_context_len, 0,
-                                0, static_cast<int32_t*>(workspace), static_cast<hipStream_t>(hip_stream));
+                                0, g.pool_pages, static_cast<hipStream_t>(hip_stream));
         if (rc != TA_OK) return rc;
     }
     DecodeArgs a{};
@@ -286,8 +319,7 @@ int ta_append_prefill(const ta_attn_desc* desc, const void* q, const int32_t* cu
     if (workspace_bytes < w.total_bytes) return TA_ERR_INVALID_ARG;
     if (ta::debug_checks_enabled()) {
         rc = ta::check_metadata(block_table, block_table_stride, context_lens, cu_q_lens, batch, max_context_len,
-                                total_q, max_q_len, static_cast<int32_t*>(workspace),
-                                static_cast<hipStream_t>(hip_stream));
+                                total_q, max_q_len, g.pool_pages, static_cast<hipStream_t>(hip_stream));
         if (rc != TA_OK) return rc;
     }
     PrefillArgs a{};
@@ -308,14 +340,14 @@ int ta_append_prefill(const ta_attn_desc* desc, const void* q, const int32_t* cu
 }
 
 size_t ta_restore_staging_min_bytes(int32_t n_pages) {
-    if (n_pages <= 0) return 0;
-    return align256(sizeof(int32_t) * size_t(n_pages));
+    (void)n_pages;   // the slot list travels in the kernel arguments: no staging is required
+    return 0;
 }
 
 size_t ta_restore_staging_full_bytes(int32_t n_pages, size_t page_bytes) {
     if (n_pages <= 0) return 0;
-    // slot list + room for at least one K page and one V page per round
-    return ta_restore_staging_min_bytes(n_pages) + 2 * align256(page_bytes);
+    // room for at least one K page and one V page per round
+    return 2 * align256(page_bytes);
 }
 
 int ta_kv_page_restore(void* k_pool, void* v_pool, size_t page_bytes, const void* host_k,
@@ -323,14 +355,14 @@ int ta_kv_page_restore(void* k_pool, void* v_pool, size_t page_bytes, const void
                        int32_t pool_pages, void* staging, size_t staging_bytes, void* hip_stream) {
     if (n_pages < 0 || pool_pages < 0) return TA_ERR_INVALID_ARG;
     if (n_pages == 0) return TA_OK;
-    if (!k_pool || !v_pool || !host_k || !host_v || !dst_slots || !staging) return TA_ERR_INVALID_ARG;
+    if (!k_pool || !v_pool || !host_k || !host_v || !dst_slots) return TA_ERR_INVALID_ARG;
+    if (staging == nullptr && staging_bytes != 0) return TA_ERR_INVALID_ARG;
     if (page_bytes == 0 || page_bytes % 16 != 0) return TA_ERR_INVALID_ARG;
     if (n_pages > pool_pages) return TA_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(v_pool) |
          reinterpret_cast<uintptr_t>(host_k) | reinterpret_cast<uintptr_t>(host_v)) & 15)
         return TA_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(staging) & 255) return TA_ERR_INVALID_ARG;
-    if (staging_bytes < ta_restore_staging_min_bytes(n_pages)) return TA_ERR_INVALID_ARG;
     // slots: in range and distinct (the list is host memory, so this is checked here)
     std::vector<uint8_t> seen(static_cast<size_t>(pool_pages), 0);
     for (int32_t i = 0; i < n_pages; ++i) {
@@ -347,13 +379,13 @@ int ta_kv_page_evict(const void* k_pool, const void* v_pool, size_t page_bytes, 
                      void* staging, size_t staging_bytes, void* hip_stream) {
     if (n_pages < 0 || pool_pages < 0) return TA_ERR_INVALID_ARG;
     if (n_pages == 0) return TA_OK;
-    if (!k_pool || !v_pool || !host_k || !host_v || !src_slots || !staging) return TA_ERR_INVALID_ARG;
+    if (!k_pool || !v_pool || !host_k || !host_v || !src_slots) return TA_ERR_INVALID_ARG;
+    if (staging == nullptr && staging_bytes != 0) return TA_ERR_INVALID_ARG;
     if (page_bytes == 0 || page_bytes % 16 != 0) return TA_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(v_pool) |
          reinterpret_cast<uintptr_t>(host_k) | reinterpret_cast<uintptr_t>(host_v)) & 15)
         return TA_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(staging) & 255) return TA_ERR_INVALID_ARG;
-    if (staging_bytes < ta_restore_staging_min_bytes(n_pages)) return TA_ERR_INVALID_ARG;
     for (int32_t i = 0; i < n_pages; ++i)
         if (src_slots[i] < 0 || src_slots[i] >= pool_pages) return TA_ERR_INVALID_ARG;
     return launch_evict(k_pool, v_pool, page_bytes, host_k, host_v, src_slots, n_pages, staging,
@@ -374,6 +406,14 @@ int ta_kv_append(const ta_attn_desc* desc, const void* new_k, const void* new_v,
     if ((reinterpret_cast<uintptr_t>(new_k) | reinterpret_cast<uintptr_t>(new_v) |
          reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(v_pool)) & 15)
         return TA_ERR_INVALID_ARG;
+    if (ta::debug_checks_enabled()) {
+        // a stale table entry or more new tokens than the context holds would overwrite other pages
+        const int drc = ta::check_metadata(block_table, block_table_stride, context_lens, cu_new_lens, batch,
+                                           static_cast<int32_t>(std::min<int64_t>(
+                                               int64_t(block_table_stride) * kPageSize, 0x7fffffff)),
+                                           total_new, total_new, g.pool_pages, static_cast<hipStream_t>(hip_stream));
+        if (drc != TA_OK) return drc;
+    }
     return launch_append(g, new_k, new_v, cu_new_lens, k_pool, v_pool, block_table, block_table_stride,
                          context_lens, batch, total_new, static_cast<hipStream_t>(hip_stream));
 }

@@ -38,6 +38,8 @@ struct Geometry {
     int32_t num_q_heads;
     int32_t num_kv_heads;
     int32_t group;            // Hq / Hkv
+    int32_t pool_pages;       // pages per pool as stated by the caller (0 = not stated; debug checks only)
+    int32_t decode_chunk_pages;  // the caller's split-K chunk length, 0 = chosen by the library
     float scale;              // multiplies q.k
     float scale_log2;         // scale * log2(e)
     int64_t stride_page_bytes;
@@ -137,10 +139,5 @@ int launch_evict(const void* k_pool, const void* v_pool, size_t page_bytes, void
 int launch_append(const Geometry& g, const void* new_k, const void* new_v, const int32_t* cu_new_lens,
                   void* k_pool, void* v_pool, const int32_t* block_table, int32_t block_table_stride,
                   const int32_t* context_lens, int32_t batch, int32_t total_new, hipStream_t stream);
-
-// Measurement aid: 256 workgroups x 4 waves x iters x 16 matrix instructions on the given operands.
-int launch_matrix_core_probe(const void* operands, int32_t iters, void* sink, hipStream_t stream);
-// Measurement aid: reads `bytes` (a multiple of 16) once with the decode kernel's load shape.
-int launch_stream_read_probe(const void* src, size_t bytes, void* sink, hipStream_t stream);
 
 }  // namespace ta

@@ -346,8 +346,15 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
         const char* src = ((i >> 1) ? v_head : k_head) + page_off + ((i >> 1) ? dma_v[i & 1] : dma_k[i & 1]);
         // Written as assembly on purpose: for the builtin form the compiler assumes that every
         // later LDS read may touch the bytes in flight and waits for the load right away.  The
-        // waits are placed by hand instead (finish_tile), one per tile.
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory");
+        // waits are placed by hand instead (finish_tile), one per tile.  The instruction takes
+        // its LDS address from m0, which the compiler manages on its own and does not expect a
+        // statement to change: the statement puts back the value it found.
+        uint32_t saved_m0;
+        asm volatile(
+            "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+            : "=&s"(saved_m0)
+            : "s"(dst), "v"(src)
+            : "memory");
     };
     auto load_tile = [&](int t, int slot) __attribute__((always_inline)) {
         const int64_t page_off = plan_load(t);

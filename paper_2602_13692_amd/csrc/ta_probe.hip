@@ -6,9 +6,11 @@
 // distributed ones (what attention feeds the matrix cores) well below it.  This kernel issues
 // nothing but independent v_mfma_f32_32x32x16_bf16 from registers, one wave per SIMD on every
 // CU, so its rate is the ceiling any matrix-core-bound kernel can reach on the same data.
-#include "ta_internal.h"
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace ta {
+#include "ta_probe.h"
+
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -69,18 +71,23 @@ __global__ __launch_bounds__(256) void stream_read_probe_kernel(const u32x4* __r
 
 }  // namespace
 
-int launch_stream_read_probe(const void* src, size_t bytes, void* sink, hipStream_t stream) {
-    hipLaunchKernelGGL(stream_read_probe_kernel, dim3(kStreamBlocks), dim3(256), 0, stream,
+extern "C" {
+
+int ta_stream_read_probe(const void* src, size_t bytes, void* sink, void* hip_stream) {
+    if (src == nullptr || sink == nullptr || bytes == 0 || (bytes & 15) != 0) return -1;
+    if ((reinterpret_cast<uintptr_t>(src) & 15) != 0 || (reinterpret_cast<uintptr_t>(sink) & 3) != 0) return -1;
+    hipLaunchKernelGGL(stream_read_probe_kernel, dim3(kStreamBlocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
                        static_cast<const u32x4*>(src), bytes / 16, static_cast<uint32_t*>(sink));
-    TA_HIP_TRY(hipGetLastError());
-    return TA_OK;
+    return hipGetLastError() == hipSuccess ? 0 : -3;
 }
 
-int launch_matrix_core_probe(const void* operands, int32_t iters, void* sink, hipStream_t stream) {
-    hipLaunchKernelGGL(matrix_core_probe_kernel, dim3(kProbeBlocks), dim3(kProbeThreads), 0, stream,
-                       static_cast<const u32x4*>(operands), iters, static_cast<float*>(sink));
-    TA_HIP_TRY(hipGetLastError());
-    return TA_OK;
+int ta_matrix_core_probe(const void* operands, int32_t iters, void* sink, void* hip_stream) {
+    if (operands == nullptr || sink == nullptr || iters < 1) return -1;
+    if ((reinterpret_cast<uintptr_t>(operands) & 15) != 0 || (reinterpret_cast<uintptr_t>(sink) & 3) != 0) return -1;
+    hipLaunchKernelGGL(matrix_core_probe_kernel, dim3(kProbeBlocks), dim3(kProbeThreads), 0,
+                       static_cast<hipStream_t>(hip_stream), static_cast<const u32x4*>(operands), iters,
+                       static_cast<float*>(sink));
+    return hipGetLastError() == hipSuccess ? 0 : -3;
 }
 
-}  // namespace ta
+}  // extern "C"

@@ -7,23 +7,36 @@
 //   staged     large host-to-device copies into staging, then a scatter kernel
 //              (device to device, HBM-bound, a small fraction of the link time);
 //   zero-copy  the scatter kernel reads the pinned host pages over the link.
-// The slot list always goes through the head of the staging buffer.
+// The caller's slot list is host memory: it travels to the device inside the kernel
+// arguments, a batch of slots per launch, so the call reads it completely before it
+// returns, needs no copy from pageable memory and waits for nothing on the stream.
 #include "ta_internal.h"
 
 namespace ta {
 namespace {
 
 constexpr int kScatterThreads = 256;
+constexpr int kSlotsPerLaunch = 960;   // 3840 bytes of the 4 KiB a kernel's arguments may take
+
+struct SlotBatch {
+    int32_t slot[kSlotsPerLaunch];
+};
+
+// Fills a batch from the caller's host list; returns the number of slots taken.
+int32_t fill_batch(SlotBatch& batch, const int32_t* slots, int64_t first, int64_t end) {
+    const int64_t n = (end - first) < kSlotsPerLaunch ? (end - first) : kSlotsPerLaunch;
+    for (int64_t i = 0; i < n; ++i) batch.slot[i] = slots[first + i];
+    return static_cast<int32_t>(n);
+}
 
 // One workgroup per (page, K-or-V): copies page_bytes with 16-byte lanes.
 __global__ __launch_bounds__(kScatterThreads) void scatter_pages_kernel(
     char* __restrict__ k_pool, char* __restrict__ v_pool, const char* __restrict__ src_k,
-    const char* __restrict__ src_v, const int32_t* __restrict__ slots, int32_t first_page,
-    int32_t n_pages, int64_t page_bytes) {
+    const char* __restrict__ src_v, const SlotBatch slots, int32_t n_pages, int64_t page_bytes) {
     const int i = blockIdx.x >> 1;
     if (i >= n_pages) return;
     const bool is_v = (blockIdx.x & 1) != 0;
-    const int64_t slot = slots[first_page + i];
+    const int64_t slot = slots.slot[i];
     const uint4* src = reinterpret_cast<const uint4*>((is_v ? src_v : src_k) + int64_t(i) * page_bytes);
     uint4* dst = reinterpret_cast<uint4*>((is_v ? v_pool : k_pool) + slot * page_bytes);
     const int64_t n16 = page_bytes / 16;
@@ -46,12 +59,11 @@ __global__ __launch_bounds__(kScatterThreads) void scatter_pages_kernel(
 // contiguous destination (pinned host memory or device staging).
 __global__ __launch_bounds__(kScatterThreads) void gather_pages_kernel(
     const char* __restrict__ k_pool, const char* __restrict__ v_pool, char* __restrict__ dst_k,
-    char* __restrict__ dst_v, const int32_t* __restrict__ slots, int32_t first_page, int32_t n_pages,
-    int64_t page_bytes) {
+    char* __restrict__ dst_v, const SlotBatch slots, int32_t n_pages, int64_t page_bytes) {
     const int i = blockIdx.x >> 1;
     if (i >= n_pages) return;
     const bool is_v = (blockIdx.x & 1) != 0;
-    const int64_t slot = slots[first_page + i];
+    const int64_t slot = slots.slot[i];
     const uint4* src = reinterpret_cast<const uint4*>((is_v ? v_pool : k_pool) + slot * page_bytes);
     uint4* dst = reinterpret_cast<uint4*>((is_v ? dst_v : dst_k) + int64_t(i) * page_bytes);
     const int64_t n16 = page_bytes / 16;
@@ -105,33 +117,38 @@ __global__ __launch_bounds__(256) void append_tokens_kernel(
 int launch_evict(const void* k_pool, const void* v_pool, size_t page_bytes, void* host_k, void* host_v,
                  const int32_t* src_slots, int32_t n_pages, void* staging, size_t staging_bytes,
                  hipStream_t stream) {
-    const size_t slot_bytes = ta_restore_staging_min_bytes(n_pages);
-    int32_t* slots_dev = static_cast<int32_t*>(staging);
-    TA_HIP_TRY(hipMemcpyAsync(slots_dev, src_slots, sizeof(int32_t) * size_t(n_pages),
-                              hipMemcpyHostToDevice, stream));
     const char* kp = static_cast<const char*>(k_pool);
     const char* vp = static_cast<const char*>(v_pool);
     char* hk = static_cast<char*>(host_k);
     char* hv = static_cast<char*>(host_v);
-    const size_t room = staging_bytes - slot_bytes;
-    const size_t half = (room / 2) & ~size_t(255);
+    const size_t half = staging != nullptr ? (staging_bytes / 2) & ~size_t(255) : 0;
     const int64_t per_round = static_cast<int64_t>(half / page_bytes);
+    SlotBatch batch;
     if (per_round < 1) {
         // zero-copy: the kernel writes the pinned host pages itself
-        hipLaunchKernelGGL(gather_pages_kernel, dim3(2u * unsigned(n_pages)), dim3(kScatterThreads), 0,
-                           stream, kp, vp, hk, hv, slots_dev, 0, n_pages, int64_t(page_bytes));
-        TA_HIP_TRY(hipGetLastError());
+        for (int64_t first = 0; first < n_pages;) {
+            const int32_t n = fill_batch(batch, src_slots, first, n_pages);
+            hipLaunchKernelGGL(gather_pages_kernel, dim3(2u * unsigned(n)), dim3(kScatterThreads), 0, stream, kp, vp,
+                               hk + size_t(first) * page_bytes, hv + size_t(first) * page_bytes, batch, n,
+                               int64_t(page_bytes));
+            TA_HIP_TRY(hipGetLastError());
+            first += n;
+        }
         return TA_OK;
     }
-    char* stage_k = static_cast<char*>(staging) + slot_bytes;
+    char* stage_k = static_cast<char*>(staging);
     char* stage_v = stage_k + half;
     for (int64_t first = 0; first < n_pages; first += per_round) {
-        const int64_t n = (n_pages - first) < per_round ? (n_pages - first) : per_round;
-        const size_t bytes = size_t(n) * page_bytes;
-        hipLaunchKernelGGL(gather_pages_kernel, dim3(2u * unsigned(n)), dim3(kScatterThreads), 0, stream,
-                           kp, vp, stage_k, stage_v, slots_dev, int32_t(first), int32_t(n),
-                           int64_t(page_bytes));
-        TA_HIP_TRY(hipGetLastError());
+        const int64_t end = (n_pages - first) < per_round ? n_pages : first + per_round;
+        for (int64_t at = first; at < end;) {
+            const int32_t n = fill_batch(batch, src_slots, at, end);
+            hipLaunchKernelGGL(gather_pages_kernel, dim3(2u * unsigned(n)), dim3(kScatterThreads), 0, stream, kp, vp,
+                               stage_k + size_t(at - first) * page_bytes, stage_v + size_t(at - first) * page_bytes,
+                               batch, n, int64_t(page_bytes));
+            TA_HIP_TRY(hipGetLastError());
+            at += n;
+        }
+        const size_t bytes = size_t(end - first) * page_bytes;
         TA_HIP_TRY(hipMemcpyAsync(hk + size_t(first) * page_bytes, stage_k, bytes, hipMemcpyDeviceToHost, stream));
         TA_HIP_TRY(hipMemcpyAsync(hv + size_t(first) * page_bytes, stage_v, bytes, hipMemcpyDeviceToHost, stream));
     }
@@ -153,36 +170,40 @@ int launch_append(const Geometry& g, const void* new_k, const void* new_v, const
 int launch_restore(void* k_pool, void* v_pool, size_t page_bytes, const void* host_k,
                    const void* host_v, const int32_t* dst_slots, int32_t n_pages, void* staging,
                    size_t staging_bytes, hipStream_t stream) {
-    const size_t slot_bytes = ta_restore_staging_min_bytes(n_pages);
-    int32_t* slots_dev = static_cast<int32_t*>(staging);
-    TA_HIP_TRY(hipMemcpyAsync(slots_dev, dst_slots, sizeof(int32_t) * size_t(n_pages),
-                              hipMemcpyHostToDevice, stream));
     char* kp = static_cast<char*>(k_pool);
     char* vp = static_cast<char*>(v_pool);
     const char* hk = static_cast<const char*>(host_k);
     const char* hv = static_cast<const char*>(host_v);
-
-    const size_t room = staging_bytes - slot_bytes;
-    const size_t half = (room / 2) & ~size_t(255);
+    const size_t half = staging != nullptr ? (staging_bytes / 2) & ~size_t(255) : 0;
     const int64_t per_round = static_cast<int64_t>(half / page_bytes);
+    SlotBatch batch;
     if (per_round < 1) {
         // zero-copy: pinned host memory is mapped into the device address space
-        hipLaunchKernelGGL(scatter_pages_kernel, dim3(2u * unsigned(n_pages)), dim3(kScatterThreads), 0,
-                           stream, kp, vp, hk, hv, slots_dev, 0, n_pages, int64_t(page_bytes));
-        TA_HIP_TRY(hipGetLastError());
+        for (int64_t first = 0; first < n_pages;) {
+            const int32_t n = fill_batch(batch, dst_slots, first, n_pages);
+            hipLaunchKernelGGL(scatter_pages_kernel, dim3(2u * unsigned(n)), dim3(kScatterThreads), 0, stream, kp, vp,
+                               hk + size_t(first) * page_bytes, hv + size_t(first) * page_bytes, batch, n,
+                               int64_t(page_bytes));
+            TA_HIP_TRY(hipGetLastError());
+            first += n;
+        }
         return TA_OK;
     }
-    char* stage_k = static_cast<char*>(staging) + slot_bytes;
+    char* stage_k = static_cast<char*>(staging);
     char* stage_v = stage_k + half;
     for (int64_t first = 0; first < n_pages; first += per_round) {
-        const int64_t n = (n_pages - first) < per_round ? (n_pages - first) : per_round;
-        const size_t bytes = size_t(n) * page_bytes;
+        const int64_t end = (n_pages - first) < per_round ? n_pages : first + per_round;
+        const size_t bytes = size_t(end - first) * page_bytes;
         TA_HIP_TRY(hipMemcpyAsync(stage_k, hk + size_t(first) * page_bytes, bytes, hipMemcpyHostToDevice, stream));
         TA_HIP_TRY(hipMemcpyAsync(stage_v, hv + size_t(first) * page_bytes, bytes, hipMemcpyHostToDevice, stream));
-        hipLaunchKernelGGL(scatter_pages_kernel, dim3(2u * unsigned(n)), dim3(kScatterThreads), 0, stream,
-                           kp, vp, stage_k, stage_v, slots_dev, int32_t(first), int32_t(n),
-                           int64_t(page_bytes));
-        TA_HIP_TRY(hipGetLastError());
+        for (int64_t at = first; at < end;) {
+            const int32_t n = fill_batch(batch, dst_slots, at, end);
+            hipLaunchKernelGGL(scatter_pages_kernel, dim3(2u * unsigned(n)), dim3(kScatterThreads), 0, stream, kp, vp,
+                               stage_k + size_t(at - first) * page_bytes, stage_v + size_t(at - first) * page_bytes,
+                               batch, n, int64_t(page_bytes));
+            TA_HIP_TRY(hipGetLastError());
+            at += n;
+        }
     }
     return TA_OK;
 }

@@ -19,17 +19,17 @@ def widen_bf16(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def desc_of(wb) -> ta.Desc:
-    return ta.Desc(wb.num_q_heads, wb.num_kv_heads)
+def desc_of(wb, **kw) -> ta.Desc:
+    return ta.Desc(wb.num_q_heads, wb.num_kv_heads, **kw)
 
 
 def geom_of(wb) -> oracle.Geometry:
     return oracle.Geometry(wb.num_q_heads, wb.num_kv_heads)
 
 
-def gpu_decode(wb, stream=None):
+def gpu_decode(wb, stream=None, chunk_pages=0):
     dev = wb.q.device
-    desc = desc_of(wb)
+    desc = desc_of(wb, decode_chunk_pages=chunk_pages)
     bt = torch.from_numpy(wb.block_table).to(dev)
     cl = torch.from_numpy(wb.context_lens).to(dev)
     out = torch.full_like(wb.q, float("nan"))

@@ -11,24 +11,32 @@ from paper_2602_13692_amd import binding as ta
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_symbols():
+def _declared_symbols(macro):
     names = set()
     for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
         text = open(os.path.join(ROOT, "include", header)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-        names.update(re.findall(r"TA_API[^;(]*?\b(ta_\w+)\s*\(", text))
+        names.update(re.findall(macro + r"\b[^;(]*?\b(ta_\w+)\s*\(", text))
     return sorted(names)
 
 
-def test_library_exports_every_declared_symbol():
-    if not os.path.exists(ta.LIB_PATH):
-        pytest.fail(f"{ta.LIB_PATH} missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
-    lib = ctypes.CDLL(ta.LIB_PATH)
-    declared = _declared_symbols()
-    assert declared, "no TA_API declarations found"
+@pytest.mark.parametrize("path,macro,exports", [(ta.LIB_PATH, "TA_API", ta.EXPORTS),
+                                                (ta.PROBE_LIB_PATH, "TA_PROBE_API", ta.PROBE_EXPORTS)])
+def test_library_exports_every_declared_symbol(path, macro, exports):
+    if not os.path.exists(path):
+        pytest.fail(f"{path} missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = ctypes.CDLL(path)
+    declared = _declared_symbols(macro)
+    assert declared, f"no {macro} declarations found"
     for name in declared:
         assert hasattr(lib, name), f"{name} is declared under include/ but not exported"
-    assert set(declared) == set(ta.EXPORTS)
+    assert set(declared) == set(exports)
+
+
+def test_the_hot_path_library_holds_no_measurement_aid():
+    lib = ctypes.CDLL(ta.LIB_PATH)
+    for name in ta.PROBE_EXPORTS:
+        assert not hasattr(lib, name)
 
 
 def test_version_and_error_strings():
@@ -69,11 +77,22 @@ def test_host_side_rejections_need_no_device():
     assert lib.ta_kv_page_restore(null, null, 32768, null, null, null, 0, 10, null, 0, null) == ta.TA_OK
     assert lib.ta_kv_page_restore(null, null, 32768, null, null, null, 3, 10, null, 0, null) == ta.TA_ERR_INVALID_ARG
     assert lib.ta_kv_page_restore(null, null, 32768, null, null, null, -1, 10, null, 0, null) == ta.TA_ERR_INVALID_ARG
-    assert lib.ta_restore_staging_min_bytes(1000) == 4096
-    assert lib.ta_restore_staging_full_bytes(1000, 32768) == 4096 + 2 * 32768
-    # the matrix-core probe rejects missing or misaligned buffers and a non-positive count
-    assert lib.ta_matrix_core_probe(null, 10, null, null) == ta.TA_ERR_INVALID_ARG
-    assert lib.ta_matrix_core_probe(ctypes.c_void_p(4096), 0, ctypes.c_void_p(8192), null) == ta.TA_ERR_INVALID_ARG
-    assert lib.ta_matrix_core_probe(ctypes.c_void_p(4100), 10, ctypes.c_void_p(8192), null) == ta.TA_ERR_INVALID_ARG
-    assert lib.ta_stream_read_probe(null, 4096, null, null) == ta.TA_ERR_INVALID_ARG
-    assert lib.ta_stream_read_probe(ctypes.c_void_p(4096), 24, ctypes.c_void_p(8192), null) == ta.TA_ERR_INVALID_ARG
+    assert lib.ta_restore_staging_min_bytes(1000) == 0      # the slot list travels in the kernel arguments
+    assert lib.ta_restore_staging_full_bytes(1000, 32768) == 2 * 32768
+    # staging may be absent only together with a size of zero
+    one = ctypes.c_void_p(4096)
+    slot = (ctypes.c_int32 * 1)(0)
+    assert lib.ta_kv_page_restore(one, one, 32768, one, one, slot, 1, 10, null, 512, null) == ta.TA_ERR_INVALID_ARG
+    assert lib.ta_kv_page_evict(one, one, 32768, one, one, slot, 1, 10, null, 512, null) == ta.TA_ERR_INVALID_ARG
+    # a chunk length the split-K plan does not offer, or one above 64 pages without eight heads per kv head
+    assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=24), 4, 1, 100) == 0
+    assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=128), 4, 1, 100) == 0
+    assert ta.ta_workspace_bytes(ta.Desc(64, 8, decode_chunk_pages=128), 4, 1, 100) > 0
+    assert ta.ta_workspace_bytes(ta.Desc(32, 8, pool_pages=-1), 4, 1, 100) == 0
+    # the measurement aids (their own library) reject missing or misaligned buffers and bad sizes
+    probe = ta._probe_lib()
+    assert probe.ta_matrix_core_probe(null, 10, null, null) == -1
+    assert probe.ta_matrix_core_probe(ctypes.c_void_p(4096), 0, ctypes.c_void_p(8192), null) == -1
+    assert probe.ta_matrix_core_probe(ctypes.c_void_p(4100), 10, ctypes.c_void_p(8192), null) == -1
+    assert probe.ta_stream_read_probe(null, 4096, null, null) == -1
+    assert probe.ta_stream_read_probe(ctypes.c_void_p(4096), 24, ctypes.c_void_p(8192), null) == -1

@@ -17,12 +17,12 @@ def _page_bytes(wb):
     return wb.num_kv_heads * 16 * 128 * 2
 
 
+@pytest.mark.parametrize("n", [301, 2203])      # the second needs several launches per slot list
 @pytest.mark.parametrize("mode", ["zero_copy", "staged_small", "staged_all"])
-def test_evict_is_bit_exact_and_leaves_the_pool_alone(mode):
+def test_evict_is_bit_exact_and_leaves_the_pool_alone(mode, n):
     wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 1100, batch=12, len_lo=100, len_hi=3000)
     page_bytes = _page_bytes(wb)
     rng = np.random.default_rng(wl.SEED_BASE + 1101)
-    n = 301
     src = rng.integers(0, wb.pool_pages, size=n).astype(np.int32)      # repeats allowed
     kp = wl.as_u16(wb.k_pool).copy().view(np.uint8).reshape(wb.pool_pages, page_bytes)
     vp = wl.as_u16(wb.v_pool).copy().view(np.uint8).reshape(wb.pool_pages, page_bytes)

@@ -29,9 +29,10 @@ def _expected_pools(wb):
     return kp, vp, page_bytes
 
 
-@pytest.mark.parametrize("mode", ["zero_copy", "staged_small", "staged_all"])
-def test_restore_is_bit_exact_and_touches_nothing_else(mode):
-    wb = _restore_case()
+@pytest.mark.parametrize("batch,median", [(24, 900), (48, 3000)])   # about 400 and 2700 pages: the second needs
+@pytest.mark.parametrize("mode", ["zero_copy", "staged_small", "staged_all"])   # several launches per slot list
+def test_restore_is_bit_exact_and_touches_nothing_else(mode, batch, median):
+    wb = _restore_case(batch=batch, median=median, cap=6 * median)
     kp, vp, page_bytes = _expected_pools(wb)
     rs = wb.restore
     n = int(rs.dst_slots.shape[0])
@@ -44,6 +45,7 @@ def test_restore_is_bit_exact_and_touches_nothing_else(mode):
     staging = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
     slots = torch.from_numpy(rs.dst_slots.copy())
     ta.ta_kv_page_restore(wb.k_pool, wb.v_pool, page_bytes, rs.host_k, rs.host_v, slots, wb.pool_pages, staging)
+    slots.fill_(-7)            # the list was read before the call returned: the caller may reuse it at once
     torch.cuda.synchronize()
     got_k = wl.as_u16(wb.k_pool).view(np.uint8).reshape(wb.pool_pages, page_bytes)
     got_v = wl.as_u16(wb.v_pool).view(np.uint8).reshape(wb.pool_pages, page_bytes)
@@ -77,10 +79,10 @@ def test_restore_rejects_bad_arguments_on_the_host():
         rc = ta.ta_kv_page_restore(wb.k_pool, wb.v_pool, page_bytes, rs.host_k, rs.host_v, bad,
                                    wb.pool_pages, staging, check=False)
         assert rc == ta.TA_ERR_INVALID_ARG
-    tiny = torch.empty(16, dtype=torch.uint8, device=DEV)
+    misaligned = torch.empty(4096, dtype=torch.uint8, device=DEV)[16:]      # staging must be 256-byte aligned
     good = torch.from_numpy(rs.dst_slots.copy())
     assert ta.ta_kv_page_restore(wb.k_pool, wb.v_pool, page_bytes, rs.host_k, rs.host_v, good, wb.pool_pages,
-                                 tiny, check=False) == ta.TA_ERR_INVALID_ARG
+                                 misaligned, check=False) == ta.TA_ERR_INVALID_ARG
     assert ta.ta_kv_page_restore(wb.k_pool, wb.v_pool, 100, rs.host_k, rs.host_v, good, wb.pool_pages,
                                  staging, check=False) == ta.TA_ERR_INVALID_ARG
     torch.cuda.synchronize()
