@@ -70,7 +70,9 @@ typedef enum ta_status {
                                 slot out of range or duplicated, ... */
     TA_ERR_UNSUPPORTED = -2, /* head_dim != 128, page_size != 16, group size not in {1,2,4,8},
                                 token stride != head_dim, misaligned strides */
-    TA_ERR_HIP = -3          /* a HIP call failed; see ta_last_hip_error() */
+    TA_ERR_HIP = -3,         /* a HIP call failed; see ta_last_hip_error() */
+    TA_ERR_TOO_LARGE = -4    /* ta_paged_decode_static: the call needs more scratch than
+                                TA_STATIC_SCRATCH_BYTES; use ta_paged_decode with a workspace */
 } ta_status;
 
 typedef struct ta_attn_desc {
@@ -144,6 +146,30 @@ TA_API int ta_paged_decode(const ta_attn_desc *desc, const void *q, const void *
                     const int32_t *context_lens, int32_t batch, int32_t max_context_len,
                     void *out, float *lse, void *workspace, size_t workspace_bytes,
                     void *hip_stream);
+
+/*
+ * ta_paged_decode for callers that cannot allocate or hand over a workspace:
+ * code under HIP graph capture that may not call an allocator, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * the same results as ta_paged_decode, without `workspace`: the split-K plan
+ * and partial results live in an array of TA_STATIC_SCRATCH_BYTES that the
+ * library holds in device memory on every GPU it runs on, from the first call
+ * on that GPU until the process ends.  The call itself allocates and frees
+ * nothing, on the host or on the device.
+ *
+ * Returns TA_ERR_TOO_LARGE (and enqueues nothing) when
+ * ta_workspace_bytes(desc, batch, 1, max_context_len) exceeds
+ * TA_STATIC_SCRATCH_BYTES; other errors as for ta_paged_decode.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on
+ * one GPU (different streams, or graphs replayed side by side) race; calls on
+ * one stream are ordered and safe.  Nothing in the array needs to survive
+ * between calls; every call writes what it later reads.
+ */
+#define TA_STATIC_SCRATCH_BYTES (64u << 20)
+TA_API int ta_paged_decode_static(const ta_attn_desc *desc, const void *q, const void *k_pool,
+                           const void *v_pool, const int32_t *block_table,
+                           int32_t block_table_stride, const int32_t *context_lens, int32_t batch,
+                           int32_t max_context_len, void *out, float *lse, void *hip_stream);
 
 /*
  * Append-prefill (Sec. 4.2: incremental prefilling of tool-execution results,

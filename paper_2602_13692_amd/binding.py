@@ -23,12 +23,14 @@ TA_OK = 0
 TA_ERR_INVALID_ARG = -1
 TA_ERR_UNSUPPORTED = -2
 TA_ERR_HIP = -3
+TA_ERR_TOO_LARGE = -4
+STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = (
     "ta_version", "ta_strerror", "ta_last_hip_error", "ta_workspace_bytes", "ta_paged_decode",
     "ta_append_prefill", "ta_restore_staging_min_bytes", "ta_restore_staging_full_bytes",
     "ta_kv_page_restore", "ta_kv_page_evict", "ta_kv_append", "ta_profile_events",
-    "ta_set_debug_checks", "ta_sched_tick",
+    "ta_set_debug_checks", "ta_sched_tick", "ta_paged_decode_static",
 )
 PROBE_EXPORTS = ("ta_matrix_core_probe", "ta_stream_read_probe")
 
@@ -96,6 +98,8 @@ def _lib():
         lib.ta_workspace_bytes.argtypes = [vp, i32, i32, i32]
         lib.ta_paged_decode.restype = ctypes.c_int
         lib.ta_paged_decode.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp, sz, vp]
+        lib.ta_paged_decode_static.restype = ctypes.c_int
+        lib.ta_paged_decode_static.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i32, vp, vp, vp]
         lib.ta_append_prefill.restype = ctypes.c_int
         lib.ta_append_prefill.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, i32, i32, i32, i32, vp, vp,
                                           vp, sz, vp]
@@ -186,6 +190,20 @@ def ta_paged_decode(desc: Desc, q, k_pool, v_pool, block_table, context_lens, ma
         _stream(stream))
     if check:
         _check(rc, "ta_paged_decode")
+    return rc
+
+
+def ta_paged_decode_static(desc: Desc, q, k_pool, v_pool, block_table, context_lens, max_context_len: int,
+                           out, lse, stream=None, check: bool = True) -> int:
+    """ta_paged_decode without a workspace: the library's own device array holds the split-K scratch."""
+    d = desc.c()
+    rc = _lib().ta_paged_decode_static(
+        ctypes.byref(d), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
+        int(block_table.shape[1]) if block_table is not None and block_table.dim() == 2 else 0,
+        _ptr(context_lens), int(context_lens.shape[0]) if context_lens is not None else 0,
+        int(max_context_len), _ptr(out), _ptr(lse), _stream(stream))
+    if check:
+        _check(rc, "ta_paged_decode_static")
     return rc
 
 

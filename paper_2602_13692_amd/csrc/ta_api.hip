@@ -216,6 +216,74 @@ int check_metadata(const int32_t* block_table, int32_t block_table_stride, const
     return host_flag == 0 ? TA_OK : TA_ERR_INVALID_ARG;
 }
 
+
+// The library's own scratch for ta_paged_decode_static: one array per GPU, held until the process
+// ends.  In host code the array's name is only a handle; its device address comes from
+// hipGetSymbolAddress, once per device, and that pointer is what kernels and copies are given.
+__device__ __align__(256) unsigned char scratch[TA_STATIC_SCRATCH_BYTES];
+
+int static_scratch_address(char** out) {
+    constexpr int kMaxDevices = 64;
+    static std::atomic<char*> cached[kMaxDevices];
+    int device = 0;
+    TA_HIP_TRY(hipGetDevice(&device));
+    if (device < 0 || device >= kMaxDevices) return TA_ERR_UNSUPPORTED;
+    char* p = cached[device].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        TA_HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)));
+        if (p == nullptr) return TA_ERR_HIP;
+        cached[device].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return TA_OK;
+}
+
+// ta_paged_decode and ta_paged_decode_static: the same validation and the same kernels; the
+// split-K workspace is the caller's buffer or this device's copy of the library's own array.
+int decode_with_scratch(const ta_attn_desc* desc, const void* q, const void* k_pool, const void* v_pool,
+                        const int32_t* block_table, int32_t block_table_stride, const int32_t* context_lens,
+                        int32_t batch, int32_t max_context_len, void* out, float* lse, void* workspace,
+                        size_t workspace_bytes, bool own_scratch, void* hip_stream) {
+    Geometry g;
+    int rc = resolve_geometry(desc, &g);
+    if (rc != TA_OK) return rc;
+    if (batch < 0 || max_context_len < 0 || block_table_stride < 0) return TA_ERR_INVALID_ARG;
+    if (batch == 0) return TA_OK;
+    if (!q || !k_pool || !v_pool || !block_table || !context_lens || !out) return TA_ERR_INVALID_ARG;
+    if (int64_t(block_table_stride) * kPageSize < int64_t(max_context_len)) return TA_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_pool) |
+         reinterpret_cast<uintptr_t>(v_pool) | reinterpret_cast<uintptr_t>(out)) & 15)
+        return TA_ERR_INVALID_ARG;
+    const WorkspaceLayout w = plan_workspace(g, batch, 1, max_context_len);
+    if (own_scratch) {
+        if (w.total_bytes > size_t(TA_STATIC_SCRATCH_BYTES)) return TA_ERR_TOO_LARGE;
+        char* p = nullptr;
+        rc = static_scratch_address(&p);
+        if (rc != TA_OK) return rc;
+        workspace = p;
+    } else {
+        if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255)) return TA_ERR_INVALID_ARG;
+        if (workspace_bytes < w.total_bytes) return TA_ERR_INVALID_ARG;
+    }
+    if (debug_checks_enabled()) {
+        rc = check_metadata(block_table, block_table_stride, context_lens, nullptr, batch, max_context_len, 0, 0,
+                            g.pool_pages, static_cast<hipStream_t>(hip_stream));
+        if (rc != TA_OK) return rc;
+    }
+    DecodeArgs a{};
+    a.q = static_cast<const uint16_t*>(q);
+    a.k_pool = static_cast<const uint16_t*>(k_pool);
+    a.v_pool = static_cast<const uint16_t*>(v_pool);
+    a.block_table = block_table;
+    a.context_lens = context_lens;
+    a.out = static_cast<uint16_t*>(out);
+    a.lse = lse;
+    a.block_table_stride = block_table_stride;
+    a.batch = batch;
+    a.max_context_len = max_context_len;
+    return launch_decode(g, a, w, static_cast<char*>(workspace), static_cast<hipStream_t>(hip_stream));
+}
+
 }  // namespace
 }  // namespace ta
 
@@ -229,6 +297,7 @@ const char* ta_strerror(int status) {
         case TA_ERR_INVALID_ARG: return "invalid argument";
         case TA_ERR_UNSUPPORTED: return "unsupported configuration";
         case TA_ERR_HIP: return "HIP runtime error";
+        case TA_ERR_TOO_LARGE: return "the call needs more scratch than the library's own array holds";
         default: return "unknown status";
     }
 }
@@ -261,37 +330,17 @@ int ta_paged_decode(const ta_attn_desc* desc, const void* q, const void* k_pool,
                     const int32_t* block_table, int32_t block_table_stride,
                     const int32_t* context_lens, int32_t batch, int32_t max_context_len, void* out,
                     float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
-    Geometry g;
-    int rc = resolve_geometry(desc, &g);
-    if (rc != TA_OK) return rc;
-    if (batch < 0 || max_context_len < 0 || block_table_stride < 0) return TA_ERR_INVALID_ARG;
-    if (batch == 0) return TA_OK;
-    if (!q || !k_pool || !v_pool || !block_table || !context_lens || !out || !workspace)
-        return TA_ERR_INVALID_ARG;
-    if (int64_t(block_table_stride) * kPageSize < int64_t(max_context_len)) return TA_ERR_INVALID_ARG;
-    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_pool) |
-         reinterpret_cast<uintptr_t>(v_pool) | reinterpret_cast<uintptr_t>(out)) & 15)
-        return TA_ERR_INVALID_ARG;
-    if (reinterpret_cast<uintptr_t>(workspace) & 255) return TA_ERR_INVALID_ARG;
-    const WorkspaceLayout w = plan_workspace(g, batch, 1, max_context_len);
-    if (workspace_bytes < w.total_bytes) return TA_ERR_INVALID_ARG;
-    if (ta::debug_checks_enabled()) {
-        rc = ta::check_metadata(block_table, block_table_stride, context_lens, nullptr, batch, max_context_len, 0,
-                                0, g.pool_pages, static_cast<hipStream_t>(hip_stream));
-        if (rc != TA_OK) return rc;
-    }
-    DecodeArgs a{};
-    a.q = static_cast<const uint16_t*>(q);
-    a.k_pool = static_cast<const uint16_t*>(k_pool);
-    a.v_pool = static_cast<const uint16_t*>(v_pool);
-    a.block_table = block_table;
-    a.context_lens = context_lens;
-    a.out = static_cast<uint16_t*>(out);
-    a.lse = lse;
-    a.block_table_stride = block_table_stride;
-    a.batch = batch;
-    a.max_context_len = max_context_len;
-    return launch_decode(g, a, w, static_cast<char*>(workspace), static_cast<hipStream_t>(hip_stream));
+    return ta::decode_with_scratch(desc, q, k_pool, v_pool, block_table, block_table_stride, context_lens, batch,
+                                   max_context_len, out, lse, workspace, workspace_bytes, /*own_scratch=*/false,
+                                   hip_stream);
+}
+
+int ta_paged_decode_static(const ta_attn_desc* desc, const void* q, const void* k_pool, const void* v_pool,
+                           const int32_t* block_table, int32_t block_table_stride,
+                           const int32_t* context_lens, int32_t batch, int32_t max_context_len, void* out,
+                           float* lse, void* hip_stream) {
+    return ta::decode_with_scratch(desc, q, k_pool, v_pool, block_table, block_table_stride, context_lens, batch,
+                                   max_context_len, out, lse, nullptr, 0, /*own_scratch=*/true, hip_stream);
 }
 
 int ta_append_prefill(const ta_attn_desc* desc, const void* q, const int32_t* cu_q_lens,
