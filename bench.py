@@ -265,7 +265,8 @@ def tiny_decode_latency(torch, ta, wl, dev, reps: int = 200):
             call(side)
     torch.cuda.synchronize()
     graph_ms = time_steps(graph.replay, reps, 10, torch)
-    return {"workload": "config 1: 4 programs, 8 q / 2 kv heads, contexts 64-512 (five kernels per call)",
+    return {"workload": "config 1: 4 programs, 8 q / 2 kv heads, contexts 64-512 (one kernel per call: every "
+                        "context fits a single item, the chunk kernel writes the output itself)",
             "us_per_call_eager": round(eager_ms * 1e3, 1), "us_per_call_hip_graph": round(graph_ms * 1e3, 1)}
 
 
@@ -632,6 +633,15 @@ def main():
             "frac_of_unique_bytes_roofline": round(unique / ms / 1e6 / HBM_PEAK_GBPS, 4),
             "dominant_kernel_ms": round(kernel_ms, 4),
         }
+        # the same batch with its programs in shuffled order: the groups are found all the same
+        import numpy as np
+
+        perm = np.random.default_rng(wl.SEED_BASE + 44).permutation(wb.batch)
+        wb.q = wb.q[torch.from_numpy(perm).to(dev)].contiguous()
+        wb.block_table = np.ascontiguousarray(wb.block_table[perm])
+        wb.context_lens = np.ascontiguousarray(wb.context_lens[perm])
+        ms_shuffled, _, out, lse = run_decode(wb, max(2, min(args.steps, 20)), 2, torch, ta)
+        extra["forked_decode"]["ms_per_step_shuffled_batch_order"] = round(ms_shuffled, 4)
         del wb, out, lse
         torch.cuda.empty_cache()
 

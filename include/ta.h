@@ -86,8 +86,8 @@ typedef struct ta_attn_desc {
     int64_t pool_stride_head;  /* elements between kv heads;    0 selects page_size*head_dim */
     int64_t pool_stride_token; /* elements between token rows;  0 selects head_dim (only value supported) */
     int32_t decode_chunk_pages; /* split-K chunk of ta_paged_decode in pages: 0 lets the library choose
-                                   (by batch and context length), else 8, 16, 32 or 64, and with eight
-                                   query heads per kv head also 128 or 256.  The same value must be
+                                   (by batch and context length), else 8, 16, 32, 64 or 128, and with
+                                   eight query heads per kv head also 256.  The same value must be
                                    given to ta_workspace_bytes. */
     int32_t reserved;          /* must be 0 */
 } ta_attn_desc;

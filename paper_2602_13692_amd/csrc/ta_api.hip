@@ -44,7 +44,7 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
     if (sh % 8 != 0 || sp % 8 != 0) return TA_ERR_UNSUPPORTED;
     if (sh < int64_t(kPageSize) * kHeadDim) return TA_ERR_INVALID_ARG;
     const int32_t cp = d->decode_chunk_pages;
-    if (cp != 0 && cp != 8 && cp != 16 && cp != 32 && cp != 64 && !((cp == 128 || cp == 256) && group == 8))
+    if (cp != 0 && cp != 8 && cp != 16 && cp != 32 && cp != 64 && cp != 128 && !(cp == 256 && group == 8))
         return TA_ERR_INVALID_ARG;
     g->num_q_heads = d->num_q_heads;
     g->num_kv_heads = d->num_kv_heads;
@@ -58,10 +58,11 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
     return TA_OK;
 }
 
-// Split-K chunk length.  Smaller chunks balance ragged batches better, larger
-// ones write fewer partial results; 64 pages (1024 tokens) keeps the partials
-// below one percent of the KV bytes, and batches too small to fill the chip
-// with that get shorter chunks.
+// Split-K chunk length (pages per bulk chunk).  Every item costs a few microseconds of its
+// workgroup's time (metadata, first loads in flight, the merge of its waves), so long chunks are
+// cheaper; short ones are only chosen when a batch is too small to fill the chip otherwise.  The
+// leftover of a program (less than one chunk) is cut finer and listed last, so that the launch
+// ends on short items.
 static int32_t choose_chunk_pages(const Geometry& g, int32_t batch, int32_t max_context_len) {
     if (g.decode_chunk_pages != 0) return g.decode_chunk_pages;   // the caller's choice, validated with the descriptor
     const int64_t pages = (int64_t(max_context_len) + kPageSize - 1) / kPageSize;
@@ -72,6 +73,9 @@ static int32_t choose_chunk_pages(const Geometry& g, int32_t batch, int32_t max_
             const int64_t items = int64_t(batch) * g.num_kv_heads * ((pages + c - 1) / c);
             if (items >= 2048) return c;
         }
+    } else {
+        const int64_t items = int64_t(batch) * g.num_kv_heads * ((pages + 127) / 128);
+        if (items >= 4096 || pages <= 128) return 128;
     }
     for (int32_t c : {64, 32, 16}) {
         const int64_t items = int64_t(batch) * g.num_kv_heads * ((pages + c - 1) / c);
@@ -89,23 +93,29 @@ WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_l
     size_t off = 0;
     if (max_q_len <= 1) {
         w.chunk_pages = choose_chunk_pages(g, batch, max_context_len);
-        const int64_t per_prog = (pages + w.chunk_pages - 1) / w.chunk_pages;
-        w.max_chunks = static_cast<int32_t>(int64_t(batch) * per_prog);
+        // with eight heads per kv head every item runs on the tile kernel, which takes a program's
+        // leftover as one item; the vector-ALU kernel gets it in quarters
+        w.rem_pages = g.group == 8 ? w.chunk_pages : (w.chunk_pages >= 32 ? w.chunk_pages / 4 : 8);
+        w.slots_per_program = static_cast<int32_t>(pages / w.chunk_pages + w.chunk_pages / w.rem_pages);
+        w.max_chunks = static_cast<int32_t>(int64_t(batch) * w.slots_per_program);
+        w.direct = (g.group != 8 && pages <= w.chunk_pages) ? 1 : 0;
         w.max_tiles = 0;
         w.off_chunk_start = off; off = align256(off + sizeof(int32_t) * (size_t(batch) + 1));
-        w.off_items = off;       off = align256(off + sizeof(int32_t) * 2 * size_t(w.max_chunks));
+        w.off_items = off;       off = align256(off + sizeof(int32_t) * 4 * size_t(w.max_chunks));
         w.off_part_ml = off;     off = align256(off + sizeof(float) * 2 * size_t(w.max_chunks) * g.num_q_heads);
         w.off_part_o = off;      off = align256(off + sizeof(float) * kHeadDim * size_t(w.max_chunks) * g.num_q_heads);
         // a shared chunk serves at least two programs; with eight heads per kv head every chunk
         // goes to the matrix-core kernel, one item each at most
         w.max_shared_items = g.group == 8 ? w.max_chunks
-                                          : static_cast<int32_t>((int64_t(batch) / 2) * per_prog);
+                                          : static_cast<int32_t>((int64_t(batch) / 2) * (pages / w.chunk_pages));
         w.off_counts = off;      off = align256(off + sizeof(int32_t) * 4);
         w.off_lcp = off;         off = align256(off + sizeof(int32_t) * size_t(batch));
+        w.off_pred = off;        off = align256(off + sizeof(int32_t) * size_t(batch));
+        w.off_order = off;       off = align256(off + sizeof(int32_t) * size_t(batch));
         w.off_shared_items = off; off = align256(off + sizeof(int32_t) * 4 * size_t(w.max_shared_items));
         w.off_tile_start = w.off_tiles = off;
     } else {
-        w.chunk_pages = 0;
+        w.chunk_pages = w.rem_pages = 0;
         w.max_chunks = 0;
         const int64_t tile_tokens = kPrefillRowsPerBlock / g.group;
         const int64_t per_prog = (int64_t(max_q_len) + tile_tokens - 1) / tile_tokens;

@@ -3,21 +3,25 @@
 // cost decomposition, Sec. 4.2, Eq. 3).
 //
 // Kernels per call:
-//   prefix  finds the leading pages consecutive programs have in common;
-//   plan    cuts every program's pages into fixed-length chunks of the key axis
-//           and lists them flat, so ragged batches keep all CUs busy; chunks that a
-//           group of programs shares go to the matrix-core tile kernel instead
-//           (one pass over the shared pages for all members);
-//   chunk   one workgroup per (chunk, kv head): streams the chunk's K and V
-//           pages from HBM once, serves all Hq/Hkv query heads of the group
-//           from the same registers, keeps an online softmax per 16-lane row,
-//           writes one partial (max, sum, unnormalised output) per query head;
+//   prefix  finds, for every program, the nearest earlier program whose block table starts
+//           alike, and the leading pages the two have in common;
+//   plan    cuts every program's pages into chunks of the key axis (bulk chunks, and finer
+//           pieces of the leftover) and lists them flat, long items first, so ragged batches
+//           keep all CUs busy and the launch ends on short items; chunks that a group of
+//           programs shares go to the matrix-core tile kernel instead (one pass over the
+//           shared pages for all members);
+//   chunk   one workgroup per (item, kv head): streams the item's K and V pages from HBM once,
+//           serves all Hq/Hkv query heads of the group from the same registers, keeps an
+//           online softmax per 16-lane row, writes one partial (max, sum, unnormalised output)
+//           per query head;
 //   merge   combines the partials of a (program, query head) and writes bf16.
+// When every context fits a single item (short contexts) the chunk kernel alone runs: it
+// normalises and writes the output itself.
 //
-// The work is HBM-bound (4 flop per KV byte at group size 4), so it runs on the
-// vector ALUs: packed bf16 dot products for q.k, fp32 FMAs for p.v.  With eight query
-// heads per kv head the per-head state of this kernel would fill the register file (one
-// wave per SIMD, compute-bound), so there every chunk goes to the matrix-core tile kernel.
+// The work is HBM-bound (4 flop per KV byte at group size 4), so it runs on the vector ALUs:
+// packed bf16 dot products for q.k, fp32 FMAs for p.v.  With eight query heads per kv head the
+// per-head state of this kernel would fill the register file (one wave per SIMD,
+// compute-bound), so there every chunk goes to the matrix-core tile kernel.
 #include "ta_internal.h"
 
 namespace ta {
@@ -60,29 +64,44 @@ __device__ __forceinline__ uint16_t to_bf16_rne(float f) {
 }
 
 // ---------------------------------------------------------------------------
-// shared-prefix detection: leading pages that program b's block table has in common
-// with program b - 1 (forked agent branches list the same prefix pages), counted only
-// as far as both programs fill the pages completely
+// shared-prefix detection, step 1 (one workgroup per program): forked agent branches list the
+// same prefix pages at the head of their block tables, wherever they sit in the batch.  The
+// predecessor of program b is the nearest earlier program whose table starts with the same page
+// (both long enough to hold one bulk chunk); lcp[b] counts the leading pages the two have in
+// common, as far as both fill them completely.  Programs linked this way form a chain whose
+// first member leads the group; what all members share is the minimum along the chain.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void common_prefix_kernel(const int32_t* __restrict__ block_table,
-                                                            int32_t block_table_stride,
-                                                            const int32_t* __restrict__ context_lens,
-                                                            int32_t* __restrict__ lcp) {
-    __shared__ int first_diff;
+__global__ __launch_bounds__(256) void predecessor_prefix_kernel(const int32_t* __restrict__ block_table,
+                                                                 int32_t block_table_stride,
+                                                                 const int32_t* __restrict__ context_lens,
+                                                                 int32_t chunk_pages,
+                                                                 int32_t* __restrict__ pred,
+                                                                 int32_t* __restrict__ lcp) {
+    __shared__ int best, first_diff;
     const int b = blockIdx.x;
-    if (b == 0) {
-        if (threadIdx.x == 0) lcp[0] = 0;
+    const int min_tokens = chunk_pages * kPageSize;
+    const int lb = context_lens[b];
+    if (b == 0 || lb < min_tokens) {           // nothing before it, or too short to share a chunk
+        if (threadIdx.x == 0) { pred[b] = -1; lcp[b] = 0; }
         return;
     }
-    const int la = context_lens[b - 1], lb = context_lens[b];
-    int n = (la < lb ? la : lb) / kPageSize;          // pages both programs fill completely
-    n = n < 0 ? 0 : n;
-    const int32_t* ta = block_table + int64_t(b - 1) * block_table_stride;
+    if (threadIdx.x == 0) best = -1;
+    __syncthreads();
+    const int32_t first = block_table[int64_t(b) * block_table_stride];
+    int cand = -1;
+    for (int o = threadIdx.x; o < b; o += blockDim.x)    // ascending: the last hit is this thread's nearest
+        if (block_table[int64_t(o) * block_table_stride] == first && context_lens[o] >= min_tokens) cand = o;
+    if (cand >= 0) atomicMax(&best, cand);
+    __syncthreads();
+    const int a = best;
+    if (a < 0) {                                          // the common case: nothing shared
+        if (threadIdx.x == 0) { pred[b] = -1; lcp[b] = 0; }
+        return;
+    }
+    const int la = context_lens[a];
+    const int n = (la < lb ? la : lb) / kPageSize;        // pages both programs fill completely
+    const int32_t* ta = block_table + int64_t(a) * block_table_stride;
     const int32_t* tb = block_table + int64_t(b) * block_table_stride;
-    if (n == 0 || ta[0] != tb[0]) {                    // the common case: nothing shared
-        if (threadIdx.x == 0) lcp[b] = 0;
-        return;
-    }
     if (threadIdx.x == 0) first_diff = n;
     __syncthreads();
     for (int i = threadIdx.x; i < n; i += blockDim.x) {
@@ -92,44 +111,53 @@ __global__ __launch_bounds__(256) void common_prefix_kernel(const int32_t* __res
         }
     }
     __syncthreads();
-    if (threadIdx.x == 0) lcp[b] = first_diff;
+    if (threadIdx.x == 0) { pred[b] = a; lcp[b] = first_diff; }
 }
 
 // ---------------------------------------------------------------------------
-// plan: cuts every program's pages into chunks, gives each chunk a slot for its partial
-// result (chunk_start[b] + chunk index), finds groups of consecutive programs that share
-// leading chunks, and lists the work flat:
-//   shared_items  (first program, members, chunk)   -> matrix-core kernel, all members at once
-//   items         (program, chunk) for every chunk that is not shared -> vector-ALU kernel
+// plan (one workgroup).  A program's pages are cut into bulk chunks of chunk_pages and its
+// leftover into pieces of rem_pages; every chunk or piece gets a slot for its partial result
+// (chunk_start[b] + index, bulk chunks first).  Step 2 of the shared-prefix detection forms the
+// groups (chains of predecessors), lists their members side by side in `order`, and hands the
+// bulk chunks all members of a group share to the matrix-core kernel, one item per (group, chunk)
+// for all members at once.  Everything else is listed flat for the vector-ALU kernel, bulk
+// chunks first and the short pieces last, so that the launch ends on short items:
+//   shared_items  (position of the first member in `order`, members, bulk chunk, 0)
+//   items         (program, first page, pages, slot)
 // counts[0] = number of items, counts[1] = number of shared items, counts[2] = 0 (the tile
 // kernel's work counter).
-// With private_on_tiles every remaining chunk is listed as a group of one program in
-// shared_items instead, and `items` stays empty.
+// With private_on_tiles (eight query heads per kv head) every remaining chunk is listed as a
+// group of one program in shared_items instead, and `items` stays empty; rem_pages equals
+// chunk_pages then, so a leftover is one item.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __restrict__ context_lens,
+                                                           const int32_t* __restrict__ pred,
                                                            const int32_t* __restrict__ lcp,
-                                                           int32_t batch, int32_t chunk_pages,
-                                                           int32_t max_per_program, int32_t max_members,
+                                                           int32_t batch, int32_t max_pages, int32_t chunk_pages,
+                                                           int32_t rem_pages, int32_t max_members,
                                                            int32_t max_shared_items, int32_t private_on_tiles,
                                                            int32_t* __restrict__ chunk_start,
-                                                           int2* __restrict__ items,
+                                                           int4* __restrict__ items,
                                                            int4* __restrict__ shared_items,
+                                                           int32_t* __restrict__ order,
                                                            int32_t* __restrict__ counts) {
-    __shared__ int32_t scan[1024];
-    __shared__ int32_t shared_chunks[1024];   // leading chunks of program b computed by its group
-    __shared__ int4 groups[512];
-    __shared__ int32_t carry, n_groups, n_shared;
-    const int tid = threadIdx.x;
-    const int chunk_tokens = chunk_pages * kPageSize;
-
-    auto chunks_of = [&](int b) {
-        const int L = context_lens[b];
-        int n = L > 0 ? (L + chunk_tokens - 1) / chunk_tokens : 0;
-        return n > max_per_program ? max_per_program : n;   // lengths above the host bound are clipped
-    };
-    // exclusive scan of `value` over one pass of up to 1024 programs (wave-level shuffles, then
-    // the sixteen wave totals); returns this thread's offset including earlier passes
+    __shared__ int32_t s_key[1024];      // (leader << 10 | program), sorted: groups side by side
+    __shared__ int32_t s_lead[1024];     // leader of each program
+    __shared__ int32_t s_lcp[1024];      // pages shared with the predecessor
+    __shared__ int32_t s_shared[1024];   // leading bulk chunks of program b computed by its group
+    __shared__ int32_t s_pos[1024];      // position of program b in `order`
     __shared__ int32_t wave_total[16];
+    __shared__ int32_t carry, n_shared;
+    const int tid = threadIdx.x;
+
+    auto pages_of = [&](int b) {
+        const int L = context_lens[b];
+        const int n = L > 0 ? (L + kPageSize - 1) / kPageSize : 0;
+        return n > max_pages ? max_pages : n;               // lengths above the host bound are clipped
+    };
+    auto pieces_of = [&](int pages) { return (pages % chunk_pages + rem_pages - 1) / rem_pages; };
+    // exclusive scan of `value` over one pass of up to 1024 threads (wave-level shuffles, then
+    // the sixteen wave totals); returns this thread's offset including earlier passes
     auto block_scan = [&](int value) {
         const int lane = tid & 63, wv = tid >> 6;
         int x = value;
@@ -153,61 +181,128 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
     __syncthreads();
     for (int base = 0; base < batch; base += 1024) {
         const int b = base + tid;
-        const int first = block_scan(b < batch ? chunks_of(b) : 0);
+        const int pages = b < batch ? pages_of(b) : 0;
+        const int first = block_scan(b < batch ? pages / chunk_pages + pieces_of(pages) : 0);
         if (b < batch) chunk_start[b] = first;
     }
     if (tid == 0) chunk_start[batch] = carry;
 
-    // 2. groups of programs with common leading chunks (batches of up to 1024 programs)
-    shared_chunks[tid] = 0;
-    if (tid == 0) { n_groups = 0; n_shared = 0; }
+    // 2. groups of programs with common leading bulk chunks (batches of up to 1024 programs)
+    const bool grouping = lcp != nullptr && batch <= 1024 && batch >= 2;
+    s_shared[tid] = 0;
+    s_pos[tid] = tid;
+    if (tid == 0) n_shared = 0;
     __syncthreads();
-    if (lcp != nullptr && batch <= 1024 && batch >= 2) {
-        scan[tid] = (tid > 0 && tid < batch) ? lcp[tid] / chunk_pages : 0;   // chunks shared with b - 1
+    if (grouping) {
+        const bool joins = tid < batch && pred[tid] >= 0 && lcp[tid] >= chunk_pages;
+        s_lcp[tid] = joins ? lcp[tid] : 0;
+        s_lead[tid] = joins ? pred[tid] : tid;
         __syncthreads();
-        if (tid == 0) {
-            int ng = 0, off = 0, b = 0;
-            while (b < batch) {
-                int e = b + 1, common = 0x7fffffff;
-                while (e < batch && e - b < max_members && scan[e] > 0) {
-                    common = scan[e] < common ? scan[e] : common;
-                    ++e;
+        for (int round = 0; round < 10; ++round) {          // predecessors have smaller indices: 2^10 hops suffice
+            const int l = s_lead[s_lead[tid]];
+            __syncthreads();
+            s_lead[tid] = l;
+            __syncthreads();
+        }
+        s_key[tid] = tid < batch ? ((s_lead[tid] << 10) | tid) : 0x7fffffff;
+        __syncthreads();
+        for (int k = 2; k <= 1024; k <<= 1) {               // bitonic sort, ascending; the keys are distinct
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                const int other = tid ^ j;
+                if (other > tid) {
+                    const int a = s_key[tid], c = s_key[other];
+                    const bool ascending = (tid & k) == 0;
+                    if ((a > c) == ascending) { s_key[tid] = c; s_key[other] = a; }
                 }
-                if (e - b >= 2 && ng < 512 && off + common <= max_shared_items) {
-                    groups[ng++] = make_int4(b, e - b, common, off);
-                    off += common;
-                    for (int i = b; i < e; ++i) shared_chunks[i] = common;
-                }
-                b = e;
+                __syncthreads();
             }
-            n_groups = ng;
-            n_shared = off;
+        }
+        const int key = s_key[tid];
+        int sc = 0, n_in_sub = 0;
+        if (tid < batch) {
+            const int prog = key & 1023, lead = key >> 10;
+            order[tid] = prog;
+            s_pos[prog] = tid;
+            // first position of the group and of the next one: binary searches over the sorted keys
+            auto lower_bound = [&](int value) {
+                int lo = 0, hi = batch;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (s_key[mid] < value) lo = mid + 1; else hi = mid;
+                }
+                return lo;
+            };
+            const int head = lower_bound(lead << 10), end = lower_bound((lead + 1) << 10);
+            if ((tid - head) % max_members == 0) {          // first member of a tile of rows
+                n_in_sub = end - tid < max_members ? end - tid : max_members;
+                if (n_in_sub >= 2) {
+                    int common = 0x7fffffff;
+                    for (int j = tid; j < tid + n_in_sub; ++j) {
+                        const int m = s_key[j] & 1023;
+                        if (m != lead) common = s_lcp[m] < common ? s_lcp[m] : common;
+                    }
+                    sc = common / chunk_pages;
+                }
+            }
         }
         __syncthreads();
-        if (tid < n_groups) {
-            const int4 gr = groups[tid];
-            for (int c = 0; c < gr.z; ++c) shared_items[gr.w + c] = make_int4(gr.x, gr.y, c, 0);
+        if (tid == 0) carry = 0;
+        __syncthreads();
+        const int first_item = block_scan(sc);
+        if (tid == 0) n_shared = carry <= max_shared_items ? carry : 0;
+        __syncthreads();
+        if (sc > 0 && n_shared > 0) {
+            for (int j = tid; j < tid + n_in_sub; ++j) s_shared[s_key[j] & 1023] = sc;
+            for (int c = 0; c < sc; ++c) shared_items[first_item + c] = make_int4(tid, n_in_sub, c, 0);
         }
+    } else {
+        for (int b = tid; b < batch; b += 1024) order[b] = b;
     }
     __syncthreads();
 
-    // 3. the remaining chunks, one item each
+    // 3. the remaining bulk chunks, then the pieces, one item each
+    const int tile_base = n_shared;
     if (tid == 0) carry = 0;
     __syncthreads();
     for (int base = 0; base < batch; base += 1024) {
         const int b = base + tid;
-        const int n = b < batch ? chunks_of(b) : 0;
-        const int sc = (b < batch && batch <= 1024) ? shared_chunks[b] : 0;
-        const int first = block_scan(n - sc);
-        if (private_on_tiles) {
-            for (int c = sc; c < n; ++c) shared_items[n_shared + first + c - sc] = make_int4(b, 1, c, 0);
-        } else {
-            for (int c = sc; c < n; ++c) items[first + c - sc] = make_int2(b, c);
+        const int bulk = b < batch ? pages_of(b) / chunk_pages : 0;
+        const int sc = (b < batch && batch <= 1024) ? s_shared[b] : 0;
+        const int first = block_scan(bulk - sc);
+        if (b < batch) {
+            const int slot0 = chunk_start[b];
+            const int pos = batch <= 1024 ? s_pos[b] : b;
+            for (int c = sc; c < bulk; ++c) {
+                if (private_on_tiles) shared_items[tile_base + first + c - sc] = make_int4(pos, 1, c, 0);
+                else items[first + c - sc] = make_int4(b, c * chunk_pages, chunk_pages, slot0 + c);
+            }
+        }
+    }
+    __syncthreads();
+    const int n_bulk = carry;
+    __syncthreads();
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int base = 0; base < batch; base += 1024) {
+        const int b = base + tid;
+        const int pages = b < batch ? pages_of(b) : 0;
+        const int bulk = pages / chunk_pages;
+        const int n = pieces_of(pages);
+        const int first = block_scan(n);
+        if (b < batch) {
+            const int slot0 = chunk_start[b];
+            const int pos = batch <= 1024 ? s_pos[b] : b;
+            for (int k = 0; k < n; ++k) {
+                const int page0 = bulk * chunk_pages + k * rem_pages;
+                const int left = pages - page0;
+                if (private_on_tiles) shared_items[tile_base + n_bulk + first + k] = make_int4(pos, 1, bulk + k, 0);
+                else items[n_bulk + first + k] = make_int4(b, page0, left < rem_pages ? left : rem_pages, slot0 + bulk + k);
+            }
         }
     }
     if (tid == 0) {
-        counts[0] = private_on_tiles ? 0 : carry;
-        counts[1] = private_on_tiles ? n_shared + carry : n_shared;
+        counts[0] = private_on_tiles ? 0 : n_bulk + carry;
+        counts[1] = private_on_tiles ? tile_base + n_bulk + carry : tile_base;
         counts[2] = 0;   // work counter of the tile kernel
     }
 }
@@ -221,20 +316,23 @@ struct ChunkParams {
     const char* v_pool;
     const int32_t* block_table;
     const int32_t* context_lens;
-    const int32_t* chunk_start;  // [batch + 1] first partial slot of each program
     const int32_t* counts;       // counts[0] = number of items
-    const int2* items;
+    const int4* items;           // (program, first page, pages, slot)
     float* part_ml;
     float* part_o;
+    uint16_t* out;               // DIRECT only
+    float* lse;                  // DIRECT only, may be null
     int64_t stride_page_bytes;
     int64_t stride_head_bytes;
     int32_t block_table_stride;
     int32_t batch;
     int32_t num_q_heads;
     int32_t num_kv_heads;
-    int32_t chunk_pages;
+    int32_t max_pages;           // DIRECT only: pages the launch was sized for
     float scale_log2;
 };
+
+constexpr int kMaxItemPages = 128;   // two page ids per lane
 
 struct PageRegs {
     u32x4 k[4];  // k[i]: token 4*i + (lane / 16), dims 8 * (lane % 16) .. + 7
@@ -336,31 +434,48 @@ __device__ __forceinline__ void process_page(const PageRegs& pg, const uint32_t 
     }
 }
 
-template <int G>
+// DIRECT: every program is one item (its whole context, at most kMaxItemPages pages); the
+// workgroup normalises and writes the bf16 output itself: no plan, no partials, no merge.
+template <int G, bool DIRECT>
 __global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams p) {
-    const int n_items = p.counts[0];
     const int item = blockIdx.x / p.num_kv_heads;
-    if (item >= n_items) return;
     const int g = blockIdx.x - item * p.num_kv_heads;
-    const int2 it = p.items[item];
-    const int b = it.x;
+    int b, page0, n_here, slot = 0;
+    if (DIRECT) {
+        b = item;
+        page0 = 0;
+    } else {
+        if (item >= p.counts[0]) return;
+        const int4 it = p.items[item];
+        b = it.x; page0 = it.y; n_here = it.z; slot = it.w;
+    }
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int row = lane >> 4;
     const int col = lane & 15;
 
     const int L = p.context_lens[b];
-    const int n_pages_b = (L + kPageSize - 1) / kPageSize;
-    const int page0 = it.y * p.chunk_pages;
-    int n_here = n_pages_b - page0;
-    n_here = n_here > p.chunk_pages ? p.chunk_pages : n_here;
-    const int tail_valid = L - (n_pages_b - 1) * kPageSize;           // 1..16
-    const bool has_tail = (page0 + n_here == n_pages_b) && tail_valid < kPageSize;
+    int n_pages_b = L > 0 ? (L + kPageSize - 1) / kPageSize : 0;
+    if (DIRECT) {
+        n_pages_b = n_pages_b > p.max_pages ? p.max_pages : n_pages_b;
+        n_here = n_pages_b;
+    }
+    const int tail_valid = L - (n_pages_b - 1) * kPageSize;           // 1..16 where the program's last page is reached
+    const bool has_tail = n_here > 0 && (page0 + n_here == n_pages_b) && tail_valid < kPageSize;
     const int n_full = has_tail ? n_here - 1 : n_here;                // pages processed unmasked
 
-    // page ids of this chunk, one per lane (chunk_pages <= 64)
-    int my_id = 0;
-    if (lane < n_here) my_id = p.block_table[int64_t(b) * p.block_table_stride + page0 + lane];
+    // page ids of this item, two per lane
+    int my_id0 = 0, my_id1 = 0;
+    {
+        const int32_t* table = p.block_table + int64_t(b) * p.block_table_stride + page0;
+        if (lane < n_here) my_id0 = table[lane];
+        if (lane + 64 < n_here) my_id1 = table[lane + 64];
+    }
+    auto page_id = [&](int idx) -> int {                              // idx is wave-uniform
+        const int lo = __builtin_amdgcn_readlane(my_id0, idx & 63);
+        const int hi = __builtin_amdgcn_readlane(my_id1, idx & 63);
+        return idx < 64 ? lo : hi;
+    };
 
     // queries of the group: 8 dims per lane, the same in all four rows
     uint32_t qreg[G][4];
@@ -388,10 +503,7 @@ __global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams
     // this wave's full pages: chunk pages wave, wave + 4, ...
     const int n_mine = n_full > wave ? (n_full - wave + kChunkWaves - 1) / kChunkWaves : 0;
     if (n_mine > 0) {
-        auto tile_of = [&](int j) -> int64_t {
-            const int id = __builtin_amdgcn_readlane(my_id, wave + kChunkWaves * j);
-            return int64_t(id) * p.stride_page_bytes;
-        };
+        auto tile_of = [&](int j) -> int64_t { return int64_t(page_id(wave + kChunkWaves * j)) * p.stride_page_bytes; };
         PageRegs bufA, bufB;
         int64_t off = tile_of(0);
         load_page(bufA, k_head + off, v_head + off, lane);
@@ -422,8 +534,7 @@ __global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams
     }
     if (has_tail && ((n_here - 1) & (kChunkWaves - 1)) == wave) {
         PageRegs t;
-        const int id = __builtin_amdgcn_readlane(my_id, n_here - 1);
-        const int64_t off = int64_t(id) * p.stride_page_bytes;
+        const int64_t off = int64_t(page_id(n_here - 1)) * p.stride_page_bytes;
         load_page(t, k_head + off, v_head + off, lane);
         process_page<G, true>(t, qreg, m, l, o, p.scale_log2, row, tail_valid);
     }
@@ -459,7 +570,33 @@ __global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams
     }
     __syncthreads();
 
-    // merge the four waves; thread t owns outputs t, t + 256, ...
+    // merge the four waves
+    if (DIRECT) {
+        // thread t owns two neighbouring dims of one head and writes them as bf16
+        for (int idx = threadIdx.x; idx < G * (kHeadDim / 2); idx += kChunkThreads) {
+            const int h = idx / (kHeadDim / 2);
+            const int c = 2 * (idx % (kHeadDim / 2));
+            float mt = sm_m[0][h];
+#pragma unroll
+            for (int w = 1; w < kChunkWaves; ++w) mt = fmaxf(mt, sm_m[w][h]);
+            float lt = 0.0f, a0 = 0.0f, a1 = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kChunkWaves; ++w) {
+                const float wt = fast_exp2((sm_m[w][h] - mt) * p.scale_log2);
+                lt = fmaf(sm_l[w][h], wt, lt);
+                a0 = fmaf(sm_o[w][h][c], wt, a0);
+                a1 = fmaf(sm_o[w][h][c + 1], wt, a1);
+            }
+            const float inv = lt > 0.0f ? 1.0f / lt : 0.0f;
+            const int64_t rid = int64_t(b) * p.num_q_heads + g * G + h;
+            *reinterpret_cast<uint32_t*>(p.out + rid * kHeadDim + c) =
+                uint32_t(to_bf16_rne(a0 * inv)) | (uint32_t(to_bf16_rne(a1 * inv)) << 16);
+            if (p.lse != nullptr && c == 0)
+                p.lse[rid] = lt > 0.0f ? (mt * p.scale_log2 + __builtin_amdgcn_logf(lt)) * kLn2 : -INFINITY;
+        }
+        return;
+    }
+    // thread t owns outputs t, t + 256, ...
     for (int idx = threadIdx.x; idx < G * kHeadDim; idx += kChunkThreads) {
         const int h = idx / kHeadDim;
         const int c = idx % kHeadDim;
@@ -473,7 +610,7 @@ __global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams
             lt = fmaf(sm_l[w][h], wt, lt);
             acc = fmaf(sm_o[w][h][c], wt, acc);
         }
-        const int64_t rowid = int64_t(p.chunk_start[b] + it.y) * p.num_q_heads + g * G + h;
+        const int64_t rowid = int64_t(slot) * p.num_q_heads + g * G + h;
         p.part_o[rowid * kHeadDim + c] = acc;
         if (c == 0) {
             p.part_ml[rowid * 2 + 0] = mt * p.scale_log2;  // max in the log2 domain
@@ -531,34 +668,69 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(MergeParams p) {
 
 int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout& w, char* workspace,
                   hipStream_t stream) {
+    const ProfileEvents ev = profile_events();
+    ChunkParams cp{};
+    cp.q = a.q;
+    cp.k_pool = reinterpret_cast<const char*>(a.k_pool);
+    cp.v_pool = reinterpret_cast<const char*>(a.v_pool);
+    cp.block_table = a.block_table;
+    cp.context_lens = a.context_lens;
+    cp.out = a.out;
+    cp.lse = a.lse;
+    cp.stride_page_bytes = g.stride_page_bytes;
+    cp.stride_head_bytes = g.stride_head_bytes;
+    cp.block_table_stride = a.block_table_stride;
+    cp.batch = a.batch;
+    cp.num_q_heads = g.num_q_heads;
+    cp.num_kv_heads = g.num_kv_heads;
+    cp.max_pages = (a.max_context_len + kPageSize - 1) / kPageSize;
+    cp.scale_log2 = g.scale_log2;
+
+    if (w.direct) {
+        // short contexts: one launch, one workgroup per (program, kv head), output written directly
+        const int64_t blocks = int64_t(a.batch) * g.num_kv_heads;
+        if (blocks > 0x7fffffff || cp.max_pages > kMaxItemPages) return TA_ERR_INVALID_ARG;
+        const dim3 grid(static_cast<unsigned>(blocks)), block(kChunkThreads);
+        if (ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
+        switch (g.group) {
+            case 1: hipLaunchKernelGGL((decode_chunk_kernel<1, true>), grid, block, 0, stream, cp); break;
+            case 2: hipLaunchKernelGGL((decode_chunk_kernel<2, true>), grid, block, 0, stream, cp); break;
+            case 4: hipLaunchKernelGGL((decode_chunk_kernel<4, true>), grid, block, 0, stream, cp); break;
+            default: return TA_ERR_UNSUPPORTED;
+        }
+        TA_HIP_TRY(hipGetLastError());
+        if (ev.stop != nullptr) TA_HIP_TRY(hipEventRecord(ev.stop, stream));
+        return TA_OK;
+    }
+
     int32_t* chunk_start = reinterpret_cast<int32_t*>(workspace + w.off_chunk_start);
-    int2* items = reinterpret_cast<int2*>(workspace + w.off_items);
+    int4* items = reinterpret_cast<int4*>(workspace + w.off_items);
     float* part_ml = reinterpret_cast<float*>(workspace + w.off_part_ml);
     float* part_o = reinterpret_cast<float*>(workspace + w.off_part_o);
     int32_t* counts = reinterpret_cast<int32_t*>(workspace + w.off_counts);
     int32_t* lcp = reinterpret_cast<int32_t*>(workspace + w.off_lcp);
+    int32_t* pred = reinterpret_cast<int32_t*>(workspace + w.off_pred);
+    int32_t* order = reinterpret_cast<int32_t*>(workspace + w.off_order);
     int4* shared_items = reinterpret_cast<int4*>(workspace + w.off_shared_items);
-    const int32_t per_prog = w.max_chunks / a.batch;
-    // sharing needs at least two programs and a non-empty block table
+    // sharing needs at least two programs with a bulk chunk each and a non-empty block table
     const bool look_for_sharing = a.batch >= 2 && a.batch <= 1024 && w.max_shared_items > 0 &&
-                                  a.block_table_stride > 0;
+                                  a.block_table_stride > 0 && cp.max_pages >= w.chunk_pages;
     // Eight query heads per kv head leave the vector-ALU kernel one wave per SIMD (its per-head
     // state fills the register file) and make it compute-bound; the matrix-core kernel takes
     // the private chunks too, as groups of one program.
     const bool private_on_tiles = g.group == 8;   // the workspace plan sizes shared_items for it
 
     if (look_for_sharing) {
-        hipLaunchKernelGGL(common_prefix_kernel, dim3(a.batch), dim3(256), 0, stream, a.block_table,
-                           a.block_table_stride, a.context_lens, lcp);
+        hipLaunchKernelGGL(predecessor_prefix_kernel, dim3(a.batch), dim3(256), 0, stream, a.block_table,
+                           a.block_table_stride, a.context_lens, w.chunk_pages, pred, lcp);
         TA_HIP_TRY(hipGetLastError());
     }
     hipLaunchKernelGGL(plan_decode_kernel, dim3(1), dim3(1024), 0, stream, a.context_lens,
-                       look_for_sharing ? lcp : nullptr, a.batch, w.chunk_pages, per_prog,
-                       256 / g.group, w.max_shared_items, private_on_tiles ? 1 : 0, chunk_start, items,
-                       shared_items, counts);
+                       look_for_sharing ? pred : nullptr, look_for_sharing ? lcp : nullptr, a.batch, cp.max_pages,
+                       w.chunk_pages, w.rem_pages, 256 / g.group, w.max_shared_items, private_on_tiles ? 1 : 0,
+                       chunk_start, items, shared_items, order, counts);
     TA_HIP_TRY(hipGetLastError());
 
-    const ProfileEvents ev = profile_events();
     if (look_for_sharing || private_on_tiles) {
         SharedPrefixArgs sa{};
         sa.q = a.q;
@@ -567,6 +739,7 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
         sa.block_table = a.block_table;
         sa.context_lens = a.context_lens;
         sa.shared_items = reinterpret_cast<const int32_t*>(shared_items);
+        sa.order = order;
         sa.counts = counts;
         sa.chunk_start = chunk_start;
         sa.part_ml = part_ml;
@@ -582,33 +755,18 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     }
 
     if (w.max_chunks > 0 && !private_on_tiles) {
-        ChunkParams cp{};
-        cp.q = a.q;
-        cp.k_pool = reinterpret_cast<const char*>(a.k_pool);
-        cp.v_pool = reinterpret_cast<const char*>(a.v_pool);
-        cp.block_table = a.block_table;
-        cp.context_lens = a.context_lens;
-        cp.chunk_start = chunk_start;
         cp.counts = counts;
         cp.items = items;
         cp.part_ml = part_ml;
         cp.part_o = part_o;
-        cp.stride_page_bytes = g.stride_page_bytes;
-        cp.stride_head_bytes = g.stride_head_bytes;
-        cp.block_table_stride = a.block_table_stride;
-        cp.batch = a.batch;
-        cp.num_q_heads = g.num_q_heads;
-        cp.num_kv_heads = g.num_kv_heads;
-        cp.chunk_pages = w.chunk_pages;
-        cp.scale_log2 = g.scale_log2;
         const int64_t blocks = int64_t(w.max_chunks) * g.num_kv_heads;
-        if (blocks > 0x7fffffff) return TA_ERR_INVALID_ARG;
+        if (blocks > 0x7fffffff || w.chunk_pages > kMaxItemPages) return TA_ERR_INVALID_ARG;
         const dim3 grid(static_cast<unsigned>(blocks)), block(kChunkThreads);
         if (ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
         switch (g.group) {
-            case 1: hipLaunchKernelGGL(decode_chunk_kernel<1>, grid, block, 0, stream, cp); break;
-            case 2: hipLaunchKernelGGL(decode_chunk_kernel<2>, grid, block, 0, stream, cp); break;
-            case 4: hipLaunchKernelGGL(decode_chunk_kernel<4>, grid, block, 0, stream, cp); break;
+            case 1: hipLaunchKernelGGL((decode_chunk_kernel<1, false>), grid, block, 0, stream, cp); break;
+            case 2: hipLaunchKernelGGL((decode_chunk_kernel<2, false>), grid, block, 0, stream, cp); break;
+            case 4: hipLaunchKernelGGL((decode_chunk_kernel<4, false>), grid, block, 0, stream, cp); break;
             default: return TA_ERR_UNSUPPORTED;
         }
         TA_HIP_TRY(hipGetLastError());

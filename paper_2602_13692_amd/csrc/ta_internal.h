@@ -50,20 +50,29 @@ struct Geometry {
 int resolve_geometry(const ta_attn_desc* desc, Geometry* g);
 
 // Layout of the caller's workspace for one call.  All offsets are multiples of 256 bytes.
+//
+// Decode cuts the pages of a program into bulk chunks of chunk_pages and cuts what is left
+// (fewer than chunk_pages pages) into pieces of rem_pages; every chunk or piece has a slot for its
+// partial result.  A program's slots are consecutive: bulk chunks first, then the pieces.
 struct WorkspaceLayout {
-    int32_t chunk_pages;       // pages per split-K chunk
-    int32_t max_chunks;        // upper bound on the number of (program, chunk) items
-    int32_t max_tiles;         // upper bound on prefill query tiles (0 for decode)
-    size_t off_chunk_start;    // int32 [batch + 1]
-    size_t off_items;          // int2  [max_chunks]
-    size_t off_part_ml;        // float [max_chunks][Hq][2]
-    size_t off_part_o;         // float [max_chunks][Hq][128]
-    int32_t max_shared_items;  // upper bound on (group, shared chunk) items
-    size_t off_counts;         // int32 [4]: private items, shared items, tile-kernel work counter
-    size_t off_lcp;            // int32 [batch] leading pages shared with the previous program
-    size_t off_shared_items;   // int4  [max_shared_items]
-    size_t off_tile_start;     // int32 [batch + 1]      (prefill)
-    size_t off_tiles;          // int2  [max_tiles]      (prefill)
+    int32_t chunk_pages;        // pages per bulk chunk
+    int32_t rem_pages;          // pages per piece of the remainder (divides chunk_pages)
+    int32_t slots_per_program;  // upper bound on the slots of one program
+    int32_t max_chunks;         // batch * slots_per_program: bound on slots and on vector-ALU items
+    int32_t direct;             // 1: every context fits one item: no plan, no partials, no merge
+    int32_t max_tiles;          // upper bound on prefill query tiles (0 for decode)
+    size_t off_chunk_start;     // int32 [batch + 1] first slot of each program
+    size_t off_items;           // int4  [max_chunks] (program, first page, pages, slot)
+    size_t off_part_ml;         // float [max_chunks][Hq][2]
+    size_t off_part_o;          // float [max_chunks][Hq][128]
+    int32_t max_shared_items;   // upper bound on the matrix-core kernel's items
+    size_t off_counts;          // int32 [4]: vector-ALU items, matrix-core items, matrix-core work counter
+    size_t off_lcp;             // int32 [batch] leading pages shared with the predecessor
+    size_t off_pred;            // int32 [batch] predecessor: the nearest earlier program with the same first page
+    size_t off_order;           // int32 [batch] programs listed group by group
+    size_t off_shared_items;    // int4  [max_shared_items] (position in `order`, members, bulk chunk, 0)
+    size_t off_tile_start;      // int32 [batch + 1]      (prefill)
+    size_t off_tiles;           // int2  [max_tiles]      (prefill)
     size_t total_bytes;
 };
 
@@ -115,8 +124,9 @@ struct SharedPrefixArgs {
     const uint16_t* v_pool;
     const int32_t* block_table;
     const int32_t* context_lens;
-    const int32_t* shared_items;   // int4 per item: first program, members, chunk, unused
-    int32_t* counts;               // counts[1] = number of shared items, counts[2] = work counter (starts at 0)
+    const int32_t* shared_items;   // int4 per item: position of the first member in `order`, members, chunk, unused
+    const int32_t* order;          // programs listed group by group
+    int32_t* counts;               // counts[1] = number of items, counts[2] = work counter (starts at 0)
     const int32_t* chunk_start;
     float* part_ml;
     float* part_o;

@@ -62,8 +62,10 @@ struct PrefillParams {
     const int2* tiles;          // (program, query tile)
     uint16_t* out;
     float* lse;
-    // shared-prefix decode only: one item = (first program of the group, members, chunk)
+    // shared-prefix decode only: one item = (position of the group's first member in `order`,
+    // members, chunk); the members are order[position .. position + members)
     const int4* shared_items;
+    const int32_t* order;
     int32_t* counts;             // counts[1] = number of shared items, counts[2] = next (item, kv head) pair to take
     const int32_t* chunk_start;  // [batch + 1] first partial slot of each program
     float* part_ml;              // [slot][Hq][2]  reference maximum (log2 domain), sum
@@ -229,10 +231,11 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     const int hl = lane >> 5;                // which half of the wave
     const int l32 = lane & 31;
 
-    int b, q0, nq, L, prefix, t0, t_begin, n_tiles, n_unmasked, members = 0, chunk = 0;
+    int b, q0, nq, L, prefix, t0, t_begin, n_tiles, n_unmasked, members = 0, chunk = 0, first_pos = 0;
     if (SHARED) {
         const int4 it = p.shared_items[tile_id];
-        b = it.x;                      // the group's first program: its block table names the pages
+        first_pos = it.x;
+        b = p.order[first_pos];        // the group's first program: its block table names the pages
         members = it.y;
         chunk = it.z;
         q0 = 0; nq = 0; prefix = 0; t0 = 0;
@@ -275,7 +278,9 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
         const int head = g * G + row % G;
         const bool ok = SHARED ? (row / G < members) : (idx < nq);
         vis[rb] = ok ? (SHARED ? L : prefix + idx + 1) : 0;
-        out_row[rb] = ok ? (int64_t(SHARED ? b + row / G : q0 + idx) * p.num_q_heads + head) * kHeadDim : int64_t(-1);
+        // a member's query row is its program's row; members sit side by side in `order`
+        const int q_row = ok ? (SHARED ? p.order[first_pos + row / G] : q0 + idx) : 0;
+        out_row[rb] = ok ? (int64_t(q_row) * p.num_q_heads + head) * kHeadDim : int64_t(-1);
         const uint16_t* qrow = p.q + (ok ? out_row[rb] : 0) + hl * 8;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
@@ -693,9 +698,9 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
             // split-K partial of (member program, head) for this chunk: unnormalised O, the
             // reference maximum it is relative to, and the sum of weights
             const int row = wave * (32 * kRB) + rb * 32 + l32;
-            const int member = row / G;
             const int head = g * G + row % G;
-            const int64_t rowid = int64_t(p.chunk_start[b + member] + chunk) * p.num_q_heads + head;
+            const int program = static_cast<int>(out_row[rb] / (int64_t(p.num_q_heads) * kHeadDim));
+            const int64_t rowid = int64_t(p.chunk_start[program] + chunk) * p.num_q_heads + head;
             float* orow = p.part_o + rowid * kHeadDim;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
@@ -820,6 +825,7 @@ int launch_shared_prefix(const Geometry& g, const SharedPrefixArgs& a, hipStream
     pp.block_table = a.block_table;
     pp.context_lens = a.context_lens;
     pp.shared_items = reinterpret_cast<const int4*>(a.shared_items);
+    pp.order = a.order;
     pp.counts = a.counts;
     pp.chunk_start = a.chunk_start;
     pp.part_ml = a.part_ml;

@@ -50,8 +50,10 @@ def test_workspace_size_and_descriptor_validation():
     good = ta.Desc(32, 8)
     n = ta.ta_workspace_bytes(good, 64, 1, 32768)
     assert n > 0 and n % 256 == 0
-    # partials dominate: chunks * Hq * 130 floats
-    assert n >= 64 * 32 * 32 * 130 * 4
+    # partials dominate: slots * Hq * 130 floats; a program of 32k tokens has 16 bulk chunks of
+    # 128 pages and up to 4 pieces of its leftover
+    assert n >= 64 * (16 + 4) * 32 * 130 * 4
+    assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=64), 64, 1, 32768) >= 64 * 36 * 32 * 130 * 4
     assert ta.ta_workspace_bytes(good, 64, 2048, 34816) > 0
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, head_dim=64), 4, 1, 100) == 0
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, page_size=32), 4, 1, 100) == 0
@@ -86,8 +88,8 @@ def test_host_side_rejections_need_no_device():
     assert lib.ta_kv_page_evict(one, one, 32768, one, one, slot, 1, 10, null, 512, null) == ta.TA_ERR_INVALID_ARG
     # a chunk length the split-K plan does not offer, or one above 64 pages without eight heads per kv head
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=24), 4, 1, 100) == 0
-    assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=128), 4, 1, 100) == 0
-    assert ta.ta_workspace_bytes(ta.Desc(64, 8, decode_chunk_pages=128), 4, 1, 100) > 0
+    assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=256), 4, 1, 100) == 0
+    assert ta.ta_workspace_bytes(ta.Desc(64, 8, decode_chunk_pages=256), 4, 1, 100) > 0
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, pool_pages=-1), 4, 1, 100) == 0
     # the measurement aids (their own library) reject missing or misaligned buffers and bad sizes
     probe = ta._probe_lib()

@@ -29,11 +29,11 @@ def test_ragged_lengths_all_group_sizes(Hq, Hkv):
     gu.assert_close(out, lse, ref, ref_lse, f"ragged Hq={Hq} Hkv={Hkv}")
 
 
-@pytest.mark.parametrize("Hq,chunk_pages", [(32, 8), (32, 16), (32, 32), (32, 64),
+@pytest.mark.parametrize("Hq,chunk_pages", [(32, 8), (32, 16), (32, 32), (32, 64), (32, 128),
                                              (64, 8), (64, 16), (64, 32), (64, 64), (64, 128), (64, 256)])
 def test_every_chunk_length(chunk_pages, Hq):
-    """Four heads per kv head run on the vector-ALU kernel (chunks of up to 64 pages), eight on
-    the matrix-core tile kernel (up to 256)."""
+    """Four heads per kv head run on the vector-ALU kernel (bulk chunks of up to 128 pages, the
+    leftover of a program in quarter-chunk pieces), eight on the matrix-core tile kernel (up to 256)."""
     wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 200, batch=9, len_lo=100, len_hi=9000, num_q_heads=Hq)
     out, lse = gu.gpu_decode(wb, chunk_pages=chunk_pages)
     ref, ref_lse = gu.oracle_decode(wb)
@@ -129,8 +129,6 @@ def test_shared_prefix_groups_take_the_matrix_core_path(Hq, Hkv, group, chunk_pa
     Groups larger than one tile of rows are split, the shared length is not a multiple of the
     chunk, and one member is cut short inside the shared region.
     """
-    if chunk_pages > 64 and Hq // Hkv != 8:
-        pytest.skip("chunks above 64 pages exist only with eight query heads per kv head")
     wb = wl.forked_decode(DEV, seed=wl.SEED_BASE + 710 + group, batch=2 * group, group=group,
                           prefix_len=2048 + 16 * 37, suffix_lo=1, suffix_hi=700, num_q_heads=Hq,
                           num_kv_heads=Hkv)
@@ -141,6 +139,34 @@ def test_shared_prefix_groups_take_the_matrix_core_path(Hq, Hkv, group, chunk_pa
     ref, ref_lse = gu.oracle_decode(wb)
     gu.assert_close(out, lse, ref, ref_lse, f"shared prefix Hq={Hq} Hkv={Hkv} group={group}",
                     lse_tol=gu.LSE_TOL_PREFILL)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(64, 8), (32, 8)])
+def test_forked_programs_in_shuffled_batch_order(Hq, Hkv):
+    """Members of a group need not be neighbours in the batch: the groups are found by what the
+    block tables name, and the result is the oracle's whatever the order."""
+    wb = wl.forked_decode(DEV, seed=wl.SEED_BASE + 730, batch=48, group=8, prefix_len=4096, suffix_lo=10,
+                          suffix_hi=900, num_q_heads=Hq, num_kv_heads=Hkv)
+    perm = np.random.default_rng(wl.SEED_BASE + 731).permutation(wb.batch)
+    wb.q = wb.q[torch.from_numpy(perm).to(wb.q.device)].contiguous()
+    wb.block_table = np.ascontiguousarray(wb.block_table[perm])
+    wb.context_lens = np.ascontiguousarray(wb.context_lens[perm])
+    out, lse = gu.gpu_decode(wb, chunk_pages=64)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, "shuffled forked batch", lse_tol=gu.LSE_TOL_PREFILL)
+
+
+def test_short_contexts_take_the_single_launch_path():
+    """Contexts of at most one bulk chunk: the chunk kernel writes the output itself (no partials)."""
+    for Hq, Hkv in ((32, 8), (8, 8), (4, 2)):
+        wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 740 + Hq, batch=11, len_lo=1, len_hi=2048, num_q_heads=Hq,
+                               num_kv_heads=Hkv, first_lens=[1, 16, 17, 2048, 2047, 1025])
+        wb.context_lens[7] = 0
+        wl.poison_padding(wb)
+        out, lse = gu.gpu_decode(wb)
+        ref, ref_lse = gu.oracle_decode(wb)
+        gu.assert_close(out, lse, ref, ref_lse, f"single launch Hq={Hq} Hkv={Hkv}")
+        assert torch.all(out[7] == 0) and torch.all(torch.isneginf(lse[7]))
 
 
 def test_tables_that_only_start_alike_are_not_grouped():
