@@ -13,5 +13,7 @@ from .ta_oracle import (  # noqa: F401
     kv_page_restore,
     num_threads,
     paged_decode,
+    paged_decode_fp8,
     row_probs,
+    widen_e4m3,
 )

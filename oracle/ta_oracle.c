@@ -36,6 +36,16 @@
  * All bf16 inputs are widened exactly to fp64.  Element type of q and the
  * pools is uint16_t holding the bf16 bit pattern.
  *
+ * FP8 KV cache (the paper serves its large models in FP8, Sec. 5.1; it says nothing
+ * about the cache format, so this is a reading): keys and values may be stored
+ * as 8-bit codes in the OCP "E4M3" format (1 sign, 4 exponent bits with bias 7,
+ * 3 mantissa bits; no infinities; S.1111.111 is NaN; exponent field 0 holds the
+ * subnormals m * 2^-9; largest finite value 448) together with one fp32 scale
+ * for all keys and one for all values of the call.  The cached key is
+ * code_value * k_scale, the cached value code_value * v_scale, both exact in
+ * fp64, and attention over them is the same definition as above.  Queries
+ * stay bf16.
+ *
  * Every function here is pinned by tests that compare it with an independent
  * numpy evaluation on contiguous arrays, closed forms (single key, equal keys,
  * two keys = logistic), invariants (probabilities sum to one, page permutation,
@@ -119,6 +129,99 @@ static void attend_row(const oracle_geom *ge, const uint16_t *q, int32_t h,
         for (int32_t c = 0; c < d; ++c) out[c] += p * widen_bf16(v[c]);
     }
     *lse = top + log(total);
+}
+
+/* Value of an OCP E4M3 code (see the header): exact in fp64. */
+static double widen_e4m3(uint8_t code)
+{
+    const int sign = code >> 7;
+    const int exponent = (code >> 3) & 15;
+    const int mantissa = code & 7;
+    double magnitude;
+    if (exponent == 15 && mantissa == 7) return NAN;
+    if (exponent == 0)
+        magnitude = ldexp((double)mantissa, -9);               /* subnormal: (m / 8) * 2^(1 - 7) */
+    else
+        magnitude = ldexp(1.0 + (double)mantissa / 8.0, exponent - 7);
+    return sign ? -magnitude : magnitude;
+}
+
+/* The values of n codes, for checking the format against its specification. */
+void ta_oracle_widen_e4m3(const uint8_t *codes, int64_t n, double *values)
+{
+    for (int64_t i = 0; i < n; ++i) values[i] = widen_e4m3(codes[i]);
+}
+
+/*
+ * attend_row for an FP8 cache: the same steps, with keys and values read as
+ * E4M3 codes times their scale.  Pools are uint8_t, strides in elements.
+ */
+static void attend_row_fp8(const oracle_geom *ge, const uint16_t *q, int32_t h,
+                           const uint8_t *k_pool, const uint8_t *v_pool, double k_scale, double v_scale,
+                           const int32_t *table_row, int64_t visible,
+                           double *weights, double *out, double *lse)
+{
+    const int32_t d = ge->head_dim;
+    const int32_t group = ge->num_q_heads / ge->num_kv_heads;
+    const int32_t g = h / group;
+
+    for (int32_t c = 0; c < d; ++c) out[c] = 0.0;
+    if (visible <= 0) {
+        *lse = -INFINITY;
+        return;
+    }
+    double top = -INFINITY;
+    for (int64_t j = 0; j < visible; ++j) {
+        const int64_t page = table_row[j / ge->page_size], row = j % ge->page_size;
+        const uint8_t *k = k_pool + page * ge->stride_page + (int64_t)g * ge->stride_head + row * ge->stride_token;
+        double dot = 0.0;
+        for (int32_t c = 0; c < d; ++c) dot += widen_bf16(q[c]) * (widen_e4m3(k[c]) * k_scale);
+        weights[j] = dot * ge->scale;
+        if (weights[j] > top) top = weights[j];
+    }
+    double total = 0.0;
+    for (int64_t j = 0; j < visible; ++j) {
+        weights[j] = exp(weights[j] - top);
+        total += weights[j];
+    }
+    for (int64_t j = 0; j < visible; ++j) weights[j] /= total;
+    for (int64_t j = 0; j < visible; ++j) {
+        const int64_t page = table_row[j / ge->page_size], row = j % ge->page_size;
+        const uint8_t *v = v_pool + page * ge->stride_page + (int64_t)g * ge->stride_head + row * ge->stride_token;
+        const double p = weights[j];
+        for (int32_t c = 0; c < d; ++c) out[c] += p * (widen_e4m3(v[c]) * v_scale);
+    }
+    *lse = top + log(total);
+}
+
+/*
+ * Decode over an FP8 cache: as ta_oracle_paged_decode, with
+ *   k_pool, v_pool  uint8 E4M3 codes, layout per ge (strides in elements)
+ *   k_scale, v_scale  the fp32 scales of the call, widened by the caller
+ */
+void ta_oracle_paged_decode_fp8(const oracle_geom *ge, const uint16_t *q,
+                                const uint8_t *k_pool, const uint8_t *v_pool, double k_scale, double v_scale,
+                                const int32_t *block_table, int64_t table_stride,
+                                const int32_t *context_lens, int32_t batch,
+                                double *out, double *lse)
+{
+    const int32_t Hq = ge->num_q_heads, d = ge->head_dim;
+    int64_t longest = 1;
+    for (int32_t b = 0; b < batch; ++b)
+        if (context_lens[b] > longest) longest = context_lens[b];
+    const int64_t rows = (int64_t)batch * Hq;
+#pragma omp parallel
+    {
+        double *weights = (double *)malloc((size_t)longest * sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t r = 0; r < rows; ++r) {
+            const int32_t b = (int32_t)(r / Hq), h = (int32_t)(r % Hq);
+            attend_row_fp8(ge, q + r * d, h, k_pool, v_pool, k_scale, v_scale,
+                           block_table + (int64_t)b * table_stride, context_lens[b], weights,
+                           out + r * d, lse + r);
+        }
+        free(weights);
+    }
 }
 
 int ta_oracle_num_threads(void)

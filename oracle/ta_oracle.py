@@ -78,6 +78,8 @@ def _load():
         _lib.ta_oracle_kv_page_restore.restype = ctypes.c_int
         _lib.ta_oracle_kv_page_evict.restype = ctypes.c_int
         _lib.ta_oracle_kv_append.restype = None
+        _lib.ta_oracle_widen_e4m3.restype = None
+        _lib.ta_oracle_paged_decode_fp8.restype = None
     return _lib
 
 
@@ -113,6 +115,37 @@ def paged_decode(geom: Geometry, q, k_pool, v_pool, block_table, context_lens):
     lib.ta_oracle_paged_decode(
         ctypes.byref(g), _p(q), _p(k_pool), _p(v_pool), _p(block_table),
         ctypes.c_int64(stride), _p(context_lens), ctypes.c_int32(B), _p(out), _p(lse),
+    )
+    return out, lse
+
+
+def widen_e4m3(codes) -> np.ndarray:
+    """Values (float64) of OCP E4M3 codes given as uint8."""
+    lib = _load()
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    values = np.zeros(codes.shape, dtype=np.float64)
+    lib.ta_oracle_widen_e4m3(_p(codes), ctypes.c_int64(codes.size), _p(values))
+    return values
+
+
+def paged_decode_fp8(geom: Geometry, q, k_pool, v_pool, k_scale, v_scale, block_table, context_lens):
+    """Decode over an FP8 cache: q uint16 bf16 [B,Hq,d]; pools uint8 E4M3 codes; scales are the
+    call's fp32 scales (the value of a cached element is code value * scale)."""
+    lib = _load()
+    q = _u16(q)
+    k_pool, v_pool = np.ascontiguousarray(k_pool), np.ascontiguousarray(v_pool)
+    assert k_pool.dtype == np.uint8 and v_pool.dtype == np.uint8, "FP8 pools travel as uint8 codes"
+    block_table = _i32(block_table)
+    context_lens = _i32(context_lens)
+    B = int(context_lens.shape[0])
+    stride = int(block_table.shape[1]) if block_table.ndim == 2 else 0
+    out = np.zeros((B, geom.num_q_heads, geom.head_dim), dtype=np.float64)
+    lse = np.zeros((B, geom.num_q_heads), dtype=np.float64)
+    g = geom.c_struct()
+    lib.ta_oracle_paged_decode_fp8(
+        ctypes.byref(g), _p(q), _p(k_pool), _p(v_pool), ctypes.c_double(float(np.float32(k_scale))),
+        ctypes.c_double(float(np.float32(v_scale))), _p(block_table), ctypes.c_int64(stride),
+        _p(context_lens), ctypes.c_int32(B), _p(out), _p(lse),
     )
     return out, lse
 

@@ -367,6 +367,31 @@ def sharpen(wb: PagedBatch, factor: float = 4.0) -> None:
     wb.q.copy_((wb.q.float() * factor).to(torch.bfloat16))
 
 
+@dataclass
+class Fp8Cache:
+    """The K and V pools of a batch as 8-bit E4M3 codes plus the two scales of the call."""
+
+    k_codes: torch.Tensor           # uint8 [P, Hkv, page, d]
+    v_codes: torch.Tensor
+    k_scale: float                  # value of a cached key element = code value * k_scale
+    v_scale: float
+
+
+def to_fp8_cache(wb: PagedBatch, k_scale: float = 0.021, v_scale: float = 0.017) -> Fp8Cache:
+    """Quantise the bf16 pools of a batch to E4M3 codes with torch's own conversion
+    (x / scale -> float8_e4m3fn, round to nearest even).  With N(0,1) values and these scales the
+    codes stay far below the format's largest value (448).  NaN rows stay NaN (code 0x7f / 0xff).
+    Input preparation only: what the codes mean is each side's own business."""
+    k = (wb.k_pool.float() / float(np.float32(k_scale))).to(torch.float8_e4m3fn).view(torch.uint8)
+    v = (wb.v_pool.float() / float(np.float32(v_scale))).to(torch.float8_e4m3fn).view(torch.uint8)
+    return Fp8Cache(k.contiguous(), v.contiguous(), float(np.float32(k_scale)), float(np.float32(v_scale)))
+
+
+def as_u8(t: torch.Tensor) -> np.ndarray:
+    """uint8 tensor -> numpy on the host."""
+    return t.detach().contiguous().cpu().numpy()
+
+
 def as_u16(t: torch.Tensor) -> np.ndarray:
     """bf16 tensor -> numpy uint16 bit patterns on the host."""
     return t.detach().contiguous().cpu().view(torch.int16).numpy().view(np.uint16)
