@@ -86,9 +86,16 @@ class KernelTimer:
         return sum(t) / max(len(t), 1)
 
 
-def run_decode(wb, steps, warmup, torch, ta):
+def run_decode(wb, steps, warmup, torch, ta, fp8_cache=None):
+    """Times ta_paged_decode on a batch; with fp8_cache (workloads.Fp8Cache) over its E4M3 codes."""
     dev = wb.q.device
-    desc = ta.Desc(wb.num_q_heads, wb.num_kv_heads)
+    if fp8_cache is None:
+        desc = ta.Desc(wb.num_q_heads, wb.num_kv_heads)
+        k_pool, v_pool = wb.k_pool, wb.v_pool
+    else:
+        desc = ta.Desc(wb.num_q_heads, wb.num_kv_heads, kv_format=ta.KV_FP8_E4M3, k_scale=fp8_cache.k_scale,
+                       v_scale=fp8_cache.v_scale)
+        k_pool, v_pool = fp8_cache.k_codes, fp8_cache.v_codes
     bt = torch.from_numpy(wb.block_table).to(dev)
     cl = torch.from_numpy(wb.context_lens).to(dev)
     out = torch.empty_like(wb.q)
@@ -97,7 +104,7 @@ def run_decode(wb, steps, warmup, torch, ta):
     timer = KernelTimer(steps, torch, ta)
 
     def step():
-        ta.ta_paged_decode(desc, wb.q, wb.k_pool, wb.v_pool, bt, cl, wb.max_context_len, out, lse, ws)
+        ta.ta_paged_decode(desc, wb.q, k_pool, v_pool, bt, cl, wb.max_context_len, out, lse, ws)
 
     def timed_step():
         timer.arm()
@@ -565,6 +572,37 @@ def main():
         result["cpu_baseline"] = base
         result["config"]["parity_vs_oracle"] = spot_check(out, lse, ref_out, ref_lse, torch)
         del ref_out, ref_lse
+    fp8_leg = None
+    if args.only in ("all", "decode"):
+        # ---------------- the same batch with its cache as FP8 (E4M3) codes: half the bytes per token ----------------
+        import oracle
+
+        fc = wl.to_fp8_cache(wb)
+        f_ms, f_kernel_ms, f_out, f_lse = run_decode(wb, args.steps, args.warmup, torch, ta, fp8_cache=fc)
+        fp8_bytes = kv_bytes // 2
+        fp8_leg = {
+            "workload": "config 2 with the KV cache as E4M3 codes (2048 B per cached token and layer), scales "
+                        f"k {fc.k_scale:.4g} / v {fc.v_scale:.4g}",
+            "metric": "paged_decode_fp8_kv_gbps", "value": round(fp8_bytes / f_ms / 1e6, 1), "unit": "GB/s",
+            "ms_per_step": round(f_ms, 4), "kv_bytes_per_step": fp8_bytes, "dtype": "fp8 e4m3 cache, bf16 q/out, f32 accumulate",
+            "layer_tokens_per_s": round(wb.batch / f_ms * 1e3, 1),
+            "roofline": {"bound": "hbm", "kernel": "decode_fp8_kernel<false>",
+                         "achieved": round(fp8_bytes / f_kernel_ms / 1e6, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                         "frac": round(fp8_bytes / f_kernel_ms / 1e6 / HBM_PEAK_GBPS, 4),
+                         "kernel_ms": round(f_kernel_ms, 4), "traffic": None},
+        }
+        if not args.no_cpu_baseline:
+            t0 = time.perf_counter()
+            r_out, r_lse = oracle.paged_decode_fp8(oracle.Geometry(wb.num_q_heads, wb.num_kv_heads), wl.as_u16(wb.q),
+                                                   wl.as_u8(fc.k_codes), wl.as_u8(fc.v_codes), fc.k_scale, fc.v_scale,
+                                                   wb.block_table, wb.context_lens)
+            dt = time.perf_counter() - t0
+            fp8_leg["parity_vs_oracle"] = spot_check(f_out, f_lse, r_out, r_lse, torch)
+            fp8_leg["cpu_baseline"] = {"value": round(fp8_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": oracle.num_threads(),
+                                       "cpu": cpu_model(), "kind": "oracle",
+                                       "sample": f"all {wb.batch} programs x {wb.num_q_heads} query heads, {dt:.2f} s wall"}
+            del r_out, r_lse
+        del fc, f_out, f_lse
     if args.calibrate_copy:
         x = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
         y = torch.empty_like(x)
@@ -575,6 +613,8 @@ def main():
     torch.cuda.empty_cache()
 
     extra = {}
+    if fp8_leg is not None:
+        extra["fp8_decode"] = fp8_leg
     if args.only in ("all", "prefill"):
         # ---------------- append-prefill (MFMA) ----------------
         wb = wl.append_prefill(dev)

@@ -89,8 +89,28 @@ typedef struct ta_attn_desc {
                                    (by batch and context length), else 8, 16, 32, 64 or 128, and with
                                    eight query heads per kv head also 256.  The same value must be
                                    given to ta_workspace_bytes. */
-    int32_t reserved;          /* must be 0 */
+    int32_t kv_format;         /* TA_KV_BF16 (0) or TA_KV_FP8_E4M3 (1), see below */
+    float k_scale;             /* TA_KV_FP8_E4M3: a cached key element is code value * k_scale; > 0, finite */
+    float v_scale;             /* TA_KV_FP8_E4M3: a cached value element is code value * v_scale; > 0, finite */
 } ta_attn_desc;
+
+/*
+ * Formats of the K and V pools.
+ *   TA_KV_BF16      16-bit patterns, the upper half of an IEEE fp32 (k_scale, v_scale ignored).
+ *   TA_KV_FP8_E4M3  8-bit codes of the OCP "E4M3" format: 1 sign bit, 4 exponent bits with
+ *                   bias 7, 3 mantissa bits, no infinities, S.1111.111 = NaN, exponent field 0 =
+ *                   subnormals m * 2^-9, largest value 448; one fp32 scale for all keys and one
+ *                   for all values of the call.  (The paper serves its large models in FP8,
+ *                   Sec. 5.1; it does not describe the cache, so format and scale granularity
+ *                   are this library's reading.)  Pool strides count elements, i.e. bytes; a
+ *                   (page, kv head) tile is 2 KiB.  Supported by ta_paged_decode and
+ *                   ta_paged_decode_static (queries and outputs stay bf16: the output is
+ *                   softmax(scale * k_scale * <q, K codes>) . (V codes) * v_scale), and by the
+ *                   byte-wise ta_kv_page_restore / ta_kv_page_evict; ta_append_prefill and
+ *                   ta_kv_append return TA_ERR_UNSUPPORTED for it.
+ */
+#define TA_KV_BF16 0
+#define TA_KV_FP8_E4M3 1
 
 /* Library version, major*10000 + minor*100 + patch. */
 TA_API int32_t ta_version(void);
@@ -131,7 +151,8 @@ TA_API size_t ta_workspace_bytes(const ta_attn_desc *desc, int32_t batch, int32_
  * A program with context length 0 gets a zero row and lse = -inf.
  *
  *   q             DEVICE bf16 [batch][Hq][128]
- *   k_pool,v_pool DEVICE bf16, layout given by desc, read only, 16-byte aligned
+ *   k_pool,v_pool DEVICE bf16 (or E4M3 codes, see kv_format), layout given by desc, read only,
+ *                 16-byte aligned
  *   block_table   DEVICE int32 [batch][block_table_stride]
  *   context_lens  DEVICE int32 [batch]
  *   max_context_len  HOST upper bound on context_lens[]; sizes the launch, so no

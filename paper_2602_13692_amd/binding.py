@@ -24,6 +24,7 @@ TA_ERR_INVALID_ARG = -1
 TA_ERR_UNSUPPORTED = -2
 TA_ERR_HIP = -3
 TA_ERR_TOO_LARGE = -4
+KV_BF16, KV_FP8_E4M3 = 0, 1
 STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = (
@@ -55,7 +56,9 @@ class AttnDesc(ctypes.Structure):
         ("pool_stride_head", ctypes.c_int64),
         ("pool_stride_token", ctypes.c_int64),
         ("decode_chunk_pages", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("kv_format", ctypes.c_int32),
+        ("k_scale", ctypes.c_float),
+        ("v_scale", ctypes.c_float),
     ]
 
 
@@ -71,11 +74,15 @@ class Desc:
     pool_stride_token: int = 0
     pool_pages: int = 0
     decode_chunk_pages: int = 0
+    kv_format: int = 0          # KV_BF16 or KV_FP8_E4M3
+    k_scale: float = 0.0
+    v_scale: float = 0.0
 
     def c(self) -> AttnDesc:
         return AttnDesc(self.num_q_heads, self.num_kv_heads, self.head_dim, self.page_size,
                         self.scale, self.pool_pages, self.pool_stride_page, self.pool_stride_head,
-                        self.pool_stride_token, self.decode_chunk_pages, 0)
+                        self.pool_stride_token, self.decode_chunk_pages, self.kv_format, self.k_scale,
+                        self.v_scale)
 
 
 _LIB = None

@@ -29,7 +29,11 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
     if (d == nullptr) return TA_ERR_INVALID_ARG;
     if (d->num_q_heads <= 0 || d->num_kv_heads <= 0) return TA_ERR_INVALID_ARG;
     if (d->num_q_heads % d->num_kv_heads != 0) return TA_ERR_INVALID_ARG;
-    if (d->reserved != 0 || d->pool_pages < 0) return TA_ERR_INVALID_ARG;
+    if (d->pool_pages < 0) return TA_ERR_INVALID_ARG;
+    if (d->kv_format != TA_KV_BF16 && d->kv_format != TA_KV_FP8_E4M3) return TA_ERR_INVALID_ARG;
+    const bool fp8 = d->kv_format == TA_KV_FP8_E4M3;
+    if (fp8 && (!(d->k_scale > 0.0f) || !(d->v_scale > 0.0f) || std::isinf(d->k_scale) || std::isinf(d->v_scale)))
+        return TA_ERR_INVALID_ARG;
     if (!(d->scale >= 0.0f) || std::isinf(d->scale)) return TA_ERR_INVALID_ARG;  // also rejects NaN
     if (d->pool_stride_page < 0 || d->pool_stride_head < 0 || d->pool_stride_token < 0)
         return TA_ERR_INVALID_ARG;
@@ -41,10 +45,11 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
     const int64_t sh = d->pool_stride_head ? d->pool_stride_head : int64_t(kPageSize) * kHeadDim;
     const int64_t sp = d->pool_stride_page ? d->pool_stride_page : sh * d->num_kv_heads;
     // a (page, head) tile is read with 16-byte accesses
-    if (sh % 8 != 0 || sp % 8 != 0) return TA_ERR_UNSUPPORTED;
+    const int64_t elem_bytes = fp8 ? 1 : 2;
+    if ((sh * elem_bytes) % 16 != 0 || (sp * elem_bytes) % 16 != 0) return TA_ERR_UNSUPPORTED;
     if (sh < int64_t(kPageSize) * kHeadDim) return TA_ERR_INVALID_ARG;
     const int32_t cp = d->decode_chunk_pages;
-    if (cp != 0 && cp != 8 && cp != 16 && cp != 32 && cp != 64 && cp != 128 && !(cp == 256 && group == 8))
+    if (cp != 0 && cp != 8 && cp != 16 && cp != 32 && cp != 64 && cp != 128 && !(cp == 256 && group == 8 && !fp8))
         return TA_ERR_INVALID_ARG;
     g->num_q_heads = d->num_q_heads;
     g->num_kv_heads = d->num_kv_heads;
@@ -53,8 +58,11 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
     g->decode_chunk_pages = cp;
     g->scale = d->scale > 0.0f ? d->scale : 1.0f / std::sqrt(static_cast<float>(kHeadDim));
     g->scale_log2 = g->scale * kLog2e;
-    g->stride_page_bytes = sp * 2;
-    g->stride_head_bytes = sh * 2;
+    g->stride_page_bytes = sp * elem_bytes;
+    g->stride_head_bytes = sh * elem_bytes;
+    g->kv_fp8 = fp8;
+    g->k_scale = fp8 ? d->k_scale : 1.0f;
+    g->v_scale = fp8 ? d->v_scale : 1.0f;
     return TA_OK;
 }
 
@@ -66,7 +74,7 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
 static int32_t choose_chunk_pages(const Geometry& g, int32_t batch, int32_t max_context_len) {
     if (g.decode_chunk_pages != 0) return g.decode_chunk_pages;   // the caller's choice, validated with the descriptor
     const int64_t pages = (int64_t(max_context_len) + kPageSize - 1) / kPageSize;
-    if (g.group == 8) {
+    if (g.group == 8 && !g.kv_fp8) {
         // every chunk runs on the matrix-core tile kernel, whose per-item cost (filling the LDS
         // ring, writing 32 to 128 rows of partials) wants long items: up to 4096 tokens
         for (int32_t c : {256, 128}) {
@@ -95,10 +103,11 @@ WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_l
         w.chunk_pages = choose_chunk_pages(g, batch, max_context_len);
         // with eight heads per kv head every item runs on the tile kernel, which takes a program's
         // leftover as one item; the vector-ALU kernel gets it in quarters
-        w.rem_pages = g.group == 8 ? w.chunk_pages : (w.chunk_pages >= 32 ? w.chunk_pages / 4 : 8);
+        const bool all_on_tiles = g.group == 8 && !g.kv_fp8;
+        w.rem_pages = all_on_tiles ? w.chunk_pages : (w.chunk_pages >= 32 ? w.chunk_pages / 4 : 8);
         w.slots_per_program = static_cast<int32_t>(pages / w.chunk_pages + w.chunk_pages / w.rem_pages);
         w.max_chunks = static_cast<int32_t>(int64_t(batch) * w.slots_per_program);
-        w.direct = (g.group != 8 && pages <= w.chunk_pages) ? 1 : 0;
+        w.direct = (!all_on_tiles && pages <= w.chunk_pages) ? 1 : 0;
         w.max_tiles = 0;
         w.off_chunk_start = off; off = align256(off + sizeof(int32_t) * (size_t(batch) + 1));
         w.off_items = off;       off = align256(off + sizeof(int32_t) * 4 * size_t(w.max_chunks));
@@ -106,7 +115,7 @@ WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_l
         w.off_part_o = off;      off = align256(off + sizeof(float) * kHeadDim * size_t(w.max_chunks) * g.num_q_heads);
         // a shared chunk serves at least two programs; with eight heads per kv head every chunk
         // goes to the matrix-core kernel, one item each at most
-        w.max_shared_items = g.group == 8 ? w.max_chunks
+        w.max_shared_items = all_on_tiles ? w.max_chunks
                                           : static_cast<int32_t>((int64_t(batch) / 2) * (pages / w.chunk_pages));
         w.off_counts = off;      off = align256(off + sizeof(int32_t) * 4);
         w.off_lcp = off;         off = align256(off + sizeof(int32_t) * size_t(batch));
@@ -361,6 +370,7 @@ int ta_append_prefill(const ta_attn_desc* desc, const void* q, const int32_t* cu
     Geometry g;
     int rc = resolve_geometry(desc, &g);
     if (rc != TA_OK) return rc;
+    if (g.kv_fp8) return TA_ERR_UNSUPPORTED;
     if (batch < 0 || total_q < 0 || max_q_len < 0 || max_context_len < 0 || block_table_stride < 0)
         return TA_ERR_INVALID_ARG;
     if (batch == 0 || total_q == 0) return TA_OK;
@@ -458,6 +468,7 @@ int ta_kv_append(const ta_attn_desc* desc, const void* new_k, const void* new_v,
     Geometry g{};
     const int rc = resolve_geometry(desc, &g);
     if (rc != TA_OK) return rc;
+    if (g.kv_fp8) return TA_ERR_UNSUPPORTED;
     if (batch < 0 || total_new < 0 || block_table_stride < 0) return TA_ERR_INVALID_ARG;
     if (batch == 0 || total_new == 0) return TA_OK;
     if (!new_k || !new_v || !cu_new_lens || !k_pool || !v_pool || !block_table || !context_lens)

@@ -310,30 +310,6 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
 // ---------------------------------------------------------------------------
 // chunk kernel
 // ---------------------------------------------------------------------------
-struct ChunkParams {
-    const uint16_t* q;
-    const char* k_pool;
-    const char* v_pool;
-    const int32_t* block_table;
-    const int32_t* context_lens;
-    const int32_t* counts;       // counts[0] = number of items
-    const int4* items;           // (program, first page, pages, slot)
-    float* part_ml;
-    float* part_o;
-    uint16_t* out;               // DIRECT only
-    float* lse;                  // DIRECT only, may be null
-    int64_t stride_page_bytes;
-    int64_t stride_head_bytes;
-    int32_t block_table_stride;
-    int32_t batch;
-    int32_t num_q_heads;
-    int32_t num_kv_heads;
-    int32_t max_pages;           // DIRECT only: pages the launch was sized for
-    float scale_log2;
-};
-
-constexpr int kMaxItemPages = 128;   // two page ids per lane
-
 struct PageRegs {
     u32x4 k[4];  // k[i]: token 4*i + (lane / 16), dims 8 * (lane % 16) .. + 7
     u32x4 v[4];
@@ -630,6 +606,7 @@ struct MergeParams {
     float* lse;
     int32_t batch;
     int32_t num_q_heads;
+    float out_scale;     // 1, or the value scale of an fp8 cache
 };
 
 __global__ __launch_bounds__(256) void decode_merge_kernel(MergeParams p) {
@@ -657,7 +634,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(MergeParams p) {
         o0 = fmaf(v.x, wt, o0);
         o1 = fmaf(v.y, wt, o1);
     }
-    const float inv = lt > 0.0f ? 1.0f / lt : 0.0f;
+    const float inv = lt > 0.0f ? p.out_scale / lt : 0.0f;
     const uint32_t packed = uint32_t(to_bf16_rne(o0 * inv)) | (uint32_t(to_bf16_rne(o1 * inv)) << 16);
     reinterpret_cast<uint32_t*>(p.out + rid * kHeadDim)[lane] = packed;
     if (p.lse != nullptr && lane == 0)
@@ -684,7 +661,8 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     cp.num_q_heads = g.num_q_heads;
     cp.num_kv_heads = g.num_kv_heads;
     cp.max_pages = (a.max_context_len + kPageSize - 1) / kPageSize;
-    cp.scale_log2 = g.scale_log2;
+    cp.scale_log2 = g.kv_fp8 ? g.scale_log2 * g.k_scale : g.scale_log2;
+    cp.out_scale = g.kv_fp8 ? g.v_scale : 1.0f;
 
     if (w.direct) {
         // short contexts: one launch, one workgroup per (program, kv head), output written directly
@@ -692,13 +670,18 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
         if (blocks > 0x7fffffff || cp.max_pages > kMaxItemPages) return TA_ERR_INVALID_ARG;
         const dim3 grid(static_cast<unsigned>(blocks)), block(kChunkThreads);
         if (ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
-        switch (g.group) {
-            case 1: hipLaunchKernelGGL((decode_chunk_kernel<1, true>), grid, block, 0, stream, cp); break;
-            case 2: hipLaunchKernelGGL((decode_chunk_kernel<2, true>), grid, block, 0, stream, cp); break;
-            case 4: hipLaunchKernelGGL((decode_chunk_kernel<4, true>), grid, block, 0, stream, cp); break;
-            default: return TA_ERR_UNSUPPORTED;
+        if (g.kv_fp8) {
+            const int rc = launch_fp8_items(cp, g.group, true, grid.x, stream);
+            if (rc != TA_OK) return rc;
+        } else {
+            switch (g.group) {
+                case 1: hipLaunchKernelGGL((decode_chunk_kernel<1, true>), grid, block, 0, stream, cp); break;
+                case 2: hipLaunchKernelGGL((decode_chunk_kernel<2, true>), grid, block, 0, stream, cp); break;
+                case 4: hipLaunchKernelGGL((decode_chunk_kernel<4, true>), grid, block, 0, stream, cp); break;
+                default: return TA_ERR_UNSUPPORTED;
+            }
+            TA_HIP_TRY(hipGetLastError());
         }
-        TA_HIP_TRY(hipGetLastError());
         if (ev.stop != nullptr) TA_HIP_TRY(hipEventRecord(ev.stop, stream));
         return TA_OK;
     }
@@ -713,12 +696,13 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     int32_t* order = reinterpret_cast<int32_t*>(workspace + w.off_order);
     int4* shared_items = reinterpret_cast<int4*>(workspace + w.off_shared_items);
     // sharing needs at least two programs with a bulk chunk each and a non-empty block table
-    const bool look_for_sharing = a.batch >= 2 && a.batch <= 1024 && w.max_shared_items > 0 &&
+    // (pools of fp8 codes take every chunk through their own item kernel: no sharing there)
+    const bool look_for_sharing = !g.kv_fp8 && a.batch >= 2 && a.batch <= 1024 && w.max_shared_items > 0 &&
                                   a.block_table_stride > 0 && cp.max_pages >= w.chunk_pages;
     // Eight query heads per kv head leave the vector-ALU kernel one wave per SIMD (its per-head
     // state fills the register file) and make it compute-bound; the matrix-core kernel takes
     // the private chunks too, as groups of one program.
-    const bool private_on_tiles = g.group == 8;   // the workspace plan sizes shared_items for it
+    const bool private_on_tiles = g.group == 8 && !g.kv_fp8;   // the workspace plan sizes shared_items for it
 
     if (look_for_sharing) {
         hipLaunchKernelGGL(predecessor_prefix_kernel, dim3(a.batch), dim3(256), 0, stream, a.block_table,
@@ -763,13 +747,18 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
         if (blocks > 0x7fffffff || w.chunk_pages > kMaxItemPages) return TA_ERR_INVALID_ARG;
         const dim3 grid(static_cast<unsigned>(blocks)), block(kChunkThreads);
         if (ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
-        switch (g.group) {
-            case 1: hipLaunchKernelGGL((decode_chunk_kernel<1, false>), grid, block, 0, stream, cp); break;
-            case 2: hipLaunchKernelGGL((decode_chunk_kernel<2, false>), grid, block, 0, stream, cp); break;
-            case 4: hipLaunchKernelGGL((decode_chunk_kernel<4, false>), grid, block, 0, stream, cp); break;
-            default: return TA_ERR_UNSUPPORTED;
+        if (g.kv_fp8) {
+            const int rc = launch_fp8_items(cp, g.group, false, grid.x, stream);
+            if (rc != TA_OK) return rc;
+        } else {
+            switch (g.group) {
+                case 1: hipLaunchKernelGGL((decode_chunk_kernel<1, false>), grid, block, 0, stream, cp); break;
+                case 2: hipLaunchKernelGGL((decode_chunk_kernel<2, false>), grid, block, 0, stream, cp); break;
+                case 4: hipLaunchKernelGGL((decode_chunk_kernel<4, false>), grid, block, 0, stream, cp); break;
+                default: return TA_ERR_UNSUPPORTED;
+            }
+            TA_HIP_TRY(hipGetLastError());
         }
-        TA_HIP_TRY(hipGetLastError());
         if (ev.stop != nullptr) TA_HIP_TRY(hipEventRecord(ev.stop, stream));
     }
 
@@ -781,6 +770,7 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     mp.lse = a.lse;
     mp.batch = a.batch;
     mp.num_q_heads = g.num_q_heads;
+    mp.out_scale = g.kv_fp8 ? g.v_scale : 1.0f;
     const int64_t rows = int64_t(a.batch) * g.num_q_heads;
     hipLaunchKernelGGL(decode_merge_kernel, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0,
                        stream, mp);

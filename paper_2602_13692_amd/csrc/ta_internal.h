@@ -40,6 +40,9 @@ struct Geometry {
     int32_t group;            // Hq / Hkv
     int32_t pool_pages;       // pages per pool as stated by the caller (0 = not stated; debug checks only)
     int32_t decode_chunk_pages;  // the caller's split-K chunk length, 0 = chosen by the library
+    bool kv_fp8;              // pools hold E4M3 codes (one byte per element)
+    float k_scale;            // fp8 only
+    float v_scale;            // fp8 only
     float scale;              // multiplies q.k
     float scale_log2;         // scale * log2(e)
     int64_t stride_page_bytes;
@@ -96,6 +99,34 @@ struct DecodeArgs {
 
 int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout& w, char* workspace,
                   hipStream_t stream);
+
+// Arguments of the kernels that work through the decode items (one workgroup per item and kv head).
+struct ChunkParams {
+    const uint16_t* q;
+    const char* k_pool;
+    const char* v_pool;
+    const int32_t* block_table;
+    const int32_t* context_lens;
+    const int32_t* counts;       // counts[0] = number of items
+    const int4* items;           // (program, first page, pages, slot)
+    float* part_ml;
+    float* part_o;
+    uint16_t* out;               // direct mode only
+    float* lse;                  // direct mode only, may be null
+    int64_t stride_page_bytes;
+    int64_t stride_head_bytes;
+    int32_t block_table_stride;
+    int32_t batch;
+    int32_t num_q_heads;
+    int32_t num_kv_heads;
+    int32_t max_pages;           // direct mode only: pages the launch was sized for
+    float scale_log2;            // fp8: the key scale is folded in
+    float out_scale;             // fp8 direct mode: the value scale (1 otherwise)
+};
+constexpr int kMaxItemPages = 128;   // two page ids per lane
+
+// The item kernel for pools of E4M3 codes (matrix cores, any group size up to 16).
+int launch_fp8_items(const ChunkParams& p, int32_t group, bool direct, unsigned blocks, hipStream_t stream);
 
 struct PrefillArgs {
     const uint16_t* q;

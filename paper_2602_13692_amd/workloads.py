@@ -362,6 +362,28 @@ def plant_needles(wb: PagedBatch, seed: int, strength: float = 30.0) -> np.ndarr
     return pos
 
 
+def plant_needles_prefill(wb: PagedBatch, seed: int, programs, strength: float = 30.0):
+    """Append-prefill batches: for each given program and every kv head, one new token's first query
+    head of the group gets a dominating key at a random visible position (as plant_needles).
+    Returns the (program, new token, query head) rows whose softmax is dominated."""
+    rng = np.random.default_rng(seed)
+    group = wb.num_q_heads // wb.num_kv_heads
+    ps = wb.page_size
+    cu = wb.cu_q_lens
+    qf = wb.q
+    rows = []
+    for b in programs:
+        n, L = int(wb.q_lens[b]), int(wb.context_lens[b])
+        for g in range(wb.num_kv_heads):
+            i = int(rng.integers(0, n))
+            j = int(rng.integers(0, L - n + i + 1))
+            qv = qf[int(cu[b]) + i, g * group].float()
+            key = qv * (strength * math.sqrt(wb.head_dim) / float((qv * qv).sum()))
+            wb.k_pool[int(wb.block_table[b, j // ps]), g, j % ps] = key.to(torch.bfloat16)
+            rows.append((int(b), i, g * group))
+    return rows
+
+
 def sharpen(wb: PagedBatch, factor: float = 4.0) -> None:
     """Scale the queries so that the softmax concentrates on few keys."""
     wb.q.copy_((wb.q.float() * factor).to(torch.bfloat16))

@@ -10,9 +10,15 @@ ABS_TOL = 2e-2      # contract: |gpu - oracle| <= 2e-2 + 1e-2 * |oracle| (bf16 i
 REL_TOL = 1e-2
 ROW_L2_TOL = 1e-2   # tighter gates of our own: relative L2 error per output row ...
 LSE_TOL = 2e-3      # ... and the log-sum-exp, which a zero output could not fake
-# Append-prefill sums the bf16-ROUNDED weights (the ones the matrix core multiplies), so when one
-# key dominates a row the sum carries that weight's rounding error, at most 2^-8 relative.
-LSE_TOL_PREFILL = 5e-3
+# The matrix-core kernels sum the bf16-ROUNDED weights (the ones the matrix core multiplies): a
+# bf16 has 8 significant bits, so each weight is off by at most 2^-8 relative (half a step of
+# 2^-7 just above a power of two), hence so is the sum, and |lse error| <= ln(1 + 2^-8) = 3.9e-3
+# whatever the input; the bound is approached when one key dominates a row (3.3e-3 seen with
+# planted needles).  fp32 rounding comes on top.
+LSE_TOL_PREFILL = 4.5e-3
+# With many keys of comparable weight (N(0,1) inputs at long context) the rounding errors average
+# out; observed 1.1e-4 on the full-size workloads.
+LSE_TOL_PREFILL_DIFFUSE = 5e-4
 
 
 def widen_bf16(t: torch.Tensor) -> np.ndarray:
@@ -38,6 +44,26 @@ def gpu_decode(wb, stream=None, chunk_pages=0):
     ta.ta_paged_decode(desc, wb.q, wb.k_pool, wb.v_pool, bt, cl, wb.max_context_len, out, lse, ws, stream)
     torch.cuda.synchronize()
     return out, lse
+
+
+def gpu_decode_fp8(wb, fc, stream=None, chunk_pages=0):
+    """Decode over the batch's cache as E4M3 codes (fc: workloads.Fp8Cache)."""
+    dev = wb.q.device
+    desc = desc_of(wb, decode_chunk_pages=chunk_pages, kv_format=ta.KV_FP8_E4M3, k_scale=fc.k_scale,
+                   v_scale=fc.v_scale)
+    bt = torch.from_numpy(wb.block_table).to(dev)
+    cl = torch.from_numpy(wb.context_lens).to(dev)
+    out = torch.full_like(wb.q, float("nan"))
+    lse = torch.full((wb.batch, wb.num_q_heads), float("nan"), dtype=torch.float32, device=dev)
+    ws = ta.alloc_workspace(desc, wb.batch, 1, wb.max_context_len, dev)
+    ta.ta_paged_decode(desc, wb.q, fc.k_codes, fc.v_codes, bt, cl, wb.max_context_len, out, lse, ws, stream)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def oracle_decode_fp8(wb, fc):
+    return oracle.paged_decode_fp8(geom_of(wb), wl.as_u16(wb.q), wl.as_u8(fc.k_codes), wl.as_u8(fc.v_codes),
+                                   fc.k_scale, fc.v_scale, wb.block_table, wb.context_lens)
 
 
 def gpu_prefill(wb, stream=None):
@@ -111,29 +137,46 @@ def compact_programs(wb, programs):
 
 
 def check_sampled_rows(wb, gpu_out, gpu_lse, rng, n_programs=6, rows_per_program=8, what="",
-                       lse_tol=LSE_TOL):
-    """Compare sampled (program, new token, head) rows of a full-size run with the oracle."""
+                       lse_tol=LSE_TOL, dense_programs=0, dense_tokens=64, extra_rows=()):
+    """Compare sampled (program, new token, head) rows of a full-size run with the oracle.
+
+    n_programs programs contribute rows_per_program random rows each plus their first and last new
+    token; the first dense_programs of them contribute ALL heads of dense_tokens consecutive new
+    tokens (a whole tile of rows, across a tile boundary); extra_rows are (program, token, head)
+    triples that must be among the rows (planted needles).
+    """
     programs = sorted(rng.choice(wb.batch, size=min(n_programs, wb.batch), replace=False).tolist())
     # always include the longest context: it crosses the most chunks / tiles
     longest = int(np.argmax(wb.context_lens))
     if longest not in programs:
         programs[0] = longest
         programs.sort()
+    for b, _, _ in extra_rows:
+        if b not in programs:
+            programs.append(int(b))
+    local_of = {b: i for i, b in enumerate(programs)}
     k_small, v_small, table = compact_programs(wb, programs)
     cu = wb.cu_q_lens
     row_b, row_t, row_h, row_vis = [], [], [], []
-    for local, b in enumerate(programs):
+
+    def add(b, i, h):
+        n, L = int(wb.q_lens[b]), int(wb.context_lens[b])
+        row_b.append(local_of[b]); row_t.append(int(cu[b]) + i); row_h.append(h); row_vis.append(L - n + i + 1)
+
+    for b, i, h in extra_rows:
+        add(int(b), int(i), int(h))
+    for rank, b in enumerate(programs[: n_programs]):
         n = int(wb.q_lens[b])
-        L = int(wb.context_lens[b])
         for _ in range(rows_per_program):
-            i = int(rng.integers(0, n))
-            row_b.append(local)
-            row_t.append(int(cu[b]) + i)
-            row_h.append(int(rng.integers(0, wb.num_q_heads)))
-            row_vis.append(L - n + i + 1)
+            add(b, int(rng.integers(0, n)), int(rng.integers(0, wb.num_q_heads)))
         # the last new token sees everything, the first sees only the prefix and itself
         for i in (0, n - 1):
-            row_b.append(local); row_t.append(int(cu[b]) + i); row_h.append(0); row_vis.append(L - n + i + 1)
+            add(b, i, 0)
+        if rank < dense_programs:
+            first = int(rng.integers(0, max(n - dense_tokens, 0) + 1))
+            for i in range(first, min(n, first + dense_tokens)):
+                for h in range(wb.num_q_heads):
+                    add(b, i, h)
     ref, ref_lse = oracle.attend_rows(geom_of(wb), wl.as_u16(wb.q), k_small, v_small, table,
                                       row_b, row_t, row_h, row_vis)
     t = torch.tensor(row_t, device=gpu_out.device)

@@ -91,6 +91,15 @@ def test_host_side_rejections_need_no_device():
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=256), 4, 1, 100) == 0
     assert ta.ta_workspace_bytes(ta.Desc(64, 8, decode_chunk_pages=256), 4, 1, 100) > 0
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, pool_pages=-1), 4, 1, 100) == 0
+    # the FP8 cache format needs its two scales, positive and finite; other formats do not exist
+    fp8 = dict(kv_format=ta.KV_FP8_E4M3)
+    assert ta.ta_workspace_bytes(ta.Desc(32, 8, k_scale=0.02, v_scale=0.02, **fp8), 4, 1, 100) > 0
+    assert ta.ta_workspace_bytes(ta.Desc(64, 8, k_scale=0.02, v_scale=0.02, **fp8), 64, 1, 32768) > 0
+    assert ta.ta_workspace_bytes(ta.Desc(32, 8, k_scale=0.0, v_scale=0.02, **fp8), 4, 1, 100) == 0
+    assert ta.ta_workspace_bytes(ta.Desc(32, 8, k_scale=0.02, v_scale=-1.0, **fp8), 4, 1, 100) == 0
+    assert ta.ta_workspace_bytes(ta.Desc(32, 8, k_scale=float("inf"), v_scale=1.0, **fp8), 4, 1, 100) == 0
+    assert ta.ta_workspace_bytes(ta.Desc(32, 8, kv_format=2, k_scale=1.0, v_scale=1.0), 4, 1, 100) == 0
+    assert ta.ta_workspace_bytes(ta.Desc(64, 8, decode_chunk_pages=256, k_scale=1.0, v_scale=1.0, **fp8), 4, 1, 100) == 0
     # the measurement aids (their own library) reject missing or misaligned buffers and bad sizes
     probe = ta._probe_lib()
     assert probe.ta_matrix_core_probe(null, 10, null, null) == -1

@@ -1,6 +1,9 @@
 """GPU parity at the full sizes of the five workload configurations, in the launch
-configuration the benchmark times: sampled output rows against the oracle, plus
-properties that hold at any size."""
+configuration the benchmark times.  Where the oracle finishes the whole batch in seconds
+(decode: configurations 2, 4 and 5) every output row is compared; append-prefill
+(configuration 3, minutes for the oracle) is compared on whole tiles of rows of some programs
+plus rows of every program.  Needle and sharpened variants make outputs of magnitude O(1), where
+the relative term of the tolerance bites, on every kernel path."""
 import numpy as np
 import pytest
 import torch
@@ -19,17 +22,34 @@ def _free():
     torch.cuda.empty_cache()
 
 
-def test_config2_llama8b_decode_full_size():
+def test_config2_llama8b_decode_full_size_every_row():
     wb = wl.llama8b_decode(DEV)
     assert wb.batch == 64 and 4096 <= wb.context_lens.min() and wb.context_lens.max() <= 32768
     out, lse = gu.gpu_decode(wb)
-    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
-    err, rel = gu.check_sampled_rows(wb, out, lse, np.random.default_rng(2), what="config 2")
-    # needle variant on the same batch: outputs of magnitude O(1), where the relative term bites
-    wl.plant_needles(wb, seed=22)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, "config 2")
+    # needle variant on the same batch: outputs of magnitude O(1)
+    pos = wl.plant_needles(wb, seed=22)
     out, lse = gu.gpu_decode(wb)
-    gu.check_sampled_rows(wb, out, lse, np.random.default_rng(3), what="config 2 + needles")
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, "config 2 + needles")
+    assert (pos >= 0).all() and np.abs(ref[:, ::4]).max() > 0.5
     del wb, out, lse
+    _free()
+
+
+def test_config2_fp8_cache_full_size_every_row():
+    wb = wl.llama8b_decode(DEV)
+    fc = wl.to_fp8_cache(wb)
+    out, lse = gu.gpu_decode_fp8(wb, fc)
+    ref, ref_lse = gu.oracle_decode_fp8(wb, fc)
+    gu.assert_close(out, lse, ref, ref_lse, "config 2, fp8 cache", lse_tol=gu.LSE_TOL_PREFILL_DIFFUSE)
+    wl.sharpen(wb, 4.0)
+    out, lse = gu.gpu_decode_fp8(wb, fc)
+    ref, ref_lse = gu.oracle_decode_fp8(wb, fc)
+    gu.assert_close(out, lse, ref, ref_lse, "config 2, fp8 cache, sharpened", lse_tol=gu.LSE_TOL_PREFILL)
+    assert np.abs(ref).max() > 0.3
+    del wb, fc, out, lse
     _free()
 
 
@@ -38,18 +58,36 @@ def test_config3_append_prefill_full_size():
     assert wb.batch == 64 and wb.q_lens.min() >= 256 and wb.q_lens.max() <= 2048
     out, lse = gu.gpu_prefill(wb)
     assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
-    gu.check_sampled_rows(wb, out, lse, np.random.default_rng(4), n_programs=5, rows_per_program=10,
-                          what="config 3", lse_tol=gu.LSE_TOL_PREFILL)
+    # every program contributes rows; four of them whole tiles of rows (all 32 heads of 96 tokens)
+    gu.check_sampled_rows(wb, out, lse, np.random.default_rng(4), n_programs=wb.batch, rows_per_program=14,
+                          dense_programs=4, dense_tokens=96, what="config 3",
+                          lse_tol=gu.LSE_TOL_PREFILL_DIFFUSE)
+    # needles: one dominated row per kv head in twelve programs; and sharpened queries
+    needle_rows = wl.plant_needles_prefill(wb, seed=33, programs=list(range(0, wb.batch, 6)))
+    out, lse = gu.gpu_prefill(wb)
+    gu.check_sampled_rows(wb, out, lse, np.random.default_rng(41), n_programs=4, rows_per_program=6,
+                          extra_rows=needle_rows, what="config 3 + needles", lse_tol=gu.LSE_TOL_PREFILL)
+    wl.sharpen(wb, 4.0)
+    out, lse = gu.gpu_prefill(wb)
+    gu.check_sampled_rows(wb, out, lse, np.random.default_rng(42), n_programs=12, rows_per_program=10,
+                          what="config 3 sharpened", lse_tol=gu.LSE_TOL_PREFILL)
     del wb, out, lse
     _free()
 
 
-def test_config4_forked_decode_full_size():
+def test_config4_forked_decode_full_size_every_row():
     wb = wl.forked_decode(DEV)
     assert wb.batch == 256 and wb.num_q_heads == 64
     out, lse = gu.gpu_decode(wb)
-    assert torch.isfinite(out.float()).all()
-    gu.check_sampled_rows(wb, out, lse, np.random.default_rng(5), what="config 4")
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, "config 4", lse_tol=gu.LSE_TOL_PREFILL_DIFFUSE)
+    # needles sit in the private suffixes (shared pages are skipped): the matrix-core decode path
+    # with eight heads per kv head gets outputs of magnitude O(1)
+    pos = wl.plant_needles(wb, seed=44)
+    out, lse = gu.gpu_decode(wb)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, "config 4 + needles", lse_tol=gu.LSE_TOL_PREFILL)
+    assert (pos >= 0).sum() > 0.05 * pos.size and np.abs(ref).max() > 0.5
     # property: two members of a group given the same query and truncated to the shared prefix agree
     wb.q[1] = wb.q[0]
     wb.context_lens[:2] = wb.notes["prefix_len"]
@@ -60,7 +98,22 @@ def test_config4_forked_decode_full_size():
     _free()
 
 
-def test_config5_restore_then_decode_full_size():
+def test_config4_in_shuffled_batch_order_every_row():
+    """The 256 programs of configuration 4 in shuffled order: same results as the oracle, and the
+    groups are still found (the benchmark shows the same step time for both orders)."""
+    wb = wl.forked_decode(DEV)
+    perm = np.random.default_rng(wl.SEED_BASE + 44).permutation(wb.batch)
+    wb.q = wb.q[torch.from_numpy(perm).to(DEV)].contiguous()
+    wb.block_table = np.ascontiguousarray(wb.block_table[perm])
+    wb.context_lens = np.ascontiguousarray(wb.context_lens[perm])
+    out, lse = gu.gpu_decode(wb)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, "config 4 shuffled", lse_tol=gu.LSE_TOL_PREFILL_DIFFUSE)
+    del wb, out, lse
+    _free()
+
+
+def test_config5_restore_then_decode_full_size_every_row():
     wb = wl.long_horizon_restore(DEV)
     assert wb.batch == 128 and wb.context_lens.max() <= 131072
     rs = wb.restore
@@ -85,19 +138,7 @@ def test_config5_restore_then_decode_full_size():
     assert torch.equal(wb.k_pool.index_select(0, keep_t).view(torch.int16), before_k.view(torch.int16))
     assert torch.equal(wb.v_pool.index_select(0, keep_t).view(torch.int16), before_v.view(torch.int16))
     out, lse = gu.gpu_decode(wb)
-    assert torch.isfinite(out.float()).all()
-    rng = np.random.default_rng(6)
-    gu.check_sampled_rows(wb, out, lse, rng, what="config 5 (all programs)")
-    # and specifically rows of restored programs
-    restored = rs.programs[:4].tolist()
-    k_small, v_small, table = gu.compact_programs(wb, restored)
-    rows_b = list(range(len(restored))) * 2
-    rows_t = restored * 2
-    rows_h = [0] * len(restored) + [31] * len(restored)
-    vis = [int(wb.context_lens[b]) for b in restored] * 2
-    ref, ref_lse = oracle.attend_rows(gu.geom_of(wb), wl.as_u16(wb.q), k_small, v_small, table,
-                                      rows_b, rows_t, rows_h, vis)
-    t = torch.tensor(rows_t, device=DEV); h = torch.tensor(rows_h, device=DEV)
-    gu.assert_close(out[t, h], lse[t, h], ref, ref_lse, "config 5 (restored programs)")
+    ref, ref_lse = gu.oracle_decode(wb)            # every row, restored programs included
+    gu.assert_close(out, lse, ref, ref_lse, "config 5 after the restore")
     del wb, out, lse
     _free()
