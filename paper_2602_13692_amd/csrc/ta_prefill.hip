@@ -348,7 +348,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     };
     auto load_step = [&](int64_t page_off, int slot, int i) __attribute__((always_inline)) {
         const uint32_t dst = lds_base + slot * kSlotBytes + (i >> 1) * kTileBytes + wave * 2048 + (i & 1) * 1024;
-        const char* src = ((i >> 1) ? v_head : k_head) + page_off + ((i >> 1) ? dma_v[i & 1] : dma_k[i & 1]);
+        // the page's address is the same for all lanes (scalar registers, scalar adds); a lane adds
+        // only the 32-bit offset of its chunk, so starting a load takes no vector instruction
+        const char* page = ((i >> 1) ? v_head : k_head) + page_off;
+        const uint32_t chunk = (i >> 1) ? dma_v[i & 1] : dma_k[i & 1];
         // Written as assembly on purpose: for the builtin form the compiler assumes that every
         // later LDS read may touch the bytes in flight and waits for the load right away.  The
         // waits are placed by hand instead (finish_tile), one per tile.  The instruction takes
@@ -356,9 +359,9 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
         // statement to change: the statement puts back the value it found.
         uint32_t saved_m0;
         asm volatile(
-            "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+            "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
             : "=&s"(saved_m0)
-            : "s"(dst), "v"(src)
+            : "s"(dst), "v"(chunk), "s"(page)
             : "memory");
     };
     auto load_tile = [&](int t, int slot) __attribute__((always_inline)) {
@@ -415,6 +418,38 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     };
     auto v_operand_at = [&](const char* vt, int kb, int idx) __attribute__((always_inline)) {   // idx = 4 step + dim block
         const char* at = vt + (kb * 32 + (idx >> 2) * 16) * 256 + v_rd[idx & 3];
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(TA_LDS_PTR(s16x4, at));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(TA_LDS_PTR(s16x4, at + 8 * 256));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    // The same reads for the pipelined body, where the slot is a compile-time value.  An LDS
+    // instruction carries a 16-bit offset, and the ring is 128 KiB: for the upper two slots the
+    // per-lane part lives in a second set of registers that already holds + 64 KiB, so that no
+    // read needs a vector add for its address.  (The value is hidden from the compiler, which
+    // would otherwise recompute it at every use, and masked so it is known to be non-negative,
+    // which the offset folding requires.)
+    int k_rd_hi[8], v_rd_hi[4];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        int x = k_rd[ks] + 65536;
+        asm volatile("" : "+v"(x));
+        k_rd_hi[ks] = x & 0x1ffff;
+    }
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+        int x = v_rd[db] + 65536;
+        asm volatile("" : "+v"(x));
+        v_rd_hi[db] = x & 0x1ffff;
+    }
+    auto k_operand_in = [&](auto slot_tag, int kb, int ks) __attribute__((always_inline)) {
+        constexpr int S = decltype(slot_tag)::value;
+        const int lane_part = S >= 2 ? k_rd_hi[ks] : k_rd[ks];
+        return *reinterpret_cast<const bf16x8*>(lds + (S & 1) * kSlotBytes + kb * 32 * 256 + lane_part);
+    };
+    auto v_operand_in = [&](auto slot_tag, int kb, int idx) __attribute__((always_inline)) {
+        constexpr int S = decltype(slot_tag)::value;
+        const int lane_part = S >= 2 ? v_rd_hi[idx & 3] : v_rd[idx & 3];
+        const char* at = lds + (S & 1) * kSlotBytes + kTileBytes + (kb * 32 + (idx >> 2) * 16) * 256 + lane_part;
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(TA_LDS_PTR(s16x4, at));
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(TA_LDS_PTR(s16x4, at + 8 * 256));
         return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -530,7 +565,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     // Region X: scores of the next block (matrix core) with the weights of the current block
     // (vector ALU).  Slice ks turns scores 2 ks and 2 ks + 1 into weights.
     bf16x8 ka[8], va[8];
-    auto region_scores_weights = [&](const char* kt, int kb, f32x16 (&s_new)[kRB], const f32x16 (&s_old)[kRB],
+    auto region_scores_weights = [&](auto&& read_k, f32x16 (&s_new)[kRB], const f32x16 (&s_old)[kRB],
                                      bf16x8 (&pf)[kRB][2], auto&& prefetch_next) __attribute__((always_inline)) {
         const uint32_t ones = 0x3f803f80u;   // (1.0, 1.0) in bf16
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -543,7 +578,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {
                 s_new[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[rb][ks], ks == 0 ? zero : s_new[rb], 0, 0, 0);
-                if (rb == 0 && ks + kKAhead < 8) ka[ks + kKAhead] = k_operand_at(kt, kb, ks + kKAhead);
+                if (rb == 0 && ks + kKAhead < 8) ka[ks + kKAhead] = read_k(ks + kKAhead);
                 if (rb == kRB - 1 && ks >= 8 - kVAhead) prefetch_next(ks - (8 - kVAhead));
                 const float p0 = __builtin_amdgcn_exp2f(fmaf(s_old[rb][2 * ks], p.scale_log2, bias[rb]));
                 const float p1 = __builtin_amdgcn_exp2f(fmaf(s_old[rb][2 * ks + 1], p.scale_log2, bias[rb]));
@@ -567,7 +602,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     };
     // Region Y: O^T += V^T P^T (matrix core) with the row maxima of the next block's scores
     // (vector ALU).  The maxima start four slices in, when the scores have left the matrix core.
-    auto region_accumulate_maxima = [&](const char* vt, int kb, const bf16x8 (&pf)[kRB][2], const f32x16 (&s_new)[kRB],
+    auto region_accumulate_maxima = [&](auto&& read_v, const bf16x8 (&pf)[kRB][2], const f32x16 (&s_new)[kRB],
                                         bool use_new, auto&& staging_step, auto&& prefetch_next)
                                         __attribute__((always_inline)) {
         float mx[kRB];
@@ -580,7 +615,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
             for (int rb = 0; rb < kRB; ++rb) {
                 o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[idx], pf[rb][step], o[db][rb], 0, 0, 0);
                 if (rb == 0) {
-                    if (idx + kVAhead < 8) va[idx + kVAhead] = v_operand_at(vt, kb, idx + kVAhead);
+                    if (idx + kVAhead < 8) va[idx + kVAhead] = read_v(idx + kVAhead);
                     if (idx >= 8 - kKAhead) prefetch_next(idx - (8 - kKAhead));
                 }
                 if (rb == kRB - 1) staging_step(idx);   // a share of the next tiles' HBM -> LDS traffic
@@ -628,18 +663,19 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     bf16x8 pf[kRB][2];
     auto pipelined_tile = [&](int t, auto slot_tag) __attribute__((always_inline)) {
         constexpr int S = decltype(slot_tag)::value;
-        const char* kt = lds + S * kSlotBytes;
-        const char* vt = kt + kTileBytes;
-        const char* kt_next = lds + ((S + 1) & 3) * kSlotBytes;
+        const std::integral_constant<int, S> here{};
+        const std::integral_constant<int, (S + 1) & 3> next{};
         const int64_t page_off = plan_load(t + 3);
-        region_scores_weights(kt, 1, sb, sa, pf, [&](int i) { va[i] = v_operand_at(vt, 0, i); });
-        region_accumulate_maxima(vt, 0, pf, sb, true,
+        region_scores_weights([&](int i) { return k_operand_in(here, 1, i); }, sb, sa, pf,
+                              [&](int i) { va[i] = v_operand_in(here, 0, i); });
+        region_accumulate_maxima([&](int i) { return v_operand_in(here, 0, i); }, pf, sb, true,
                                  [&](int i) { if (i < 4) load_step(page_off, (S + 3) & 3, i); },
-                                 [&](int i) { ka[i] = k_operand_at(kt_next, 0, i); });
-        region_scores_weights(kt_next, 0, sa, sb, pf, [&](int i) { va[i] = v_operand_at(vt, 1, i); });
+                                 [&](int i) { ka[i] = k_operand_in(next, 0, i); });
+        region_scores_weights([&](int i) { return k_operand_in(next, 0, i); }, sa, sb, pf,
+                              [&](int i) { va[i] = v_operand_in(here, 1, i); });
         // the next tile's first region reads K of tile t + 1, block 1 (in LDS since the last barrier)
-        region_accumulate_maxima(vt, 1, pf, sa, t + 1 < n_unmasked, [&](int) {},
-                                 [&](int i) { ka[i] = k_operand_at(kt_next, 1, i); });
+        region_accumulate_maxima([&](int i) { return v_operand_in(here, 1, i); }, pf, sa, t + 1 < n_unmasked,
+                                 [&](int) {}, [&](int i) { ka[i] = k_operand_in(next, 1, i); });
         finish_tile(t + 2, (S + 2) & 3);
     };
 
