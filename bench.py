@@ -293,7 +293,7 @@ def matrix_core_sustained_tflops(torch, ta, dev, iters: int = 60000) -> float:
     return ta.PROBE_FLOP_PER_ITER * iters / e0.elapsed_time(e1) / 1e9
 
 
-def crossover(torch, ta, wl, dev):
+def crossover(torch, ta, wl, dev, contexts=(1024, 2048, 4096, 8192, 16384, 32768, 65536, 131072)):
     """Restore against recompute for one program and one layer, context c = 1k .. 128k.
 
     Recompute is ta_append_prefill with an empty prefix (the attention part of re-prefilling the
@@ -302,7 +302,7 @@ def crossover(torch, ta, wl, dev):
     Small contexts are batched so the GPU is full; times are per program.
     """
     rows = []
-    for c in (1024, 2048, 4096, 8192, 16384, 32768, 65536, 131072):
+    for c in contexts:
         batch = max(1, 16384 // c)
         wb = wl.append_prefill(dev, seed=wl.SEED_BASE + 60, batch=batch, new_lo=c, new_hi=c,
                                prefix_lo=0, prefix_hi=0)
@@ -328,169 +328,43 @@ def crossover(torch, ta, wl, dev):
     return rows
 
 
-def schedule_demo(torch, ta, wl, dev, decay_base: float, ticks_per_time_unit: float = 1.0, ticks: int = 48,
-                  n_programs: int = 64, seed: int = 77):
-    """The scheduling tick driving the kernels on a synthetic agent trace (one backend, one layer).
+def schedule_demo(torch, ta, wl, dev, decay_base: float, time_per_tick: float = 1.0, ticks: int = 48,
+                  n_programs: int = 64, n_backends: int = 2, seed: int = 77, pool_tokens: int = 320 * 1024):
+    """The policy simulator (ta_sim_*, host code) driving the kernels on a synthetic agent trace.
 
-    Programs alternate reasoning (16 decode steps per tick, the context grows) and acting (a tool
-    call with a heavy-tailed latency, whose output is then appended and prefilled).  Every tick
-    ta_sched_tick decides who keeps its pages: a paused program's pages go to pinned host memory
+    Programs alternate reasoning turns (16 decode steps per tick, the context grows) and tool calls of
+    heavy-tailed latency whose output is then appended and prefilled.  Every tick the simulator decides
+    who keeps its pages on which backend; a paused program's pages go to pinned host memory
     (ta_kv_page_evict) and come back on restore (ta_kv_page_restore).  GPU time is split into
-    productive (append, decode, prefill) and overhead (evict, restore) with events around each call.
+    productive (append, decode, prefill) and overhead (evict, restore), events around each call.
     """
-    import numpy as np
+    from paper_2602_13692_amd import sim_driver
 
-    rng = np.random.default_rng(seed)
-    Hq, Hkv, d, S = 32, 8, 128, 16
-    desc = ta.Desc(Hq, Hkv)
-    page_bytes = Hkv * S * d * 2
-    cap_ctx = 32768                                   # a program that reaches this length finishes
-    max_pages = cap_ctx // S + 80
-    pool_tokens = 640 * 1024
-    capacity = 0.85 * pool_tokens                     # C_total: the rest absorbs growth within a tick
-    P = pool_tokens // S
-    k_pool = torch.empty((P, Hkv, S, d), dtype=torch.bfloat16, device=dev).normal_()
-    v_pool = torch.empty_like(k_pool).normal_()
-    free = list(range(P - 1, -1, -1))
-    host_k = torch.empty((n_programs, max_pages, page_bytes), dtype=torch.uint8).pin_memory()
-    host_v = torch.empty((n_programs, max_pages, page_bytes), dtype=torch.uint8).pin_memory()
-    table = np.full((n_programs, max_pages), -1, np.int32)
-    progs = np.zeros(n_programs, ta.PROGRAM_DTYPE)
-    progs["id"] = np.arange(n_programs)
-    progs["context"] = rng.integers(4096, 20480, size=n_programs)
-    progs["phase"] = ta.PHASE_REASONING
-    progs["status"] = ta.STATUS_PAUSED                # everybody starts in the waiting queue, cache on the host
-    progs["backend"] = -1
-    turn_left = rng.integers(64, 257, size=n_programs)      # decode tokens left in this reasoning turn
-    tool_left = np.zeros(n_programs, np.int64)               # ticks until the tool returns
-    pending = np.zeros(n_programs, np.int64)                 # tool-output tokens waiting to be prefilled
-    staging = torch.empty(ta.ta_restore_staging_min_bytes(max_pages) + 2 * (64 << 20), dtype=torch.uint8, device=dev)
-    ws_dec = ta.alloc_workspace(desc, n_programs, 1, cap_ctx + 2048, dev)
-    ws_pre = ta.alloc_workspace(desc, n_programs, 1024, cap_ctx + 2048, dev)
-    spent = {"append": 0.0, "decode": 0.0, "prefill": 0.0, "evict": 0.0, "restore": 0.0}
-    moved = {"evict": 0, "restore": 0}
-    steps_done = 0
-    forced = [0]
+    Hq, Hkv = 32, 8
+    max_context = 32768 + 2048
+    capacity = 0.85 * pool_tokens                      # C_total: the rest absorbs growth within a tick
+    tr = wl.agent_trace(wl.SEED_BASE + seed, n_programs, n_turns=8, context_lo=4096, context_hi=20480, turn_lo=64,
+                        turn_hi=256, tool_median_ticks=3.0, tool_sigma=1.0, out_lo=128, out_hi=1024)
+    sim = ta.Sim(n_backends, pool_tokens // 16, 16, max_context, time_per_tick, capacity, 1.0, 1.0, decay_base,
+                 tr.initial_context, tr.turn_tokens, tr.tool_ticks, tr.tool_tokens)
 
-    def timed(kind, fn):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        fn()
-        e1.record()
-        e1.synchronize()
-        spent[kind] += e0.elapsed_time(e1)
+    def source(p, first, n):                           # values do not matter here, only shapes
+        k = torch.empty((n, Hkv, 128), dtype=torch.bfloat16, device=dev).normal_()
+        return k, torch.empty_like(k).normal_(), torch.empty((n, Hq, 128), dtype=torch.bfloat16, device=dev).normal_()
 
-    def pages_of(c):
-        return (int(c) + S - 1) // S
-
-    def evict(i):
-        n = pages_of(progs["context"][i])
-        slots = torch.from_numpy(table[i, :n].copy())
-        timed("evict", lambda: ta.ta_kv_page_evict(k_pool, v_pool, page_bytes, host_k[i], host_v[i], slots, P, staging))
-        moved["evict"] += 2 * n * page_bytes
-        free.extend(int(s) for s in table[i, :n])
-        table[i, :n] = -1
-
-    def ensure_free(n, keep):
-        """The decayed check counts an idle acting program for less than the pages it holds; when the
-        pool itself runs out, the cache with the highest S_pause outside `keep` goes (Sec. 4.3: the
-        growth of the admitted programs triggers the eviction of the idle cache)."""
-        while len(free) < n:
-            cands = [j for j in range(n_programs) if progs["status"][j] == ta.STATUS_ACTIVE and j not in keep]
-            if not cands:
-                raise RuntimeError("pool exhausted by the programs that are running")
-            j = max(cands, key=lambda j: (1.0 / progs["context"][j] + (progs["phase"][j] == ta.PHASE_ACTING), -j))
-            evict(j)
-            progs["status"][j], progs["backend"][j] = ta.STATUS_PAUSED, -1
-            forced[0] += 1
-
-    def grow(i, new_c, keep):                         # pages for tokens up to new_c
-        have, need = pages_of(progs["context"][i]), pages_of(new_c)
-        ensure_free(need - have, keep)
-        for j in range(have, need):
-            table[i, j] = free.pop()
-        progs["context"][i] = new_c
-
-    def run_active(sel, q_lens):
-        """append the new tokens' K/V, then attend (decode when every q_len is 1, else prefill)"""
-        b = len(sel)
-        lens = progs["context"][sel].astype(np.int32)
-        bt = torch.from_numpy(np.ascontiguousarray(table[sel])).to(dev)
-        cl = torch.from_numpy(lens).to(dev)
-        cu_np = np.zeros(b + 1, np.int32)
-        np.cumsum(q_lens, out=cu_np[1:])
-        cu = torch.from_numpy(cu_np).to(dev)
-        total = int(cu_np[-1])
-        nk = torch.empty((total, Hkv, d), dtype=torch.bfloat16, device=dev).normal_()
-        nv = torch.empty_like(nk).normal_()
-        q = torch.empty((total, Hq, d), dtype=torch.bfloat16, device=dev).normal_()
-        out = torch.empty_like(q)
-        timed("append", lambda: ta.ta_kv_append(desc, nk, nv, cu, k_pool, v_pool, bt, cl, total))
-        if int(q_lens.max()) == 1:
-            timed("decode", lambda: ta.ta_paged_decode(desc, q, k_pool, v_pool, bt, cl, int(lens.max()), out, None, ws_dec))
-        else:
-            timed("prefill", lambda: ta.ta_append_prefill(desc, q, cu, k_pool, v_pool, bt, cl, total, int(q_lens.max()),
-                                                          int(lens.max()), out, None, ws_pre))
-
-    for tick in range(ticks):
-        # tools that return: their output waits to be prefilled (as soon as the program is active)
-        acting = progs["phase"] == ta.PHASE_ACTING
-        progs["acting_time"][acting] += 1.0 / ticks_per_time_unit   # t of f(t), in the decay's time unit
-        tool_left[acting] -= 1
-        for i in np.nonzero(acting & (tool_left <= 0))[0]:
-            progs["phase"][i] = ta.PHASE_REASONING
-            progs["acting_time"][i] = 0.0
-            pending[i] = int(rng.integers(128, 1025))
-            turn_left[i] = int(rng.integers(64, 257))
-        # the periodic check
-        _, paused, restored, _ = ta.ta_sched_tick(progs, 1, capacity, 1.0, 1.0, decay_base)
-        for i in paused:
-            evict(i)
-        for i in restored:
-            n = pages_of(progs["context"][i])
-            ensure_free(n, set(int(r) for r in restored))
-            table[i, :n] = [free.pop() for _ in range(n)]
-            slots = torch.from_numpy(table[i, :n].copy())
-            timed("restore", lambda: ta.ta_kv_page_restore(k_pool, v_pool, page_bytes, host_k[i], host_v[i], slots, P, staging))
-            moved["restore"] += 2 * n * page_bytes
-        active = (progs["status"] == ta.STATUS_ACTIVE) & (progs["phase"] == ta.PHASE_REASONING)
-        # tool output first (append-prefill), then 16 decode steps
-        sel = np.nonzero(active & (pending > 0))[0]
-        if len(sel):
-            for i in sel:
-                grow(i, progs["context"][i] + pending[i], set(int(x) for x in sel))
-            sel = np.array([i for i in sel if progs["status"][i] == ta.STATUS_ACTIVE], np.int64)
-            run_active(sel, pending[sel].astype(np.int32))
-            pending[sel] = 0
-        for _ in range(16):
-            sel = np.nonzero(active & (turn_left > 0) & (progs["status"] == ta.STATUS_ACTIVE))[0]
-            if not len(sel):
-                break
-            for i in sel:
-                grow(i, progs["context"][i] + 1, set(int(x) for x in sel))
-            run_active(sel, np.ones(len(sel), np.int32))
-            turn_left[sel] -= 1
-            steps_done += len(sel)
-        # a finished reasoning turn starts a tool call; a full context ends the program (a new one takes its place)
-        for i in np.nonzero(active & (turn_left <= 0) & (progs["status"] == ta.STATUS_ACTIVE))[0]:
-            if progs["context"][i] >= cap_ctx:
-                n = pages_of(progs["context"][i])
-                free.extend(int(s) for s in table[i, :n])
-                table[i, :] = -1
-                progs["context"][i] = int(rng.integers(2048, 8192))
-                progs["status"][i], progs["backend"][i] = ta.STATUS_PAUSED, -1
-                turn_left[i] = int(rng.integers(64, 257))
-            else:
-                progs["phase"][i] = ta.PHASE_ACTING
-                progs["acting_time"][i] = 0.0
-                tool_left[i] = max(1, int(round(float(np.exp(rng.normal(np.log(3.0), 1.0))))))
-    productive = spent["append"] + spent["decode"] + spent["prefill"]
-    overhead = spent["evict"] + spent["restore"]
-    return {"decay_base": decay_base, "ticks_per_time_unit": ticks_per_time_unit, "ticks": ticks, "programs": n_programs, "capacity_tokens": capacity,
-            "decode_tokens": steps_done, "gpu_ms": {k: round(v, 2) for k, v in spent.items()},
-            "moved_gb": {k: round(v / 1e9, 2) for k, v in moved.items()}, "forced_evictions": forced[0],
-            "overhead_fraction_of_gpu_time": round(overhead / (productive + overhead), 4),
-            "decode_tokens_per_gpu_s": round(steps_done / (productive + overhead) * 1e3, 1)}
+    drv = sim_driver.Backends(sim, n_backends, pool_tokens // 16, Hq, Hkv, max_context, tr.initial_context, source, dev)
+    for _ in range(ticks):
+        drv.run_tick()
+    torch.cuda.synchronize()
+    productive = drv.gpu_ms["append"] + drv.gpu_ms["decode"] + drv.gpu_ms["prefill"]
+    overhead = drv.gpu_ms["evict"] + drv.gpu_ms["restore"]
+    sim.close()
+    return {"decay_base": decay_base, "time_per_tick": time_per_tick, "ticks": ticks, "programs": n_programs,
+            "backends": n_backends, "capacity_tokens_per_backend": capacity, "events": drv.counts,
+            "gpu_ms": {k: round(v, 2) for k, v in drv.gpu_ms.items()},
+            "moved_gb": {k: round(v / 1e9, 2) for k, v in drv.moved_bytes.items()},
+            "overhead_fraction_of_gpu_time": round(overhead / max(productive + overhead, 1e-9), 4),
+            "decode_tokens_per_gpu_s": round(drv.counts["decode_tokens"] / max(productive + overhead, 1e-9) * 1e3, 1)}
 
 
 def main():
@@ -528,8 +402,8 @@ def main():
     torch.cuda.set_device(dev)
     if args.schedule_demo:
         print(json.dumps({"metric": "schedule_demo_one_backend_one_layer", "data": "synthetic",
-                          "runs": [schedule_demo(torch, ta, wl, dev, base, unit)
-                                   for base, unit in ((2.0, 1.0), (2.0, 4.0), (1.0, 1.0))]}), flush=True)
+                          "runs": [schedule_demo(torch, ta, wl, dev, base, dt)
+                                   for base, dt in ((2.0, 1.0), (2.0, 0.25), (1.0, 1.0))]}), flush=True)
         return
     if args.crossover:
         print(json.dumps({"metric": "restore_vs_recompute_one_layer", "data": "synthetic",
@@ -741,6 +615,15 @@ def main():
         }
         del wb, out, lse
         torch.cuda.empty_cache()
+    if args.only == "all":
+        # ---------------- restore against recompute (short sweep; --crossover runs 1k .. 128k) ----------------
+        extra["restore_vs_recompute"] = {
+            "what": "one program, one layer: ta_append_prefill with an empty prefix (attention part of a re-prefill, "
+                    "quadratic in the context) against ta_kv_page_restore of the same context (linear)",
+            "rows": crossover(torch, ta, wl, dev, contexts=(2048, 8192, 32768))}
+        # ---------------- the policy simulator driving the kernels (short run; --schedule-demo compares decays) ------
+        extra["scheduler_sim"] = schedule_demo(torch, ta, wl, dev, 2.0, 0.25, ticks=24, n_programs=32, n_backends=2,
+                                               pool_tokens=128 * 1024)
     result["extra"] = extra
     print(json.dumps(result), flush=True)
 

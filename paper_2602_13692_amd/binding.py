@@ -32,6 +32,7 @@ EXPORTS = (
     "ta_append_prefill", "ta_restore_staging_min_bytes", "ta_restore_staging_full_bytes",
     "ta_kv_page_restore", "ta_kv_page_evict", "ta_kv_append", "ta_profile_events",
     "ta_set_debug_checks", "ta_sched_tick", "ta_paged_decode_static",
+    "ta_sim_create", "ta_sim_destroy", "ta_sim_tick", "ta_sim_fetch", "ta_sim_programs", "ta_sim_page_table",
 )
 PROBE_EXPORTS = ("ta_matrix_core_probe", "ta_stream_read_probe")
 
@@ -122,6 +123,18 @@ def _lib():
         lib.ta_kv_append.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, vp, i32, i32, vp]
         lib.ta_sched_tick.restype = ctypes.c_int
         lib.ta_sched_tick.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp]
+        lib.ta_sim_create.restype = vp
+        lib.ta_sim_create.argtypes = [vp, vp, vp, vp, vp]
+        lib.ta_sim_destroy.restype = None
+        lib.ta_sim_destroy.argtypes = [vp]
+        lib.ta_sim_tick.restype = ctypes.c_int
+        lib.ta_sim_tick.argtypes = [vp, vp, vp]
+        lib.ta_sim_fetch.restype = ctypes.c_int
+        lib.ta_sim_fetch.argtypes = [vp, vp, vp]
+        lib.ta_sim_programs.restype = ctypes.c_int
+        lib.ta_sim_programs.argtypes = [vp, vp]
+        lib.ta_sim_page_table.restype = i32
+        lib.ta_sim_page_table.argtypes = [vp, i32, vp, i32]
         lib.ta_profile_events.restype = None
         lib.ta_profile_events.argtypes = [vp, vp]
         lib.ta_set_debug_checks.restype = ctypes.c_int
@@ -338,6 +351,68 @@ def ta_sched_tick(programs: np.ndarray, n_backends: int, capacity_tokens: float,
     if check:
         _check(rc, "ta_sched_tick")
     return rc, paused[: n_p.value], restored[: n_r.value], backends[: n_r.value]
+
+
+# ---- trace-driven simulator of the policy (host code) ----
+SIM_EVICT, SIM_EVICT_FORCED, SIM_RESTORE, SIM_PREFILL, SIM_DECODE, SIM_RELEASE = 1, 2, 3, 4, 5, 6
+SIM_EVENT_DTYPE = np.dtype([("kind", "<i4"), ("program", "<i4"), ("backend", "<i4"), ("tokens", "<i4"),
+                            ("context", "<i4"), ("first_slot", "<i4"), ("n_slots", "<i4")])
+
+
+class SimConfig(ctypes.Structure):
+    _fields_ = [("n_programs", ctypes.c_int32), ("n_backends", ctypes.c_int32), ("n_turns", ctypes.c_int32),
+                ("pool_pages", ctypes.c_int32), ("steps_per_tick", ctypes.c_int32), ("max_context", ctypes.c_int32),
+                ("time_per_tick", ctypes.c_double), ("sched", SchedConfig)]
+
+
+class Sim:
+    """Owner of a ta_sim handle: argument marshalling only, the decisions are the library's."""
+
+    def __init__(self, n_backends: int, pool_pages: int, steps_per_tick: int, max_context: int, time_per_tick: float,
+                 capacity_tokens: float, lambda_max: float, lambda_min: float, decay_base: float,
+                 initial_context, turn_tokens, tool_ticks, tool_tokens):
+        init = np.ascontiguousarray(initial_context, dtype=np.int32)
+        arrays = [np.ascontiguousarray(a, dtype=np.int32) for a in (turn_tokens, tool_ticks, tool_tokens)]
+        self.n_programs, self.n_turns = int(arrays[0].shape[0]), int(arrays[0].shape[1])
+        cfg = SimConfig(self.n_programs, n_backends, self.n_turns, pool_pages, steps_per_tick, max_context,
+                        time_per_tick, SchedConfig(capacity_tokens, lambda_max, lambda_min, decay_base))
+        self._h = _lib().ta_sim_create(ctypes.byref(cfg), init.ctypes.data_as(ctypes.c_void_p),
+                                       *[a.ctypes.data_as(ctypes.c_void_p) for a in arrays])
+        if not self._h:
+            raise TaError(TA_ERR_INVALID_ARG, "ta_sim_create")
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _lib().ta_sim_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:      # interpreter shutdown: the library may already be gone
+            pass
+
+    def tick(self):
+        """Advances one tick; returns (events as SIM_EVENT_DTYPE array, slots int32 array)."""
+        n_e, n_s = ctypes.c_int32(0), ctypes.c_int32(0)
+        _check(_lib().ta_sim_tick(self._h, ctypes.byref(n_e), ctypes.byref(n_s)), "ta_sim_tick")
+        events = np.zeros(n_e.value, SIM_EVENT_DTYPE)
+        slots = np.zeros(max(n_s.value, 1), np.int32)
+        _check(_lib().ta_sim_fetch(self._h, events.ctypes.data_as(ctypes.c_void_p),
+                                   slots.ctypes.data_as(ctypes.c_void_p)), "ta_sim_fetch")
+        return events, slots[: n_s.value]
+
+    def programs(self) -> np.ndarray:
+        out = np.zeros(self.n_programs, PROGRAM_DTYPE)
+        _check(_lib().ta_sim_programs(self._h, out.ctypes.data_as(ctypes.c_void_p)), "ta_sim_programs")
+        return out
+
+    def page_table(self, program: int, max_pages: int = 1 << 16) -> np.ndarray:
+        out = np.zeros(max_pages, np.int32)
+        n = int(_lib().ta_sim_page_table(self._h, int(program), out.ctypes.data_as(ctypes.c_void_p), max_pages))
+        if n < 0:
+            raise TaError(TA_ERR_INVALID_ARG, "ta_sim_page_table")
+        return out[:n]
 
 
 def alloc_workspace(desc: Desc, batch: int, max_q_len: int, max_context_len: int, device="cuda"):

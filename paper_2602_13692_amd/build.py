@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libta_hip.so")
-SOURCES = ["ta_api.hip", "ta_decode.hip", "ta_decode_fp8.hip", "ta_prefill.hip", "ta_restore.hip", "ta_sched.cpp"]
+SOURCES = ["ta_api.hip", "ta_decode.hip", "ta_decode_fp8.hip", "ta_prefill.hip", "ta_restore.hip", "ta_sched.cpp", "ta_sim.cpp"]
 # measurement aids of the benchmark: a library of their own, nothing of the hot path is in it
 PROBE_LIB = os.path.join(HERE, "libta_probe.so")
 PROBE_SOURCES = ["ta_probe.hip"]

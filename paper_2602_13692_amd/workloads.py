@@ -390,6 +390,33 @@ def sharpen(wb: PagedBatch, factor: float = 4.0) -> None:
 
 
 @dataclass
+class AgentTrace:
+    """Workflows of multi-turn agent programs: reasoning turns separated by tool calls."""
+
+    initial_context: np.ndarray     # int32 [n] tokens each program starts with (system prompt + task)
+    turn_tokens: np.ndarray         # int32 [n, turns] tokens decoded in each reasoning turn
+    tool_ticks: np.ndarray          # int32 [n, turns] latency of the tool call after each turn, in ticks
+    tool_tokens: np.ndarray         # int32 [n, turns] tokens of that tool's output
+
+
+def agent_trace(seed: int, n_programs: int, n_turns: int, context_lo: int = 4096, context_hi: int = 20480,
+                turn_lo: int = 64, turn_hi: int = 256, tool_median_ticks: float = 3.0, tool_sigma: float = 1.0,
+                out_lo: int = 128, out_hi: int = 1024) -> AgentTrace:
+    """A seeded trace: uniform contexts, turn lengths and tool-output sizes, and lognormal tool
+    latencies (a heavy tail: most tools return within a few ticks, a few take ten times longer, the
+    shape the paper reports for its agent workloads in App. B).  Integers only, no arithmetic of
+    the method."""
+    rng = np.random.default_rng(seed)
+    shape = (n_programs, n_turns)
+    ticks = np.maximum(1, np.rint(np.exp(rng.normal(math.log(tool_median_ticks), tool_sigma, size=shape))))
+    return AgentTrace(
+        initial_context=rng.integers(context_lo, context_hi + 1, size=n_programs).astype(np.int32),
+        turn_tokens=rng.integers(turn_lo, turn_hi + 1, size=shape).astype(np.int32),
+        tool_ticks=ticks.astype(np.int32),
+        tool_tokens=rng.integers(out_lo, out_hi + 1, size=shape).astype(np.int32))
+
+
+@dataclass
 class Fp8Cache:
     """The K and V pools of a batch as 8-bit E4M3 codes plus the two scales of the call."""
 
