@@ -272,16 +272,33 @@ def tiny_decode_latency(torch, ta, wl, dev, reps: int = 200):
             call(side)
     torch.cuda.synchronize()
     graph_ms = time_steps(graph.replay, reps, 10, torch)
-    return {"workload": "config 1: 4 programs, 8 q / 2 kv heads, contexts 64-512 (one kernel per call: every "
+    # what a replay costs on this runtime whatever it holds: a graph of one one-element fill kernel
+    one = torch.zeros(1, device=dev)
+    floor = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        one.fill_(1.0)
+        side.synchronize()
+        with torch.cuda.graph(floor, stream=side):
+            one.fill_(1.0)
+    torch.cuda.synchronize()
+    floor_ms = time_steps(floor.replay, reps, 10, torch)
+    fill_ms = time_steps(lambda: one.fill_(1.0), reps, 10, torch)
+    return {"us_per_replay_of_a_graph_with_one_trivial_kernel": round(floor_ms * 1e3, 1),
+            "us_per_trivial_kernel_launched_eagerly": round(fill_ms * 1e3, 1),
+            "workload": "config 1: 4 programs, 8 q / 2 kv heads, contexts 64-512 (one kernel per call: every "
                         "context fits a single item, the chunk kernel writes the output itself)",
             "us_per_call_eager": round(eager_ms * 1e3, 1), "us_per_call_hip_graph": round(graph_ms * 1e3, 1)}
 
 
-def matrix_core_sustained_tflops(torch, ta, dev, iters: int = 60000) -> float:
-    """Rate of ta_matrix_core_probe on N(0,1) bf16 operands over roughly 20 ms."""
+def matrix_core_sustained_tflops(torch, ta, dev, iters: int = 60000, operands: str = "normal") -> float:
+    """Rate of ta_matrix_core_probe over roughly 20 ms on operands of one kind: N(0,1) in bf16 (what
+    attention feeds the matrix cores), all zero, or all 1.0."""
     gen = torch.Generator(device=dev)
     gen.manual_seed(260213692)
-    ops = torch.randn(8 * 64 * 8, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    if operands == "normal":
+        ops = torch.randn(8 * 64 * 8, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    else:
+        ops = torch.full((8 * 64 * 8,), 0.0 if operands == "zero" else 1.0, device=dev, dtype=torch.bfloat16)
     sink = torch.empty(ta.PROBE_SINK_BYTES, dtype=torch.uint8, device=dev)
     ta.ta_matrix_core_probe(ops, 1000, sink)
     torch.cuda.synchronize()
@@ -291,6 +308,26 @@ def matrix_core_sustained_tflops(torch, ta, dev, iters: int = 60000) -> float:
     e1.record()
     torch.cuda.synchronize()
     return ta.PROBE_FLOP_PER_ITER * iters / e0.elapsed_time(e1) / 1e9
+
+
+def issue_port_ns(torch, ta, dev, iters: int = 20000):
+    """ta_issue_port_probe: nanoseconds per iteration and SIMD (two waves, 16 matrix instructions and / or
+    160 FMAs per iteration) for matrix only, vector only and both."""
+    sink = torch.empty(ta.ISSUE_SINK_BYTES, dtype=torch.uint8, device=dev)
+    out = {}
+    for name, (nm, nv) in (("matrix_only", (8, 0)), ("vector_only", (0, 80)), ("both", (8, 80))):
+        ta.ta_issue_port_probe(nm, nv, 1000, sink)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ta.ta_issue_port_probe(nm, nv, iters, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = round(e0.elapsed_time(e1) * 1e6 / iters, 1)
+    # time the vector port was unavailable per matrix instruction, as a share of that instruction's time
+    out["vector_port_blocked_share_of_a_matrix_instruction"] = round(
+        (out["both"] - out["vector_only"]) / max(out["matrix_only"], 1e-9), 3)
+    return out
 
 
 def crossover(torch, ta, wl, dev, contexts=(1024, 2048, 4096, 8192, 16384, 32768, 65536, 131072)):
@@ -528,6 +565,23 @@ def main():
         sustained = matrix_core_sustained_tflops(torch, ta, dev)
         extra["append_prefill"]["matrix_cores_alone_same_operand_kind_tflops"] = round(sustained, 1)
         extra["append_prefill"]["frac_of_matrix_cores_alone"] = round(flops / kernel_ms / 1e9 / sustained, 4)
+        # the same probe on operands that toggle no bits: the gap to the N(0,1) rate is the power management's
+        extra["append_prefill"]["matrix_cores_alone_tflops_by_operand_kind"] = {
+            "normal": round(sustained, 1),
+            "zero": round(matrix_core_sustained_tflops(torch, ta, dev, operands="zero"), 1),
+            "one": round(matrix_core_sustained_tflops(torch, ta, dev, operands="one"), 1)}
+        # do matrix and vector instructions of two waves overlap on a SIMD?
+        extra["append_prefill"]["issue_port_probe_ns_per_iteration"] = issue_port_ns(torch, ta, dev)
+        # the same batch with every block table folded onto 64 pages: K and V never leave the L2
+        import numpy as np
+
+        folded = wb.block_table.copy()
+        folded[folded >= 0] %= 64
+        keep = wb.block_table
+        wb.block_table = folded
+        _, hot_ms, _, _ = run_prefill(wb, 3, 1, torch, ta)
+        wb.block_table = keep
+        extra["append_prefill"]["kernel_ms_with_kv_always_in_l2"] = round(hot_ms, 3)
         del wb, out, lse
         torch.cuda.empty_cache()
 

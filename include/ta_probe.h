@@ -59,6 +59,23 @@ TA_PROBE_API int ta_matrix_core_probe(const void *operands, int32_t iters, void 
 #define TA_STREAM_SINK_BYTES (8192 * 256 * 4)
 TA_PROBE_API int ta_stream_read_probe(const void *src, size_t bytes, void *sink, void *hip_stream);
 
+/*
+ * Measurement aid (no paper passage).  Two waves per SIMD on every CU; per iteration every wave
+ * issues matrix_per_iter independent v_mfma_f32_32x32x16_bf16 and vector_per_iter independent
+ * fp32 FMAs, interleaved.  Timing (8, 0), (0, 80) and (8, 80) shows whether the two kinds of
+ * work overlap on a SIMD: if a matrix instruction left the vector issue port alone, (8, 80) would
+ * take as long as the longer of the other two.
+ *
+ *   matrix_per_iter  0 or 8;  vector_per_iter  0, 40 or 80 (not both 0)
+ *   iters            >= 1
+ *   sink             DEVICE, TA_ISSUE_SINK_BYTES, written
+ *
+ * Returns -1 for a combination that is not built, a NULL sink or iters < 1.
+ */
+#define TA_ISSUE_SINK_BYTES (256 * 512 * 4)
+TA_PROBE_API int ta_issue_port_probe(int32_t matrix_per_iter, int32_t vector_per_iter, int32_t iters, void *sink,
+                                     void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -34,7 +34,7 @@ EXPORTS = (
     "ta_set_debug_checks", "ta_sched_tick", "ta_paged_decode_static",
     "ta_sim_create", "ta_sim_destroy", "ta_sim_tick", "ta_sim_fetch", "ta_sim_programs", "ta_sim_page_table",
 )
-PROBE_EXPORTS = ("ta_matrix_core_probe", "ta_stream_read_probe")
+PROBE_EXPORTS = ("ta_matrix_core_probe", "ta_stream_read_probe", "ta_issue_port_probe")
 
 
 class TaError(RuntimeError):
@@ -157,6 +157,8 @@ def _probe_lib():
         lib.ta_matrix_core_probe.argtypes = [vp, i32, vp, vp]
         lib.ta_stream_read_probe.restype = ctypes.c_int
         lib.ta_stream_read_probe.argtypes = [vp, sz, vp, vp]
+        lib.ta_issue_port_probe.restype = ctypes.c_int
+        lib.ta_issue_port_probe.argtypes = [i32, i32, i32, vp, vp]
         _PROBE_LIB = lib
     return _PROBE_LIB
 
@@ -309,6 +311,17 @@ def ta_matrix_core_probe(operands, iters: int, sink, stream=None, check: bool = 
 
 
 STREAM_SINK_BYTES = 8192 * 256 * 4
+ISSUE_SINK_BYTES = 256 * 512 * 4
+
+
+def ta_issue_port_probe(matrix_per_iter: int, vector_per_iter: int, iters: int, sink, stream=None, check: bool = True) -> int:
+    """Two waves per SIMD issuing matrix and vector instructions side by side; sink: ISSUE_SINK_BYTES."""
+    rc = _probe_lib().ta_issue_port_probe(int(matrix_per_iter), int(vector_per_iter), int(iters), _ptr(sink),
+                                          _stream(stream))
+    if check:
+        _check(rc, "ta_issue_port_probe")
+    return rc
+
 
 
 def ta_stream_read_probe(src, sink, stream=None, check: bool = True) -> int:

@@ -69,9 +69,62 @@ __global__ __launch_bounds__(256) void stream_read_probe_kernel(const u32x4* __r
     sink[blockIdx.x * blockDim.x + threadIdx.x] = acc.x ^ acc.y ^ acc.z ^ acc.w;
 }
 
+// Two waves per SIMD (512 threads on every CU); per iteration each wave issues NM independent
+// matrix instructions and NV independent fp32 FMAs, interleaved.  Timing the three cases (matrix
+// only, vector only, both) shows how much of a matrix instruction's time the vector issue port
+// is unavailable to the other wave.
+template <int NM, int NV>
+__global__ __launch_bounds__(512) void issue_port_probe_kernel(float* __restrict__ sink, int32_t iters, float seed) {
+    bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = static_cast<__bf16>(seed + i);
+        b[i] = static_cast<__bf16>(seed * 0.5f + (threadIdx.x & 7));
+    }
+    f32x16 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = seed + i + threadIdx.x;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (u < NM) acc[u & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[u & 3], 0, 0, 0);
+#pragma unroll
+            for (int w = 0; w < NV / 8; ++w) v[(u + w) & 7] = __builtin_fmaf(v[(u + w) & 7], 1.0001f, 0.5f);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[j][r];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += v[i];
+    sink[blockIdx.x * 512 + threadIdx.x] = s;
+}
+
 }  // namespace
 
 extern "C" {
+
+int ta_issue_port_probe(int32_t matrix_per_iter, int32_t vector_per_iter, int32_t iters, void* sink, void* hip_stream) {
+    if (sink == nullptr || iters < 1 || (reinterpret_cast<uintptr_t>(sink) & 3) != 0) return -1;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    float* out = static_cast<float*>(sink);
+    const dim3 grid(kProbeBlocks), block(512);
+    if (matrix_per_iter == 8 && vector_per_iter == 0) hipLaunchKernelGGL((issue_port_probe_kernel<8, 0>), grid, block, 0, st, out, iters, 1.0f);
+    else if (matrix_per_iter == 0 && vector_per_iter == 40) hipLaunchKernelGGL((issue_port_probe_kernel<0, 40>), grid, block, 0, st, out, iters, 1.0f);
+    else if (matrix_per_iter == 0 && vector_per_iter == 80) hipLaunchKernelGGL((issue_port_probe_kernel<0, 80>), grid, block, 0, st, out, iters, 1.0f);
+    else if (matrix_per_iter == 8 && vector_per_iter == 40) hipLaunchKernelGGL((issue_port_probe_kernel<8, 40>), grid, block, 0, st, out, iters, 1.0f);
+    else if (matrix_per_iter == 8 && vector_per_iter == 80) hipLaunchKernelGGL((issue_port_probe_kernel<8, 80>), grid, block, 0, st, out, iters, 1.0f);
+    else return -1;
+    return hipGetLastError() == hipSuccess ? 0 : -3;
+}
 
 int ta_stream_read_probe(const void* src, size_t bytes, void* sink, void* hip_stream) {
     if (src == nullptr || sink == nullptr || bytes == 0 || (bytes & 15) != 0) return -1;
