@@ -415,6 +415,9 @@ def main():
                     help="print the restore-versus-recompute table (one JSON line) instead of the benchmark")
     ap.add_argument("--schedule-demo", action="store_true",
                     help="drive the kernels with the scheduling tick on a synthetic agent trace (one JSON line)")
+    ap.add_argument("--kernels-only", action="store_true",
+                    help="leave out the legs that run many small calls (restore-versus-recompute sweep, simulator): "
+                         "what a kernel trace of the five workloads needs")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -669,7 +672,7 @@ def main():
         }
         del wb, out, lse
         torch.cuda.empty_cache()
-    if args.only == "all":
+    if args.only == "all" and not args.kernels_only:
         # ---------------- restore against recompute (short sweep; --crossover runs 1k .. 128k) ----------------
         extra["restore_vs_recompute"] = {
             "what": "one program, one layer: ta_append_prefill with an empty prefix (attention part of a re-prefill, "

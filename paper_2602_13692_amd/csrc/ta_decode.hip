@@ -193,12 +193,20 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
     s_pos[tid] = tid;
     if (tid == 0) n_shared = 0;
     __syncthreads();
-    if (grouping) {
-        const bool joins = tid < batch && pred[tid] >= 0 && lcp[tid] >= chunk_pages;
+    __shared__ int32_t any_joins;
+    if (tid == 0) any_joins = 0;
+    __syncthreads();
+    const bool joins = grouping && tid < batch && pred[tid] >= 0 && lcp[tid] >= chunk_pages;
+    if (joins) any_joins = 1;
+    __syncthreads();
+    if (grouping && any_joins != 0) {      // the common case (no program has a predecessor) skips all of this
         s_lcp[tid] = joins ? lcp[tid] : 0;
         s_lead[tid] = joins ? pred[tid] : tid;
         __syncthreads();
-        for (int round = 0; round < 10; ++round) {          // predecessors have smaller indices: 2^10 hops suffice
+        // only the first n_sort = 2^k >= batch entries take part in the pointer jumping and the sort
+        int n_sort = 2, log_n = 1;
+        while (n_sort < batch) { n_sort <<= 1; ++log_n; }
+        for (int round = 0; round < log_n; ++round) {       // predecessors have smaller indices: 2^k hops suffice
             const int l = s_lead[s_lead[tid]];
             __syncthreads();
             s_lead[tid] = l;
@@ -206,10 +214,10 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
         }
         s_key[tid] = tid < batch ? ((s_lead[tid] << 10) | tid) : 0x7fffffff;
         __syncthreads();
-        for (int k = 2; k <= 1024; k <<= 1) {               // bitonic sort, ascending; the keys are distinct
+        for (int k = 2; k <= n_sort; k <<= 1) {             // bitonic sort, ascending; the keys are distinct
             for (int j = k >> 1; j > 0; j >>= 1) {
                 const int other = tid ^ j;
-                if (other > tid) {
+                if (other > tid && other < n_sort) {
                     const int a = s_key[tid], c = s_key[other];
                     const bool ascending = (tid & k) == 0;
                     if ((a > c) == ascending) { s_key[tid] = c; s_key[other] = a; }
@@ -256,7 +264,7 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
             for (int c = 0; c < sc; ++c) shared_items[first_item + c] = make_int4(tid, n_in_sub, c, 0);
         }
     } else {
-        for (int b = tid; b < batch; b += 1024) order[b] = b;
+        for (int b = tid; b < batch; b += 1024) order[b] = b;     // s_pos is the identity already
     }
     __syncthreads();
 
