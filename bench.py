@@ -34,9 +34,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # HBM bytes per decode-chunk launch from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by
 # the same counter on a 1 GiB device copy), keyed by the hash of the kernel source they were
 # taken with.  A changed kernel source gives null until the counters are taken again.
-TRAFFIC_BYTES = {"712500f065c91c3f": 5089000000}
+TRAFFIC_BYTES = {"d09fac2167aa9da8": 5081000000}
+# The same for the FP8-cache decode kernel.
+FP8_TRAFFIC_BYTES = {"bc3cc5f35fa140eb": 2560000000}
 # The same for the append-prefill tile kernel: bytes that left the L2 per launch (FETCH_SIZE scaled).
-PREFILL_TRAFFIC_BYTES = {"3683c927a45907fe": 16744000000}
+PREFILL_TRAFFIC_BYTES = {"b26ccbb8a76849cc": 16870000000}
 
 
 def source_hash(name: str) -> str:
@@ -503,7 +505,8 @@ def main():
             "roofline": {"bound": "hbm", "kernel": "decode_fp8_kernel<false>",
                          "achieved": round(fp8_bytes / f_kernel_ms / 1e6, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                          "frac": round(fp8_bytes / f_kernel_ms / 1e6 / HBM_PEAK_GBPS, 4),
-                         "kernel_ms": round(f_kernel_ms, 4), "traffic": None},
+                         "kernel_ms": round(f_kernel_ms, 4),
+                         "traffic": FP8_TRAFFIC_BYTES.get(source_hash("ta_decode_fp8.hip"))},
         }
         if not args.no_cpu_baseline:
             t0 = time.perf_counter()
