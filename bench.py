@@ -599,7 +599,7 @@ def main():
         wb = wl.forked_decode(dev)
         logical = int(wb.context_lens.astype("int64").sum()) * wb.kv_bytes_per_token
         unique = wb.unique_tokens() * wb.kv_bytes_per_token
-        ms, kernel_ms, out, lse = run_decode(wb, max(2, min(args.steps, 20)), 2, torch, ta)
+        ms, kernel_ms, out, lse = run_decode(wb, max(2, min(args.steps, 30)), 5, torch, ta)
         extra["forked_decode"] = {
             "workload": "config 4: 256 programs, 64 q / 8 kv heads, groups of 16 share a 16k prefix",
             "ms_per_step": round(ms, 4), "logical_kv_gbps": round(logical / ms / 1e6, 1),
@@ -614,7 +614,7 @@ def main():
         wb.q = wb.q[torch.from_numpy(perm).to(dev)].contiguous()
         wb.block_table = np.ascontiguousarray(wb.block_table[perm])
         wb.context_lens = np.ascontiguousarray(wb.context_lens[perm])
-        ms_shuffled, _, out, lse = run_decode(wb, max(2, min(args.steps, 20)), 2, torch, ta)
+        ms_shuffled, _, out, lse = run_decode(wb, max(2, min(args.steps, 30)), 5, torch, ta)
         extra["forked_decode"]["ms_per_step_shuffled_batch_order"] = round(ms_shuffled, 4)
         del wb, out, lse
         torch.cuda.empty_cache()

@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256) void predecessor_prefix_kernel(const int32_t* 
 // bulk chunks all members of a group share to the matrix-core kernel, one item per (group, chunk)
 // for all members at once.  Everything else is listed flat for the vector-ALU kernel, bulk
 // chunks first and the short pieces last, so that the launch ends on short items:
-//   shared_items  (position of the first member in `order`, members, bulk chunk, 0)
+//   shared_items  (position of the first member in `order`, members, bulk chunk, first member)
 //   items         (program, first page, pages, slot)
 // counts[0] = number of items, counts[1] = number of shared items, counts[2] = 0 (the tile
 // kernel's work counter).
@@ -149,6 +149,7 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
     __shared__ int32_t wave_total[16];
     __shared__ int32_t carry, n_shared;
     const int tid = threadIdx.x;
+    const int nt = blockDim.x;           // a power of two, 64 .. 1024, at least the batch when the batch is at most 1024
 
     auto pages_of = [&](int b) {
         const int L = context_lens[b];
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
         return n > max_pages ? max_pages : n;               // lengths above the host bound are clipped
     };
     auto pieces_of = [&](int pages) { return (pages % chunk_pages + rem_pages - 1) / rem_pages; };
-    // exclusive scan of `value` over one pass of up to 1024 threads (wave-level shuffles, then
+    // exclusive scan of `value` over one pass of the workgroup's threads (wave-level shuffles, then
     // the sixteen wave totals); returns this thread's offset including earlier passes
     auto block_scan = [&](int value) {
         const int lane = tid & 63, wv = tid >> 6;
@@ -171,7 +172,7 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
         int before = carry;
         for (int w = 0; w < wv; ++w) before += wave_total[w];
         __syncthreads();
-        if (tid == 1023) carry = before + x;
+        if (tid == nt - 1) carry = before + x;
         __syncthreads();
         return before + x - value;
     };
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
     // 1. partial slots
     if (tid == 0) carry = 0;
     __syncthreads();
-    for (int base = 0; base < batch; base += 1024) {
+    for (int base = 0; base < batch; base += nt) {
         const int b = base + tid;
         const int pages = b < batch ? pages_of(b) : 0;
         const int first = block_scan(b < batch ? pages / chunk_pages + pieces_of(pages) : 0);
@@ -261,10 +262,10 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
         __syncthreads();
         if (sc > 0 && n_shared > 0) {
             for (int j = tid; j < tid + n_in_sub; ++j) s_shared[s_key[j] & 1023] = sc;
-            for (int c = 0; c < sc; ++c) shared_items[first_item + c] = make_int4(tid, n_in_sub, c, 0);
+            for (int c = 0; c < sc; ++c) shared_items[first_item + c] = make_int4(tid, n_in_sub, c, key & 1023);
         }
     } else {
-        for (int b = tid; b < batch; b += 1024) order[b] = b;     // s_pos is the identity already
+        for (int b = tid; b < batch; b += nt) order[b] = b;     // s_pos is the identity already
     }
     __syncthreads();
 
@@ -272,7 +273,7 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
     const int tile_base = n_shared;
     if (tid == 0) carry = 0;
     __syncthreads();
-    for (int base = 0; base < batch; base += 1024) {
+    for (int base = 0; base < batch; base += nt) {
         const int b = base + tid;
         const int bulk = b < batch ? pages_of(b) / chunk_pages : 0;
         const int sc = (b < batch && batch <= 1024) ? s_shared[b] : 0;
@@ -281,7 +282,7 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
             const int slot0 = chunk_start[b];
             const int pos = batch <= 1024 ? s_pos[b] : b;
             for (int c = sc; c < bulk; ++c) {
-                if (private_on_tiles) shared_items[tile_base + first + c - sc] = make_int4(pos, 1, c, 0);
+                if (private_on_tiles) shared_items[tile_base + first + c - sc] = make_int4(pos, 1, c, b);
                 else items[first + c - sc] = make_int4(b, c * chunk_pages, chunk_pages, slot0 + c);
             }
         }
@@ -291,11 +292,20 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
     __syncthreads();
     if (tid == 0) carry = 0;
     __syncthreads();
-    for (int base = 0; base < batch; base += 1024) {
+    // On the tile kernel a program's leftover is one item of up to chunk_pages pages, taken from a
+    // work counter: listing the long leftovers first (four classes of length) lets the launch end
+    // on short items.  The vector-ALU kernel's pieces are all short already: one pass.
+    const int n_pass = private_on_tiles ? 4 : 1;
+    for (int pass = 0; pass < n_pass; ++pass)
+    for (int base = 0; base < batch; base += nt) {
         const int b = base + tid;
         const int pages = b < batch ? pages_of(b) : 0;
         const int bulk = pages / chunk_pages;
-        const int n = pieces_of(pages);
+        int n = pieces_of(pages);
+        if (n_pass > 1 && n > 0) {
+            const int cls = 3 - ((pages - bulk * chunk_pages - 1) * 4) / chunk_pages;   // 0 = the longest quarter
+            if (cls != pass) n = 0;
+        }
         const int first = block_scan(n);
         if (b < batch) {
             const int slot0 = chunk_start[b];
@@ -303,7 +313,7 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
             for (int k = 0; k < n; ++k) {
                 const int page0 = bulk * chunk_pages + k * rem_pages;
                 const int left = pages - page0;
-                if (private_on_tiles) shared_items[tile_base + n_bulk + first + k] = make_int4(pos, 1, bulk + k, 0);
+                if (private_on_tiles) shared_items[tile_base + n_bulk + first + k] = make_int4(pos, 1, bulk + k, b);
                 else items[n_bulk + first + k] = make_int4(b, page0, left < rem_pages ? left : rem_pages, slot0 + bulk + k);
             }
         }
@@ -717,9 +727,12 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
                            a.block_table_stride, a.context_lens, w.chunk_pages, pred, lcp);
         TA_HIP_TRY(hipGetLastError());
     }
-    hipLaunchKernelGGL(plan_decode_kernel, dim3(1), dim3(1024), 0, stream, a.context_lens,
+    // one workgroup, as small as the batch allows: its many barriers cost less with fewer waves
+    unsigned plan_threads = 64;
+    while (plan_threads < 1024 && plan_threads < static_cast<unsigned>(a.batch)) plan_threads <<= 1;
+    hipLaunchKernelGGL(plan_decode_kernel, dim3(1), dim3(plan_threads), 0, stream, a.context_lens,
                        look_for_sharing ? pred : nullptr, look_for_sharing ? lcp : nullptr, a.batch, cp.max_pages,
-                       w.chunk_pages, w.rem_pages, 256 / g.group, w.max_shared_items, private_on_tiles ? 1 : 0,
+                       w.chunk_pages, w.rem_pages, 128 / g.group, w.max_shared_items, private_on_tiles ? 1 : 0,
                        chunk_start, items, shared_items, order, counts);
     TA_HIP_TRY(hipGetLastError());
 

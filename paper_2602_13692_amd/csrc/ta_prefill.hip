@@ -63,7 +63,7 @@ struct PrefillParams {
     uint16_t* out;
     float* lse;
     // shared-prefix decode only: one item = (position of the group's first member in `order`,
-    // members, chunk); the members are order[position .. position + members)
+    // members, chunk, first member); the members are order[position .. position + members)
     const int4* shared_items;
     const int32_t* order;
     int32_t* counts;             // counts[1] = number of shared items, counts[2] = next (item, kv head) pair to take
@@ -221,8 +221,10 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
         __syncthreads();
         return v;
     };
-    for (int blk = SHARED ? take_pair() : int(blockIdx.x); blk < n_items * p.num_kv_heads;
-         blk = SHARED ? take_pair() : blk + int(gridDim.x)) {
+    // (Claiming the next pair one item ahead hides the counter's round trip but costs more at the
+    // end of the launch, where a claimed item waits for its owner: measured slower.)
+    int blk = SHARED ? take_pair() : int(blockIdx.x);
+    while (blk < n_items * p.num_kv_heads) {
     const int tile_id = blk / p.num_kv_heads;
     const int g = blk - tile_id * p.num_kv_heads;
     const int tid = threadIdx.x;
@@ -230,12 +232,20 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hl = lane >> 5;                // which half of the wave
     const int l32 = lane & 31;
+    // Append-prefill: wave w owns rows 32 w .. 32 w + 31 and computes on both 32-key blocks of
+    // every tile.  Decode side: a workgroup has at most 128 rows; waves 2 j and 2 j + 1 both own
+    // rows 32 j .. 32 j + 31 and split the keys, wave 2 j + kb taking block kb of every tile (the
+    // two sit on different SIMDs); their results meet in LDS at the end of the item.  A private
+    // chunk (eight rows) then keeps two matrix cores busy instead of one, and a tile is
+    // consumed in half the time.
+    const int row_block = SHARED ? (wave >> 1) : wave;
+    const int kb_mine = wave & 1;
 
     int b, q0, nq, L, prefix, t0, t_begin, n_tiles, n_unmasked, members = 0, chunk = 0, first_pos = 0;
     if (SHARED) {
         const int4 it = p.shared_items[tile_id];
         first_pos = it.x;
-        b = p.order[first_pos];        // the group's first program: its block table names the pages
+        b = it.w;                      // the group's first program: its block table names the pages
         members = it.y;
         chunk = it.z;
         q0 = 0; nq = 0; prefix = 0; t0 = 0;
@@ -273,7 +283,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     int64_t out_row[kRB];    // element offset of the row in q / out, or -1
 #pragma unroll
     for (int rb = 0; rb < kRB; ++rb) {
-        const int row = wave * (32 * kRB) + rb * 32 + l32;
+        const int row = row_block * (32 * kRB) + rb * 32 + l32;
         const int idx = t0 + row / G;
         const int head = g * G + row % G;
         const bool ok = SHARED ? (row / G < members) : (idx < nq);
@@ -357,12 +367,22 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
         // waits are placed by hand instead (finish_tile), one per tile.  The instruction takes
         // its LDS address from m0, which the compiler manages on its own and does not expect a
         // statement to change: the statement puts back the value it found.
+        // On the decode side every K/V byte is used once by one workgroup: the loads carry the
+        // non-temporal hint, like those of the other decode kernels.  Append-prefill re-reads
+        // K/V from the L2 (the query tiles of a program run side by side) and keeps the default.
         uint32_t saved_m0;
-        asm volatile(
-            "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
-            : "=&s"(saved_m0)
-            : "s"(dst), "v"(chunk), "s"(page)
-            : "memory");
+        if constexpr (SHARED)
+            asm volatile(
+                "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3 nt\n\ts_mov_b32 m0, %0"
+                : "=&s"(saved_m0)
+                : "s"(dst), "v"(chunk), "s"(page)
+                : "memory");
+        else
+            asm volatile(
+                "s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+                : "=&s"(saved_m0)
+                : "s"(dst), "v"(chunk), "s"(page)
+                : "memory");
     };
     auto load_tile = [&](int t, int slot) __attribute__((always_inline)) {
         const int64_t page_off = plan_load(t);
@@ -400,7 +420,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     // K operand of (block kb, step ks): key l32 + 32 kb, dims 16 ks + 8 hl .. + 7 = chunk 2 ks + hl
     int k_rd[8];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) k_rd[ks] = l32 * 256 + (((2 * ks + hl) ^ (l32 & 15)) << 4);
+    for (int ks = 0; ks < 8; ++ks)
+        k_rd[ks] = l32 * 256 + (((2 * ks + hl) ^ (l32 & 15)) << 4) + (SHARED ? kb_mine * 32 * 256 : 0);
     // V operand of (block kb, step, dim block db): lane (l32, hl) needs dim 32 db + l32 of the keys
     // 32 kb + 16 step + 4 hl + {0..3, 8..11} (the keys whose weights sit in its B operand).  Two
     // transposing reads (ds_read_b64_tr_b16) fetch four keys each: in every group of 16 lanes,
@@ -411,7 +432,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     for (int db = 0; db < 4; ++db) {
         const int key = 4 * hl + (l16 >> 2);                      // + 32 kb + 16 step + 8 half
         const int c = 4 * db + 2 * (lrow & 1) + ((lane & 3) >> 1);   // 16-byte chunk of the dims
-        v_rd[db] = key * 256 + ((c ^ ((key & 3) << 2)) << 4) + (lane & 1) * 8;
+        v_rd[db] = key * 256 + ((c ^ ((key & 3) << 2)) << 4) + (lane & 1) * 8 + (SHARED ? kb_mine * 32 * 256 : 0);
     }
     auto k_operand_at = [&](const char* kt, int kb, int ks) __attribute__((always_inline)) {
         return *reinterpret_cast<const bf16x8*>(kt + kb * 32 * 256 + k_rd[ks]);
@@ -650,6 +671,14 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
         scrub_tail(t_landed, slot_landed);
         __syncthreads();
     };
+    // The decode side reads nothing but tile t in iteration t, so it only needs tile t + 1 at the
+    // barrier: two tiles (eight loads per wave) stay in flight across it, three while it computes.
+    // Short iterations are bound by memory latency over tiles in flight, not by arithmetic.
+    auto finish_tile_early = [&](int t_landed, int slot_landed) __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        scrub_tail(t_landed, slot_landed);
+        __syncthreads();
+    };
 #pragma unroll
     for (int i = 0; i < 3; ++i) load_tile(t_begin + i, i);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -680,49 +709,135 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     };
 
     int t = t_begin;
-    // ---- pipelined body, four tiles per trip.  Append-prefill pipelines the tiles whose
-    // successor is also unmasked; a shared chunk without a masked tile is pipelined to its end
-    // (the scores of the block after its last one are computed and thrown away). ----
-    const int pipe_limit = (SHARED && n_unmasked == n_tiles) ? n_tiles : n_unmasked - 1;
-    const int pipe_end = t_begin + ((pipe_limit - t_begin) & ~3);
-    if (!wave_active) {
-        // nothing to compute: keep the workgroup's loads and barriers going
+    if constexpr (SHARED) {
+        // ---- decode side.  A private chunk (two waves at work) is bound by memory latency over
+        // the tiles in flight: plain body, three tiles in flight.  A chunk that several programs
+        // share keeps up to eight waves busy and is bound by their arithmetic: the same two
+        // regions as append-prefill, one block per tile and wave, looking one tile ahead for
+        // the scores (so two tiles in flight).  All waves of the workgroup follow the item's
+        // cadence of waits, whether they have rows or not. ----
+        const int pipe_end = members >= 2 ? t_begin + ((n_tiles - t_begin) & ~3) : t_begin;
+        auto pipelined_half_tile = [&](int tt, auto slot_tag, f32x16 (&s_cur)[kRB], f32x16 (&s_nxt)[kRB])
+                                       __attribute__((always_inline)) {
+            constexpr int S = decltype(slot_tag)::value;
+            const std::integral_constant<int, S> here{};
+            const std::integral_constant<int, (S + 1) & 3> next{};
+            const int64_t page_off = plan_load(tt + 3);
+            // tile tt + 1 has landed with the barrier just passed: its first operands cannot be
+            // asked for any earlier
+#pragma unroll
+            for (int i = 0; i < kKAhead; ++i) ka[i] = k_operand_in(next, 0, i);
+            region_scores_weights([&](int i) { return k_operand_in(next, 0, i); }, s_nxt, s_cur, pf,
+                                  [&](int i) { va[i] = v_operand_in(here, 0, i); });
+            region_accumulate_maxima([&](int i) { return v_operand_in(here, 0, i); }, pf, s_nxt, tt + 1 < n_tiles,
+                                     [&](int i) { if (i < 4) load_step(page_off, (S + 3) & 3, i); }, [&](int) {});
+            finish_tile(tt + 2, (S + 2) & 3);
+        };
+        if (!wave_active) {
+            for (; t < n_tiles; ++t) {
+                const int s = (t - t_begin) & 3;
+                load_tile(t + 3, (s + 3) & 3);
+                if (t < pipe_end) finish_tile(t + 2, (s + 2) & 3);
+                else finish_tile_early(t + 1, (s + 1) & 3);
+            }
+        } else {
+            if (pipe_end > t_begin) {
+                scores(slot_ptr(0), 0, sa);          // the read offsets already point at this wave's block
+                raise_reference(sa);
+                for (; t < pipe_end; t += 4) {
+                    pipelined_half_tile(t, std::integral_constant<int, 0>{}, sa, sb);
+                    pipelined_half_tile(t + 1, std::integral_constant<int, 1>{}, sb, sa);
+                    pipelined_half_tile(t + 2, std::integral_constant<int, 2>{}, sa, sb);
+                    pipelined_half_tile(t + 3, std::integral_constant<int, 3>{}, sb, sa);
+                }
+            }
+            int slot = 0;                            // the pipelined trips are whole turns of the ring
+            for (; t < n_tiles; ++t) {
+                load_tile(t + 3, (slot + 3) & 3);
+                const char* kt = slot_ptr(slot);
+                f32x16 s[kRB];
+                scores(kt, 0, s);
+                if (t >= n_unmasked) mask_scores(t * kTileKeys + kb_mine * 32, s);
+                raise_reference(s);
+                weights(s, pf);
+                accumulate(kt + kTileBytes, 0, pf);
+                finish_tile_early(t + 1, (slot + 1) & 3);
+                slot = (slot + 1) & 3;
+            }
+        }
+    } else {
+        // ---- pipelined body, four tiles per trip: the tiles whose successor is also unmasked ----
+        const int pipe_end = t_begin + ((n_unmasked - 1 - t_begin) & ~3);
+        if (!wave_active) {
+            // nothing to compute: keep the workgroup's loads and barriers going
+            for (; t < n_tiles; ++t) {
+                const int s = (t - t_begin) & 3;
+                load_tile(t + 3, (s + 3) & 3);
+                finish_tile(t + 2, (s + 2) & 3);
+            }
+        } else if (pipe_end > t_begin) {
+            scores(slot_ptr(0), 0, sa);
+            raise_reference(sa);
+#pragma unroll
+            for (int i = 0; i < kKAhead; ++i) ka[i] = k_operand_at(slot_ptr(0), 1, i);
+            for (; t < pipe_end; t += 4) {
+                pipelined_tile(t, std::integral_constant<int, 0>{});
+                pipelined_tile(t + 1, std::integral_constant<int, 1>{});
+                pipelined_tile(t + 2, std::integral_constant<int, 2>{});
+                pipelined_tile(t + 3, std::integral_constant<int, 3>{});
+            }
+            // sa holds the first block of tile t, which the plain body below computes again
+        }
+        // ---- plain body: the last unmasked tiles and the tiles that straddle the diagonal ----
+        int slot = 0;                                // (t - t_begin) % 4: the pipelined trips are whole turns
         for (; t < n_tiles; ++t) {
-            const int s = (t - t_begin) & 3;
-            load_tile(t + 3, (s + 3) & 3);
-            finish_tile(t + 2, (s + 2) & 3);
-        }
-    } else if (pipe_end > t_begin) {
-        scores(slot_ptr(0), 0, sa);
-        raise_reference(sa);
+            load_tile(t + 3, (slot + 3) & 3);
+            const char* kt = slot_ptr(slot);
+            const char* vt = kt + kTileBytes;
+            const bool masked = t >= n_unmasked;
 #pragma unroll
-        for (int i = 0; i < kKAhead; ++i) ka[i] = k_operand_at(slot_ptr(0), 1, i);
-        for (; t < pipe_end; t += 4) {
-            pipelined_tile(t, std::integral_constant<int, 0>{});
-            pipelined_tile(t + 1, std::integral_constant<int, 1>{});
-            pipelined_tile(t + 2, std::integral_constant<int, 2>{});
-            pipelined_tile(t + 3, std::integral_constant<int, 3>{});
+            for (int kb = 0; kb < 2; ++kb) {
+                f32x16 s[kRB];
+                scores(kt, kb, s);
+                if (masked) mask_scores(t * kTileKeys + kb * 32, s);
+                raise_reference(s);
+                weights(s, pf);
+                accumulate(vt, kb, pf);
+            }
+            finish_tile(t + 2, (slot + 2) & 3);
+            slot = (slot + 1) & 3;
         }
-        // sa holds the first block of tile t, which the plain body below computes again
     }
-    // ---- plain body: the last unmasked tiles and the tiles that straddle the diagonal ----
-    int slot = 0;                                // (t - t_begin) % 4: the pipelined trips are whole turns
-    for (; t < n_tiles; ++t) {
-        load_tile(t + 3, (slot + 3) & 3);
-        const char* kt = slot_ptr(slot);
-        const char* vt = kt + kTileBytes;
-        const bool masked = t >= n_unmasked;
+
+    if constexpr (SHARED) {
+        // The two waves of a row block hold results over disjoint keys of the same rows, lane for
+        // lane: wave 2 j + 1 hands its (m, l, O) to wave 2 j through the ring, which is idle now
+        // (every load has landed, every operand read is done), laid out [value][lane].
+        static_assert(kRB == 1, "one row block per wave");
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        float* xch = reinterpret_cast<float*>(lds) + row_block * (66 * 64) + lane;
+        if (wave_active && kb_mine == 1) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            f32x16 s[kRB];
-            scores(kt, kb, s);
-            if (masked) mask_scores(t * kTileKeys + kb * 32, s);
-            raise_reference(s);
-            weights(s, pf);
-            accumulate(vt, kb, pf);
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) xch[(db * 16 + r) * 64] = o[db][0][r];
+            xch[64 * 64] = m[0];
+            xch[65 * 64] = lsum[0];
         }
-        finish_tile(t + 2, (slot + 2) & 3);
-        slot = (slot + 1) & 3;
+        __syncthreads();
+        if (wave_active && kb_mine == 0) {
+            const float m_other = xch[64 * 64];
+            const float m_new = fmaxf(m[0], m_other);
+            const float mine = __builtin_amdgcn_exp2f(m[0] - m_new);
+            const float other = __builtin_amdgcn_exp2f(m_other - m_new);
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[db][0][r] = o[db][0][r] * mine + xch[(db * 16 + r) * 64] * other;
+            lsum[0] = lsum[0] * mine + xch[65 * 64] * other;
+            m[0] = m_new;
+        }
     }
 
     // ---- epilogue ----
@@ -730,10 +845,11 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     for (int rb = 0; rb < kRB; ++rb) {
         const float total = lsum[rb] + __shfl_xor(lsum[rb], 32);
         if (out_row[rb] < 0) continue;
+        if (SHARED && kb_mine == 1) continue;      // its partner writes the merged result
         if (SHARED) {
             // split-K partial of (member program, head) for this chunk: unnormalised O, the
             // reference maximum it is relative to, and the sum of weights
-            const int row = wave * (32 * kRB) + rb * 32 + l32;
+            const int row = row_block * (32 * kRB) + rb * 32 + l32;
             const int head = g * G + row % G;
             const int program = static_cast<int>(out_row[rb] / (int64_t(p.num_q_heads) * kHeadDim));
             const int64_t rowid = int64_t(p.chunk_start[program] + chunk) * p.num_q_heads + head;
@@ -775,6 +891,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     // the next item reuses the LDS ring: no load may still be on its way into it
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    blk = SHARED ? take_pair() : blk + int(gridDim.x);
     }
 }
 
