@@ -3,18 +3,19 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--only decode|prefill|all] [--calibrate-copy]
 
-A step is one ta_paged_decode call (work plan, split-K chunk kernel, merge) on
-the Llama-3-8B-shaped decode batch: 64 programs, 32 q / 8 kv heads, context
+A step is one ta_paged_decode call (work plan, the split-K kernel that streams
+the chunks, merge) on the Llama-3-8B-shaped decode batch: 64 programs, 32 q / 8 kv heads, context
 lengths uniform in 4k..32k, 16-token pages scattered over the pool by a seeded
 permutation.  All inputs are resident in HBM before the timed region.  The
 headline value is KV bytes read per second (K and V of every cached token once).
 
 The same JSON line carries
-  roofline      the chunk kernel's own duration (HIP events recorded inside the
-                library around that kernel) against the 8 TB/s HBM peak;
+  roofline      the streaming kernel's own duration (HIP events recorded inside
+                the library around that kernel) against the 8 TB/s HBM peak;
   cpu_baseline  the fp64 oracle timed on this host's cores on the same batch;
-  extra         append-prefill (MFMA, TFLOP/s), forked-prefix decode and
-                restore-then-decode on the other workload shapes.
+  extra         the same batch on the vector-ALU kernel and over an FP8 cache,
+                append-prefill (MFMA, TFLOP/s), forked-prefix decode,
+                restore-then-decode, restore against recompute, the policy simulator.
 """
 from __future__ import annotations
 
@@ -31,10 +32,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 
-# HBM bytes per decode-chunk launch from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, each scaled by
-# the same counter on a 1 GiB device copy), keyed by the hash of the kernel source they were
-# taken with.  A changed kernel source gives null until the counters are taken again.
-TRAFFIC_BYTES = {"d09fac2167aa9da8": 5081000000}
+# HBM bytes per launch of the kernel that streams the decode batch, from rocprofv3 --pmc
+# (FETCH_SIZE + WRITE_SIZE, each scaled by the same counter on a 1 GiB device copy), keyed by the
+# hash of the kernel source they were taken with.  A changed kernel source gives null until the
+# counters are taken again.
+TRAFFIC_BYTES = {}
+# The same batch on the vector-ALU kernel (the library's choice for smaller batches).
+VECTOR_TRAFFIC_BYTES = {"d09fac2167aa9da8": 5081000000}
 # The same for the FP8-cache decode kernel.
 FP8_TRAFFIC_BYTES = {"bc3cc5f35fa140eb": 2560000000}
 # The same for the append-prefill tile kernel: bytes that left the L2 per launch (FETCH_SIZE scaled).
@@ -88,11 +92,12 @@ class KernelTimer:
         return sum(t) / max(len(t), 1)
 
 
-def run_decode(wb, steps, warmup, torch, ta, fp8_cache=None):
-    """Times ta_paged_decode on a batch; with fp8_cache (workloads.Fp8Cache) over its E4M3 codes."""
+def run_decode(wb, steps, warmup, torch, ta, fp8_cache=None, chunk_pages=0):
+    """Times ta_paged_decode on a batch; with fp8_cache (workloads.Fp8Cache) over its E4M3 codes.
+    chunk_pages is the descriptor's decode_chunk_pages (0: the library chooses chunk and kernel)."""
     dev = wb.q.device
     if fp8_cache is None:
-        desc = ta.Desc(wb.num_q_heads, wb.num_kv_heads)
+        desc = ta.Desc(wb.num_q_heads, wb.num_kv_heads, decode_chunk_pages=chunk_pages)
         k_pool, v_pool = wb.k_pool, wb.v_pool
     else:
         desc = ta.Desc(wb.num_q_heads, wb.num_kv_heads, kv_format=ta.KV_FP8_E4M3, k_scale=fp8_cache.k_scale,
@@ -460,7 +465,7 @@ def main():
     stream_gbps = stream_read_gbps(torch, ta, wb.k_pool)
     value = kv_bytes / ms / 1e6
     achieved = kv_bytes / kernel_ms / 1e6
-    traffic = TRAFFIC_BYTES.get(source_hash("ta_decode.hip"))
+    traffic = TRAFFIC_BYTES.get(source_hash("ta_prefill.hip"))
     result = {
         "metric": "paged_decode_kv_gbps", "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
@@ -473,7 +478,7 @@ def main():
             "kv_bytes_per_step": kv_bytes, "layer_tokens_per_s": round(wb.batch / ms * 1e3, 1),
         },
         "roofline": {
-            "bound": "hbm", "kernel": "decode_chunk_kernel<4>", "achieved": round(achieved, 1),
+            "bound": "hbm", "kernel": "attention_tile_kernel<4, true>", "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
             "kernel_ms": round(kernel_ms, 4), "kernel_ms_median": round(ktimes[len(ktimes) // 2], 4),
             "kernel_ms_min": round(ktimes[0], 4), "traffic": traffic,
@@ -489,7 +494,17 @@ def main():
         result["config"]["parity_vs_oracle"] = spot_check(out, lse, ref_out, ref_lse, torch)
         del ref_out, ref_lse
     fp8_leg = None
+    vector_leg = None
     if args.only in ("all", "decode"):
+        # ---------------- the same batch on the vector-ALU kernel (a chunk size given by the caller keeps it there) ----
+        v_ms, v_kernel_ms, _, _ = run_decode(wb, args.steps, args.warmup, torch, ta, chunk_pages=128)
+        vector_leg = {
+            "what": "config 2 streamed by decode_chunk_kernel<4, false> (decode_chunk_pages = 128): what the "
+                    "library picks for batches too small to fill the tile kernel",
+            "ms_per_step": round(v_ms, 4), "kv_gbps": round(kv_bytes / v_ms / 1e6, 1),
+            "kernel_ms": round(v_kernel_ms, 4), "kernel_frac_of_hbm_peak": round(kv_bytes / v_kernel_ms / 1e6 / HBM_PEAK_GBPS, 4),
+            "traffic": VECTOR_TRAFFIC_BYTES.get(source_hash("ta_decode.hip")),
+        }
         # ---------------- the same batch with its cache as FP8 (E4M3) codes: half the bytes per token ----------------
         import oracle
 
@@ -530,6 +545,8 @@ def main():
     torch.cuda.empty_cache()
 
     extra = {}
+    if vector_leg is not None:
+        extra["decode_on_vector_alu_kernel"] = vector_leg
     if fp8_leg is not None:
         extra["fp8_decode"] = fp8_leg
     if args.only in ("all", "prefill"):

@@ -71,12 +71,27 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
 // cheaper; short ones are only chosen when a batch is too small to fill the chip otherwise.  The
 // leftover of a program (less than one chunk) is cut finer and listed last, so that the launch
 // ends on short items.
+// Which kernel streams the private chunks of a bf16 cache.  The matrix-core tile kernel brings
+// K/V in through global-to-LDS loads with three tiles in flight per CU and spends no vector
+// instruction on them: with enough work to keep one eight-wave workgroup per CU on long items it
+// streams faster than the vector-ALU kernel (measured: from about 20,000 pages in the batch).
+// Below that the vector-ALU kernel's finer items fill the chip better.  With eight query heads
+// per kv head the vector-ALU kernel does not exist (its per-head state would fill the register
+// file).  The host knows only the batch and the bound on the context length: it takes their
+// product, the most the batch can hold.
+static bool decode_on_tiles(const Geometry& g, int32_t batch, int32_t max_context_len) {
+    if (g.kv_fp8) return false;
+    if (g.group == 8) return true;
+    const int64_t pages = (int64_t(max_context_len) + kPageSize - 1) / kPageSize;
+    return g.group == 4 && g.decode_chunk_pages == 0 && int64_t(batch) * pages >= 40000;
+}
+
 static int32_t choose_chunk_pages(const Geometry& g, int32_t batch, int32_t max_context_len) {
     if (g.decode_chunk_pages != 0) return g.decode_chunk_pages;   // the caller's choice, validated with the descriptor
     const int64_t pages = (int64_t(max_context_len) + kPageSize - 1) / kPageSize;
-    if (g.group == 8 && !g.kv_fp8) {
-        // every chunk runs on the matrix-core tile kernel, whose per-item cost (filling the LDS
-        // ring, writing 32 to 128 rows of partials) wants long items: up to 4096 tokens
+    if (decode_on_tiles(g, batch, max_context_len)) {
+        // the tile kernel's per-item cost (filling the LDS ring, writing 32 to 128 rows of
+        // partials) wants long items: up to 4096 tokens
         for (int32_t c : {256, 128}) {
             const int64_t items = int64_t(batch) * g.num_kv_heads * ((pages + c - 1) / c);
             if (items >= 2048) return c;
@@ -101,9 +116,9 @@ WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_l
     size_t off = 0;
     if (max_q_len <= 1) {
         w.chunk_pages = choose_chunk_pages(g, batch, max_context_len);
-        // with eight heads per kv head every item runs on the tile kernel, which takes a program's
-        // leftover as one item; the vector-ALU kernel gets it in quarters
-        const bool all_on_tiles = g.group == 8 && !g.kv_fp8;
+        // the tile kernel takes a program's leftover as one item; the vector-ALU kernel gets it in quarters
+        const bool all_on_tiles = decode_on_tiles(g, batch, max_context_len);
+        w.private_on_tiles = all_on_tiles ? 1 : 0;
         w.rem_pages = all_on_tiles ? w.chunk_pages : (w.chunk_pages >= 32 ? w.chunk_pages / 4 : 8);
         w.slots_per_program = static_cast<int32_t>(pages / w.chunk_pages + w.chunk_pages / w.rem_pages);
         w.max_chunks = static_cast<int32_t>(int64_t(batch) * w.slots_per_program);
@@ -113,8 +128,8 @@ WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_l
         w.off_items = off;       off = align256(off + sizeof(int32_t) * 4 * size_t(w.max_chunks));
         w.off_part_ml = off;     off = align256(off + sizeof(float) * 2 * size_t(w.max_chunks) * g.num_q_heads);
         w.off_part_o = off;      off = align256(off + sizeof(float) * kHeadDim * size_t(w.max_chunks) * g.num_q_heads);
-        // a shared chunk serves at least two programs; with eight heads per kv head every chunk
-        // goes to the matrix-core kernel, one item each at most
+        // a shared chunk serves at least two programs; when every chunk goes to the matrix-core
+        // kernel, one item each at most
         w.max_shared_items = all_on_tiles ? w.max_chunks
                                           : static_cast<int32_t>((int64_t(batch) / 2) * (pages / w.chunk_pages));
         w.off_counts = off;      off = align256(off + sizeof(int32_t) * 4);

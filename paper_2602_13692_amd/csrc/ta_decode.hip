@@ -717,10 +717,9 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     // (pools of fp8 codes take every chunk through their own item kernel: no sharing there)
     const bool look_for_sharing = !g.kv_fp8 && a.batch >= 2 && a.batch <= 1024 && w.max_shared_items > 0 &&
                                   a.block_table_stride > 0 && cp.max_pages >= w.chunk_pages;
-    // Eight query heads per kv head leave the vector-ALU kernel one wave per SIMD (its per-head
-    // state fills the register file) and make it compute-bound; the matrix-core kernel takes
-    // the private chunks too, as groups of one program.
-    const bool private_on_tiles = g.group == 8 && !g.kv_fp8;   // the workspace plan sizes shared_items for it
+    // The workspace plan has decided which kernel streams the private chunks (and sized
+    // shared_items for it): the matrix-core kernel takes them as groups of one program.
+    const bool private_on_tiles = w.private_on_tiles != 0;
 
     if (look_for_sharing) {
         hipLaunchKernelGGL(predecessor_prefix_kernel, dim3(a.batch), dim3(256), 0, stream, a.block_table,
@@ -753,6 +752,7 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
         sa.batch = a.batch;
         sa.tiles_per_chunk = w.chunk_pages / 4;
         sa.max_items = w.max_shared_items;
+        sa.private_on_tiles = private_on_tiles ? 1 : 0;
         if (private_on_tiles && ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
         const int rc = launch_shared_prefix(g, sa, stream);
         if (rc != TA_OK) return rc;

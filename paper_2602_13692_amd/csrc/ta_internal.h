@@ -63,6 +63,7 @@ struct WorkspaceLayout {
     int32_t slots_per_program;  // upper bound on the slots of one program
     int32_t max_chunks;         // batch * slots_per_program: bound on slots and on vector-ALU items
     int32_t direct;             // 1: every context fits one item: no plan, no partials, no merge
+    int32_t private_on_tiles;   // 1: every chunk runs on the matrix-core tile kernel (groups of one program)
     int32_t max_tiles;          // upper bound on prefill query tiles (0 for decode)
     size_t off_chunk_start;     // int32 [batch + 1] first slot of each program
     size_t off_items;           // int4  [max_chunks] (program, first page, pages, slot)
@@ -73,7 +74,7 @@ struct WorkspaceLayout {
     size_t off_lcp;             // int32 [batch] leading pages shared with the predecessor
     size_t off_pred;            // int32 [batch] predecessor: the nearest earlier program with the same first page
     size_t off_order;           // int32 [batch] programs listed group by group
-    size_t off_shared_items;    // int4  [max_shared_items] (position in `order`, members, bulk chunk, 0)
+    size_t off_shared_items;    // int4  [max_shared_items] (position in `order`, members, bulk chunk, first member)
     size_t off_tile_start;      // int32 [batch + 1]      (prefill)
     size_t off_tiles;           // int2  [max_tiles]      (prefill)
     size_t total_bytes;
@@ -155,7 +156,7 @@ struct SharedPrefixArgs {
     const uint16_t* v_pool;
     const int32_t* block_table;
     const int32_t* context_lens;
-    const int32_t* shared_items;   // int4 per item: position of the first member in `order`, members, chunk, unused
+    const int32_t* shared_items;   // int4 per item: position of the first member in `order`, members, chunk, first member
     const int32_t* order;          // programs listed group by group
     int32_t* counts;               // counts[1] = number of items, counts[2] = work counter (starts at 0)
     const int32_t* chunk_start;
@@ -165,6 +166,7 @@ struct SharedPrefixArgs {
     int32_t batch;
     int32_t tiles_per_chunk;
     int32_t max_items;
+    int32_t private_on_tiles;      // 1: the batch's private chunks are in the list too
 };
 
 int launch_shared_prefix(const Geometry& g, const SharedPrefixArgs& a, hipStream_t stream);

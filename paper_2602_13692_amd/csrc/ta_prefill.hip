@@ -994,10 +994,9 @@ int launch_shared_prefix(const Geometry& g, const SharedPrefixArgs& a, hipStream
     int64_t blocks = int64_t(a.max_items) * g.num_kv_heads;
     if (blocks <= 0) return TA_OK;
     // One workgroup fits per CU and they take items from a counter.  Twice the CU count keeps the
-    // tail of a launch busy when every chunk of the batch runs here (eight heads per kv head);
-    // when only shared chunks can (usually none at all), one workgroup per CU is enough and an
-    // empty launch is over sooner.
-    const int64_t cap = g.group == 8 ? 512 : 256;
+    // tail of a launch busy when every chunk of the batch runs here; when only shared chunks can
+    // (usually none at all), one workgroup per CU is enough and an empty launch is over sooner.
+    const int64_t cap = a.private_on_tiles ? 512 : 256;
     if (blocks > cap) blocks = cap;
     return launch_tile_kernel<true>(g.group, static_cast<unsigned>(blocks), pp, stream);
 }

@@ -25,14 +25,21 @@ def _free():
 def test_config2_llama8b_decode_full_size_every_row():
     wb = wl.llama8b_decode(DEV)
     assert wb.batch == 64 and 4096 <= wb.context_lens.min() and wb.context_lens.max() <= 32768
+    # a batch of this size streams on the matrix-core tile kernel, whose row sums add up bf16-rounded
+    # weights (the bound on the lse error that follows from that is derived in gpu_util)
     out, lse = gu.gpu_decode(wb)
     ref, ref_lse = gu.oracle_decode(wb)
-    gu.assert_close(out, lse, ref, ref_lse, "config 2")
+    gu.assert_close(out, lse, ref, ref_lse, "config 2", lse_tol=gu.LSE_TOL_PREFILL_DIFFUSE)
+    # the same batch on the vector-ALU kernel (a chunk size given by the caller keeps it there)
+    out, lse = gu.gpu_decode(wb, chunk_pages=128)
+    gu.assert_close(out, lse, ref, ref_lse, "config 2, vector-ALU kernel")
     # needle variant on the same batch: outputs of magnitude O(1)
     pos = wl.plant_needles(wb, seed=22)
-    out, lse = gu.gpu_decode(wb)
     ref, ref_lse = gu.oracle_decode(wb)
-    gu.assert_close(out, lse, ref, ref_lse, "config 2 + needles")
+    out, lse = gu.gpu_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, "config 2 + needles", lse_tol=gu.LSE_TOL_PREFILL)
+    out, lse = gu.gpu_decode(wb, chunk_pages=128)
+    gu.assert_close(out, lse, ref, ref_lse, "config 2 + needles, vector-ALU kernel")
     assert (pos >= 0).all() and np.abs(ref[:, ::4]).max() > 0.5
     del wb, out, lse
     _free()
@@ -139,6 +146,6 @@ def test_config5_restore_then_decode_full_size_every_row():
     assert torch.equal(wb.v_pool.index_select(0, keep_t).view(torch.int16), before_v.view(torch.int16))
     out, lse = gu.gpu_decode(wb)
     ref, ref_lse = gu.oracle_decode(wb)            # every row, restored programs included
-    gu.assert_close(out, lse, ref, ref_lse, "config 5 after the restore")
+    gu.assert_close(out, lse, ref, ref_lse, "config 5 after the restore", lse_tol=gu.LSE_TOL_PREFILL_DIFFUSE)
     del wb, out, lse
     _free()
