@@ -90,9 +90,10 @@ static int32_t choose_chunk_pages(const Geometry& g, int32_t batch, int32_t max_
     if (g.decode_chunk_pages != 0) return g.decode_chunk_pages;   // the caller's choice, validated with the descriptor
     const int64_t pages = (int64_t(max_context_len) + kPageSize - 1) / kPageSize;
     if (decode_on_tiles(g, batch, max_context_len)) {
-        // the tile kernel's per-item cost (filling the LDS ring, writing 32 to 128 rows of
-        // partials) wants long items: up to 4096 tokens
-        for (int32_t c : {256, 128}) {
+        // the tile kernel's per-item cost (filling the LDS ring anew, writing 32 to 128 rows of
+        // partials) wants long items: up to 8192 tokens.  (Longer still would stream a little
+        // faster, but the chunk is also the unit in which a shared prefix is recognised.)
+        for (int32_t c : {512, 256, 128}) {
             const int64_t items = int64_t(batch) * g.num_kv_heads * ((pages + c - 1) / c);
             if (items >= 2048) return c;
         }

@@ -346,8 +346,12 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     // Exactly four per tile, always (tiles past the end re-read the last page): the waits below
     // count on it.
     auto plan_load = [&](int t) -> int64_t {
-        // the ring runs three tiles ahead: past the item's last tile it re-reads that tile
-        // (still in L2) instead of pulling pages nobody will use through the fabric
+        // The ring runs three tiles ahead.  Past the item's last tile, append-prefill re-reads
+        // that tile (still in L2) instead of pulling pages nobody will use through the fabric.
+        // The decode side's loads do not stay in L2, so there the surplus loads all read the
+        // pool's first page: one line set that every workgroup keeps warm.  (Nothing computes
+        // on these tiles.)
+        if (SHARED && t >= n_tiles) return 0;
         t = t < n_tiles ? t : n_tiles - 1;
         if ((t >> 4) != ids_group) {      // tiles are visited in order, so this is group + 1
             ids_group = t >> 4;

@@ -47,9 +47,21 @@ def test_forked_programs_and_eight_heads_per_kv_head_use_the_same_array():
     assert _same(_static_decode(wb), gu.gpu_decode(wb))
 
 
+def test_a_batch_large_enough_for_the_tile_kernel_route_uses_the_same_array():
+    """72 programs x a bound of 10,000 tokens: the private chunks stream on the matrix-core kernel,
+    whose items, work counter and partials live in the library's array as well."""
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 1503, batch=72, len_lo=2000, len_hi=10000)
+    got, want = _static_decode(wb), gu.gpu_decode(wb)
+    assert _same(got, want)
+    small = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 1504, batch=3, len_lo=1, len_hi=300)
+    assert _same(_static_decode(small), gu.gpu_decode(small))
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(got[0], got[1], ref, ref_lse, "static scratch, tile route", lse_tol=gu.LSE_TOL_PREFILL_DIFFUSE)
+
+
 def test_a_call_beyond_the_array_is_refused_and_writes_nothing():
     desc = ta.Desc(32, 8)
-    batch, max_len = 128, 131072
+    batch, max_len = 512, 131072
     assert ta.ta_workspace_bytes(desc, batch, 1, max_len) > ta.STATIC_SCRATCH_BYTES
     q = torch.zeros((batch, 32, 128), dtype=torch.bfloat16, device=DEV)
     out = torch.full_like(q, 3.0)
