@@ -53,9 +53,9 @@ def test_workspace_size_and_descriptor_validation():
     # partials dominate: slots * Hq * 130 floats.  A batch this large streams on the tile kernel:
     # a program of 32k tokens has 4 bulk chunks of 512 pages and one leftover item
     assert 64 * (4 + 1) * 32 * 130 * 4 <= n < 64 * (4 + 2) * 32 * 130 * 4
-    # a quarter of the programs stays on the vector-ALU kernel: 32 bulk chunks of 64 pages and up
+    # a quarter of the programs stays on the vector-ALU kernel: 16 bulk chunks of 128 pages and up
     # to 4 pieces of the leftover
-    assert ta.ta_workspace_bytes(good, 16, 1, 32768) >= 16 * (32 + 4) * 32 * 130 * 4
+    assert ta.ta_workspace_bytes(good, 16, 1, 32768) >= 16 * (16 + 4) * 32 * 130 * 4
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=64), 64, 1, 32768) >= 64 * 36 * 32 * 130 * 4
     assert ta.ta_workspace_bytes(good, 64, 2048, 34816) > 0
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, head_dim=64), 4, 1, 100) == 0
