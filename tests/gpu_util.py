@@ -61,6 +61,27 @@ def gpu_decode_fp8(wb, fc, stream=None, chunk_pages=0):
     return out, lse
 
 
+def gpu_decode_bound(wb, max_context_len):
+    """ta_paged_decode with a context-length bound (and block-table width) far above the batch's own
+    lengths, as a serving loop sizes them once for its longest admissible program.  With up to four
+    query heads per kv head a large batch x bound sends the private chunks to the matrix-core tile
+    kernel instead of the vector-ALU kernel."""
+    dev = wb.q.device
+    width = (max_context_len + 15) // 16
+    assert width >= wb.block_table.shape[1]
+    table = np.full((wb.batch, width), -1, np.int32)
+    table[:, : wb.block_table.shape[1]] = wb.block_table
+    desc = desc_of(wb)
+    bt = torch.from_numpy(table).to(dev)
+    cl = torch.from_numpy(wb.context_lens).to(dev)
+    out = torch.full_like(wb.q, float("nan"))
+    lse = torch.full((wb.batch, wb.num_q_heads), float("nan"), dtype=torch.float32, device=dev)
+    ws = ta.alloc_workspace(desc, wb.batch, 1, max_context_len, dev)
+    ta.ta_paged_decode(desc, wb.q, wb.k_pool, wb.v_pool, bt, cl, max_context_len, out, lse, ws)
+    torch.cuda.synchronize()
+    return out, lse
+
+
 def oracle_decode_fp8(wb, fc):
     return oracle.paged_decode_fp8(geom_of(wb), wl.as_u16(wb.q), wl.as_u8(fc.k_codes), wl.as_u8(fc.v_codes),
                                    fc.k_scale, fc.v_scale, wb.block_table, wb.context_lens)

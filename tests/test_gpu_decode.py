@@ -180,23 +180,6 @@ def test_tables_that_only_start_alike_are_not_grouped():
     gu.assert_close(out, lse, ref, ref_lse, "partly aliased tables")
 
 
-def _decode_with_bound(wb, max_context_len):
-    """ta_paged_decode with a context-length bound (and block-table width) far above the batch's own
-    lengths, as a serving loop sizes them once for its longest admissible program."""
-    width = (max_context_len + 15) // 16
-    table = np.full((wb.batch, width), -1, np.int32)
-    table[:, : wb.block_table.shape[1]] = wb.block_table
-    desc = gu.desc_of(wb)
-    bt = torch.from_numpy(table).to(DEV)
-    cl = torch.from_numpy(wb.context_lens).to(DEV)
-    out = torch.full_like(wb.q, float("nan"))
-    lse = torch.full((wb.batch, wb.num_q_heads), float("nan"), dtype=torch.float32, device=DEV)
-    ws = ta.alloc_workspace(desc, wb.batch, 1, max_context_len, DEV)
-    ta.ta_paged_decode(desc, wb.q, wb.k_pool, wb.v_pool, bt, cl, max_context_len, out, lse, ws)
-    torch.cuda.synchronize()
-    return out, lse
-
-
 @pytest.mark.parametrize("poison", [False, True])
 def test_large_bounds_send_four_heads_per_kv_head_to_the_tile_kernel(poison):
     """With up to four query heads per kv head the library streams the private chunks on the
@@ -210,6 +193,6 @@ def test_large_bounds_send_four_heads_per_kv_head_to_the_tile_kernel(poison):
     ref, ref_lse = gu.oracle_decode(wb)
     out_v, lse_v = gu.gpu_decode(wb)                          # 12 x 313 pages: vector-ALU kernel
     gu.assert_close(out_v, lse_v, ref, ref_lse, "small bound")
-    out_t, lse_t = _decode_with_bound(wb, 64000)              # 12 x 4000 pages: tile kernel, 128-page chunks
+    out_t, lse_t = gu.gpu_decode_bound(wb, 64000)              # 12 x 4000 pages: tile kernel, 128-page chunks
     gu.assert_close(out_t, lse_t, ref, ref_lse, "large bound", lse_tol=gu.LSE_TOL_PREFILL)
     assert ta.ta_workspace_bytes(gu.desc_of(wb), wb.batch, 1, 64000) > 0

@@ -47,6 +47,34 @@ def test_forked_decode_random_shapes(seed):
                     lse_tol=gu.LSE_TOL_PREFILL)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_tile_kernel_route_random_shapes_four_heads_per_kv_head(seed):
+    """Up to four query heads per kv head under a large batch x bound: private chunks, leftovers and
+    chunks shared by forked groups (cut into sub-groups of 128 rows) all run on the matrix-core tile
+    kernel, where the two waves of a row block split the keys and meet in LDS."""
+    rng = np.random.default_rng(wl.SEED_BASE + 5600 + seed)
+    Hq, Hkv = [(32, 8), (16, 4), (8, 2), (4, 1)][seed % 4]
+    if seed % 3 == 0:
+        batch = int(rng.integers(1, 30))
+        firsts = [int(x) for x in rng.choice([0, 1, 16, 17, 2047, 2048, 2049, 4095, 4097], size=min(batch, 4))]
+        wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 5700 + seed, batch=batch, len_lo=1,
+                               len_hi=int(rng.choice([100, 3000, 7000])), num_q_heads=Hq, num_kv_heads=Hkv,
+                               first_lens=firsts)
+    else:
+        group = int(rng.choice([2, 3, 16, 33, 40]))
+        n_groups = int(rng.integers(1, 3))
+        wb = wl.forked_decode(DEV, seed=wl.SEED_BASE + 5700 + seed, batch=group * n_groups, group=group,
+                              prefix_len=int(rng.choice([2048, 4096, 6000 // 16 * 16])), suffix_lo=1,
+                              suffix_hi=int(rng.choice([5, 900, 3000])), num_q_heads=Hq, num_kv_heads=Hkv)
+    if seed % 2:
+        wl.poison_padding(wb)
+    bound = max(16 * (40000 // wb.batch + 2), wb.max_context_len)
+    out, lse = gu.gpu_decode_bound(wb, bound)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, f"tile route seed={seed} Hq={Hq} Hkv={Hkv} B={wb.batch}",
+                    lse_tol=gu.LSE_TOL_PREFILL)
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_prefill_random_shapes(seed):
     rng = np.random.default_rng(wl.SEED_BASE + 5400 + seed)
