@@ -36,13 +36,13 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # (FETCH_SIZE + WRITE_SIZE, each scaled by the same counter on a 1 GiB device copy), keyed by the
 # hash of the kernel source they were taken with.  A changed kernel source gives null until the
 # counters are taken again.
-TRAFFIC_BYTES = {"c00b98835964bbdc": 5081000000}
+TRAFFIC_BYTES = {"24a064bd2fcbf7de": 5081000000}
 # The same batch on the vector-ALU kernel (the library's choice for smaller batches).
-VECTOR_TRAFFIC_BYTES = {"5667174ba34b0264": 5081000000}
+VECTOR_TRAFFIC_BYTES = {"2eb4740e53043875": 5081000000}
 # The same for the FP8-cache decode kernel.
 FP8_TRAFFIC_BYTES = {"bc3cc5f35fa140eb": 2560000000}
 # The same for the append-prefill tile kernel: bytes that left the L2 per launch (FETCH_SIZE scaled).
-PREFILL_TRAFFIC_BYTES = {"c00b98835964bbdc": 16870000000}
+PREFILL_TRAFFIC_BYTES = {"24a064bd2fcbf7de": 16870000000}
 
 
 def source_hash(name: str) -> str:

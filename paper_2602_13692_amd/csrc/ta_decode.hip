@@ -18,10 +18,12 @@
 // When every context fits a single item (short contexts) the chunk kernel alone runs: it
 // normalises and writes the output itself.
 //
-// The work is HBM-bound (4 flop per KV byte at group size 4), so it runs on the vector ALUs:
-// packed bf16 dot products for q.k, fp32 FMAs for p.v.  With eight query heads per kv head the
-// per-head state of this kernel would fill the register file (one wave per SIMD,
-// compute-bound), so there every chunk goes to the matrix-core tile kernel.
+// The work is HBM-bound (4 flop per KV byte at group size 4), so the chunk kernel here runs on the
+// vector ALUs: packed bf16 dot products for q.k, fp32 FMAs for p.v.  It serves small batches with
+// up to four query heads per kv head.  With eight, its per-head state would fill the register file
+// (one wave per SIMD, compute-bound); and a batch large enough to keep one eight-wave workgroup
+// per CU on long items streams faster through the matrix-core tile kernel, whose K/V arrive by
+// global-to-LDS loads: in both cases every chunk goes there (the host decides, once per call).
 #include "ta_internal.h"
 
 namespace ta {

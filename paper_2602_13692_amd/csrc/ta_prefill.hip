@@ -198,8 +198,10 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 //                 (forked agent branches): rows = (member program, head), keys = one chunk of
 //                 the shared prefix, no mask, writes split-K partials for the decode merge.
 //                 A group of one program is a private chunk (used when G = 8, where the
-//                 vector-ALU decode kernel runs out of registers): it may hold the end of the
-//                 program's context, so its last tile is masked like a causal one.
+//                 vector-ALU decode kernel runs out of registers, and for large batches,
+//                 which stream faster here): it may hold the end of the program's context,
+//                 so its last tile is masked like a causal one.  At most 128 rows; the two
+//                 waves of a row block split the keys of every tile.
 // Waves none of whose 32 rows exist take part in the loads and barriers only.
 template <int G, bool SHARED>
 __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillParams p) {
