@@ -74,7 +74,8 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
 // Which kernel streams the private chunks of a bf16 cache.  The matrix-core tile kernel brings
 // K/V in through global-to-LDS loads with three tiles in flight per CU and spends no vector
 // instruction on them: with enough work to keep one eight-wave workgroup per CU on long items it
-// streams faster than the vector-ALU kernel (measured: from about 20,000 pages in the batch).
+// streams faster than the vector-ALU kernel (measured with one, two and four query heads per kv
+// head: from about 20,000 pages in the batch).
 // Below that the vector-ALU kernel's finer items fill the chip better.  With eight query heads
 // per kv head the vector-ALU kernel does not exist (its per-head state would fill the register
 // file).  The host knows only the batch and the bound on the context length: it takes their
@@ -83,7 +84,7 @@ static bool decode_on_tiles(const Geometry& g, int32_t batch, int32_t max_contex
     if (g.kv_fp8) return false;
     if (g.group == 8) return true;
     const int64_t pages = (int64_t(max_context_len) + kPageSize - 1) / kPageSize;
-    return g.group == 4 && g.decode_chunk_pages == 0 && int64_t(batch) * pages >= 40000;
+    return g.decode_chunk_pages == 0 && int64_t(batch) * pages >= 40000;   // one, two or four heads per kv head
 }
 
 static int32_t choose_chunk_pages(const Geometry& g, int32_t batch, int32_t max_context_len) {

@@ -47,13 +47,13 @@ def test_forked_decode_random_shapes(seed):
                     lse_tol=gu.LSE_TOL_PREFILL)
 
 
-@pytest.mark.parametrize("seed", range(12))
-def test_tile_kernel_route_random_shapes_four_heads_per_kv_head(seed):
-    """Up to four query heads per kv head under a large batch x bound: private chunks, leftovers and
-    chunks shared by forked groups (cut into sub-groups of 128 rows) all run on the matrix-core tile
-    kernel, where the two waves of a row block split the keys and meet in LDS."""
+@pytest.mark.parametrize("seed", range(16))
+def test_tile_kernel_route_random_shapes_up_to_four_heads_per_kv_head(seed):
+    """One, two or four query heads per kv head under a large batch x bound: private chunks, leftovers
+    and chunks shared by forked groups (cut into sub-groups of 128 rows) all run on the matrix-core
+    tile kernel, where the two waves of a row block split the keys and meet in LDS."""
     rng = np.random.default_rng(wl.SEED_BASE + 5600 + seed)
-    Hq, Hkv = [(32, 8), (16, 4), (8, 2), (4, 1)][seed % 4]
+    Hq, Hkv = [(32, 8), (16, 4), (8, 2), (4, 1), (16, 8), (8, 8), (2, 1), (1, 1)][seed % 8]
     if seed % 3 == 0:
         batch = int(rng.integers(1, 30))
         firsts = [int(x) for x in rng.choice([0, 1, 16, 17, 2047, 2048, 2049, 4095, 4097], size=min(batch, 4))]
