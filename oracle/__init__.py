@@ -9,11 +9,13 @@ from .ta_oracle import (  # noqa: F401
     attend_rows,
     build,
     kv_append,
+    kv_append_fp8,
     kv_page_evict,
     kv_page_restore,
     num_threads,
     paged_decode,
     paged_decode_fp8,
+    quantise_e4m3,
     row_probs,
     widen_e4m3,
 )

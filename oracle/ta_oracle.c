@@ -45,6 +45,13 @@
  * code_value * k_scale, the cached value code_value * v_scale, both exact in
  * fp64, and attention over them is the same definition as above.  Queries
  * stay bf16.
+ * Writing such a cache (the new tokens of a program arrive as bf16 rows): the
+ * code of an element x is the E4M3 value nearest to x / scale, the quotient
+ * taken in fp32 as the GPU takes it (x is exact in fp32), ties going to the
+ * code whose mantissa is even; a quotient beyond the largest value becomes
+ * +-448 (a cache must never acquire a NaN the model did not produce), NaN
+ * stays NaN, and the sign of zero is kept.  Written below as that definition:
+ * a search over all finite codes for the nearest value.
  *
  * Every function here is pinned by tests that compare it with an independent
  * numpy evaluation on contiguous arrays, closed forms (single key, equal keys,
@@ -150,6 +157,39 @@ static double widen_e4m3(uint8_t code)
 void ta_oracle_widen_e4m3(const uint8_t *codes, int64_t n, double *values)
 {
     for (int64_t i = 0; i < n; ++i) values[i] = widen_e4m3(codes[i]);
+}
+
+/*
+ * The E4M3 code nearest to q (see the header): a search over the 127 positive
+ * finite codes 0x00 .. 0x7e for the smallest distance, exact in fp64; of two
+ * codes at the same distance the even one wins (adjacent codes alternate in
+ * parity, also across a change of exponent).
+ */
+static uint8_t quantise_e4m3(float q)
+{
+    const uint8_t sign = signbit(q) ? 0x80 : 0x00;
+    if (isnan(q)) return (uint8_t)(sign | 0x7f);
+    const double a = fabs((double)q);
+    if (a >= 448.0) return (uint8_t)(sign | 0x7e);             /* beyond the largest value: saturate */
+    int best = 0;
+    double best_dist = a;                                      /* distance to code 0 */
+    for (int code = 1; code <= 0x7e; ++code) {
+        const double dist = fabs(a - widen_e4m3((uint8_t)code));
+        if (dist < best_dist || (dist == best_dist && (code & 1) == 0)) {
+            best = code;
+            best_dist = dist;
+        }
+    }
+    return (uint8_t)(sign | best);
+}
+
+/* Codes of n values x[i] / scale (x given as fp32, the division in fp32). */
+void ta_oracle_quantise_e4m3(const float *x, int64_t n, float scale, uint8_t *codes)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        const volatile float q = x[i] / scale;                 /* rounded to fp32 here, not kept wider */
+        codes[i] = quantise_e4m3(q);
+    }
 }
 
 /*
@@ -431,6 +471,37 @@ void ta_oracle_kv_append(const oracle_geom *ge, const uint16_t *new_k, const uin
                 for (int64_t c = 0; c < d; ++c) {
                     k_pool[dst + c] = new_k[src + c];
                     v_pool[dst + c] = new_v[src + c];
+                }
+            }
+        }
+    }
+}
+
+/*
+ * The same for an FP8 cache: the new tokens' bf16 rows are quantised on the way in,
+ * keys with k_scale and values with v_scale (pools uint8, strides in elements).
+ */
+void ta_oracle_kv_append_fp8(const oracle_geom *ge, const uint16_t *new_k, const uint16_t *new_v,
+                             const int32_t *cu_new, uint8_t *k_pool, uint8_t *v_pool, float k_scale, float v_scale,
+                             const int32_t *block_table, int64_t table_stride,
+                             const int32_t *context_lens, int32_t batch)
+{
+    const int64_t d = ge->head_dim, Hkv = ge->num_kv_heads, S = ge->page_size;
+    for (int32_t b = 0; b < batch; ++b) {
+        const int64_t n = cu_new[b + 1] - cu_new[b];
+        const int64_t first = (int64_t)context_lens[b] - n;
+        for (int64_t i = 0; i < n; ++i) {
+            const int64_t token = first + i;
+            const int64_t page = block_table[(int64_t)b * table_stride + token / S];
+            const int64_t row = token % S;
+            for (int64_t g = 0; g < Hkv; ++g) {
+                const int64_t dst = page * ge->stride_page + g * ge->stride_head + row * ge->stride_token;
+                const int64_t src = ((int64_t)(cu_new[b] + i) * Hkv + g) * d;
+                for (int64_t c = 0; c < d; ++c) {
+                    const volatile float kq = (float)widen_bf16(new_k[src + c]) / k_scale;
+                    const volatile float vq = (float)widen_bf16(new_v[src + c]) / v_scale;
+                    k_pool[dst + c] = quantise_e4m3(kq);
+                    v_pool[dst + c] = quantise_e4m3(vq);
                 }
             }
         }

@@ -79,6 +79,8 @@ def _load():
         _lib.ta_oracle_kv_page_evict.restype = ctypes.c_int
         _lib.ta_oracle_kv_append.restype = None
         _lib.ta_oracle_widen_e4m3.restype = None
+        _lib.ta_oracle_quantise_e4m3.restype = None
+        _lib.ta_oracle_kv_append_fp8.restype = None
         _lib.ta_oracle_paged_decode_fp8.restype = None
     return _lib
 
@@ -126,6 +128,36 @@ def widen_e4m3(codes) -> np.ndarray:
     values = np.zeros(codes.shape, dtype=np.float64)
     lib.ta_oracle_widen_e4m3(_p(codes), ctypes.c_int64(codes.size), _p(values))
     return values
+
+
+def quantise_e4m3(x, scale) -> np.ndarray:
+    """E4M3 codes (uint8) of x / scale: x float32, the division in float32, nearest value with ties to
+    the even code, saturating at +-448, NaN kept."""
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    codes = np.zeros(x.shape, dtype=np.uint8)
+    lib.ta_oracle_quantise_e4m3(_p(x), ctypes.c_int64(x.size), ctypes.c_float(float(np.float32(scale))), _p(codes))
+    return codes
+
+
+def kv_append_fp8(geom: Geometry, new_k, new_v, cu_new_lens, k_pool, v_pool, k_scale, v_scale, block_table,
+                  context_lens) -> None:
+    """Quantise the new tokens' bf16 rows (uint16 [total_new,Hkv,d]) into the uint8 code pools in place."""
+    lib = _load()
+    new_k, new_v = _u16(new_k), _u16(new_v)
+    for a in (k_pool, v_pool):
+        assert a.dtype == np.uint8 and a.flags["C_CONTIGUOUS"]
+    cu_new_lens = _i32(cu_new_lens)
+    block_table = _i32(block_table)
+    context_lens = _i32(context_lens)
+    B = int(context_lens.shape[0])
+    stride = int(block_table.shape[1]) if block_table.ndim == 2 else 0
+    g = geom.c_struct()
+    lib.ta_oracle_kv_append_fp8(
+        ctypes.byref(g), _p(new_k), _p(new_v), _p(cu_new_lens), _p(k_pool), _p(v_pool),
+        ctypes.c_float(float(np.float32(k_scale))), ctypes.c_float(float(np.float32(v_scale))),
+        _p(block_table), ctypes.c_int64(stride), _p(context_lens), ctypes.c_int32(B),
+    )
 
 
 def paged_decode_fp8(geom: Geometry, q, k_pool, v_pool, k_scale, v_scale, block_table, context_lens):

@@ -182,3 +182,100 @@ def test_the_generator_quantises_with_torchs_conversion_and_stays_in_range():
     deq = _dequant(kc, fc.k_scale)
     ref = wb.k_pool.float().numpy().astype(np.float64)
     assert np.max(np.abs(deq - ref)) <= np.abs(ref).max() * 2.0 ** -4 + fc.k_scale      # half a step of 3 mantissa bits
+
+
+# ---- writing an FP8 cache: the quantiser and the quantising append ----
+# The reading (nearest E4M3 value of x / scale taken in fp32, ties to the even code, saturation at
+# +-448, NaN kept) is pinned by the format's own structure -- every code maps to itself, every
+# midpoint of two neighbours goes to the even one, a hair to either side of a midpoint goes to the
+# nearer one -- by hand cases of the saturation rule, and by torch's own conversion on every bf16
+# value in range.
+
+def _finite_positive_values():
+    """The 127 positive finite values in code order, from the landmark-pinned, torch-pinned widening."""
+    return oracle.widen_e4m3(np.arange(127, dtype=np.uint8))
+
+
+def test_every_code_is_the_quantisation_of_its_own_value():
+    codes = np.array([c for c in range(256) if c & 0x7f != 0x7f], np.uint8)
+    values = torch.from_numpy(codes).view(torch.float8_e4m3fn).float().numpy()      # torch's widening, exact in fp32
+    assert np.array_equal(oracle.quantise_e4m3(values, 1.0), codes)                  # -0 keeps its sign: 0x80
+    # and with a scale that is a power of two the division is exact as well
+    assert np.array_equal(oracle.quantise_e4m3(values * np.float32(0.25), 0.25), codes)
+
+
+def test_midpoints_go_to_the_even_code_and_their_neighbourhood_to_the_nearer_one():
+    v = _finite_positive_values()
+    mid = ((v[:-1] + v[1:]) / 2).astype(np.float32)
+    assert np.array_equal(mid.astype(np.float64), (v[:-1] + v[1:]) / 2), "midpoints are exact in fp32"
+    lower = np.arange(126, dtype=np.uint8)
+    even = np.where(lower % 2 == 0, lower, lower + 1).astype(np.uint8)
+    assert np.array_equal(oracle.quantise_e4m3(mid, 1.0), even)
+    assert np.array_equal(oracle.quantise_e4m3(-mid, 1.0), even | 0x80)
+    below = np.nextafter(mid, np.float32(0))
+    above = np.nextafter(mid, np.float32(np.inf))
+    assert np.array_equal(oracle.quantise_e4m3(below, 1.0), lower)
+    assert np.array_equal(oracle.quantise_e4m3(above, 1.0), lower + 1)
+
+
+def test_saturation_nan_and_signed_zero_by_hand():
+    x = np.array([448.0, 449.0, 464.0, 465.0, 480.0, 1e30, np.inf, -448.0, -449.0, -np.inf, np.nan, 0.0, -0.0,
+                  2.0 ** -10, 2.0 ** -10 * 1.0001, 2.0 ** -11, -2.0 ** -10], np.float32)
+    want = [0x7e, 0x7e, 0x7e, 0x7e, 0x7e, 0x7e, 0x7e, 0xfe, 0xfe, 0xfe, 0x7f, 0x00, 0x80,
+            0x00, 0x01, 0x00, 0x80]     # half the smallest subnormal ties to the even code 0; just above it rounds up
+    got = oracle.quantise_e4m3(x, 1.0)
+    assert [int(g) & 0x7f if math.isnan(float(v)) else int(g) for g, v in zip(got, x)] == want
+
+
+def test_quantiser_is_monotone():
+    rng = np.random.default_rng(wl.SEED_BASE + 830)
+    x = np.sort(np.concatenate([rng.standard_normal(20000) * 100, rng.standard_normal(20000) * 0.01]).astype(np.float32))
+    codes = oracle.quantise_e4m3(x, 1.0).astype(np.int32)
+    signed = np.where(codes & 0x80, -(codes & 0x7f), codes & 0x7f)
+    assert np.all(np.diff(signed) >= 0)
+
+
+@pytest.mark.parametrize("scale", [1.0, 0.021, 0.017, 3.0, 2.0 ** -7])
+def test_quantiser_matches_torchs_conversion_on_every_bf16_value_in_range(scale):
+    """All 65536 bf16 bit patterns: x / scale in fp32 (the same division on both sides), then torch's
+    float8_e4m3fn conversion.  Compared where the quotient is within the format's range (beyond it
+    torch makes NaN and the reading here saturates: covered by hand above)."""
+    bits = np.arange(65536, dtype=np.uint32)
+    x = (bits << 16).view(np.float32)
+    with np.errstate(over="ignore", invalid="ignore"):
+        q = x / np.float32(scale)
+    in_range = np.isfinite(q) & (np.abs(q) <= 448.0)
+    want = (torch.from_numpy(x) / torch.tensor(scale, dtype=torch.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = oracle.quantise_e4m3(x, scale)
+    assert np.array_equal(got[in_range], want[in_range])
+    assert in_range.sum() > 30000
+
+
+def test_fp8_append_equals_direct_indexing_of_quantised_rows():
+    rng = np.random.default_rng(wl.SEED_BASE + 831)
+    Hkv, B = 2, 4
+    new = np.array([1, 16, 37, 0], np.int32)
+    lens = np.array([1, 50, 37, 12], np.int32)                  # the first and third programs are all new
+    n_pages = (lens.astype(np.int64) + PS - 1) // PS
+    P = int(n_pages.sum()) + 3
+    table = wl.scatter_tables(rng, n_pages, rng.permutation(P).astype(np.int32), stride=int(n_pages.max()) + 2)
+    cu = np.zeros(B + 1, np.int32); np.cumsum(new, out=cu[1:])
+    f = (rng.standard_normal((int(cu[-1]), Hkv, D)) * 3).astype(np.float32)
+    bits = f.view(np.uint32)
+    new_k = (((bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000) >> 16).astype(np.uint16)
+    new_v = new_k[::-1].copy()
+    k_pool = rng.integers(0, 256, size=(P, Hkv, PS, D)).astype(np.uint8)
+    v_pool = rng.integers(0, 256, size=(P, Hkv, PS, D)).astype(np.uint8)
+    want_k, want_v = k_pool.copy(), v_pool.copy()
+    ks, vs = 0.05, 0.031
+    qk = oracle.quantise_e4m3(widen_bf16(new_k).astype(np.float32), ks)       # the quantiser is pinned above
+    qv = oracle.quantise_e4m3(widen_bf16(new_v).astype(np.float32), vs)
+    for b in range(B):
+        for i in range(int(new[b])):
+            token = int(lens[b] - new[b]) + i
+            page, row = int(table[b, token // PS]), token % PS
+            want_k[page, :, row, :] = qk[cu[b] + i]
+            want_v[page, :, row, :] = qv[cu[b] + i]
+    oracle.kv_append_fp8(oracle.Geometry(8, Hkv), new_k, new_v, cu, k_pool, v_pool, ks, vs, table, lens)
+    assert np.array_equal(k_pool, want_k) and np.array_equal(v_pool, want_v)
+    assert not np.array_equal(want_k, want_v)
