@@ -582,7 +582,15 @@ def main():
         moved = 2.0 * 2.0 * new_k.numel() * 2      # K and V, read once and written once
         extra["append_prefill"]["kv_append"] = {"ms": round(a_ms, 4), "bytes_read_plus_written": moved,
                                                 "gbps": round(moved / a_ms / 1e6, 1)}
-        del new_k, new_v
+        # the same tokens quantised into an FP8 cache of the same shape (bf16 rows in, E4M3 codes out)
+        f_desc = ta.Desc(wb.num_q_heads, wb.num_kv_heads, kv_format=ta.KV_FP8_E4M3, k_scale=0.021, v_scale=0.017)
+        k8 = torch.zeros(wb.k_pool.shape, dtype=torch.uint8, device=dev)
+        v8 = torch.zeros_like(k8)
+        f_ms = time_steps(lambda: ta.ta_kv_append(f_desc, new_k, new_v, a_cu, k8, v8, a_bt, a_cl, wb.total_q), 5, 1, torch)
+        moved8 = 2.0 * new_k.numel() * (2 + 1)      # K and V: two bytes read, one written per element
+        extra["append_prefill"]["kv_append_fp8"] = {"ms": round(f_ms, 4), "bytes_read_plus_written": moved8,
+                                                    "gbps": round(moved8 / f_ms / 1e6, 1)}
+        del new_k, new_v, k8, v8
         # What the matrix cores sustain on operands of the same kind (N(0,1) in bf16) when they do
         # nothing else: under such a load the power management, not the nominal clock, sets the rate.
         sustained = matrix_core_sustained_tflops(torch, ta, dev)

@@ -108,8 +108,11 @@ typedef struct ta_attn_desc {
  *                   (page, kv head) tile is 2 KiB.  Supported by ta_paged_decode and
  *                   ta_paged_decode_static (queries and outputs stay bf16: the output is
  *                   softmax(scale * k_scale * <q, K codes>) . (V codes) * v_scale), and by the
- *                   byte-wise ta_kv_page_restore / ta_kv_page_evict; ta_append_prefill and
- *                   ta_kv_append return TA_ERR_UNSUPPORTED for it.
+ *                   byte-wise ta_kv_page_restore / ta_kv_page_evict.  ta_kv_append writes such
+ *                   a cache: the code of an element x is the E4M3 value nearest to x / scale
+ *                   (the quotient in fp32, ties to the code with an even mantissa, anything
+ *                   beyond the largest value becomes +-448, NaN stays NaN).
+ *                   ta_append_prefill returns TA_ERR_UNSUPPORTED for it.
  */
 #define TA_KV_BF16 0
 #define TA_KV_FP8_E4M3 1
@@ -284,7 +287,8 @@ TA_API int ta_kv_page_evict(const void *k_pool, const void *v_pool, size_t page_
  * already); bit patterns are copied:
  *     pool[block_table[b][t / 16]][g][t % 16][:] = new[cu_new_lens[b] + i][g][:],
  *     t = context_lens[b] - n_b + i,  for K and for V, every kv head g
- * The pages named by the block table must exist; no other byte changes.
+ * (into a TA_KV_FP8_E4M3 cache: the E4M3 codes of new / k_scale and new / v_scale, see the
+ * formats above).  The pages named by the block table must exist; no other byte changes.
  *
  *   new_k,new_v   DEVICE bf16 [total_new][Hkv][128], programs packed back to back
  *   cu_new_lens   DEVICE int32 [batch+1], non-decreasing, cu_new_lens[0] = 0

@@ -487,7 +487,6 @@ int ta_kv_append(const ta_attn_desc* desc, const void* new_k, const void* new_v,
     Geometry g{};
     const int rc = resolve_geometry(desc, &g);
     if (rc != TA_OK) return rc;
-    if (g.kv_fp8) return TA_ERR_UNSUPPORTED;
     if (batch < 0 || total_new < 0 || block_table_stride < 0) return TA_ERR_INVALID_ARG;
     if (batch == 0 || total_new == 0) return TA_OK;
     if (!new_k || !new_v || !cu_new_lens || !k_pool || !v_pool || !block_table || !context_lens)

@@ -112,6 +112,62 @@ __global__ __launch_bounds__(256) void append_tokens_kernel(
     }
 }
 
+// The E4M3 code nearest to q: ties to the code with an even mantissa, saturation at +-448 (a cache
+// never acquires a NaN the model did not produce), NaN stays NaN, the sign of zero is kept.
+//   below 2^-6 the format is a fixed-point grid of 2^-9 steps: round(|q| * 512), 8 being the first normal code;
+//   above, the fp32 pattern is rounded at its bit 20 (3 mantissa bits stay) and the exponent re-biased (127 -> 7).
+// The sign is the element's own (the scale is positive; the sign a division gives a NaN is not defined).
+__device__ __forceinline__ uint32_t quantise_e4m3(float q, uint32_t element_bits) {
+    const uint32_t sign = (element_bits >> 24) & 0x80u;
+    const uint32_t a = __builtin_bit_cast(uint32_t, q) & 0x7fffffffu;
+    if (a > 0x7f800000u) return sign | 0x7fu;
+    if (a >= 0x43e00000u) return sign | 0x7eu;                    // |q| >= 448
+    if (a < 0x3c800000u)                                          // |q| < 2^-6
+        return sign | static_cast<uint32_t>(__builtin_rintf(__builtin_bit_cast(float, a) * 512.0f));
+    const uint32_t r = a + 0x7ffffu + ((a >> 20) & 1u);
+    return sign | ((r >> 20) - (120u << 3));
+}
+
+// KV append into an FP8 cache: as append_tokens_kernel, the bf16 rows being quantised on the way
+// (x / scale in fp32, correctly rounded).  A lane takes eight elements: 16 bytes in, 8 bytes out.
+__global__ __launch_bounds__(256) void append_tokens_fp8_kernel(
+    const char* __restrict__ new_k, const char* __restrict__ new_v, const int32_t* __restrict__ cu_new,
+    char* __restrict__ k_pool, char* __restrict__ v_pool, const int32_t* __restrict__ block_table,
+    int32_t block_table_stride, const int32_t* __restrict__ context_lens, int32_t batch, int32_t num_kv_heads,
+    int64_t stride_page_bytes, int64_t stride_head_bytes, float k_scale, float v_scale) {
+    const int row = blockIdx.x;
+    if (row >= cu_new[batch]) return;
+    int lo = 0, hi = batch - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (cu_new[mid] <= row) lo = mid; else hi = mid - 1;
+    }
+    const int b = lo;
+    const int n = cu_new[b + 1] - cu_new[b];
+    const int token = context_lens[b] - n + (row - cu_new[b]);
+    const int64_t page = block_table[int64_t(b) * block_table_stride + token / kPageSize];
+    const int64_t dst_row = page * stride_page_bytes + int64_t(token % kPageSize) * kHeadDim;
+    const int64_t src_row = int64_t(row) * num_kv_heads * (kHeadDim * 2);
+    for (int piece = threadIdx.x; piece < num_kv_heads * 16 * 2; piece += blockDim.x) {
+        const int is_v = piece / (num_kv_heads * 16);
+        const int rest = piece - is_v * num_kv_heads * 16;
+        const int g = rest >> 4, c = rest & 15;
+        const float scale = is_v ? v_scale : k_scale;
+        const uint4 x = *reinterpret_cast<const uint4*>((is_v ? new_v : new_k) + src_row + g * (kHeadDim * 2) + c * 16);
+        const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+        uint32_t codes[2] = {0u, 0u};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t lo_bits = w[i] << 16, hi_bits = w[i] & 0xffff0000u;   // elements 2 i and 2 i + 1 as fp32
+            const uint32_t pair = quantise_e4m3(__builtin_bit_cast(float, lo_bits) / scale, lo_bits) |
+                                  (quantise_e4m3(__builtin_bit_cast(float, hi_bits) / scale, hi_bits) << 8);
+            codes[i >> 1] |= pair << (16 * (i & 1));
+        }
+        *reinterpret_cast<uint2*>((is_v ? v_pool : k_pool) + dst_row + g * stride_head_bytes + c * 8) =
+            make_uint2(codes[0], codes[1]);
+    }
+}
+
 }  // namespace
 
 int launch_evict(const void* k_pool, const void* v_pool, size_t page_bytes, void* host_k, void* host_v,
@@ -158,6 +214,15 @@ int launch_evict(const void* k_pool, const void* v_pool, size_t page_bytes, void
 int launch_append(const Geometry& g, const void* new_k, const void* new_v, const int32_t* cu_new_lens,
                   void* k_pool, void* v_pool, const int32_t* block_table, int32_t block_table_stride,
                   const int32_t* context_lens, int32_t batch, int32_t total_new, hipStream_t stream) {
+    if (g.kv_fp8) {
+        hipLaunchKernelGGL(append_tokens_fp8_kernel, dim3(unsigned(total_new)), dim3(256), 0, stream,
+                           static_cast<const char*>(new_k), static_cast<const char*>(new_v), cu_new_lens,
+                           static_cast<char*>(k_pool), static_cast<char*>(v_pool), block_table,
+                           block_table_stride, context_lens, batch, g.num_kv_heads, g.stride_page_bytes,
+                           g.stride_head_bytes, g.k_scale, g.v_scale);
+        TA_HIP_TRY(hipGetLastError());
+        return TA_OK;
+    }
     hipLaunchKernelGGL(append_tokens_kernel, dim3(unsigned(total_new)), dim3(256), 0, stream,
                        static_cast<const char*>(new_k), static_cast<const char*>(new_v), cu_new_lens,
                        static_cast<char*>(k_pool), static_cast<char*>(v_pool), block_table,

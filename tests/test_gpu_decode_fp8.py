@@ -121,9 +121,62 @@ def test_forked_programs_read_aliased_pages():
     gu.assert_close(out, lse, ref, ref_lse, "fp8 forked", lse_tol=gu.LSE_TOL_PREFILL)
 
 
-def test_append_prefill_and_kv_append_refuse_an_fp8_cache():
+def test_append_prefill_refuses_an_fp8_cache():
     desc = ta.Desc(8, 2, kv_format=ta.KV_FP8_E4M3, k_scale=1.0, v_scale=1.0)
     z = torch.zeros(4096, dtype=torch.uint8, device=DEV)
     i = torch.zeros(8, dtype=torch.int32, device=DEV)
     assert ta.ta_append_prefill(desc, z, i, z, z, i.view(2, 4), i[:2], 2, 2, 64, z, None, z, check=False) == ta.TA_ERR_UNSUPPORTED
-    assert ta.ta_kv_append(desc, z, z, i, z, z, i.view(2, 4), i[:2], 2, check=False) == ta.TA_ERR_UNSUPPORTED
+
+
+def _append_fp8(desc, new_k, new_v, cu, k_codes, v_codes, table, lens):
+    ta.ta_kv_append(desc, new_k, new_v, torch.from_numpy(cu).to(DEV), k_codes, v_codes,
+                    torch.from_numpy(table).to(DEV), torch.from_numpy(lens).to(DEV), int(cu[-1]))
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("scale", [1.0, 0.021, 3.0, 2.0 ** -7])
+def test_append_quantises_every_bf16_pattern_as_the_oracle_does(scale):
+    """All 65536 bf16 bit patterns (NaN, infinities, subnormals, ties of the format at scale 1) go
+    through ta_kv_append as the 512 new tokens of one program with one kv head: codes bit-exact."""
+    bits = torch.arange(65536, dtype=torch.int32).to(torch.int16).view(512, 1, 128).to(DEV)
+    new_k = bits.view(torch.bfloat16)
+    new_v = torch.flip(bits, dims=[0]).contiguous().view(torch.bfloat16)
+    lens = np.array([512 + 40], np.int32)                       # 40 tokens are cached already
+    cu = np.array([0, 512], np.int32)
+    pages = (int(lens[0]) + 15) // 16
+    table = np.random.default_rng(wl.SEED_BASE + 3800).permutation(pages + 3)[:pages].astype(np.int32)[None, :]
+    k_codes = torch.full((pages + 3, 1, 16, 128), 0x55, dtype=torch.uint8, device=DEV)
+    v_codes = torch.full((pages + 3, 1, 16, 128), 0x66, dtype=torch.uint8, device=DEV)
+    want_k, want_v = wl.as_u8(k_codes).copy(), wl.as_u8(v_codes).copy()
+    desc = ta.Desc(4, 1, kv_format=ta.KV_FP8_E4M3, k_scale=scale, v_scale=scale * 0.5)
+    oracle.kv_append_fp8(oracle.Geometry(4, 1), wl.as_u16(new_k), wl.as_u16(new_v), cu, want_k, want_v, scale,
+                         scale * 0.5, table, lens)
+    _append_fp8(desc, new_k, new_v, cu, k_codes, v_codes, table, lens)
+    got_k, got_v = wl.as_u8(k_codes), wl.as_u8(v_codes)
+    assert np.array_equal(got_k, want_k), np.argwhere(got_k != want_k)[:5]
+    assert np.array_equal(got_v, want_v), np.argwhere(got_v != want_v)[:5]
+    assert (want_k == 0x55).sum() >= (40 + 3 * 16) * 128        # what was cached or unused stayed as it was
+
+
+def test_a_cache_grown_by_append_decodes_like_the_oracles():
+    """Ragged batch, eight kv heads: append the last tokens of every program into an FP8 cache that
+    holds the earlier ones, then decode over it; codes bit-exact, attention within tolerance."""
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 3801, batch=9, len_lo=3, len_hi=1500,
+                           first_lens=[1, 16, 17, 33])
+    fc = wl.to_fp8_cache(wb)
+    rng = np.random.default_rng(wl.SEED_BASE + 3802)
+    new = np.minimum(wb.context_lens, rng.integers(0, 70, size=wb.batch)).astype(np.int32)
+    new[0] = wb.context_lens[0]                                  # a program that is all new
+    cu = np.zeros(wb.batch + 1, np.int32); np.cumsum(new, out=cu[1:])
+    total = int(cu[-1])
+    new_k = (torch.randn(total, wb.num_kv_heads, 128, device=DEV) * 1.5).to(torch.bfloat16)
+    new_v = torch.randn(total, wb.num_kv_heads, 128, device=DEV).to(torch.bfloat16)
+    want_k, want_v = wl.as_u8(fc.k_codes).copy(), wl.as_u8(fc.v_codes).copy()
+    oracle.kv_append_fp8(gu.geom_of(wb), wl.as_u16(new_k), wl.as_u16(new_v), cu, want_k, want_v, fc.k_scale,
+                         fc.v_scale, wb.block_table, wb.context_lens)
+    desc = gu.desc_of(wb, kv_format=ta.KV_FP8_E4M3, k_scale=fc.k_scale, v_scale=fc.v_scale, pool_pages=wb.pool_pages)
+    _append_fp8(desc, new_k, new_v, cu, fc.k_codes, fc.v_codes, wb.block_table, wb.context_lens)
+    assert np.array_equal(wl.as_u8(fc.k_codes), want_k) and np.array_equal(wl.as_u8(fc.v_codes), want_v)
+    out, lse = gu.gpu_decode_fp8(wb, fc)
+    ref, ref_lse = gu.oracle_decode_fp8(wb, fc)
+    gu.assert_close(out, lse, ref, ref_lse, "fp8 cache grown by append", lse_tol=gu.LSE_TOL_PREFILL)
