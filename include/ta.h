@@ -40,8 +40,8 @@
  *     In debug mode (ta_set_debug_checks(1), or the environment variable
  *     TA_DEBUG=1 when the library makes its first call) ta_paged_decode,
  *     ta_append_prefill and ta_kv_append first run a checking kernel and wait
- *     for it (the call then synchronises the stream and cannot be captured in a
- *     graph): context lengths outside [0, max_context_len], block-table entries
+ *     for it (the call then synchronises the stream; a call made while its stream
+ *     is being captured into a graph goes unchecked): context lengths outside [0, max_context_len], block-table entries
  *     among the pages in use that are negative or, when the descriptor states
  *     pool_pages, not below it, and prefix sums (cu_q_lens, cu_new_lens) that do
  *     not start at 0, decrease, do not end at the stated total, or give a

@@ -238,6 +238,10 @@ int debug_flag_address(int32_t** out) {
 int check_metadata(const int32_t* block_table, int32_t block_table_stride, const int32_t* context_lens,
                    const int32_t* cu_q_lens, int32_t batch, int32_t max_context_len, int32_t total_q,
                    int32_t max_q_len, int32_t pool_pages, hipStream_t stream) {
+    // The verdict has to reach the host, which a stream under graph capture cannot give: a call
+    // that is being captured goes unchecked (check it once eagerly, before the capture).
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &capture) == hipSuccess && capture != hipStreamCaptureStatusNone) return TA_OK;
     int32_t* flag = nullptr;
     const int rc = debug_flag_address(&flag);
     if (rc != TA_OK) return rc;
