@@ -34,20 +34,26 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 
 # HBM bytes per launch of the kernel that streams the decode batch, from rocprofv3 --pmc
 # (FETCH_SIZE + WRITE_SIZE, each scaled by the same counter on a 1 GiB device copy), keyed by the
-# hash of the kernel source they were taken with.  A changed kernel source gives null until the
-# counters are taken again.
-TRAFFIC_BYTES = {"24a064bd2fcbf7de": 5081000000}
+# hash of the kernel source's code (comments aside) they were taken with.  A changed kernel gives
+# null until the counters are taken again.
+TRAFFIC_BYTES = {"6898bfa80d57dec5": 5081000000}
 # The same batch on the vector-ALU kernel (the library's choice for smaller batches).
-VECTOR_TRAFFIC_BYTES = {"2eb4740e53043875": 5081000000}
+VECTOR_TRAFFIC_BYTES = {"1b5ce47e6da76fa4": 5081000000}
 # The same for the FP8-cache decode kernel.
-FP8_TRAFFIC_BYTES = {"bc3cc5f35fa140eb": 2560000000}
+FP8_TRAFFIC_BYTES = {"1d82709dd3cd9ea6": 2560000000}
 # The same for the append-prefill tile kernel: bytes that left the L2 per launch (FETCH_SIZE scaled).
-PREFILL_TRAFFIC_BYTES = {"24a064bd2fcbf7de": 16870000000}
+PREFILL_TRAFFIC_BYTES = {"6898bfa80d57dec5": 16870000000}
 
 
 def source_hash(name: str) -> str:
+    """Hash of a kernel source's code: // comments and blank space do not count."""
     path = os.path.join(ROOT, "paper_2602_13692_amd", "csrc", name)
-    return hashlib.sha256(open(path, "rb").read()).hexdigest()[:16]
+    code = []
+    for line in open(path, encoding="utf-8"):
+        line = line.split("//", 1)[0].strip()
+        if line:
+            code.append(" ".join(line.split()))
+    return hashlib.sha256("\n".join(code).encode()).hexdigest()[:16]
 
 
 def time_steps(fn, steps: int, warmup: int, torch):

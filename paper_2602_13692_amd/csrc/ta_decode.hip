@@ -128,9 +128,10 @@ __global__ __launch_bounds__(256) void predecessor_prefix_kernel(const int32_t* 
 //   items         (program, first page, pages, slot)
 // counts[0] = number of items, counts[1] = number of shared items, counts[2] = 0 (the tile
 // kernel's work counter).
-// With private_on_tiles (eight query heads per kv head) every remaining chunk is listed as a
-// group of one program in shared_items instead, and `items` stays empty; rem_pages equals
-// chunk_pages then, so a leftover is one item.
+// With private_on_tiles (eight query heads per kv head, or a large batch) every remaining chunk
+// is listed as a group of one program in shared_items instead, and `items` stays empty;
+// rem_pages equals chunk_pages then, so a leftover is one item, and the leftovers are listed in
+// four classes of length, long first.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __restrict__ context_lens,
                                                            const int32_t* __restrict__ pred,

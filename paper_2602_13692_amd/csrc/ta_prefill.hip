@@ -205,7 +205,7 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 // Waves none of whose 32 rows exist take part in the loads and barriers only.
 template <int G, bool SHARED>
 __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillParams p) {
-    constexpr int kTileTokens = kRowsPerBlock / G;   // programs per item when SHARED
+    constexpr int kTileTokens = kRowsPerBlock / G;   // new tokens per query tile (append-prefill)
     extern __shared__ __attribute__((aligned(16))) char lds[];   // [kRing][K tile | V tile]
 
     // Append-prefill is launched with one workgroup per (item, kv head) pair.  The decode side
