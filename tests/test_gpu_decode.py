@@ -95,6 +95,20 @@ def test_runs_are_deterministic():
     assert torch.equal(a.view(torch.int16), b.view(torch.int16)) and torch.equal(la, lb)
 
 
+def test_runs_on_the_tile_kernel_route_are_deterministic():
+    """There the workgroups take items from a counter in whatever order they finish: every item writes
+    its own partial slots, so the result must not depend on who ran what."""
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 801, batch=40, len_lo=100, len_hi=12000)
+    runs = [gu.gpu_decode_bound(wb, 16 * 1100) for _ in range(4)]          # 40 x 1100 pages: tile route
+    for out, lse in runs[1:]:
+        assert torch.equal(out.view(torch.int16), runs[0][0].view(torch.int16)) and torch.equal(lse, runs[0][1])
+    wf = wl.forked_decode(DEV, seed=wl.SEED_BASE + 802, batch=48, group=16, prefix_len=4096, suffix_lo=10,
+                          suffix_hi=3000)
+    runs = [gu.gpu_decode(wf) for _ in range(4)]
+    for out, lse in runs[1:]:
+        assert torch.equal(out.view(torch.int16), runs[0][0].view(torch.int16)) and torch.equal(lse, runs[0][1])
+
+
 def test_scale_override_and_strided_pool():
     """A non-default scale, and a pool whose page stride is larger than the packed tile size."""
     wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 900, batch=5, len_lo=50, len_hi=900,
