@@ -6,6 +6,7 @@ this package.  It never imports the HIP library or its Python binding.
 from .ta_oracle import (  # noqa: F401
     Geometry,
     append_prefill,
+    append_prefill_fp8,
     attend_rows,
     build,
     kv_append,

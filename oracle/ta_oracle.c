@@ -351,6 +351,44 @@ void ta_oracle_append_prefill(const oracle_geom *ge, const uint16_t *q,
 }
 
 /*
+ * Append-prefill over an FP8 cache: as ta_oracle_append_prefill, the keys and values (the new
+ * tokens' own included: they were quantised when they were appended) read as E4M3 codes times
+ * their scale, as in ta_oracle_paged_decode_fp8.
+ */
+void ta_oracle_append_prefill_fp8(const oracle_geom *ge, const uint16_t *q, const int32_t *cu_q_lens,
+                                  const uint8_t *k_pool, const uint8_t *v_pool, double k_scale, double v_scale,
+                                  const int32_t *block_table, int64_t table_stride,
+                                  const int32_t *context_lens, int32_t batch, double *out, double *lse)
+{
+    const int32_t Hq = ge->num_q_heads, d = ge->head_dim;
+    int64_t longest = 1;
+    for (int32_t b = 0; b < batch; ++b)
+        if (context_lens[b] > longest) longest = context_lens[b];
+    const int64_t total_q = batch > 0 ? cu_q_lens[batch] : 0;
+    int32_t *owner = (int32_t *)malloc((size_t)(total_q > 0 ? total_q : 1) * sizeof(int32_t));
+    for (int32_t b = 0; b < batch; ++b)
+        for (int64_t t = cu_q_lens[b]; t < cu_q_lens[b + 1]; ++t) owner[t] = b;
+    const int64_t rows = total_q * Hq;
+#pragma omp parallel
+    {
+        double *weights = (double *)malloc((size_t)longest * sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t r = 0; r < rows; ++r) {
+            const int64_t t = r / Hq;
+            const int32_t h = (int32_t)(r % Hq);
+            const int32_t b = owner[t];
+            const int64_t n = cu_q_lens[b + 1] - cu_q_lens[b];
+            const int64_t i = t - cu_q_lens[b];
+            const int64_t visible = (int64_t)context_lens[b] - n + i + 1;
+            attend_row_fp8(ge, q + r * d, h, k_pool, v_pool, k_scale, v_scale,
+                           block_table + (int64_t)b * table_stride, visible, weights, out + r * d, lse + r);
+        }
+        free(weights);
+    }
+    free(owner);
+}
+
+/*
  * Selected rows only (for checking sampled outputs of a large workload).
  * Row r is (program row_b[r], packed query token row_t[r], query head row_h[r])
  * and sees row_visible[r] keys.  q is the full packed bf16 [.][Hq][d] array.

@@ -81,6 +81,7 @@ def _load():
         _lib.ta_oracle_widen_e4m3.restype = None
         _lib.ta_oracle_quantise_e4m3.restype = None
         _lib.ta_oracle_kv_append_fp8.restype = None
+        _lib.ta_oracle_append_prefill_fp8.restype = None
         _lib.ta_oracle_paged_decode_fp8.restype = None
     return _lib
 
@@ -198,6 +199,29 @@ def append_prefill(geom: Geometry, q, cu_q_lens, k_pool, v_pool, block_table, co
     lib.ta_oracle_append_prefill(
         ctypes.byref(g), _p(q), _p(cu_q_lens), _p(k_pool), _p(v_pool), _p(block_table),
         ctypes.c_int64(stride), _p(context_lens), ctypes.c_int32(B), _p(out), _p(lse),
+    )
+    return out, lse
+
+
+def append_prefill_fp8(geom: Geometry, q, cu_q_lens, k_pool, v_pool, k_scale, v_scale, block_table, context_lens):
+    """Append-prefill over an FP8 cache: q uint16 bf16 [total_q,Hq,d]; pools uint8 E4M3 codes."""
+    lib = _load()
+    q = _u16(q)
+    k_pool, v_pool = np.ascontiguousarray(k_pool), np.ascontiguousarray(v_pool)
+    assert k_pool.dtype == np.uint8 and v_pool.dtype == np.uint8, "FP8 pools travel as uint8 codes"
+    block_table = _i32(block_table)
+    context_lens = _i32(context_lens)
+    cu_q_lens = _i32(cu_q_lens)
+    B = int(context_lens.shape[0])
+    total_q = int(cu_q_lens[B]) if B > 0 else 0
+    stride = int(block_table.shape[1]) if block_table.ndim == 2 else 0
+    out = np.zeros((total_q, geom.num_q_heads, geom.head_dim), dtype=np.float64)
+    lse = np.zeros((total_q, geom.num_q_heads), dtype=np.float64)
+    g = geom.c_struct()
+    lib.ta_oracle_append_prefill_fp8(
+        ctypes.byref(g), _p(q), _p(cu_q_lens), _p(k_pool), _p(v_pool), ctypes.c_double(float(np.float32(k_scale))),
+        ctypes.c_double(float(np.float32(v_scale))), _p(block_table), ctypes.c_int64(stride), _p(context_lens),
+        ctypes.c_int32(B), _p(out), _p(lse),
     )
     return out, lse
 

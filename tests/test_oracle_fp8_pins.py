@@ -279,3 +279,74 @@ def test_fp8_append_equals_direct_indexing_of_quantised_rows():
     oracle.kv_append_fp8(oracle.Geometry(8, Hkv), new_k, new_v, cu, k_pool, v_pool, ks, vs, table, lens)
     assert np.array_equal(k_pool, want_k) and np.array_equal(v_pool, want_v)
     assert not np.array_equal(want_k, want_v)
+
+
+# ---- append-prefill over an FP8 cache ----
+
+def _prefill_case(rng, Hq, Hkv, new, prefix):
+    new, prefix = np.asarray(new, np.int32), np.asarray(prefix, np.int32)
+    lens = (new + prefix).astype(np.int32)
+    B = len(lens)
+    _, k, v, table, lens = _case(rng, B, Hq, Hkv, lens)
+    cu = np.zeros(B + 1, np.int32); np.cumsum(new, out=cu[1:])
+    f = rng.standard_normal((int(cu[-1]), Hq, D)).astype(np.float32)
+    bits = f.view(np.uint32)
+    q = (((bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000) >> 16).astype(np.uint16)
+    return q, cu, k, v, table, lens
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(2, 1), (8, 2), (4, 4)])
+def test_fp8_prefill_matches_dense_numpy_with_a_causal_mask(Hq, Hkv):
+    """New token i of a program sees its prefix and the new tokens 0 .. i (itself included): dense
+    numpy attention over the dequantised arrays (torch's widening), one row at a time."""
+    rng = np.random.default_rng(wl.SEED_BASE + 2100 + Hq)
+    new, prefix = [1, 3, 17, 2, 0], [0, 14, 20, 100, 5]
+    q, cu, k, v, table, lens = _prefill_case(rng, Hq, Hkv, new, prefix)
+    ks, vs = 0.03, 0.4
+    out, lse = oracle.append_prefill_fp8(oracle.Geometry(Hq, Hkv), q, cu, k, v, ks, vs, table, lens)
+    assert out.shape == (int(cu[-1]), Hq, D)
+    kd, vd = _dequant(k, ks), _dequant(v, vs)
+    G = Hq // Hkv
+    for b in range(len(new)):
+        L = int(lens[b])
+        pages = table[b, : (L + PS - 1) // PS].astype(np.int64)
+        for i in range(new[b]):
+            visible = prefix[b] + i + 1
+            for h in range(Hq):
+                K = kd[pages, h // G].reshape(-1, D)[:visible]
+                V = vd[pages, h // G].reshape(-1, D)[:visible]
+                s = (K @ widen_bf16(q[cu[b] + i, h])) / math.sqrt(D)
+                e = np.exp(s - s.max())
+                ref = (e / e.sum()) @ V
+                assert np.max(np.abs(out[cu[b] + i, h] - ref)) <= 1e-12 * max(1.0, np.abs(ref).max())
+                assert abs(lse[cu[b] + i, h] - (s.max() + math.log(e.sum()))) <= 1e-12
+
+
+def test_fp8_prefill_rows_equal_fp8_decodes_of_the_growing_context():
+    """Row i of a program is what the (separately pinned) FP8 decode gives for a context of
+    prefix + i + 1 tokens and the same query: bit-identical, both walk the same steps."""
+    rng = np.random.default_rng(wl.SEED_BASE + 2110)
+    Hq, Hkv = 4, 2
+    new, prefix = [5, 18], [30, 0]
+    q, cu, k, v, table, lens = _prefill_case(rng, Hq, Hkv, new, prefix)
+    ks, vs = 0.021, 0.017
+    out, lse = oracle.append_prefill_fp8(oracle.Geometry(Hq, Hkv), q, cu, k, v, ks, vs, table, lens)
+    for b in range(2):
+        for i in range(new[b]):
+            one, one_lse = oracle.paged_decode_fp8(oracle.Geometry(Hq, Hkv), q[cu[b] + i][None], k, v, ks, vs,
+                                                   table[b][None], np.array([prefix[b] + i + 1], np.int32))
+            assert np.array_equal(one[0], out[cu[b] + i]) and np.array_equal(one_lse[0], lse[cu[b] + i])
+
+
+def test_fp8_prefill_ignores_nan_codes_behind_the_causal_boundary():
+    rng = np.random.default_rng(wl.SEED_BASE + 2120)
+    Hq, Hkv = 2, 1
+    q, cu, k, v, table, lens = _prefill_case(rng, Hq, Hkv, [6], [10])
+    want = oracle.append_prefill_fp8(oracle.Geometry(Hq, Hkv), q, cu, k, v, 0.05, 0.05, table, lens)
+    # the LAST new token's key and value only matter to itself: NaN there must leave rows 0 .. 4 alone
+    page, row = int(table[0, 15 // PS]), 15 % PS
+    k[page, :, row, :] = 0x7f
+    v[page, :, row, :] = 0xff
+    got = oracle.append_prefill_fp8(oracle.Geometry(Hq, Hkv), q, cu, k, v, 0.05, 0.05, table, lens)
+    assert np.array_equal(got[0][:5], want[0][:5]) and np.array_equal(got[1][:5], want[1][:5])
+    assert np.all(np.isnan(got[0][5]))
