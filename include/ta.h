@@ -112,7 +112,10 @@ typedef struct ta_attn_desc {
  *                   a cache: the code of an element x is the E4M3 value nearest to x / scale
  *                   (the quotient in fp32, ties to the code with an even mantissa, anything
  *                   beyond the largest value becomes +-448, NaN stays NaN).
- *                   ta_append_prefill returns TA_ERR_UNSUPPORTED for it.
+ *                   ta_append_prefill reads such a cache through a bf16 copy of the batch's
+ *                   pages that it makes in the workspace first (exact: every code value is a
+ *                   bf16 value), so ta_workspace_bytes then also counts
+ *                   batch * ceil(max_context_len / 16) pages of Hkv * 8 KiB for K and V together.
  */
 #define TA_KV_BF16 0
 #define TA_KV_FP8_E4M3 1

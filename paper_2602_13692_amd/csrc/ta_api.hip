@@ -151,6 +151,15 @@ WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_l
         w.off_chunk_start = w.off_items = w.off_part_ml = w.off_part_o = off;
         w.off_tile_start = off; off = align256(off + sizeof(int32_t) * (size_t(batch) + 1));
         w.off_tiles = off;      off = align256(off + sizeof(int32_t) * 2 * size_t(w.max_tiles));
+        if (g.kv_fp8) {
+            // the tile kernel reads a bf16 copy of the batch's pages: room for every program's bound
+            w.wide_width = static_cast<int32_t>(pages);
+            const size_t slots = size_t(batch) * size_t(pages);
+            const size_t pool_bytes = slots * size_t(g.num_kv_heads) * kPageSize * kHeadDim * 2;
+            w.off_wide_table = off; off = align256(off + sizeof(int32_t) * slots);
+            w.off_wide_k = off;     off = align256(off + pool_bytes);
+            w.off_wide_v = off;     off = align256(off + pool_bytes);
+        }
     }
     w.total_bytes = off;
     return w;
@@ -393,10 +402,10 @@ int ta_append_prefill(const ta_attn_desc* desc, const void* q, const int32_t* cu
     Geometry g;
     int rc = resolve_geometry(desc, &g);
     if (rc != TA_OK) return rc;
-    if (g.kv_fp8) return TA_ERR_UNSUPPORTED;
     if (batch < 0 || total_q < 0 || max_q_len < 0 || max_context_len < 0 || block_table_stride < 0)
         return TA_ERR_INVALID_ARG;
     if (batch == 0 || total_q == 0) return TA_OK;
+    if (g.kv_fp8 && batch > 65535) return TA_ERR_UNSUPPORTED;   // the widening pass has one grid row per program
     if (!q || !cu_q_lens || !k_pool || !v_pool || !block_table || !context_lens || !out || !workspace)
         return TA_ERR_INVALID_ARG;
     if (max_q_len == 0 || max_q_len > max_context_len) return TA_ERR_INVALID_ARG;

@@ -359,7 +359,50 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
     }
 }
 
+// Append-prefill over an FP8 cache runs the bf16 tile kernel on a widened copy of the batch's
+// pages: the contraction there is bound by the matrix cores and their issue port, and widening
+// every operand on the fly would add vector work to exactly that port, while one streaming pass
+// (codes in, twice the bytes out) costs a few per cent of the prefill's time.  The copy holds
+// code VALUES; the scales enter the softmax scale and the output as in the decode kernel.
+__global__ __launch_bounds__(256) void widen_pages_kernel(
+    const char* __restrict__ k_codes, const char* __restrict__ v_codes, const int32_t* __restrict__ block_table,
+    int32_t block_table_stride, const int32_t* __restrict__ context_lens, int32_t width, int32_t num_kv_heads,
+    int64_t stride_page_bytes, int64_t stride_head_bytes, char* __restrict__ wide_k, char* __restrict__ wide_v,
+    int32_t* __restrict__ wide_table) {
+    const int b = blockIdx.y, i = blockIdx.x;
+    const int slot = b * width + i;
+    if (threadIdx.x == 0) wide_table[slot] = slot;
+    const int L = context_lens[b];
+    int pages = L > 0 ? (L + kPageSize - 1) / kPageSize : 0;
+    pages = pages < width ? pages : width;
+    if (i >= pages) return;
+    const int64_t src = int64_t(block_table[int64_t(b) * block_table_stride + i]) * stride_page_bytes;
+    const int64_t dst = int64_t(slot) * num_kv_heads * (kPageBytes * 2);
+    // a lane takes 16 codes (16 bytes in, 32 bytes out); a (page, kv head) tile is 128 such pieces
+    for (int piece = threadIdx.x; piece < num_kv_heads * 128 * 2; piece += blockDim.x) {
+        const int is_v = piece / (num_kv_heads * 128);
+        const int rest = piece - is_v * num_kv_heads * 128;
+        const int g = rest >> 7, c = rest & 127;
+        const u32x4 codes = *reinterpret_cast<const u32x4*>((is_v ? v_codes : k_codes) + src + g * stride_head_bytes + c * 16);
+        u32x4* out = reinterpret_cast<u32x4*>((is_v ? wide_v : wide_k) + dst + int64_t(g) * (kPageBytes * 2) + c * 32);
+        out[0] = widen8_bits(codes.x, codes.y);
+        out[1] = widen8_bits(codes.z, codes.w);
+    }
+}
+
 }  // namespace
+
+int launch_widen_pages(const Geometry& g, const void* k_codes, const void* v_codes, const int32_t* block_table,
+                       int32_t block_table_stride, const int32_t* context_lens, int32_t batch, int32_t width,
+                       void* wide_k, void* wide_v, int32_t* wide_table, hipStream_t stream) {
+    if (batch < 1 || width < 1 || batch > 65535) return TA_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(widen_pages_kernel, dim3(unsigned(width), unsigned(batch)), dim3(256), 0, stream,
+                       static_cast<const char*>(k_codes), static_cast<const char*>(v_codes), block_table,
+                       block_table_stride, context_lens, width, g.num_kv_heads, g.stride_page_bytes,
+                       g.stride_head_bytes, static_cast<char*>(wide_k), static_cast<char*>(wide_v), wide_table);
+    TA_HIP_TRY(hipGetLastError());
+    return TA_OK;
+}
 
 int launch_fp8_items(const ChunkParams& p, int32_t group, bool direct, unsigned blocks, hipStream_t stream) {
     if (group < 1 || group > kMaxGroup) return TA_ERR_UNSUPPORTED;

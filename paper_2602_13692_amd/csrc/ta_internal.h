@@ -77,6 +77,11 @@ struct WorkspaceLayout {
     size_t off_shared_items;    // int4  [max_shared_items] (position in `order`, members, bulk chunk, first member)
     size_t off_tile_start;      // int32 [batch + 1]      (prefill)
     size_t off_tiles;           // int2  [max_tiles]      (prefill)
+    // prefill over an FP8 cache: the batch's pages widened to bf16, program by program
+    int32_t wide_width;         // pages per program in the widened pools (0: not used)
+    size_t off_wide_table;      // int32 [batch][wide_width], entry (b, i) = b * wide_width + i
+    size_t off_wide_k;          // bf16  [batch * wide_width][Hkv][16][128] code values of K
+    size_t off_wide_v;          // the same for V
     size_t total_bytes;
 };
 
@@ -128,6 +133,13 @@ constexpr int kMaxItemPages = 128;   // two page ids per lane
 
 // The item kernel for pools of E4M3 codes (matrix cores, any group size up to 16).
 int launch_fp8_items(const ChunkParams& p, int32_t group, bool direct, unsigned blocks, hipStream_t stream);
+
+// Widens the pages of a batch from E4M3 codes to bf16 code values (exact), program by program:
+// logical page i of program b goes to slot b * width + i of the wide pools, and wide_table gets
+// the identity map into them.  Pages beyond a program's context are left alone.
+int launch_widen_pages(const Geometry& g, const void* k_codes, const void* v_codes, const int32_t* block_table,
+                       int32_t block_table_stride, const int32_t* context_lens, int32_t batch, int32_t width,
+                       void* wide_k, void* wide_v, int32_t* wide_table, hipStream_t stream);
 
 struct PrefillArgs {
     const uint16_t* q;

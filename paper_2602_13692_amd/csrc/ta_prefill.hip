@@ -78,6 +78,7 @@ struct PrefillParams {
     int32_t num_q_heads;
     int32_t num_kv_heads;
     float scale_log2;
+    float out_scale;             // append-prefill: multiplies the normalised output (the value scale of an FP8 cache, else 1)
 };
 
 // plan: query tiles of tile_tokens tokens per program, listed flat.  Workgroups are dispatched
@@ -873,7 +874,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
                 p.part_ml[rowid * 2 + 1] = total;
             }
         } else {
-            const float inv = total > 0.0f ? 1.0f / total : 0.0f;
+            const float inv = total > 0.0f ? p.out_scale / total : 0.0f;
             uint16_t* orow = p.out + out_row[rb];
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
@@ -952,19 +953,37 @@ int launch_prefill(const Geometry& g, const PrefillArgs& a, const WorkspaceLayou
     pp.k_pool = reinterpret_cast<const char*>(a.k_pool);
     pp.v_pool = reinterpret_cast<const char*>(a.v_pool);
     pp.block_table = a.block_table;
+    pp.stride_page_bytes = g.stride_page_bytes;
+    pp.stride_head_bytes = g.stride_head_bytes;
+    pp.block_table_stride = a.block_table_stride;
+    pp.scale_log2 = g.scale_log2;
+    pp.out_scale = 1.0f;
+    if (g.kv_fp8) {
+        // an FP8 cache: the kernel reads the batch's pages from a widened copy (code values in bf16)
+        char* wide_k = workspace + w.off_wide_k;
+        char* wide_v = workspace + w.off_wide_v;
+        int32_t* wide_table = reinterpret_cast<int32_t*>(workspace + w.off_wide_table);
+        const int rc = launch_widen_pages(g, a.k_pool, a.v_pool, a.block_table, a.block_table_stride, a.context_lens,
+                                          a.batch, w.wide_width, wide_k, wide_v, wide_table, stream);
+        if (rc != TA_OK) return rc;
+        pp.k_pool = wide_k;
+        pp.v_pool = wide_v;
+        pp.block_table = wide_table;
+        pp.block_table_stride = w.wide_width;
+        pp.stride_head_bytes = int64_t(kPageSize) * kHeadDim * 2;
+        pp.stride_page_bytes = pp.stride_head_bytes * g.num_kv_heads;
+        pp.scale_log2 = g.scale_log2 * g.k_scale;
+        pp.out_scale = g.v_scale;
+    }
     pp.context_lens = a.context_lens;
     pp.cu_q_lens = a.cu_q_lens;
     pp.tile_start = tile_start;
     pp.tiles = tiles;
     pp.out = a.out;
     pp.lse = a.lse;
-    pp.stride_page_bytes = g.stride_page_bytes;
-    pp.stride_head_bytes = g.stride_head_bytes;
-    pp.block_table_stride = a.block_table_stride;
     pp.batch = a.batch;
     pp.num_q_heads = g.num_q_heads;
     pp.num_kv_heads = g.num_kv_heads;
-    pp.scale_log2 = g.scale_log2;
 
     const int64_t blocks = max_tiles * g.num_kv_heads;
     if (blocks > 0x7fffffff) return TA_ERR_INVALID_ARG;
@@ -997,6 +1016,7 @@ int launch_shared_prefix(const Geometry& g, const SharedPrefixArgs& a, hipStream
     pp.num_q_heads = g.num_q_heads;
     pp.num_kv_heads = g.num_kv_heads;
     pp.scale_log2 = g.scale_log2;
+    pp.out_scale = 1.0f;
     int64_t blocks = int64_t(a.max_items) * g.num_kv_heads;
     if (blocks <= 0) return TA_OK;
     // One workgroup fits per CU and they take items from a counter.  Twice the CU count keeps the

@@ -102,6 +102,27 @@ def gpu_prefill(wb, stream=None):
     return out, lse
 
 
+def gpu_prefill_fp8(wb, fc, stream=None):
+    """Append-prefill over the batch's cache as E4M3 codes (fc: workloads.Fp8Cache)."""
+    dev = wb.q.device
+    desc = desc_of(wb, kv_format=ta.KV_FP8_E4M3, k_scale=fc.k_scale, v_scale=fc.v_scale)
+    bt = torch.from_numpy(wb.block_table).to(dev)
+    cl = torch.from_numpy(wb.context_lens).to(dev)
+    cu = torch.from_numpy(wb.cu_q_lens).to(dev)
+    out = torch.full_like(wb.q, float("nan"))
+    lse = torch.full((wb.total_q, wb.num_q_heads), float("nan"), dtype=torch.float32, device=dev)
+    ws = ta.alloc_workspace(desc, wb.batch, max(wb.max_q_len, 2), wb.max_context_len, dev)
+    ta.ta_append_prefill(desc, wb.q, cu, fc.k_codes, fc.v_codes, bt, cl, wb.total_q, wb.max_q_len,
+                         wb.max_context_len, out, lse, ws, stream)
+    torch.cuda.synchronize()
+    return out, lse
+
+
+def oracle_prefill_fp8(wb, fc):
+    return oracle.append_prefill_fp8(geom_of(wb), wl.as_u16(wb.q), wb.cu_q_lens, wl.as_u8(fc.k_codes),
+                                     wl.as_u8(fc.v_codes), fc.k_scale, fc.v_scale, wb.block_table, wb.context_lens)
+
+
 def oracle_decode(wb):
     return oracle.paged_decode(geom_of(wb), wl.as_u16(wb.q), wl.as_u16(wb.k_pool), wl.as_u16(wb.v_pool),
                                wb.block_table, wb.context_lens)

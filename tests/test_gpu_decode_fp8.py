@@ -121,11 +121,58 @@ def test_forked_programs_read_aliased_pages():
     gu.assert_close(out, lse, ref, ref_lse, "fp8 forked", lse_tol=gu.LSE_TOL_PREFILL)
 
 
-def test_append_prefill_refuses_an_fp8_cache():
-    desc = ta.Desc(8, 2, kv_format=ta.KV_FP8_E4M3, k_scale=1.0, v_scale=1.0)
-    z = torch.zeros(4096, dtype=torch.uint8, device=DEV)
-    i = torch.zeros(8, dtype=torch.int32, device=DEV)
-    assert ta.ta_append_prefill(desc, z, i, z, z, i.view(2, 4), i[:2], 2, 2, 64, z, None, z, check=False) == ta.TA_ERR_UNSUPPORTED
+@pytest.mark.parametrize("Hq,Hkv", [(32, 8), (8, 8), (16, 2), (8, 1)])
+def test_append_prefill_over_an_fp8_cache(Hq, Hkv):
+    """Ragged new-token counts on prefixes from zero to a few thousand tokens: the tile kernel runs on
+    the widened copy of the batch's pages; the scales enter as in the decode kernel."""
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 3900 + Hq + Hkv, batch=6, new_lo=1, new_hi=300, prefix_lo=0,
+                           prefix_hi=2500, num_q_heads=Hq, num_kv_heads=Hkv)
+    fc = wl.to_fp8_cache(wb, k_scale=0.03, v_scale=0.019)
+    out, lse = gu.gpu_prefill_fp8(wb, fc)
+    ref, ref_lse = gu.oracle_prefill_fp8(wb, fc)
+    gu.assert_close(out, lse, ref, ref_lse, f"fp8 prefill Hq={Hq} Hkv={Hkv}", lse_tol=gu.LSE_TOL_PREFILL)
+
+
+def test_append_prefill_over_an_fp8_cache_ignores_unreadable_codes():
+    """NaN codes in every row no block table can legally read (the tails of last pages, unused pool
+    pages) reach the widened copy as NaN and must never reach a result."""
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 3950, batch=5, new_lo=3, new_hi=90, prefix_lo=0, prefix_hi=700)
+    wl.poison_padding(wb)
+    fc = wl.to_fp8_cache(wb)
+    assert int((wl.as_u8(fc.k_codes) & 0x7f == 0x7f).sum()) > 0
+    out, lse = gu.gpu_prefill_fp8(wb, fc)
+    ref, ref_lse = gu.oracle_prefill_fp8(wb, fc)
+    gu.assert_close(out, lse, ref, ref_lse, "fp8 prefill, poisoned padding", lse_tol=gu.LSE_TOL_PREFILL)
+
+
+def test_append_then_prefill_then_decode_on_one_fp8_cache():
+    """The serving sequence on an FP8 cache: quantise the tool output's tokens into the tail pages,
+    attend from them (append-prefill), then decode one more step over the same cache."""
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 3960, batch=4, new_lo=10, new_hi=200, prefix_lo=50, prefix_hi=1500)
+    fc = wl.to_fp8_cache(wb)
+    new_k = torch.randn(wb.total_q, wb.num_kv_heads, 128, device=DEV).to(torch.bfloat16)
+    new_v = torch.randn(wb.total_q, wb.num_kv_heads, 128, device=DEV).to(torch.bfloat16)
+    want_k, want_v = wl.as_u8(fc.k_codes).copy(), wl.as_u8(fc.v_codes).copy()
+    oracle.kv_append_fp8(gu.geom_of(wb), wl.as_u16(new_k), wl.as_u16(new_v), wb.cu_q_lens, want_k, want_v, fc.k_scale,
+                         fc.v_scale, wb.block_table, wb.context_lens)
+    desc = gu.desc_of(wb, kv_format=ta.KV_FP8_E4M3, k_scale=fc.k_scale, v_scale=fc.v_scale)
+    _append_fp8(desc, new_k, new_v, wb.cu_q_lens, fc.k_codes, fc.v_codes, wb.block_table, wb.context_lens)
+    assert np.array_equal(wl.as_u8(fc.k_codes), want_k) and np.array_equal(wl.as_u8(fc.v_codes), want_v)
+    out, lse = gu.gpu_prefill_fp8(wb, fc)
+    ref, ref_lse = gu.oracle_prefill_fp8(wb, fc)
+    gu.assert_close(out, lse, ref, ref_lse, "fp8 prefill after append", lse_tol=gu.LSE_TOL_PREFILL)
+    # the decode step: one query per program over the same cache
+    q1 = torch.randn(wb.batch, wb.num_q_heads, 128, device=DEV).to(torch.bfloat16)
+    bt = torch.from_numpy(wb.block_table).to(DEV)
+    cl = torch.from_numpy(wb.context_lens).to(DEV)
+    out1 = torch.empty_like(q1)
+    lse1 = torch.empty((wb.batch, wb.num_q_heads), dtype=torch.float32, device=DEV)
+    ws = ta.alloc_workspace(desc, wb.batch, 1, wb.max_context_len, DEV)
+    ta.ta_paged_decode(desc, q1, fc.k_codes, fc.v_codes, bt, cl, wb.max_context_len, out1, lse1, ws)
+    torch.cuda.synchronize()
+    ref1, ref1_lse = oracle.paged_decode_fp8(gu.geom_of(wb), wl.as_u16(q1), want_k, want_v, fc.k_scale, fc.v_scale,
+                                             wb.block_table, wb.context_lens)
+    gu.assert_close(out1, lse1, ref1, ref1_lse, "fp8 decode after append and prefill", lse_tol=gu.LSE_TOL_PREFILL)
 
 
 def _append_fp8(desc, new_k, new_v, cu, k_codes, v_codes, table, lens):
