@@ -49,7 +49,9 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
     if ((sh * elem_bytes) % 16 != 0 || (sp * elem_bytes) % 16 != 0) return TA_ERR_UNSUPPORTED;
     if (sh < int64_t(kPageSize) * kHeadDim) return TA_ERR_INVALID_ARG;
     const int32_t cp = d->decode_chunk_pages;
-    if (cp != 0 && cp != 8 && cp != 16 && cp != 32 && cp != 64 && cp != 128 && !(cp == 256 && group == 8 && !fp8))
+    // chunks of 256 and 512 pages exist on the matrix-core tile kernel only (a bf16 cache): asking for
+    // one also asks for that kernel
+    if (cp != 0 && cp != 8 && cp != 16 && cp != 32 && cp != 64 && cp != 128 && !((cp == 256 || cp == 512) && !fp8))
         return TA_ERR_INVALID_ARG;
     g->num_q_heads = d->num_q_heads;
     g->num_kv_heads = d->num_kv_heads;
@@ -82,9 +84,12 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
 // product, the most the batch can hold.
 static bool decode_on_tiles(const Geometry& g, int32_t batch, int32_t max_context_len) {
     if (g.kv_fp8) return false;
-    if (g.group == 8) return true;
+    if (g.group == 8 || g.decode_chunk_pages >= 256) return true;
     const int64_t pages = (int64_t(max_context_len) + kPageSize - 1) / kPageSize;
-    return g.decode_chunk_pages == 0 && int64_t(batch) * pages >= 40000;   // one, two or four heads per kv head
+    // one, two or four heads per kv head.  The bound may be far above the real lengths (a serving
+    // loop sizes it once): then every program is a single leftover item per kv head, and only a
+    // batch with at least one such item per CU keeps the tile kernel's workgroups busy.
+    return g.decode_chunk_pages == 0 && int64_t(batch) * pages >= 40000 && int64_t(batch) * g.num_kv_heads >= 256;
 }
 
 static int32_t choose_chunk_pages(const Geometry& g, int32_t batch, int32_t max_context_len) {

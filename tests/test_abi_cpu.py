@@ -89,10 +89,12 @@ def test_host_side_rejections_need_no_device():
     slot = (ctypes.c_int32 * 1)(0)
     assert lib.ta_kv_page_restore(one, one, 32768, one, one, slot, 1, 10, null, 512, null) == ta.TA_ERR_INVALID_ARG
     assert lib.ta_kv_page_evict(one, one, 32768, one, one, slot, 1, 10, null, 512, null) == ta.TA_ERR_INVALID_ARG
-    # a chunk length the split-K plan does not offer, or one above 64 pages without eight heads per kv head
+    # a chunk length the split-K plan does not offer; 256 and 512 pages ask for the tile kernel (any head
+    # shape, a bf16 cache only)
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=24), 4, 1, 100) == 0
-    assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=256), 4, 1, 100) == 0
-    assert ta.ta_workspace_bytes(ta.Desc(64, 8, decode_chunk_pages=256), 4, 1, 100) > 0
+    assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=1024), 4, 1, 100) == 0
+    assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=256), 4, 1, 100) > 0
+    assert ta.ta_workspace_bytes(ta.Desc(64, 8, decode_chunk_pages=512), 4, 1, 100) > 0
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, pool_pages=-1), 4, 1, 100) == 0
     # the FP8 cache format needs its two scales, positive and finite; other formats do not exist
     fp8 = dict(kv_format=ta.KV_FP8_E4M3)

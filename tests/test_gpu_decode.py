@@ -29,16 +29,18 @@ def test_ragged_lengths_all_group_sizes(Hq, Hkv):
     gu.assert_close(out, lse, ref, ref_lse, f"ragged Hq={Hq} Hkv={Hkv}")
 
 
-@pytest.mark.parametrize("Hq,chunk_pages", [(32, 8), (32, 16), (32, 32), (32, 64), (32, 128),
-                                             (64, 8), (64, 16), (64, 32), (64, 64), (64, 128), (64, 256)])
+@pytest.mark.parametrize("Hq,chunk_pages", [(32, 8), (32, 16), (32, 32), (32, 64), (32, 128), (32, 256), (32, 512),
+                                             (64, 8), (64, 16), (64, 32), (64, 64), (64, 128), (64, 256), (64, 512)])
 def test_every_chunk_length(chunk_pages, Hq):
-    """Four heads per kv head run on the vector-ALU kernel (bulk chunks of up to 128 pages, the
-    leftover of a program in quarter-chunk pieces), eight on the matrix-core tile kernel (up to 256)."""
+    """Four heads per kv head run on the vector-ALU kernel with chunks of up to 128 pages (the leftover
+    of a program in quarter-chunk pieces) and on the matrix-core tile kernel with 256 or 512; eight
+    heads per kv head always on the tile kernel."""
     wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 200, batch=9, len_lo=100, len_hi=9000, num_q_heads=Hq)
     out, lse = gu.gpu_decode(wb, chunk_pages=chunk_pages)
     ref, ref_lse = gu.oracle_decode(wb)
+    on_tiles = Hq == 64 or chunk_pages >= 256
     gu.assert_close(out, lse, ref, ref_lse, f"chunk_pages={chunk_pages} Hq={Hq}",
-                    lse_tol=gu.LSE_TOL if Hq == 32 else gu.LSE_TOL_PREFILL)
+                    lse_tol=gu.LSE_TOL_PREFILL if on_tiles else gu.LSE_TOL)
 
 
 def test_padding_poison_is_never_read():
@@ -99,7 +101,7 @@ def test_runs_on_the_tile_kernel_route_are_deterministic():
     """There the workgroups take items from a counter in whatever order they finish: every item writes
     its own partial slots, so the result must not depend on who ran what."""
     wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 801, batch=40, len_lo=100, len_hi=12000)
-    runs = [gu.gpu_decode_bound(wb, 16 * 1100) for _ in range(4)]          # 40 x 1100 pages: tile route
+    runs = [gu.gpu_decode_bound(wb, 16 * 1100) for _ in range(4)]          # 40 x 1100 pages, 320 pairs: tile route
     for out, lse in runs[1:]:
         assert torch.equal(out.view(torch.int16), runs[0][0].view(torch.int16)) and torch.equal(lse, runs[0][1])
     wf = wl.forked_decode(DEV, seed=wl.SEED_BASE + 802, batch=48, group=16, prefix_len=4096, suffix_lo=10,
@@ -199,14 +201,14 @@ def test_large_bounds_send_four_heads_per_kv_head_to_the_tile_kernel(poison):
     """With up to four query heads per kv head the library streams the private chunks on the
     vector-ALU kernel for small batches and on the matrix-core tile kernel once batch x bound is
     large.  A small ragged batch under a large bound takes the second route: same results."""
-    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 260, batch=12, len_lo=1, len_hi=5000,
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 260, batch=36, len_lo=1, len_hi=5000,
                            first_lens=[1, 16, 17, 2047, 2048, 2049, 4096])
     wb.context_lens[11] = 0
     if poison:
         wl.poison_padding(wb)
     ref, ref_lse = gu.oracle_decode(wb)
-    out_v, lse_v = gu.gpu_decode(wb)                          # 12 x 313 pages: vector-ALU kernel
+    out_v, lse_v = gu.gpu_decode(wb)                          # 36 x 313 pages: vector-ALU kernel
     gu.assert_close(out_v, lse_v, ref, ref_lse, "small bound")
-    out_t, lse_t = gu.gpu_decode_bound(wb, 64000)              # 12 x 4000 pages: tile kernel, 128-page chunks
+    out_t, lse_t = gu.gpu_decode_bound(wb, 32000)              # 36 x 2000 pages, 288 (program, kv head) pairs: tile kernel
     gu.assert_close(out_t, lse_t, ref, ref_lse, "large bound", lse_tol=gu.LSE_TOL_PREFILL)
-    assert ta.ta_workspace_bytes(gu.desc_of(wb), wb.batch, 1, 64000) > 0
+    assert ta.ta_workspace_bytes(gu.desc_of(wb), wb.batch, 1, 32000) > 0

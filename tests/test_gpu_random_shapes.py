@@ -49,9 +49,10 @@ def test_forked_decode_random_shapes(seed):
 
 @pytest.mark.parametrize("seed", range(16))
 def test_tile_kernel_route_random_shapes_up_to_four_heads_per_kv_head(seed):
-    """One, two or four query heads per kv head under a large batch x bound: private chunks, leftovers
-    and chunks shared by forked groups (cut into sub-groups of 128 rows) all run on the matrix-core
-    tile kernel, where the two waves of a row block split the keys and meet in LDS."""
+    """One, two or four query heads per kv head on the tile-kernel route (asked for by its chunk
+    lengths): private chunks, leftovers and chunks shared by forked groups (cut into sub-groups of
+    128 rows) all run on the matrix-core tile kernel, where the two waves of a row block split the
+    keys and meet in LDS."""
     rng = np.random.default_rng(wl.SEED_BASE + 5600 + seed)
     Hq, Hkv = [(32, 8), (16, 4), (8, 2), (4, 1), (16, 8), (8, 8), (2, 1), (1, 1)][seed % 8]
     if seed % 3 == 0:
@@ -64,12 +65,11 @@ def test_tile_kernel_route_random_shapes_up_to_four_heads_per_kv_head(seed):
         group = int(rng.choice([2, 3, 16, 33, 40]))
         n_groups = int(rng.integers(1, 3))
         wb = wl.forked_decode(DEV, seed=wl.SEED_BASE + 5700 + seed, batch=group * n_groups, group=group,
-                              prefix_len=int(rng.choice([2048, 4096, 6000 // 16 * 16])), suffix_lo=1,
+                              prefix_len=int(rng.choice([4096, 8192, 9000 // 16 * 16, 16384])), suffix_lo=1,
                               suffix_hi=int(rng.choice([5, 900, 3000])), num_q_heads=Hq, num_kv_heads=Hkv)
     if seed % 2:
         wl.poison_padding(wb)
-    bound = max(16 * (40000 // wb.batch + 2), wb.max_context_len)
-    out, lse = gu.gpu_decode_bound(wb, bound)
+    out, lse = gu.gpu_decode(wb, chunk_pages=256 if seed % 4 < 2 else 512)     # chunks of this length run on the tile kernel
     ref, ref_lse = gu.oracle_decode(wb)
     gu.assert_close(out, lse, ref, ref_lse, f"tile route seed={seed} Hq={Hq} Hkv={Hkv} B={wb.batch}",
                     lse_tol=gu.LSE_TOL_PREFILL)
