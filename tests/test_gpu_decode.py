@@ -212,3 +212,22 @@ def test_large_bounds_send_four_heads_per_kv_head_to_the_tile_kernel(poison):
     out_t, lse_t = gu.gpu_decode_bound(wb, 32000)              # 36 x 2000 pages, 288 (program, kv head) pairs: tile kernel
     gu.assert_close(out_t, lse_t, ref, ref_lse, "large bound", lse_tol=gu.LSE_TOL_PREFILL)
     assert ta.ta_workspace_bytes(gu.desc_of(wb), wb.batch, 1, 32000) > 0
+
+
+def test_more_than_1024_programs_on_every_route():
+    """Above 1024 programs the plan kernel walks the batch in passes and does not look for shared
+    prefixes; both routes, and a forked batch (whose groups then simply are not shared), stay exact."""
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 270, batch=1100, len_lo=1, len_hi=3000, num_q_heads=8,
+                           num_kv_heads=2, first_lens=[0, 1, 2047, 2048, 2049])
+    ref, ref_lse = gu.oracle_decode(wb)
+    out, lse = gu.gpu_decode(wb)                       # 1100 x 188 pages, 2200 pairs: tile route
+    gu.assert_close(out, lse, ref, ref_lse, "1100 programs, tile route", lse_tol=gu.LSE_TOL_PREFILL)
+    out, lse = gu.gpu_decode(wb, chunk_pages=64)       # vector-ALU route
+    gu.assert_close(out, lse, ref, ref_lse, "1100 programs, vector-ALU route")
+    del wb
+    torch.cuda.empty_cache()
+    wf = wl.forked_decode(DEV, seed=wl.SEED_BASE + 271, batch=1040, group=16, prefix_len=2048, suffix_lo=1,
+                          suffix_hi=300, num_q_heads=8, num_kv_heads=2)
+    out, lse = gu.gpu_decode(wf, chunk_pages=64)
+    ref, ref_lse = gu.oracle_decode(wf)
+    gu.assert_close(out, lse, ref, ref_lse, "1040 forked programs")
