@@ -69,19 +69,19 @@ __device__ __forceinline__ uint16_t to_bf16_rne(float f) {
 // shared-prefix detection, step 1 (one workgroup per program): forked agent branches list the
 // same prefix pages at the head of their block tables, wherever they sit in the batch.  The
 // predecessor of program b is the nearest earlier program whose table starts with the same page
-// (both long enough to hold one bulk chunk); lcp[b] counts the leading pages the two have in
-// common, as far as both fill them completely.  Programs linked this way form a chain whose
+// (both long enough to hold the shortest chunk there is); lcp[b] counts the leading pages the two
+// have in common, as far as both fill them completely.  (The plan kernel, which chooses the chunk
+// length, decides what of that is worth sharing.)  Programs linked this way form a chain whose
 // first member leads the group; what all members share is the minimum along the chain.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void predecessor_prefix_kernel(const int32_t* __restrict__ block_table,
                                                                  int32_t block_table_stride,
                                                                  const int32_t* __restrict__ context_lens,
-                                                                 int32_t chunk_pages,
                                                                  int32_t* __restrict__ pred,
                                                                  int32_t* __restrict__ lcp) {
     __shared__ int best, first_diff;
     const int b = blockIdx.x;
-    const int min_tokens = chunk_pages * kPageSize;
+    const int min_tokens = kMinChunkPages * kPageSize;
     const int lb = context_lens[b];
     if (b == 0 || lb < min_tokens) {           // nothing before it, or too short to share a chunk
         if (threadIdx.x == 0) { pred[b] = -1; lcp[b] = 0; }
@@ -117,7 +117,14 @@ __global__ __launch_bounds__(256) void predecessor_prefix_kernel(const int32_t* 
 }
 
 // ---------------------------------------------------------------------------
-// plan (one workgroup).  A program's pages are cut into bulk chunks of chunk_pages and its
+// plan (one workgroup).  The host sized the workspace for chunks of chunk_pages_max pages, from
+// the bound on the context length it was given; the real lengths may be far below that bound (a
+// serving loop sizes it once), and chunks that long would then leave most of the chip without an
+// item.  So the kernel first adds up the pages that exist and halves the chunk until the batch
+// gives about as many items as the host's rule asks for (never more slots than the workspace
+// holds).  A chunk length that the caller gave is kept as it is.  The length the kernel settles on
+// is left in counts[3] for the tile kernel.
+// A program's pages are cut into bulk chunks of chunk_pages and its
 // leftover into pieces of rem_pages; every chunk or piece gets a slot for its partial result
 // (chunk_start[b] + index, bulk chunks first).  Step 2 of the shared-prefix detection forms the
 // groups (chains of predecessors), lists their members side by side in `order`, and hands the
@@ -127,7 +134,7 @@ __global__ __launch_bounds__(256) void predecessor_prefix_kernel(const int32_t* 
 //   shared_items  (position of the first member in `order`, members, bulk chunk, first member)
 //   items         (program, first page, pages, slot)
 // counts[0] = number of items, counts[1] = number of shared items, counts[2] = 0 (the tile
-// kernel's work counter).
+// kernel's work counter), counts[3] = the chunk length in pages.
 // With private_on_tiles (eight query heads per kv head, or a large batch) every remaining chunk
 // is listed as a group of one program in shared_items instead, and `items` stays empty;
 // rem_pages equals chunk_pages then, so a leftover is one item, and the leftovers are listed in
@@ -136,8 +143,9 @@ __global__ __launch_bounds__(256) void predecessor_prefix_kernel(const int32_t* 
 __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __restrict__ context_lens,
                                                            const int32_t* __restrict__ pred,
                                                            const int32_t* __restrict__ lcp,
-                                                           int32_t batch, int32_t max_pages, int32_t chunk_pages,
-                                                           int32_t rem_pages, int32_t max_members,
+                                                           int32_t batch, int32_t max_pages, int32_t chunk_pages_max,
+                                                           int32_t adapt_chunk, int32_t num_kv_heads, int32_t max_chunks,
+                                                           int32_t max_members,
                                                            int32_t max_shared_items, int32_t private_on_tiles,
                                                            int32_t* __restrict__ chunk_start,
                                                            int4* __restrict__ items,
@@ -159,7 +167,13 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
         const int n = L > 0 ? (L + kPageSize - 1) / kPageSize : 0;
         return n > max_pages ? max_pages : n;               // lengths above the host bound are clipped
     };
+    int chunk_pages = chunk_pages_max, rem_pages = chunk_pages_max;     // settled below
     auto pieces_of = [&](int pages) { return (pages % chunk_pages + rem_pages - 1) / rem_pages; };
+    auto set_chunk = [&](int c) {
+        chunk_pages = c;
+        // the tile kernel takes a program's leftover as one item; the vector-ALU kernel gets it in quarters
+        rem_pages = private_on_tiles ? c : (c >= 32 ? c / 4 : kMinChunkPages);
+    };
     // exclusive scan of `value` over one pass of the workgroup's threads (wave-level shuffles, then
     // the sixteen wave totals); returns this thread's offset including earlier passes
     auto block_scan = [&](int value) {
@@ -180,14 +194,33 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
         return before + x - value;
     };
 
-    // 1. partial slots
+    // 0. the chunk: the longest one that still gives the item count the host's rule aims at
     if (tid == 0) carry = 0;
     __syncthreads();
-    for (int base = 0; base < batch; base += nt) {
-        const int b = base + tid;
-        const int pages = b < batch ? pages_of(b) : 0;
-        const int first = block_scan(b < batch ? pages / chunk_pages + pieces_of(pages) : 0);
-        if (b < batch) chunk_start[b] = first;
+    for (int base = 0; base < batch; base += nt) block_scan(base + tid < batch ? pages_of(base + tid) : 0);
+    {
+        const int64_t total_pages = carry;
+        const int64_t target = private_on_tiles ? 512 : 2048;   // the tile kernel pays more per item
+        int c = chunk_pages_max;
+        while (adapt_chunk && c > kMinChunkPages && total_pages * num_kv_heads / c < target) c >>= 1;
+        set_chunk(c);
+    }
+    __syncthreads();
+
+    // 1. partial slots (with the host's chunk if the shorter one would need more slots than there are)
+    for (int attempt = 0; attempt < 2; ++attempt) {
+        if (tid == 0) carry = 0;
+        __syncthreads();
+        for (int base = 0; base < batch; base += nt) {
+            const int b = base + tid;
+            const int pages = b < batch ? pages_of(b) : 0;
+            const int first = block_scan(b < batch ? pages / chunk_pages + pieces_of(pages) : 0);
+            if (b < batch) chunk_start[b] = first;
+        }
+        const int total_slots = carry;
+        __syncthreads();
+        if (total_slots <= max_chunks || chunk_pages == chunk_pages_max) break;
+        set_chunk(chunk_pages_max);
     }
     if (tid == 0) chunk_start[batch] = carry;
 
@@ -325,6 +358,7 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
         counts[0] = private_on_tiles ? 0 : n_bulk + carry;
         counts[1] = private_on_tiles ? tile_base + n_bulk + carry : tile_base;
         counts[2] = 0;   // work counter of the tile kernel
+        counts[3] = chunk_pages;
     }
 }
 
@@ -719,14 +753,14 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     // sharing needs at least two programs with a bulk chunk each and a non-empty block table
     // (pools of fp8 codes take every chunk through their own item kernel: no sharing there)
     const bool look_for_sharing = !g.kv_fp8 && a.batch >= 2 && a.batch <= 1024 && w.max_shared_items > 0 &&
-                                  a.block_table_stride > 0 && cp.max_pages >= w.chunk_pages;
+                                  a.block_table_stride > 0 && cp.max_pages >= kMinChunkPages;
     // The workspace plan has decided which kernel streams the private chunks (and sized
     // shared_items for it): the matrix-core kernel takes them as groups of one program.
     const bool private_on_tiles = w.private_on_tiles != 0;
 
     if (look_for_sharing) {
         hipLaunchKernelGGL(predecessor_prefix_kernel, dim3(a.batch), dim3(256), 0, stream, a.block_table,
-                           a.block_table_stride, a.context_lens, w.chunk_pages, pred, lcp);
+                           a.block_table_stride, a.context_lens, pred, lcp);
         TA_HIP_TRY(hipGetLastError());
     }
     // one workgroup, as small as the batch allows: its many barriers cost less with fewer waves
@@ -734,7 +768,9 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     while (plan_threads < 1024 && plan_threads < static_cast<unsigned>(a.batch)) plan_threads <<= 1;
     hipLaunchKernelGGL(plan_decode_kernel, dim3(1), dim3(plan_threads), 0, stream, a.context_lens,
                        look_for_sharing ? pred : nullptr, look_for_sharing ? lcp : nullptr, a.batch, cp.max_pages,
-                       w.chunk_pages, w.rem_pages, 128 / g.group, w.max_shared_items, private_on_tiles ? 1 : 0,
+                       w.chunk_pages, g.decode_chunk_pages == 0 ? 1 : 0, g.num_kv_heads, w.max_chunks, 128 / g.group,
+                       w.max_shared_items,
+                       private_on_tiles ? 1 : 0,
                        chunk_start, items, shared_items, order, counts);
     TA_HIP_TRY(hipGetLastError());
 
@@ -753,7 +789,6 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
         sa.part_o = part_o;
         sa.block_table_stride = a.block_table_stride;
         sa.batch = a.batch;
-        sa.tiles_per_chunk = w.chunk_pages / 4;
         sa.max_items = w.max_shared_items;
         sa.private_on_tiles = private_on_tiles ? 1 : 0;
         if (private_on_tiles && ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));

@@ -16,6 +16,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 // Finite stand-in for "no key seen yet": keeps (m_old - m_new) free of inf - inf.
 constexpr float kNegBig = -1.0e30f;
+constexpr int kMinChunkPages = 8;    // the shortest split-K chunk (two 64-key tiles)
 
 // Records a failed HIP call for ta_last_hip_error(); returns TA_ERR_HIP.
 int note_hip_error(hipError_t e);
@@ -170,13 +171,12 @@ struct SharedPrefixArgs {
     const int32_t* context_lens;
     const int32_t* shared_items;   // int4 per item: position of the first member in `order`, members, chunk, first member
     const int32_t* order;          // programs listed group by group
-    int32_t* counts;               // counts[1] = number of items, counts[2] = work counter (starts at 0)
+    int32_t* counts;               // counts[1] = number of items, counts[2] = work counter (starts at 0), counts[3] = chunk length in pages
     const int32_t* chunk_start;
     float* part_ml;
     float* part_o;
     int32_t block_table_stride;
     int32_t batch;
-    int32_t tiles_per_chunk;
     int32_t max_items;
     int32_t private_on_tiles;      // 1: the batch's private chunks are in the list too
 };

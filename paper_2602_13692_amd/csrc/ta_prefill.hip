@@ -66,11 +66,11 @@ struct PrefillParams {
     // members, chunk, first member); the members are order[position .. position + members)
     const int4* shared_items;
     const int32_t* order;
-    int32_t* counts;             // counts[1] = number of shared items, counts[2] = next (item, kv head) pair to take
+    int32_t* counts;             // counts[1] = number of shared items, counts[2] = next (item, kv head) pair to take,
+                                 // counts[3] = pages per chunk (the plan kernel settles it)
     const int32_t* chunk_start;  // [batch + 1] first partial slot of each program
     float* part_ml;              // [slot][Hq][2]  reference maximum (log2 domain), sum
     float* part_o;               // [slot][Hq][128] unnormalised output
-    int32_t tiles_per_chunk;
     int64_t stride_page_bytes;
     int64_t stride_head_bytes;
     int32_t block_table_stride;
@@ -216,6 +216,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     // stride left the tail of the launch unbalanced.  Every item writes its own partial slots,
     // so the result does not depend on which workgroup ran it.
     const int n_items = SHARED ? p.counts[1] : p.tile_start[p.batch];
+    const int tiles_per_chunk = SHARED ? p.counts[3] / 4 : 0;   // read once: the line it shares with the work counter is busy
     __shared__ int next_pair;
     auto take_pair = [&]() {
         if (threadIdx.x == 0) next_pair = atomicAdd(p.counts + 2, 1);
@@ -252,8 +253,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
         members = it.y;
         chunk = it.z;
         q0 = 0; nq = 0; prefix = 0; t0 = 0;
-        t_begin = chunk * p.tiles_per_chunk;
-        n_tiles = t_begin + p.tiles_per_chunk;
+        t_begin = chunk * tiles_per_chunk;
+        n_tiles = t_begin + tiles_per_chunk;
         n_unmasked = n_tiles;
         L = 0x7fffffff;                // every key of a shared chunk exists
         if (members == 1) {            // a private chunk ends where its program's context ends
@@ -1008,7 +1009,6 @@ int launch_shared_prefix(const Geometry& g, const SharedPrefixArgs& a, hipStream
     pp.chunk_start = a.chunk_start;
     pp.part_ml = a.part_ml;
     pp.part_o = a.part_o;
-    pp.tiles_per_chunk = a.tiles_per_chunk;
     pp.stride_page_bytes = g.stride_page_bytes;
     pp.stride_head_bytes = g.stride_head_bytes;
     pp.block_table_stride = a.block_table_stride;

@@ -231,3 +231,22 @@ def test_more_than_1024_programs_on_every_route():
     out, lse = gu.gpu_decode(wf, chunk_pages=64)
     ref, ref_lse = gu.oracle_decode(wf)
     gu.assert_close(out, lse, ref, ref_lse, "1040 forked programs")
+
+
+@pytest.mark.parametrize("Hq", [32, 64])
+def test_a_loose_context_bound_changes_nothing_but_the_plan(Hq):
+    """Under a bound far above the real lengths the host sizes the workspace for long chunks and the
+    plan kernel, which sees the lengths, settles on shorter ones (and recognises shared prefixes at that
+    finer grain): same results as under a tight bound, on both routes."""
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 280 + Hq, batch=8, len_lo=1, len_hi=3000, num_q_heads=Hq,
+                           first_lens=[0, 1, 127, 128, 129])
+    ref, ref_lse = gu.oracle_decode(wb)
+    for bound in (wb.max_context_len, 32768, 131072):
+        out, lse = gu.gpu_decode_bound(wb, bound)
+        gu.assert_close(out, lse, ref, ref_lse, f"bound {bound} Hq={Hq}", lse_tol=gu.LSE_TOL_PREFILL)
+    wf = wl.forked_decode(DEV, seed=wl.SEED_BASE + 290 + Hq, batch=12, group=6, prefix_len=1024, suffix_lo=1,
+                          suffix_hi=300, num_q_heads=Hq, num_kv_heads=8)
+    ref, ref_lse = gu.oracle_decode(wf)
+    for bound in (wf.max_context_len, 131072):
+        out, lse = gu.gpu_decode_bound(wf, bound)
+        gu.assert_close(out, lse, ref, ref_lse, f"forked, bound {bound} Hq={Hq}", lse_tol=gu.LSE_TOL_PREFILL)
