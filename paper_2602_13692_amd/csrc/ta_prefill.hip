@@ -96,6 +96,7 @@ __global__ __launch_bounds__(1024) void plan_tiles_kernel(const int32_t* __restr
     __shared__ int32_t length[1024];   // its context length (sort key)
     __shared__ int32_t carry;
     const int tid = threadIdx.x;
+    const int nt = blockDim.x;         // a power of two, 64 .. 1024, at least the batch when the batch is at most 1024
     auto tiles_of = [&](int b) {
         const int nq = cu_q_lens[b + 1] - cu_q_lens[b];
         const int n = nq > 0 ? (nq + tile_tokens - 1) / tile_tokens : 0;
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(1024) void plan_tiles_kernel(const int32_t* __restr
         length[tid] = tid < batch ? context_lens[tid] : -1;
         __syncthreads();
         // bitonic sort, descending by length, ties by program index (a total order: deterministic)
-        for (int k = 2; k <= 1024; k <<= 1) {
+        for (int k = 2; k <= nt; k <<= 1) {
             for (int j = k >> 1; j > 0; j >>= 1) {
                 const int other = tid ^ j;
                 if (other > tid) {
@@ -125,13 +126,13 @@ __global__ __launch_bounds__(1024) void plan_tiles_kernel(const int32_t* __restr
         }
     }
     __syncthreads();
-    for (int base = 0; base < batch; base += 1024) {
+    for (int base = 0; base < batch; base += nt) {
         const int pos = base + tid;
         const int b = sorted ? order[tid] : pos;
         const int n = pos < batch ? tiles_of(b) : 0;
         scan[tid] = n;
         __syncthreads();
-        for (int off = 1; off < 1024; off <<= 1) {
+        for (int off = 1; off < nt; off <<= 1) {
             const int v = tid >= off ? scan[tid - off] : 0;
             __syncthreads();
             scan[tid] += v;
@@ -143,7 +144,7 @@ __global__ __launch_bounds__(1024) void plan_tiles_kernel(const int32_t* __restr
             for (int c = 0; c < n; ++c) tiles[first + c] = make_int2(b, c);
         }
         __syncthreads();
-        if (tid == 1023) carry += scan[1023];
+        if (tid == nt - 1) carry += scan[nt - 1];
         __syncthreads();
     }
     if (tid == 0) tile_start[batch] = carry;
@@ -945,7 +946,10 @@ int launch_prefill(const Geometry& g, const PrefillArgs& a, const WorkspaceLayou
     const int64_t max_tiles = int64_t(per_prog) * a.batch;
     if (max_tiles > w.max_tiles) return TA_ERR_INVALID_ARG;
 
-    hipLaunchKernelGGL(plan_tiles_kernel, dim3(1), dim3(1024), 0, stream, a.cu_q_lens, a.context_lens, a.batch,
+    // one workgroup, as small as the batch allows (its sort and scan are all barriers)
+    unsigned plan_threads = 64;
+    while (plan_threads < 1024 && plan_threads < static_cast<unsigned>(a.batch)) plan_threads <<= 1;
+    hipLaunchKernelGGL(plan_tiles_kernel, dim3(1), dim3(plan_threads), 0, stream, a.cu_q_lens, a.context_lens, a.batch,
                        tile_tokens, per_prog, tile_start, tiles);
     TA_HIP_TRY(hipGetLastError());
 
