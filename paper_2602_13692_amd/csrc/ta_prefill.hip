@@ -46,6 +46,9 @@ constexpr int kRowsPerBlock = 256;   // score rows per workgroup
 constexpr int kRB = 1;               // 32-row blocks per wave
 constexpr int kTileKeys = 64;        // keys per LDS tile (4 pages)
 constexpr float kRescaleThreshold = 8.0f;  // log2 units
+#ifndef TA_PAIRS_IN_X
+#define TA_PAIRS_IN_X 6
+#endif
 constexpr int kRing = 4;                   // LDS slots (tiles in flight); the slot arithmetic below is "& 3"
 static_assert(kRing == 4, "slot indices are computed modulo four");
 constexpr int kKAhead = 3;                 // LDS operand reads in flight ahead of their matrix instruction
@@ -156,11 +159,6 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     const f32x2 v = {lo, hi};
     const bf16x2 r = __builtin_convertvector(v, bf16x2);
     return __builtin_bit_cast(uint32_t, r);
-}
-
-__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b),
-                                           acc, false);
 }
 
 __device__ __forceinline__ uint16_t to_bf16_rne(float f) {
@@ -545,15 +543,14 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     };
     // B2: weights 2^(s c - m), row-sum share, packing into the B operands of the two k = 16 steps
     auto weights = [&](const f32x16 (&s)[kRB], bf16x8 (&pf)[kRB][2]) {
-        const uint32_t ones = 0x3f803f80u;   // (1.0, 1.0) in bf16
 #pragma unroll
         for (int rb = 0; rb < kRB; ++rb) {
             const float bias = -m[rb];
             float pr[16];
 #pragma unroll
             for (int r = 0; r < 16; ++r) pr[r] = __builtin_amdgcn_exp2f(fmaf(s[rb][r], p.scale_log2, bias));
-            // the row sum adds up the ROUNDED weights (the ones the matrix core multiplies),
-            // two per instruction
+            // the row sum adds up the weights as computed (before rounding), in the same order
+            // as the pipelined body
             float acc = lsum[rb];
 #pragma unroll
             for (int step = 0; step < 2; ++step) {
@@ -562,10 +559,8 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
                 w.y = pack_bf16(pr[8 * step + 2], pr[8 * step + 3]);
                 w.z = pack_bf16(pr[8 * step + 4], pr[8 * step + 5]);
                 w.w = pack_bf16(pr[8 * step + 6], pr[8 * step + 7]);
-                acc = dot2_bf16(w.x, ones, acc);
-                acc = dot2_bf16(w.y, ones, acc);
-                acc = dot2_bf16(w.z, ones, acc);
-                acc = dot2_bf16(w.w, ones, acc);
+#pragma unroll
+                for (int r = 0; r < 8; ++r) acc += pr[8 * step + r];
                 pf[rb][step] = __builtin_bit_cast(bf16x8, w);
             }
             lsum[rb] = acc;
@@ -593,16 +588,40 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     // ka[0 .. kKAhead) and va[0 .. kVAhead) are always in flight or loaded on entry.
     //
     // Region X: scores of the next block (matrix core) with the weights of the current block
-    // (vector ALU).  Slice ks turns scores 2 ks and 2 ks + 1 into weights.
+    // (vector ALU).  Turning a pair of scores into weights is seven vector instructions (two
+    // multiply-adds, two exponentials, one packing conversion, two additions into the row sum).
+    // All eight pairs in this region would be seven vector instructions per matrix instruction
+    // here and nearly none in region Y, so this region converts pairs 0 .. kPairsInX - 1 and the
+    // first slices of region Y, which otherwise only wait for the scores to leave the matrix
+    // core, convert the rest; the matrix instructions that multiply with those come four slices
+    // later.
+    //
+    // The row sum adds up the weights before they are rounded to bf16, with plain additions:
+    // summing the rounded ones two at a time with the dot-product instruction was measured at
+    // several times the cost of an addition (it does not overlap with matrix instructions).
     bf16x8 ka[8], va[8];
+    constexpr int kPairsInX = TA_PAIRS_IN_X, kPairSteps = 7;
+    uint32_t pw[kRB][8];          // packed weights of the current block, pair by pair
+    float wf[kRB][8][2];          // a pair on its way through the steps
+    auto weight_step = [&](const f32x16 (&s_old)[kRB], int rb, int j) __attribute__((always_inline)) {
+        const int c = j / kPairSteps, part = j % kPairSteps;
+        if (part < 2) {
+            wf[rb][c][part] = fmaf(s_old[rb][2 * c + part], p.scale_log2, -m[rb]);
+            asm volatile("" ::"v"(wf[rb][c][part]));
+        } else if (part < 4) {
+            wf[rb][c][part - 2] = __builtin_amdgcn_exp2f(wf[rb][c][part - 2]);
+            asm volatile("" ::"v"(wf[rb][c][part - 2]));
+        } else if (part == 4) {
+            pw[rb][c] = pack_bf16(wf[rb][c][0], wf[rb][c][1]);
+            asm volatile("" ::"v"(pw[rb][c]));
+        } else {
+            lsum[rb] += wf[rb][c][part - 5];
+            asm volatile("" ::"v"(lsum[rb]));
+        }
+    };
     auto region_scores_weights = [&](auto&& read_k, f32x16 (&s_new)[kRB], const f32x16 (&s_old)[kRB],
                                      bf16x8 (&pf)[kRB][2], auto&& prefetch_next) __attribute__((always_inline)) {
-        const uint32_t ones = 0x3f803f80u;   // (1.0, 1.0) in bf16
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        uint32_t pw[kRB][8];
-        float acc[kRB], bias[kRB];
-#pragma unroll
-        for (int rb = 0; rb < kRB; ++rb) { acc[rb] = lsum[rb]; bias[rb] = -m[rb]; }
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
@@ -610,31 +629,26 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
                 s_new[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qf[rb][ks], ks == 0 ? zero : s_new[rb], 0, 0, 0);
                 if (rb == 0 && ks + kKAhead < 8) ka[ks + kKAhead] = read_k(ks + kKAhead);
                 if (rb == kRB - 1 && ks >= 8 - kVAhead) prefetch_next(ks - (8 - kVAhead));
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(s_old[rb][2 * ks], p.scale_log2, bias[rb]));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(s_old[rb][2 * ks + 1], p.scale_log2, bias[rb]));
-                pw[rb][ks] = pack_bf16(p0, p1);
-                acc[rb] = dot2_bf16(pw[rb][ks], ones, acc[rb]);   // row sum of the ROUNDED weights
-                // the vector results are "used" here, so instruction selection cannot let them
-                // drift past the barrier to the end of the region
-                asm volatile("" ::"v"(pw[rb][ks]), "v"(acc[rb]));
+                // an eighth of this region's share of the steps, in order
+#pragma unroll
+                for (int j = ks * (kPairSteps * kPairsInX) / 8; j < (ks + 1) * (kPairSteps * kPairsInX) / 8; ++j)
+                    weight_step(s_old, rb, j);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
 #pragma unroll
-        for (int rb = 0; rb < kRB; ++rb) lsum[rb] = acc[rb];
-#pragma unroll
-        for (int rb = 0; rb < kRB; ++rb)
-#pragma unroll
-            for (int step = 0; step < 2; ++step) {
-                const u32x4 w = {pw[rb][4 * step], pw[rb][4 * step + 1], pw[rb][4 * step + 2], pw[rb][4 * step + 3]};
-                pf[rb][step] = __builtin_bit_cast(bf16x8, w);
-            }
+        for (int rb = 0; rb < kRB; ++rb) {
+            const u32x4 w = {pw[rb][0], pw[rb][1], pw[rb][2], pw[rb][3]};
+            pf[rb][0] = __builtin_bit_cast(bf16x8, w);
+        }
     };
-    // Region Y: O^T += V^T P^T (matrix core) with the row maxima of the next block's scores
-    // (vector ALU).  The maxima start four slices in, when the scores have left the matrix core.
-    auto region_accumulate_maxima = [&](auto&& read_v, const bf16x8 (&pf)[kRB][2], const f32x16 (&s_new)[kRB],
-                                        bool use_new, auto&& staging_step, auto&& prefetch_next)
-                                        __attribute__((always_inline)) {
+    // Region Y: O^T += V^T P^T (matrix core) with the last pairs of the current block's weights
+    // (slices 0 .. 3) and the row maxima of the next block's scores (slices 4 .. 7, when those
+    // scores have left the matrix core) on the vector ALU.
+    auto region_accumulate_maxima = [&](auto&& read_v, bf16x8 (&pf)[kRB][2], const f32x16 (&s_old)[kRB],
+                                        const f32x16 (&s_new)[kRB], bool use_new, auto&& staging_step,
+                                        auto&& prefetch_next) __attribute__((always_inline)) {
+        constexpr int kLeft = 8 - kPairsInX;    // pairs converted here
         float mx[kRB];
 #pragma unroll
         for (int rb = 0; rb < kRB; ++rb) mx[rb] = -INFINITY;
@@ -643,13 +657,27 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
             const int step = idx >> 2, db = idx & 3;
 #pragma unroll
             for (int rb = 0; rb < kRB; ++rb) {
+                if (idx == 4) {
+                    const u32x4 w = {pw[rb][4], pw[rb][5], pw[rb][6], pw[rb][7]};
+                    pf[rb][1] = __builtin_bit_cast(bf16x8, w);
+                }
                 o[db][rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[idx], pf[rb][step], o[db][rb], 0, 0, 0);
                 if (rb == 0) {
                     if (idx + kVAhead < 8) va[idx + kVAhead] = read_v(idx + kVAhead);
                     if (idx >= 8 - kKAhead) prefetch_next(idx - (8 - kKAhead));
                 }
                 if (rb == kRB - 1) staging_step(idx);   // a share of the next tiles' HBM -> LDS traffic
-                if (idx >= 4) {   // four slices, four scores per slice
+                if (idx < 3) {          // the packed weights are complete one slice before their first use
+#pragma unroll
+                    for (int j = idx * (5 * kLeft) / 3; j < (idx + 1) * (5 * kLeft) / 3; ++j)
+                        weight_step(s_old, rb, (kPairsInX + j / 5) * kPairSteps + j % 5);
+                } else if (idx == 3) {  // their shares of the row sum
+#pragma unroll
+                    for (int c = kPairsInX; c < 8; ++c) {
+                        weight_step(s_old, rb, c * kPairSteps + 5);
+                        weight_step(s_old, rb, c * kPairSteps + 6);
+                    }
+                } else {                // four slices, four scores per slice
                     const int r0 = (idx - 4) * 4;
                     mx[rb] = fmaxf(fmaxf(mx[rb], s_new[rb][r0]), s_new[rb][r0 + 1]);
                     mx[rb] = fmaxf(fmaxf(mx[rb], s_new[rb][r0 + 2]), s_new[rb][r0 + 3]);
@@ -706,13 +734,13 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
         const int64_t page_off = plan_load(t + 3);
         region_scores_weights([&](int i) { return k_operand_in(here, 1, i); }, sb, sa, pf,
                               [&](int i) { va[i] = v_operand_in(here, 0, i); });
-        region_accumulate_maxima([&](int i) { return v_operand_in(here, 0, i); }, pf, sb, true,
+        region_accumulate_maxima([&](int i) { return v_operand_in(here, 0, i); }, pf, sa, sb, true,
                                  [&](int i) { if (i < 4) load_step(page_off, (S + 3) & 3, i); },
                                  [&](int i) { ka[i] = k_operand_in(next, 0, i); });
         region_scores_weights([&](int i) { return k_operand_in(next, 0, i); }, sa, sb, pf,
                               [&](int i) { va[i] = v_operand_in(here, 1, i); });
         // the next tile's first region reads K of tile t + 1, block 1 (in LDS since the last barrier)
-        region_accumulate_maxima([&](int i) { return v_operand_in(here, 1, i); }, pf, sa, t + 1 < n_unmasked,
+        region_accumulate_maxima([&](int i) { return v_operand_in(here, 1, i); }, pf, sb, sa, t + 1 < n_unmasked,
                                  [&](int) {}, [&](int i) { ka[i] = k_operand_in(next, 1, i); });
         finish_tile(t + 2, (S + 2) & 3);
     };
@@ -738,7 +766,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
             for (int i = 0; i < kKAhead; ++i) ka[i] = k_operand_in(next, 0, i);
             region_scores_weights([&](int i) { return k_operand_in(next, 0, i); }, s_nxt, s_cur, pf,
                                   [&](int i) { va[i] = v_operand_in(here, 0, i); });
-            region_accumulate_maxima([&](int i) { return v_operand_in(here, 0, i); }, pf, s_nxt, tt + 1 < n_tiles,
+            region_accumulate_maxima([&](int i) { return v_operand_in(here, 0, i); }, pf, s_cur, s_nxt, tt + 1 < n_tiles,
                                      [&](int i) { if (i < 4) load_step(page_off, (S + 3) & 3, i); }, [&](int) {});
             finish_tile(tt + 2, (S + 2) & 3);
         };
