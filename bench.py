@@ -36,13 +36,13 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # (FETCH_SIZE + WRITE_SIZE, each scaled by the same counter on a 1 GiB device copy), keyed by the
 # hash of the kernel source's code (comments aside) they were taken with.  A changed kernel gives
 # null until the counters are taken again.
-TRAFFIC_BYTES = {"0f90dbca0817c53c": 5081000000}
+TRAFFIC_BYTES = {"9d52305fcf5496bb": 5081000000}
 # The same batch on the vector-ALU kernel (the library's choice for smaller batches).
 VECTOR_TRAFFIC_BYTES = {"fccca5a5a1ecda87": 5081000000}
 # The same for the FP8-cache decode kernel.
 FP8_TRAFFIC_BYTES = {"04057d67ced349b5": 2560000000}
 # The same for the append-prefill tile kernel: bytes that left the L2 per launch (FETCH_SIZE scaled).
-PREFILL_TRAFFIC_BYTES = {"0f90dbca0817c53c": 16950000000}
+PREFILL_TRAFFIC_BYTES = {"9d52305fcf5496bb": 16850000000}
 
 
 def source_hash(name: str) -> str:
@@ -444,8 +444,9 @@ def main():
     ap.add_argument("--schedule-demo", action="store_true",
                     help="drive the kernels with the scheduling tick on a synthetic agent trace (one JSON line)")
     ap.add_argument("--kernels-only", action="store_true",
-                    help="leave out the legs that run many small calls (restore-versus-recompute sweep, simulator): "
-                         "what a kernel trace of the five workloads needs")
+                    help="leave out the legs that run many small calls (restore-versus-recompute sweep, simulator) "
+                         "and the append-prefill launch on all-zero operands: what a kernel trace of the five "
+                         "workloads needs")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy (reference for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -648,6 +649,17 @@ def main():
         _, hot_ms, _, _ = run_prefill(wb, 3, 1, torch, ta)
         wb.block_table = keep
         extra["append_prefill"]["kernel_ms_with_kv_always_in_l2"] = round(hot_ms, 3)
+        # the same launch on operands that toggle no bits (Q, K and V all zero): the instruction stream is
+        # the same, so what separates the two times is the clock that the power management allows
+        # (left out of a kernel trace, where it would be averaged with the launches on the real batch)
+        if not args.kernels_only:
+            wb.q.zero_()
+            wb.k_pool.zero_()
+            wb.v_pool.zero_()
+            _, zero_ms, _, _ = run_prefill(wb, 3, 2, torch, ta)
+            extra["append_prefill"]["kernel_ms_on_all_zero_operands"] = round(zero_ms, 3)
+            extra["append_prefill"]["frac_of_peak_on_all_zero_operands"] = round(
+                flops / zero_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)
         del wb, out, lse
         torch.cuda.empty_cache()
 

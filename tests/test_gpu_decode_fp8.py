@@ -52,7 +52,7 @@ def test_ragged_lengths_all_group_sizes(Hq, Hkv):
     fc = wl.to_fp8_cache(wb)
     out, lse = gu.gpu_decode_fp8(wb, fc)
     ref, ref_lse = gu.oracle_decode_fp8(wb, fc)
-    gu.assert_close(out, lse, ref, ref_lse, f"fp8 ragged Hq={Hq} Hkv={Hkv}", lse_tol=gu.LSE_TOL_PREFILL)
+    gu.assert_close(out, lse, ref, ref_lse, f"fp8 ragged Hq={Hq} Hkv={Hkv}", lse_tol=gu.LSE_TOL_FP8)
 
 
 @pytest.mark.parametrize("Hq", [32, 64])
@@ -62,7 +62,7 @@ def test_every_chunk_length(chunk_pages, Hq):
     fc = wl.to_fp8_cache(wb)
     out, lse = gu.gpu_decode_fp8(wb, fc, chunk_pages=chunk_pages)
     ref, ref_lse = gu.oracle_decode_fp8(wb, fc)
-    gu.assert_close(out, lse, ref, ref_lse, f"fp8 chunk_pages={chunk_pages} Hq={Hq}", lse_tol=gu.LSE_TOL_PREFILL)
+    gu.assert_close(out, lse, ref, ref_lse, f"fp8 chunk_pages={chunk_pages} Hq={Hq}", lse_tol=gu.LSE_TOL_FP8)
 
 
 def test_short_contexts_single_launch_and_empty_program():
@@ -74,7 +74,7 @@ def test_short_contexts_single_launch_and_empty_program():
     assert bool(((fc.k_codes & 0x7f) == 0x7f).any())
     out, lse = gu.gpu_decode_fp8(wb, fc)
     ref, ref_lse = gu.oracle_decode_fp8(wb, fc)
-    gu.assert_close(out, lse, ref, ref_lse, "fp8 short", lse_tol=gu.LSE_TOL_PREFILL)
+    gu.assert_close(out, lse, ref, ref_lse, "fp8 short", lse_tol=gu.LSE_TOL_FP8)
     assert torch.all(out[9] == 0) and torch.all(torch.isneginf(lse[9]))
 
 
@@ -84,7 +84,7 @@ def test_nan_codes_in_unreadable_rows_are_never_read():
     wl.poison_padding(wb)
     fc = wl.to_fp8_cache(wb)
     out, lse = gu.gpu_decode_fp8(wb, fc, chunk_pages=16)
-    gu.assert_close(out, lse, ref, ref_lse, "fp8 poisoned padding", lse_tol=gu.LSE_TOL_PREFILL)
+    gu.assert_close(out, lse, ref, ref_lse, "fp8 poisoned padding", lse_tol=gu.LSE_TOL_FP8)
 
 
 def test_sharpened_queries_and_other_scales():
@@ -93,7 +93,7 @@ def test_sharpened_queries_and_other_scales():
     fc = wl.to_fp8_cache(wb, k_scale=0.0125, v_scale=0.03)
     out, lse = gu.gpu_decode_fp8(wb, fc)
     ref, ref_lse = gu.oracle_decode_fp8(wb, fc)
-    gu.assert_close(out, lse, ref, ref_lse, "fp8 sharp", lse_tol=gu.LSE_TOL_PREFILL)
+    gu.assert_close(out, lse, ref, ref_lse, "fp8 sharp", lse_tol=gu.LSE_TOL_FP8)
     assert np.abs(ref).max() > 0.3              # outputs large enough for the relative term to bite
 
 
@@ -118,7 +118,7 @@ def test_forked_programs_read_aliased_pages():
     fc = wl.to_fp8_cache(wb)
     out, lse = gu.gpu_decode_fp8(wb, fc)
     ref, ref_lse = gu.oracle_decode_fp8(wb, fc)
-    gu.assert_close(out, lse, ref, ref_lse, "fp8 forked", lse_tol=gu.LSE_TOL_PREFILL)
+    gu.assert_close(out, lse, ref, ref_lse, "fp8 forked", lse_tol=gu.LSE_TOL_FP8)
 
 
 @pytest.mark.parametrize("Hq,Hkv", [(32, 8), (8, 8), (16, 2), (8, 1)])
@@ -130,7 +130,7 @@ def test_append_prefill_over_an_fp8_cache(Hq, Hkv):
     fc = wl.to_fp8_cache(wb, k_scale=0.03, v_scale=0.019)
     out, lse = gu.gpu_prefill_fp8(wb, fc)
     ref, ref_lse = gu.oracle_prefill_fp8(wb, fc)
-    gu.assert_close(out, lse, ref, ref_lse, f"fp8 prefill Hq={Hq} Hkv={Hkv}", lse_tol=gu.LSE_TOL_PREFILL)
+    gu.assert_close(out, lse, ref, ref_lse, f"fp8 prefill Hq={Hq} Hkv={Hkv}", lse_tol=gu.LSE_TOL)
 
 
 def test_append_prefill_over_an_fp8_cache_ignores_unreadable_codes():
@@ -142,7 +142,7 @@ def test_append_prefill_over_an_fp8_cache_ignores_unreadable_codes():
     assert int((wl.as_u8(fc.k_codes) & 0x7f == 0x7f).sum()) > 0
     out, lse = gu.gpu_prefill_fp8(wb, fc)
     ref, ref_lse = gu.oracle_prefill_fp8(wb, fc)
-    gu.assert_close(out, lse, ref, ref_lse, "fp8 prefill, poisoned padding", lse_tol=gu.LSE_TOL_PREFILL)
+    gu.assert_close(out, lse, ref, ref_lse, "fp8 prefill, poisoned padding", lse_tol=gu.LSE_TOL)
 
 
 def test_append_then_prefill_then_decode_on_one_fp8_cache():
@@ -160,7 +160,7 @@ def test_append_then_prefill_then_decode_on_one_fp8_cache():
     assert np.array_equal(wl.as_u8(fc.k_codes), want_k) and np.array_equal(wl.as_u8(fc.v_codes), want_v)
     out, lse = gu.gpu_prefill_fp8(wb, fc)
     ref, ref_lse = gu.oracle_prefill_fp8(wb, fc)
-    gu.assert_close(out, lse, ref, ref_lse, "fp8 prefill after append", lse_tol=gu.LSE_TOL_PREFILL)
+    gu.assert_close(out, lse, ref, ref_lse, "fp8 prefill after append", lse_tol=gu.LSE_TOL)
     # the decode step: one query per program over the same cache
     q1 = torch.randn(wb.batch, wb.num_q_heads, 128, device=DEV).to(torch.bfloat16)
     bt = torch.from_numpy(wb.block_table).to(DEV)
@@ -172,7 +172,7 @@ def test_append_then_prefill_then_decode_on_one_fp8_cache():
     torch.cuda.synchronize()
     ref1, ref1_lse = oracle.paged_decode_fp8(gu.geom_of(wb), wl.as_u16(q1), want_k, want_v, fc.k_scale, fc.v_scale,
                                              wb.block_table, wb.context_lens)
-    gu.assert_close(out1, lse1, ref1, ref1_lse, "fp8 decode after append and prefill", lse_tol=gu.LSE_TOL_PREFILL)
+    gu.assert_close(out1, lse1, ref1, ref1_lse, "fp8 decode after append and prefill", lse_tol=gu.LSE_TOL_FP8)
 
 
 def _append_fp8(desc, new_k, new_v, cu, k_codes, v_codes, table, lens):
@@ -226,4 +226,4 @@ def test_a_cache_grown_by_append_decodes_like_the_oracles():
     assert np.array_equal(wl.as_u8(fc.k_codes), want_k) and np.array_equal(wl.as_u8(fc.v_codes), want_v)
     out, lse = gu.gpu_decode_fp8(wb, fc)
     ref, ref_lse = gu.oracle_decode_fp8(wb, fc)
-    gu.assert_close(out, lse, ref, ref_lse, "fp8 cache grown by append", lse_tol=gu.LSE_TOL_PREFILL)
+    gu.assert_close(out, lse, ref, ref_lse, "fp8 cache grown by append", lse_tol=gu.LSE_TOL_FP8)

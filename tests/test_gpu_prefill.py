@@ -15,7 +15,7 @@ DEV = "cuda:0"
 def _check(wb, what):
     out, lse = gu.gpu_prefill(wb)
     ref, ref_lse = gu.oracle_prefill(wb)
-    return gu.assert_close(out, lse, ref, ref_lse, what, lse_tol=gu.LSE_TOL_PREFILL)
+    return gu.assert_close(out, lse, ref, ref_lse, what, lse_tol=gu.LSE_TOL)
 
 
 def test_config3_shape_small():
@@ -46,7 +46,7 @@ def test_padding_poison_is_never_read():
     ref, ref_lse = gu.oracle_prefill(wb)
     wl.poison_padding(wb)
     out, lse = gu.gpu_prefill(wb)
-    gu.assert_close(out, lse, ref, ref_lse, "poisoned padding", lse_tol=gu.LSE_TOL_PREFILL)
+    gu.assert_close(out, lse, ref, ref_lse, "poisoned padding", lse_tol=gu.LSE_TOL)
 
 
 def test_sharpened_queries():
@@ -79,7 +79,7 @@ def test_single_new_token_agrees_with_decode():
                            num_kv_heads=2)
     out_p, lse_p = gu.gpu_prefill(wb)
     ref, ref_lse = gu.oracle_decode(wb)
-    gu.assert_close(out_p, lse_p, ref, ref_lse, "prefill n=1", lse_tol=gu.LSE_TOL_PREFILL)
+    gu.assert_close(out_p, lse_p, ref, ref_lse, "prefill n=1", lse_tol=gu.LSE_TOL)
 
 
 def test_runs_are_deterministic():
@@ -99,4 +99,4 @@ def test_long_causal_sequences_without_a_prefix():
     assert torch.isfinite(out.float()).all()
     rng = np.random.default_rng(wl.SEED_BASE + 951)
     gu.check_sampled_rows(wb, out, lse, rng, n_programs=3, rows_per_program=24, what="long causal",
-                          lse_tol=gu.LSE_TOL_PREFILL)
+                          lse_tol=gu.LSE_TOL)

@@ -118,7 +118,7 @@ def test_policy_drives_the_kernels_and_the_caches_stay_exact(n_backends, pool_pa
                         grown[int(e["program"])] += 1
                 ctx = [c - grown[p] for p, c in zip(programs, ctx)]
                 ref, ref_lse = _oracle_rows(rec, programs, q_lens, ctx)
-                gu.assert_close(out, lse, ref, ref_lse, f"prefill, tick {tick}", lse_tol=gu.LSE_TOL_PREFILL)
+                gu.assert_close(out, lse, ref, ref_lse, f"prefill, tick {tick}", lse_tol=gu.LSE_TOL)
                 checked_prefills += 1
         if all(int(s) == ta.STATUS_TERMINATED for s in sim.programs()["status"]):
             break
