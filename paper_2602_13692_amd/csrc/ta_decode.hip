@@ -157,7 +157,10 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
     __shared__ int32_t s_lcp[1024];      // pages shared with the predecessor
     __shared__ int32_t s_shared[1024];   // leading bulk chunks of program b computed by its group
     __shared__ int32_t s_pos[1024];      // position of program b in `order`
+    __shared__ int32_t s_count[1024];    // members of the group that program b leads
+    __shared__ int32_t s_common[1024];   // per position: a sub-group's common prefix in pages, later in bulk chunks
     __shared__ int32_t wave_total[16];
+    __shared__ unsigned long long wave_total64[16];
     __shared__ int32_t carry, n_shared;
     const int tid = threadIdx.x;
     const int nt = blockDim.x;           // a power of two, 64 .. 1024, at least the batch when the batch is at most 1024
@@ -228,6 +231,7 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
     const bool grouping = lcp != nullptr && batch <= 1024 && batch >= 2;
     s_shared[tid] = 0;
     s_pos[tid] = tid;
+    s_count[tid] = 0;
     if (tid == 0) n_shared = 0;
     __syncthreads();
     __shared__ int32_t any_joins;
@@ -240,65 +244,69 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
         s_lcp[tid] = joins ? lcp[tid] : 0;
         s_lead[tid] = joins ? pred[tid] : tid;
         __syncthreads();
-        // only the first n_sort = 2^k >= batch entries take part in the pointer jumping and the sort
-        int n_sort = 2, log_n = 1;
-        while (n_sort < batch) { n_sort <<= 1; ++log_n; }
+        int log_n = 1;
+        while ((2 << (log_n - 1)) < batch) ++log_n;
         for (int round = 0; round < log_n; ++round) {       // predecessors have smaller indices: 2^k hops suffice
             const int l = s_lead[s_lead[tid]];
-            __syncthreads();
+            if (__syncthreads_or(l != s_lead[tid]) == 0) break;     // every chain has reached its leader
             s_lead[tid] = l;
             __syncthreads();
         }
-        s_key[tid] = tid < batch ? ((s_lead[tid] << 10) | tid) : 0x7fffffff;
-        __syncthreads();
-        for (int k = 2; k <= n_sort; k <<= 1) {             // bitonic sort, ascending; the keys are distinct
+        // Bitonic sort of the nt keys (the entries from `batch` on hold the largest key and stay
+        // at the end), ascending; the keys are distinct.  Partners less than a wave apart trade
+        // through a lane exchange, the others through LDS.
+        int key = tid < batch ? ((s_lead[tid] << 10) | tid) : 0x7fffffff;
+        for (int k = 2; k <= nt; k <<= 1) {
             for (int j = k >> 1; j > 0; j >>= 1) {
-                const int other = tid ^ j;
-                if (other > tid && other < n_sort) {
-                    const int a = s_key[tid], c = s_key[other];
-                    const bool ascending = (tid & k) == 0;
-                    if ((a > c) == ascending) { s_key[tid] = c; s_key[other] = a; }
+                int other;
+                if (j >= kWaveSize) {
+                    s_key[tid] = key;
+                    __syncthreads();
+                    other = s_key[tid ^ j];
+                    __syncthreads();
+                } else {
+                    other = __shfl_xor(key, j);
                 }
-                __syncthreads();
+                const bool keep_low = ((tid & j) == 0) == ((tid & k) == 0);
+                key = keep_low ? (key < other ? key : other) : (key > other ? key : other);
             }
         }
-        const int key = s_key[tid];
-        int sc = 0, n_in_sub = 0;
+        s_key[tid] = key;
+        // where each program went; members of each leader's group; nothing shared yet
+        const int prog = key & 1023, lead = (key >> 10) & 1023;     // meaningless from position `batch` on
         if (tid < batch) {
-            const int prog = key & 1023, lead = key >> 10;
             order[tid] = prog;
             s_pos[prog] = tid;
-            // first position of the group and of the next one: binary searches over the sorted keys
-            auto lower_bound = [&](int value) {
-                int lo = 0, hi = batch;
-                while (lo < hi) {
-                    const int mid = (lo + hi) >> 1;
-                    if (s_key[mid] < value) lo = mid + 1; else hi = mid;
-                }
-                return lo;
-            };
-            const int head = lower_bound(lead << 10), end = lower_bound((lead + 1) << 10);
-            if ((tid - head) % max_members == 0) {          // first member of a tile of rows
-                n_in_sub = end - tid < max_members ? end - tid : max_members;
-                if (n_in_sub >= 2) {
-                    int common = 0x7fffffff;
-                    for (int j = tid; j < tid + n_in_sub; ++j) {
-                        const int m = s_key[j] & 1023;
-                        if (m != lead) common = s_lcp[m] < common ? s_lcp[m] : common;
-                    }
-                    sc = common / chunk_pages;
-                }
-            }
+            atomicAdd(&s_count[lead], 1);
+        }
+        s_common[tid] = 0x7fffffff;
+        __syncthreads();
+        // a group sits side by side from its leader's position on (the leader has the smallest
+        // key of its group); it is cut into tiles of max_members rows, each a sub-group whose
+        // common prefix is the shortest prefix its members other than the leader share with theirs
+        int head = 0, end = 0, sub_head = 0;
+        if (tid < batch) {
+            head = s_pos[lead];
+            end = head + s_count[lead];
+            sub_head = head + (tid - head) / max_members * max_members;
+            if (prog != lead) atomicMin(&s_common[sub_head], s_lcp[prog]);
+        }
+        __syncthreads();
+        int sc = 0, n_in_sub = 0;
+        if (tid < batch && tid == sub_head) {
+            n_in_sub = end - tid < max_members ? end - tid : max_members;
+            if (n_in_sub >= 2) sc = s_common[tid] / chunk_pages;
         }
         __syncthreads();
         if (tid == 0) carry = 0;
+        s_common[tid] = sc;                 // from here on: shared bulk chunks of the sub-group that starts here
         __syncthreads();
         const int first_item = block_scan(sc);
         if (tid == 0) n_shared = carry <= max_shared_items ? carry : 0;
         __syncthreads();
-        if (sc > 0 && n_shared > 0) {
-            for (int j = tid; j < tid + n_in_sub; ++j) s_shared[s_key[j] & 1023] = sc;
-            for (int c = 0; c < sc; ++c) shared_items[first_item + c] = make_int4(tid, n_in_sub, c, key & 1023);
+        if (n_shared > 0) {
+            if (tid < batch) s_shared[prog] = s_common[sub_head];
+            for (int c = 0; c < sc; ++c) shared_items[first_item + c] = make_int4(tid, n_in_sub, c, prog);
         }
     } else {
         for (int b = tid; b < batch; b += nt) order[b] = b;     // s_pos is the identity already
@@ -331,6 +339,36 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
     // On the tile kernel a program's leftover is one item of up to chunk_pages pages, taken from a
     // work counter: listing the long leftovers first (four classes of length) lets the launch end
     // on short items.  The vector-ALU kernel's pieces are all short already: one pass.
+    int n_rest = 0;
+    if (private_on_tiles && batch <= nt) {
+        // one pass: the four classes are counted side by side, 16 bits each (at most 1024 programs)
+        const int b = tid;
+        const int pages = b < batch ? pages_of(b) : 0;
+        const int bulk = pages / chunk_pages;
+        const int n = pieces_of(pages);                       // 0 or 1: a leftover is one item here
+        const int cls = n > 0 ? 3 - ((pages - bulk * chunk_pages - 1) * 4) / chunk_pages : 0;   // 0 = the longest quarter
+        const unsigned long long mine = n > 0 ? 1ull << (16 * cls) : 0ull;
+        // exclusive scan of the packed counts (wave-level shuffles, then the wave totals)
+        const int lane = tid & 63, wv = tid >> 6;
+        unsigned long long x = mine;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const unsigned long long y = __shfl_up(x, off);
+            if (lane >= off) x += y;
+        }
+        if (lane == 63) wave_total64[wv] = x;
+        __syncthreads();
+        unsigned long long before = 0, total = 0;
+        for (int w = 0; w < (nt >> 6); ++w) {
+            if (w < wv) before += wave_total64[w];
+            total += wave_total64[w];
+        }
+        const unsigned long long prefix = before + x - mine;
+        int first = int((prefix >> (16 * cls)) & 0xffff);
+        for (int k = 0; k < cls; ++k) first += int((total >> (16 * k)) & 0xffff);
+        if (n > 0) shared_items[tile_base + n_bulk + first] = make_int4(s_pos[b], 1, bulk, b);
+        n_rest = int(total & 0xffff) + int((total >> 16) & 0xffff) + int((total >> 32) & 0xffff) + int(total >> 48);
+    } else {
     const int n_pass = private_on_tiles ? 4 : 1;
     for (int pass = 0; pass < n_pass; ++pass)
     for (int base = 0; base < batch; base += nt) {
@@ -354,9 +392,12 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
             }
         }
     }
+    __syncthreads();
+    n_rest = carry;
+    }
     if (tid == 0) {
-        counts[0] = private_on_tiles ? 0 : n_bulk + carry;
-        counts[1] = private_on_tiles ? tile_base + n_bulk + carry : tile_base;
+        counts[0] = private_on_tiles ? 0 : n_bulk + n_rest;
+        counts[1] = private_on_tiles ? tile_base + n_bulk + n_rest : tile_base;
         counts[2] = 0;   // work counter of the tile kernel
         counts[3] = chunk_pages;
     }
