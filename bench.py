@@ -38,9 +38,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # null until the counters are taken again.
 TRAFFIC_BYTES = {"9d52305fcf5496bb": 5081000000}
 # The same batch on the vector-ALU kernel (the library's choice for smaller batches).
-VECTOR_TRAFFIC_BYTES = {"196d860a89d79890": 5081000000}
+VECTOR_TRAFFIC_BYTES = {"79ba7f1832cb5de5": 5081000000}
 # The same for the FP8-cache decode kernel.
-FP8_TRAFFIC_BYTES = {"04057d67ced349b5": 2560000000}
+FP8_TRAFFIC_BYTES = {"5633779bb5476c37": 2556000000}
 # The same for the append-prefill tile kernel: bytes that left the L2 per launch (FETCH_SIZE scaled).
 PREFILL_TRAFFIC_BYTES = {"9d52305fcf5496bb": 16850000000}
 

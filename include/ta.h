@@ -88,10 +88,11 @@ typedef struct ta_attn_desc {
     int32_t decode_chunk_pages; /* split-K chunk of ta_paged_decode in pages: 0 lets the library choose
                                    the chunk and the kernel that streams the private chunks (the kernel by
                                    batch and the bound on the context length, the chunk on the device
-                                   from the real lengths), else 8, 16, 32, 64 or 128 (with up to four
-                                   query heads per kv head: on the vector-ALU kernel), or 256 or 512 (a
-                                   bf16 cache only: on the matrix-core tile kernel).  The same value must
-                                   be given to ta_workspace_bytes. */
+                                   from the real lengths), else 8, 16, 32, 64 or 128 (a bf16 cache with
+                                   up to four query heads per kv head: on the vector-ALU kernel), or 256
+                                   or 512 (a bf16 cache: on the matrix-core tile kernel; an FP8 cache:
+                                   longer items of its one kernel).  The same value must be given to
+                                   ta_workspace_bytes. */
     int32_t kv_format;         /* TA_KV_BF16 (0) or TA_KV_FP8_E4M3 (1), see below */
     float k_scale;             /* TA_KV_FP8_E4M3: a cached key element is code value * k_scale; > 0, finite */
     float v_scale;             /* TA_KV_FP8_E4M3: a cached value element is code value * v_scale; > 0, finite */

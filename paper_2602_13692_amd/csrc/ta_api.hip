@@ -49,9 +49,9 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
     if ((sh * elem_bytes) % 16 != 0 || (sp * elem_bytes) % 16 != 0) return TA_ERR_UNSUPPORTED;
     if (sh < int64_t(kPageSize) * kHeadDim) return TA_ERR_INVALID_ARG;
     const int32_t cp = d->decode_chunk_pages;
-    // chunks of 256 and 512 pages exist on the matrix-core tile kernel only (a bf16 cache): asking for
-    // one also asks for that kernel
-    if (cp != 0 && cp != 8 && cp != 16 && cp != 32 && cp != 64 && cp != 128 && !((cp == 256 || cp == 512) && !fp8))
+    // with a bf16 cache chunks of 256 and 512 pages exist on the matrix-core tile kernel only: asking
+    // for one also asks for that kernel
+    if (cp != 0 && cp != 8 && cp != 16 && cp != 32 && cp != 64 && cp != 128 && cp != 256 && cp != 512)
         return TA_ERR_INVALID_ARG;
     g->num_q_heads = d->num_q_heads;
     g->num_kv_heads = d->num_kv_heads;
@@ -95,15 +95,19 @@ static bool decode_on_tiles(const Geometry& g, int32_t batch, int32_t max_contex
 static int32_t choose_chunk_pages(const Geometry& g, int32_t batch, int32_t max_context_len) {
     if (g.decode_chunk_pages != 0) return g.decode_chunk_pages;   // the caller's choice, validated with the descriptor
     const int64_t pages = (int64_t(max_context_len) + kPageSize - 1) / kPageSize;
-    if (decode_on_tiles(g, batch, max_context_len)) {
+    const bool on_tiles = decode_on_tiles(g, batch, max_context_len);
+    if (on_tiles || g.kv_fp8) {
         // the tile kernel's per-item cost (filling the LDS ring anew, writing 32 to 128 rows of
         // partials) wants long items: up to 8192 tokens.  (Longer still would stream a little
-        // faster, but the chunk is also the unit in which a shared prefix is recognised.)
+        // faster, but the chunk is also the unit in which a shared prefix is recognised.)  The
+        // kernel for FP8 caches likes them as long: the start of an item is a microsecond in which
+        // its workgroup streams nothing.
         for (int32_t c : {512, 256, 128}) {
             const int64_t items = int64_t(batch) * g.num_kv_heads * ((pages + c - 1) / c);
             if (items >= 2048) return c;
         }
-    } else {
+    }
+    if (!on_tiles) {
         const int64_t items = int64_t(batch) * g.num_kv_heads * ((pages + 127) / 128);
         if (items >= 2048 || pages <= 128) return 128;
     }

@@ -763,7 +763,7 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     if (w.direct) {
         // short contexts: one launch, one workgroup per (program, kv head), output written directly
         const int64_t blocks = int64_t(a.batch) * g.num_kv_heads;
-        if (blocks > 0x7fffffff || cp.max_pages > kMaxItemPages) return TA_ERR_INVALID_ARG;
+        if (blocks > 0x7fffffff || cp.max_pages > (g.kv_fp8 ? kMaxItemPagesFp8 : kMaxItemPages)) return TA_ERR_INVALID_ARG;
         const dim3 grid(static_cast<unsigned>(blocks)), block(kChunkThreads);
         if (ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
         if (g.kv_fp8) {
@@ -844,7 +844,7 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
         cp.part_ml = part_ml;
         cp.part_o = part_o;
         const int64_t blocks = int64_t(w.max_chunks) * g.num_kv_heads;
-        if (blocks > 0x7fffffff || w.chunk_pages > kMaxItemPages) return TA_ERR_INVALID_ARG;
+        if (blocks > 0x7fffffff || w.chunk_pages > (g.kv_fp8 ? kMaxItemPagesFp8 : kMaxItemPages)) return TA_ERR_INVALID_ARG;
         const dim3 grid(static_cast<unsigned>(blocks)), block(kChunkThreads);
         if (ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
         if (g.kv_fp8) {

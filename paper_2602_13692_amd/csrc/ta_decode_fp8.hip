@@ -193,6 +193,7 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
     __shared__ __attribute__((aligned(16))) char smem[kWaves * kStageBytes];
     __shared__ float sm_m[kWaves][kMaxGroup];
     __shared__ float sm_l[kWaves][kMaxGroup];
+    __shared__ int32_t sm_ids[kMaxItemPagesFp8];
     static_assert(kWaves * kStageBytes >= kWaves * kMaxGroup * kHeadDim * 4, "the merge reuses the V tiles' memory");
 
     const int item = blockIdx.x / p.num_kv_heads;
@@ -223,17 +224,15 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
     const int rest_pages = n_here - 2 * full_blocks;                   // 0, 1 or 2 pages in a last, masked block
     const int rest_valid = rest_pages == 0 ? 0 : (rest_pages - 1) * kPageSize + (has_tail ? tail_valid : kPageSize);
 
-    // page ids of this item, two per lane
-    int my_id0 = 0, my_id1 = 0;
+    // page ids of this item (up to 512: the start of an item costs its workgroup a microsecond
+    // in which it streams nothing, so items are as long as the batch allows), kept in LDS
     {
         const int32_t* table = p.block_table + int64_t(b) * p.block_table_stride + page0;
-        if (lane < n_here) my_id0 = table[lane];
-        if (lane + 64 < n_here) my_id1 = table[lane + 64];
+        for (int i = threadIdx.x; i < n_here; i += kThreads) sm_ids[i] = table[i];
+        __syncthreads();
     }
     auto page_off = [&](int idx) -> int64_t {                          // idx is wave-uniform
-        const int lo = __builtin_amdgcn_readlane(my_id0, idx & 63);
-        const int hi = __builtin_amdgcn_readlane(my_id1, idx & 63);
-        return int64_t(idx < 64 ? lo : hi) * p.stride_page_bytes;
+        return int64_t(__builtin_amdgcn_readfirstlane(sm_ids[idx])) * p.stride_page_bytes;
     };
 
     // B operands: head r16 of the group (zero columns beyond it), dims 16 (c + 4 i) + 8 hf ..

@@ -130,7 +130,8 @@ struct ChunkParams {
     float scale_log2;            // fp8: the key scale is folded in
     float out_scale;             // fp8 direct mode: the value scale (1 otherwise)
 };
-constexpr int kMaxItemPages = 128;   // two page ids per lane
+constexpr int kMaxItemPages = 128;      // vector-ALU kernel: two page ids per lane
+constexpr int kMaxItemPagesFp8 = 512;   // FP8 kernel: the item's page ids sit in LDS
 
 // The item kernel for pools of E4M3 codes (matrix cores, any group size up to 16).
 int launch_fp8_items(const ChunkParams& p, int32_t group, bool direct, unsigned blocks, hipStream_t stream);

@@ -89,8 +89,8 @@ def test_host_side_rejections_need_no_device():
     slot = (ctypes.c_int32 * 1)(0)
     assert lib.ta_kv_page_restore(one, one, 32768, one, one, slot, 1, 10, null, 512, null) == ta.TA_ERR_INVALID_ARG
     assert lib.ta_kv_page_evict(one, one, 32768, one, one, slot, 1, 10, null, 512, null) == ta.TA_ERR_INVALID_ARG
-    # a chunk length the split-K plan does not offer; 256 and 512 pages ask for the tile kernel (any head
-    # shape, a bf16 cache only)
+    # a chunk length the split-K plan does not offer; with a bf16 cache 256 and 512 pages ask for the tile
+    # kernel (any head shape), with an FP8 cache they are item lengths of its own kernel
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=24), 4, 1, 100) == 0
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=1024), 4, 1, 100) == 0
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=256), 4, 1, 100) > 0
@@ -104,7 +104,8 @@ def test_host_side_rejections_need_no_device():
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, k_scale=0.02, v_scale=-1.0, **fp8), 4, 1, 100) == 0
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, k_scale=float("inf"), v_scale=1.0, **fp8), 4, 1, 100) == 0
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, kv_format=2, k_scale=1.0, v_scale=1.0), 4, 1, 100) == 0
-    assert ta.ta_workspace_bytes(ta.Desc(64, 8, decode_chunk_pages=256, k_scale=1.0, v_scale=1.0, **fp8), 4, 1, 100) == 0
+    assert ta.ta_workspace_bytes(ta.Desc(64, 8, decode_chunk_pages=256, k_scale=1.0, v_scale=1.0, **fp8), 4, 1, 100) > 0
+    assert ta.ta_workspace_bytes(ta.Desc(64, 8, decode_chunk_pages=1024, k_scale=1.0, v_scale=1.0, **fp8), 4, 1, 100) == 0
     # the measurement aids (their own library) reject missing or misaligned buffers and bad sizes
     probe = ta._probe_lib()
     assert probe.ta_matrix_core_probe(null, 10, null, null) == -1

@@ -56,7 +56,7 @@ def test_ragged_lengths_all_group_sizes(Hq, Hkv):
 
 
 @pytest.mark.parametrize("Hq", [32, 64])
-@pytest.mark.parametrize("chunk_pages", [8, 16, 32, 64, 128])
+@pytest.mark.parametrize("chunk_pages", [8, 16, 32, 64, 128, 256, 512])
 def test_every_chunk_length(chunk_pages, Hq):
     wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 3200, batch=9, len_lo=100, len_hi=9000, num_q_heads=Hq)
     fc = wl.to_fp8_cache(wb)
