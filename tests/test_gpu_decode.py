@@ -170,6 +170,23 @@ def test_forked_programs_in_shuffled_batch_order(Hq, Hkv):
     gu.assert_close(out, lse, ref, ref_lse, "shuffled forked batch", lse_tol=gu.LSE_TOL)
 
 
+@pytest.mark.parametrize("batch,group,Hq,Hkv,chunk_pages", [(600, 20, 32, 8, 16), (1000, 50, 32, 8, 8), (330, 33, 64, 8, 32),
+                                                          (130, 5, 8, 2, 0), (1024, 16, 16, 4, 16)])
+def test_many_forked_programs_in_shuffled_order(batch, group, Hq, Hkv, chunk_pages):
+    """Hundreds of programs in groups of irregular size (larger than one tile of rows too), shuffled:
+    the plan sorts them with several waves and cuts the groups into sub-groups; the result is the
+    oracle's."""
+    wb = wl.forked_decode(DEV, seed=wl.SEED_BASE + 760 + group, batch=batch // group * group, group=group,
+                          prefix_len=1024, suffix_lo=1, suffix_hi=200, num_q_heads=Hq, num_kv_heads=Hkv)
+    perm = np.random.default_rng(wl.SEED_BASE + 761).permutation(wb.batch)
+    wb.q = wb.q[torch.from_numpy(perm).to(wb.q.device)].contiguous()
+    wb.block_table = np.ascontiguousarray(wb.block_table[perm])
+    wb.context_lens = np.ascontiguousarray(wb.context_lens[perm])
+    out, lse = gu.gpu_decode(wb, chunk_pages=chunk_pages)
+    ref, ref_lse = gu.oracle_decode(wb)
+    gu.assert_close(out, lse, ref, ref_lse, f"{wb.batch} forked programs, groups of {group}")
+
+
 def test_short_contexts_take_the_single_launch_path():
     """Contexts of at most one bulk chunk: the chunk kernel writes the output itself (no partials)."""
     for Hq, Hkv in ((32, 8), (8, 8), (4, 2)):
