@@ -28,18 +28,28 @@ HEAD_DIM = 128
 
 class Backends:
     def __init__(self, sim: ta.Sim, n_backends: int, pool_pages: int, num_q_heads: int, num_kv_heads: int,
-                 max_context: int, initial_context, token_source: Callable, device="cuda:0"):
+                 max_context: int, initial_context, token_source: Callable, device="cuda:0",
+                 kv_format: int = ta.KV_BF16, k_scale: float = 1.0, v_scale: float = 1.0):
         """token_source(program, first_token, n) -> (k, v, q): bf16 device tensors [n, Hkv, 128],
-        [n, Hkv, 128], [n, Hq, 128] for the program's tokens first_token .. first_token + n - 1."""
+        [n, Hkv, 128], [n, Hq, 128] for the program's tokens first_token .. first_token + n - 1.
+        With kv_format = KV_FP8_E4M3 the pools and the host stores hold E4M3 codes (one byte per
+        element), written by the library's quantising append."""
         self.sim, self.dev = sim, device
         self.nb, self.P, self.Hq, self.Hkv = n_backends, pool_pages, num_q_heads, num_kv_heads
         self.max_pages = (max_context + PAGE - 1) // PAGE
-        self.page_bytes = num_kv_heads * PAGE * HEAD_DIM * 2
-        self.desc = ta.Desc(num_q_heads, num_kv_heads, pool_pages=pool_pages)
+        self.fp8 = kv_format == ta.KV_FP8_E4M3
+        fmt = dict(kv_format=kv_format, k_scale=k_scale, v_scale=v_scale) if self.fp8 else {}
+        pool_dtype = torch.uint8 if self.fp8 else torch.bfloat16
+        self.page_bytes = num_kv_heads * PAGE * HEAD_DIM * (1 if self.fp8 else 2)
+        self.desc = ta.Desc(num_q_heads, num_kv_heads, pool_pages=pool_pages, **fmt)
         self.source = token_source
-        self.k_pool = [torch.zeros((pool_pages, num_kv_heads, PAGE, HEAD_DIM), dtype=torch.bfloat16, device=device)
+        self.k_pool = [torch.zeros((pool_pages, num_kv_heads, PAGE, HEAD_DIM), dtype=pool_dtype, device=device)
                        for _ in range(n_backends)]
         self.v_pool = [torch.zeros_like(k) for k in self.k_pool]
+        # a pool of one program's size: where an initial context is laid out before it goes to the host
+        self._first_desc = ta.Desc(num_q_heads, num_kv_heads, pool_pages=self.max_pages, **fmt)
+        self._first_k = torch.zeros((self.max_pages, num_kv_heads, PAGE, HEAD_DIM), dtype=pool_dtype, device=device)
+        self._first_v = torch.zeros_like(self._first_k)
         n = len(initial_context)
         self.context = [int(c) for c in initial_context]
         self.table: List[List[int]] = [[] for _ in range(n)]       # pool pages of each program (empty while paused)
@@ -60,12 +70,20 @@ class Backends:
 
     # ---- helpers ----
     def _tokens_to_host(self, p, k, v, c):
+        """A program's first c tokens into its host store, the way they would have got there:
+        appended to pages (quantised on the way into an FP8 cache), then evicted."""
         pages = (c + PAGE - 1) // PAGE
-        for src, dst in ((k, self.host_k[p]), (v, self.host_v[p])):
-            padded = torch.zeros((pages * PAGE, self.Hkv, HEAD_DIM), dtype=torch.bfloat16, device=src.device)
-            padded[:c] = src
-            paged = padded.view(pages, PAGE, self.Hkv, HEAD_DIM).permute(0, 2, 1, 3).contiguous()   # [page][head][row][d]
-            dst[:pages].copy_(paged.view(torch.uint8).view(pages, self.page_bytes).cpu())
+        if pages == 0:
+            return
+        self._first_k.zero_()
+        self._first_v.zero_()
+        table = torch.arange(pages, dtype=torch.int32, device=self.dev).view(1, pages)
+        lens = torch.tensor([c], dtype=torch.int32, device=self.dev)
+        cu = torch.tensor([0, c], dtype=torch.int32, device=self.dev)
+        ta.ta_kv_append(self._first_desc, k.contiguous(), v.contiguous(), cu, self._first_k, self._first_v, table, lens, c)
+        ta.ta_kv_page_evict(self._first_k, self._first_v, self.page_bytes, self.host_k[p][:pages], self.host_v[p][:pages],
+                            torch.arange(pages, dtype=torch.int32), self.max_pages, self.staging)
+        torch.cuda.synchronize()
 
     def _timed(self, kind, fn):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
