@@ -38,9 +38,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # null until the counters are taken again.
 TRAFFIC_BYTES = {"9d52305fcf5496bb": 5081000000}
 # The same batch on the vector-ALU kernel (the library's choice for smaller batches).
-VECTOR_TRAFFIC_BYTES = {"79ba7f1832cb5de5": 5081000000}
+VECTOR_TRAFFIC_BYTES = {"d06630c76b396928": 5081000000}
 # The same for the FP8-cache decode kernel.
-FP8_TRAFFIC_BYTES = {"5633779bb5476c37": 2556000000}
+FP8_TRAFFIC_BYTES = {"a89d347f0788530d": 2556000000}
 # The same for the append-prefill tile kernel: bytes that left the L2 per launch (FETCH_SIZE scaled).
 PREFILL_TRAFFIC_BYTES = {"9d52305fcf5496bb": 16850000000}
 
@@ -539,7 +539,7 @@ def main():
             "metric": "paged_decode_fp8_kv_gbps", "value": round(fp8_bytes / f_ms / 1e6, 1), "unit": "GB/s",
             "ms_per_step": round(f_ms, 4), "kv_bytes_per_step": fp8_bytes, "dtype": "fp8 e4m3 cache, bf16 q/out, f32 accumulate",
             "layer_tokens_per_s": round(wb.batch / f_ms * 1e3, 1),
-            "roofline": {"bound": "hbm", "kernel": "decode_fp8_kernel<false>",
+            "roofline": {"bound": "hbm", "kernel": "decode_fp8_kernel<false, false>",
                          "achieved": round(fp8_bytes / f_kernel_ms / 1e6, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                          "frac": round(fp8_bytes / f_kernel_ms / 1e6 / HBM_PEAK_GBPS, 4),
                          "kernel_ms": round(f_kernel_ms, 4),
@@ -683,6 +683,15 @@ def main():
             "dominant_kernel_ms": round(kernel_ms, 4),
             "ms_per_step_with_event_records_inside_the_call": round(ms_ev, 4),
         }
+        # the same batch over an FP8 cache: shared chunks go through the FP8 kernel, two programs (sixteen
+        # query heads) per workgroup
+        fc4 = wl.to_fp8_cache(wb)
+        f8_ms, f8_kernel_ms, _, _ = run_decode(wb, f_steps, 5, torch, ta, fp8_cache=fc4, events_in_timed_steps=False)
+        extra["forked_decode"]["fp8_cache"] = {
+            "ms_per_step": round(f8_ms, 4), "unique_kv_gbps_of_2048_B_per_token": round(unique / 2 / f8_ms / 1e6, 1),
+            "private_chunks_kernel_ms": round(f8_kernel_ms, 4)}
+        del fc4
+        torch.cuda.empty_cache()
         # the same batch with its programs in shuffled order: the groups are found all the same
         import numpy as np
 

@@ -143,8 +143,9 @@ WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_l
         w.off_part_o = off;      off = align256(off + sizeof(float) * kHeadDim * size_t(w.max_chunks) * g.num_q_heads);
         // a shared chunk serves at least two programs; when every chunk goes to the matrix-core
         // kernel, one item each at most
-        w.max_shared_items = all_on_tiles ? w.max_chunks
-                                          : static_cast<int32_t>((int64_t(batch) / 2) * (pages / w.chunk_pages));
+        // (a chunk chosen on the device may be shorter than the host's: room for the shortest one then)
+        const int64_t finest = g.decode_chunk_pages == 0 ? kMinChunkPages : w.chunk_pages;
+        w.max_shared_items = all_on_tiles ? w.max_chunks : static_cast<int32_t>((int64_t(batch) / 2) * (pages / finest));
         w.off_counts = off;      off = align256(off + sizeof(int32_t) * 4);
         w.off_lcp = off;         off = align256(off + sizeof(int32_t) * size_t(batch));
         w.off_pred = off;        off = align256(off + sizeof(int32_t) * size_t(batch));

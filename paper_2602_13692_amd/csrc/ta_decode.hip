@@ -767,7 +767,7 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
         const dim3 grid(static_cast<unsigned>(blocks)), block(kChunkThreads);
         if (ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
         if (g.kv_fp8) {
-            const int rc = launch_fp8_items(cp, g.group, true, grid.x, stream);
+            const int rc = launch_fp8_items(cp, g.group, true, false, grid.x, stream);
             if (rc != TA_OK) return rc;
         } else {
             switch (g.group) {
@@ -792,9 +792,11 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     int32_t* order = reinterpret_cast<int32_t*>(workspace + w.off_order);
     int4* shared_items = reinterpret_cast<int4*>(workspace + w.off_shared_items);
     // sharing needs at least two programs with a bulk chunk each and a non-empty block table
-    // (pools of fp8 codes take every chunk through their own item kernel: no sharing there)
-    const bool look_for_sharing = !g.kv_fp8 && a.batch >= 2 && a.batch <= 1024 && w.max_shared_items > 0 &&
+    const bool look_for_sharing = a.batch >= 2 && a.batch <= 1024 && w.max_shared_items > 0 &&
                                   a.block_table_stride > 0 && cp.max_pages >= kMinChunkPages;
+    // rows of one workgroup of the kernel that computes the shared chunks: 128 on the tile kernel,
+    // the sixteen columns of the score tile in the kernel for FP8 caches
+    const int32_t max_members = (g.kv_fp8 ? 16 : 128) / g.group;
     // The workspace plan has decided which kernel streams the private chunks (and sized
     // shared_items for it): the matrix-core kernel takes them as groups of one program.
     const bool private_on_tiles = w.private_on_tiles != 0;
@@ -809,13 +811,26 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     while (plan_threads < 1024 && plan_threads < static_cast<unsigned>(a.batch)) plan_threads <<= 1;
     hipLaunchKernelGGL(plan_decode_kernel, dim3(1), dim3(plan_threads), 0, stream, a.context_lens,
                        look_for_sharing ? pred : nullptr, look_for_sharing ? lcp : nullptr, a.batch, cp.max_pages,
-                       w.chunk_pages, g.decode_chunk_pages == 0 ? 1 : 0, g.num_kv_heads, w.max_chunks, 128 / g.group,
+                       w.chunk_pages, g.decode_chunk_pages == 0 ? 1 : 0, g.num_kv_heads, w.max_chunks, max_members,
                        w.max_shared_items,
                        private_on_tiles ? 1 : 0,
                        chunk_start, items, shared_items, order, counts);
     TA_HIP_TRY(hipGetLastError());
 
-    if (look_for_sharing || private_on_tiles) {
+    cp.counts = counts;
+    cp.items = items;
+    cp.part_ml = part_ml;
+    cp.part_o = part_o;
+    if (look_for_sharing && g.kv_fp8) {
+        // an FP8 cache: the shared chunks go through the same kernel as the private ones, a few
+        // member programs per workgroup
+        cp.shared_items = shared_items;
+        cp.order = order;
+        cp.chunk_start = chunk_start;
+        const int64_t walkers = w.max_shared_items < 256 ? w.max_shared_items : 256;     // each walks the list
+        const int rc = launch_fp8_items(cp, g.group, false, true, static_cast<unsigned>(walkers * g.num_kv_heads), stream);
+        if (rc != TA_OK) return rc;
+    } else if (look_for_sharing || private_on_tiles) {
         SharedPrefixArgs sa{};
         sa.q = a.q;
         sa.k_pool = a.k_pool;
@@ -839,16 +854,12 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     }
 
     if (w.max_chunks > 0 && !private_on_tiles) {
-        cp.counts = counts;
-        cp.items = items;
-        cp.part_ml = part_ml;
-        cp.part_o = part_o;
         const int64_t blocks = int64_t(w.max_chunks) * g.num_kv_heads;
         if (blocks > 0x7fffffff || w.chunk_pages > (g.kv_fp8 ? kMaxItemPagesFp8 : kMaxItemPages)) return TA_ERR_INVALID_ARG;
         const dim3 grid(static_cast<unsigned>(blocks)), block(kChunkThreads);
         if (ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
         if (g.kv_fp8) {
-            const int rc = launch_fp8_items(cp, g.group, false, grid.x, stream);
+            const int rc = launch_fp8_items(cp, g.group, false, false, grid.x, stream);
             if (rc != TA_OK) return rc;
         } else {
             switch (g.group) {

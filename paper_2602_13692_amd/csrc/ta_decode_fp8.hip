@@ -187,7 +187,11 @@ __device__ __forceinline__ void process_block(const BlockRegs& r, const bf16x8 (
 
 // DIRECT: every program is one item (its whole context); the workgroup normalises and writes the
 // bf16 output itself.
-template <bool DIRECT>
+// SHARED: an item is a bulk chunk that `members` programs have in common (their block tables
+// name the same pages there): the sixteen columns of the score tile hold the heads of all of
+// them (column = member * group + head), the pages are streamed once, and every member gets its
+// partial in its own slot.
+template <bool DIRECT, bool SHARED>
 __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int32_t group) {
     // the waves' V tiles during the walk, the waves' results afterwards
     __shared__ __attribute__((aligned(16))) char smem[kWaves * kStageBytes];
@@ -196,10 +200,19 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
     __shared__ int32_t sm_ids[kMaxItemPagesFp8];
     static_assert(kWaves * kStageBytes >= kWaves * kMaxGroup * kHeadDim * 4, "the merge reuses the V tiles' memory");
 
-    const int item = blockIdx.x / p.num_kv_heads;
-    const int g = blockIdx.x - item * p.num_kv_heads;
-    int b, page0, n_here, slot = 0;
-    if (DIRECT) {
+    const int g = blockIdx.x % p.num_kv_heads;
+    // (shared form: the launch is sized for the most shared chunks a batch could have, far more
+    // than it usually has, so a bounded number of workgroups walks the list)
+    const int item_step = SHARED ? int(gridDim.x) / p.num_kv_heads : 0;
+    for (int item = blockIdx.x / p.num_kv_heads;; item += item_step) {
+    int b, page0, n_here, slot = 0, members = 1, chunk = 0, first_pos = 0;
+    if (SHARED) {
+        if (item >= p.counts[1]) return;
+        const int4 it = p.shared_items[item];
+        first_pos = it.x; members = it.y; chunk = it.z; b = it.w;
+        n_here = p.counts[3];                      // a whole bulk chunk, every key of it exists
+        page0 = chunk * n_here;
+    } else if (DIRECT) {
         b = item;
         page0 = 0;
     } else {
@@ -218,7 +231,7 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
         n_here = n_pages_b;
     }
     const int tail_valid = L - (n_pages_b - 1) * kPageSize;           // 1..16 where the program's last page is reached
-    const bool has_tail = n_here > 0 && (page0 + n_here == n_pages_b) && tail_valid < kPageSize;
+    const bool has_tail = !SHARED && n_here > 0 && (page0 + n_here == n_pages_b) && tail_valid < kPageSize;
     const int n_full_pages = has_tail ? n_here - 1 : n_here;
     const int full_blocks = n_full_pages >> 1;                         // blocks of two complete pages
     const int rest_pages = n_here - 2 * full_blocks;                   // 0, 1 or 2 pages in a last, masked block
@@ -238,8 +251,10 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
     // B operands: head r16 of the group (zero columns beyond it), dims 16 (c + 4 i) + 8 hf ..
     bf16x8 qop[2][2];
     {
-        const bool head_ok = r16 < group;
-        const uint16_t* qrow = p.q + (int64_t(b) * p.num_q_heads + g * group + (head_ok ? r16 : 0)) * kHeadDim;
+        const bool head_ok = r16 < members * group;
+        const int member = head_ok ? r16 / group : 0, head = head_ok ? r16 % group : 0;
+        const int q_program = SHARED ? p.order[first_pos + member] : b;
+        const uint16_t* qrow = p.q + (int64_t(q_program) * p.num_q_heads + g * group + head) * kHeadDim;
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -313,7 +328,7 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
     lt += __shfl_xor(lt, 32);
     __syncthreads();                                   // every wave is done with its V tile
     float* sm_o = reinterpret_cast<float*>(smem);      // [wave][head][128]
-    if (r16 < group) {
+    if (r16 < members * group) {
         float* dst = sm_o + (wave * kMaxGroup + r16) * kHeadDim + 4 * c;
 #pragma unroll
         for (int db = 0; db < 8; ++db) *reinterpret_cast<f32x4*>(dst + 16 * db) = st.o[db];
@@ -325,7 +340,7 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
     __syncthreads();
 
     // thread t owns two neighbouring dims of one head
-    for (int idx = threadIdx.x; idx < group * (kHeadDim / 2); idx += kThreads) {
+    for (int idx = threadIdx.x; idx < members * group * (kHeadDim / 2); idx += kThreads) {
         const int h = idx / (kHeadDim / 2);
         const int d0 = 2 * (idx % (kHeadDim / 2));
         float mt = sm_m[0][h];
@@ -348,13 +363,19 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
             if (p.lse != nullptr && d0 == 0)
                 p.lse[rid] = sum > 0.0f ? (mt + __builtin_amdgcn_logf(sum)) * kLn2 : -INFINITY;
         } else {
-            const int64_t rowid = int64_t(slot) * p.num_q_heads + g * group + h;
+            // (shared form: column h is head h % group of member h / group, whose partial of this chunk
+            // sits at its own first slot + chunk)
+            const int my_slot = SHARED ? p.chunk_start[p.order[first_pos + h / group]] + chunk : slot;
+            const int64_t rowid = int64_t(my_slot) * p.num_q_heads + g * group + (SHARED ? h % group : h);
             *reinterpret_cast<float2*>(p.part_o + rowid * kHeadDim + d0) = make_float2(a0, a1);
             if (d0 == 0) {
                 p.part_ml[rowid * 2 + 0] = mt;    // already in the log2 domain
                 p.part_ml[rowid * 2 + 1] = sum;
             }
         }
+    }
+    if (!SHARED) break;
+    __syncthreads();                               // the merge buffers are the next item's V tiles
     }
 }
 
@@ -403,10 +424,11 @@ int launch_widen_pages(const Geometry& g, const void* k_codes, const void* v_cod
     return TA_OK;
 }
 
-int launch_fp8_items(const ChunkParams& p, int32_t group, bool direct, unsigned blocks, hipStream_t stream) {
-    if (group < 1 || group > kMaxGroup) return TA_ERR_UNSUPPORTED;
-    if (direct) hipLaunchKernelGGL(decode_fp8_kernel<true>, dim3(blocks), dim3(kThreads), 0, stream, p, group);
-    else hipLaunchKernelGGL(decode_fp8_kernel<false>, dim3(blocks), dim3(kThreads), 0, stream, p, group);
+int launch_fp8_items(const ChunkParams& p, int32_t group, bool direct, bool shared, unsigned blocks, hipStream_t stream) {
+    if (group < 1 || group > kMaxGroup || (direct && shared)) return TA_ERR_UNSUPPORTED;
+    if (shared) hipLaunchKernelGGL((decode_fp8_kernel<false, true>), dim3(blocks), dim3(kThreads), 0, stream, p, group);
+    else if (direct) hipLaunchKernelGGL((decode_fp8_kernel<true, false>), dim3(blocks), dim3(kThreads), 0, stream, p, group);
+    else hipLaunchKernelGGL((decode_fp8_kernel<false, false>), dim3(blocks), dim3(kThreads), 0, stream, p, group);
     TA_HIP_TRY(hipGetLastError());
     return TA_OK;
 }

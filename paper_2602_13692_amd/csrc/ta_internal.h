@@ -114,8 +114,12 @@ struct ChunkParams {
     const char* v_pool;
     const int32_t* block_table;
     const int32_t* context_lens;
-    const int32_t* counts;       // counts[0] = number of items
+    const int32_t* counts;       // counts[0] = number of items; shared form: counts[1] items, counts[3] chunk length in pages
     const int4* items;           // (program, first page, pages, slot)
+    // shared form of the FP8 kernel only: chunks that a few programs share, as for the tile kernel
+    const int4* shared_items;    // (position of the first member in `order`, members, bulk chunk, first member)
+    const int32_t* order;        // programs listed group by group
+    const int32_t* chunk_start;  // first partial slot of each program
     float* part_ml;
     float* part_o;
     uint16_t* out;               // direct mode only
@@ -133,8 +137,10 @@ struct ChunkParams {
 constexpr int kMaxItemPages = 128;      // vector-ALU kernel: two page ids per lane
 constexpr int kMaxItemPagesFp8 = 512;   // FP8 kernel: the item's page ids sit in LDS
 
-// The item kernel for pools of E4M3 codes (matrix cores, any group size up to 16).
-int launch_fp8_items(const ChunkParams& p, int32_t group, bool direct, unsigned blocks, hipStream_t stream);
+// The item kernel for pools of E4M3 codes (matrix cores, any group size up to 16).  Shared form:
+// one workgroup per (shared chunk, kv head) computes the partials of up to 16 / group programs at
+// once (their heads fill the sixteen columns of the score tile).
+int launch_fp8_items(const ChunkParams& p, int32_t group, bool direct, bool shared, unsigned blocks, hipStream_t stream);
 
 // Widens the pages of a batch from E4M3 codes to bf16 code values (exact), program by program:
 // logical page i of program b goes to slot b * width + i of the wide pools, and wide_table gets

@@ -121,6 +121,24 @@ def test_forked_programs_read_aliased_pages():
     gu.assert_close(out, lse, ref, ref_lse, "fp8 forked", lse_tol=gu.LSE_TOL_FP8)
 
 
+@pytest.mark.parametrize("Hq,Hkv,group,batch,chunk_pages", [(32, 8, 16, 48, 0), (8, 8, 20, 60, 16), (64, 8, 6, 30, 64),
+                                                             (16, 8, 3, 33, 8), (32, 8, 5, 300, 32), (64, 8, 16, 64, 128)])
+def test_shared_chunks_of_forked_programs_in_shuffled_order(Hq, Hkv, group, batch, chunk_pages):
+    """Programs whose block tables start with the same pages share the chunks there: one workgroup
+    computes the partials of up to 16 / (heads per kv head) of them at once (groups larger than that
+    are cut), wherever the members sit in the batch."""
+    wb = wl.forked_decode(DEV, seed=wl.SEED_BASE + 3720 + group, batch=batch, group=group, prefix_len=3072, suffix_lo=1,
+                          suffix_hi=700, num_q_heads=Hq, num_kv_heads=Hkv)
+    perm = np.random.default_rng(wl.SEED_BASE + 3721).permutation(wb.batch)
+    wb.q = wb.q[torch.from_numpy(perm).to(wb.q.device)].contiguous()
+    wb.block_table = np.ascontiguousarray(wb.block_table[perm])
+    wb.context_lens = np.ascontiguousarray(wb.context_lens[perm])
+    fc = wl.to_fp8_cache(wb)
+    out, lse = gu.gpu_decode_fp8(wb, fc, chunk_pages=chunk_pages)
+    ref, ref_lse = gu.oracle_decode_fp8(wb, fc)
+    gu.assert_close(out, lse, ref, ref_lse, f"fp8 shared chunks Hq={Hq} group={group}", lse_tol=gu.LSE_TOL_FP8)
+
+
 @pytest.mark.parametrize("Hq,Hkv", [(32, 8), (8, 8), (16, 2), (8, 1)])
 def test_append_prefill_over_an_fp8_cache(Hq, Hkv):
     """Ragged new-token counts on prefixes from zero to a few thousand tokens: the tile kernel runs on
