@@ -38,9 +38,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # null until the counters are taken again.
 TRAFFIC_BYTES = {"9d52305fcf5496bb": 5081000000}
 # The same batch on the vector-ALU kernel (the library's choice for smaller batches).
-VECTOR_TRAFFIC_BYTES = {"d06630c76b396928": 5081000000}
+VECTOR_TRAFFIC_BYTES = {"8e48069d81f3315e": 5081000000}
 # The same for the FP8-cache decode kernel.
-FP8_TRAFFIC_BYTES = {"a89d347f0788530d": 2556000000}
+FP8_TRAFFIC_BYTES = {"bdb0d2155170f1cb": 2556000000}
 # The same for the append-prefill tile kernel: bytes that left the L2 per launch (FETCH_SIZE scaled).
 PREFILL_TRAFFIC_BYTES = {"9d52305fcf5496bb": 16850000000}
 
@@ -683,7 +683,7 @@ def main():
             "dominant_kernel_ms": round(kernel_ms, 4),
             "ms_per_step_with_event_records_inside_the_call": round(ms_ev, 4),
         }
-        # the same batch over an FP8 cache: shared chunks go through the FP8 kernel, two programs (sixteen
+        # the same batch over an FP8 cache: shared chunks go through the FP8 kernel, four programs (32
         # query heads) per workgroup
         fc4 = wl.to_fp8_cache(wb)
         f8_ms, f8_kernel_ms, _, _ = run_decode(wb, f_steps, 5, torch, ta, fp8_cache=fc4, events_in_timed_steps=False)

@@ -795,8 +795,8 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     const bool look_for_sharing = a.batch >= 2 && a.batch <= 1024 && w.max_shared_items > 0 &&
                                   a.block_table_stride > 0 && cp.max_pages >= kMinChunkPages;
     // rows of one workgroup of the kernel that computes the shared chunks: 128 on the tile kernel,
-    // the sixteen columns of the score tile in the kernel for FP8 caches
-    const int32_t max_members = (g.kv_fp8 ? 16 : 128) / g.group;
+    // two sets of sixteen columns of the score tile in the kernel for FP8 caches
+    const int32_t max_members = (g.kv_fp8 ? 32 : 128) / g.group;
     // The workspace plan has decided which kernel streams the private chunks (and sized
     // shared_items for it): the matrix-core kernel takes them as groups of one program.
     const bool private_on_tiles = w.private_on_tiles != 0;
@@ -822,8 +822,8 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     cp.part_ml = part_ml;
     cp.part_o = part_o;
     if (look_for_sharing && g.kv_fp8) {
-        // an FP8 cache: the shared chunks go through the same kernel as the private ones, a few
-        // member programs per workgroup
+        // an FP8 cache: the shared chunks go through a form of the kernel that streams the private
+        // ones, up to 32 / group member programs per workgroup
         cp.shared_items = shared_items;
         cp.order = order;
         cp.chunk_start = chunk_start;

@@ -97,22 +97,30 @@ struct SoftmaxState {
     f32x4 o[8];       // O^T: dims 16 db + 4 (lane / 16) + 0..3 of head lane % 16
 };
 
-// One block of up to 32 keys.  valid = keys of the block that exist (32 unless MASKED).
-template <bool MASKED>
-__device__ __forceinline__ void process_block(const BlockRegs& r, const bf16x8 (&qop)[2][2], SoftmaxState& st,
+// One block of up to 32 keys.  valid = keys of the block that exist (32 unless MASKED).  SETS sets
+// of sixteen columns (query heads) take their turn on every operand once it is in registers.
+template <bool MASKED, int SETS>
+__device__ __forceinline__ void process_block(const BlockRegs& r, const bf16x8 (&qop)[SETS][2][2], SoftmaxState (&st)[SETS],
                                               char* stage, float scale_log2, int lane, int valid) {
     const int r16 = lane & 15, c = lane >> 4;
     // ---- scores: 16 keys x 16 heads per page, contraction over the 128 dims in four steps ----
-    f32x4 s[2];
+    f32x4 s[SETS][2];
 #pragma unroll
     for (int pg = 0; pg < 2; ++pg) {
-        f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        f32x4 acc[SETS];
+#pragma unroll
+        for (int q = 0; q < SETS; ++q) acc[q] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen8(r.k[pg][i].x, r.k[pg][i].y), qop[i][0], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(widen8(r.k[pg][i].z, r.k[pg][i].w), qop[i][1], acc, 0, 0, 0);
+            const bf16x8 lo = widen8(r.k[pg][i].x, r.k[pg][i].y), hi = widen8(r.k[pg][i].z, r.k[pg][i].w);
+#pragma unroll
+            for (int q = 0; q < SETS; ++q) {
+                acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(lo, qop[q][i][0], acc[q], 0, 0, 0);
+                acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hi, qop[q][i][1], acc[q], 0, 0, 0);
+            }
         }
-        s[pg] = acc;
+#pragma unroll
+        for (int q = 0; q < SETS; ++q) s[q][pg] = acc[q];
     }
     // ---- V: widen and park it in this wave's LDS tile, row-major bf16, 16-byte chunks permuted
     // per row (chunk ch of key k at ch ^ 4 (k % 4)) so that the transposing reads below spread
@@ -133,42 +141,46 @@ __device__ __forceinline__ void process_block(const BlockRegs& r, const bf16x8 (
             *reinterpret_cast<u32x4*>(row + ((ch ^ swz) << 4)) = lo;
             *reinterpret_cast<u32x4*>(row + (((ch + 1) ^ swz) << 4)) = hi;
         }
-    // ---- softmax: this lane holds head r16, keys 4 c .. 4 c + 3 of each page ----
-    float t[2][4];
-    float mx = -INFINITY;
+    // ---- softmax: this lane holds head r16 of each set, keys 4 c .. 4 c + 3 of each page ----
+    bf16x8 pf[SETS];
 #pragma unroll
-    for (int pg = 0; pg < 2; ++pg)
+    for (int q = 0; q < SETS; ++q) {
+        float t[2][4];
+        float mx = -INFINITY;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            float x = s[pg][e] * scale_log2;
-            if (MASKED) x = (pg * kPageSize + 4 * c + e) < valid ? x : -INFINITY;
-            t[pg][e] = x;
-            mx = fmaxf(mx, x);
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float x = s[q][pg][e] * scale_log2;
+                if (MASKED) x = (pg * kPageSize + 4 * c + e) < valid ? x : -INFINITY;
+                t[pg][e] = x;
+                mx = fmaxf(mx, x);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        if (__builtin_amdgcn_ballot_w64(mx > st[q].m) != 0) {         // wave-uniform; rare after the first blocks
+            const float m_new = fmaxf(st[q].m, mx);
+            const float alpha = fast_exp2(st[q].m - m_new);
+            st[q].m = m_new;
+            st[q].l *= alpha;
+#pragma unroll
+            for (int db = 0; db < 8; ++db) st[q].o[db] *= alpha;
         }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    if (__builtin_amdgcn_ballot_w64(mx > st.m) != 0) {            // wave-uniform; rare after the first blocks
-        const float m_new = fmaxf(st.m, mx);
-        const float alpha = fast_exp2(st.m - m_new);
-        st.m = m_new;
-        st.l *= alpha;
-#pragma unroll
-        for (int db = 0; db < 8; ++db) st.o[db] *= alpha;
+        const uint32_t ones = 0x3f803f80u;   // (1.0, 1.0) in bf16
+        u32x4 pw;
+        pw.x = pack_bf16(fast_exp2(t[0][0] - st[q].m), fast_exp2(t[0][1] - st[q].m));
+        pw.y = pack_bf16(fast_exp2(t[0][2] - st[q].m), fast_exp2(t[0][3] - st[q].m));
+        pw.z = pack_bf16(fast_exp2(t[1][0] - st[q].m), fast_exp2(t[1][1] - st[q].m));
+        pw.w = pack_bf16(fast_exp2(t[1][2] - st[q].m), fast_exp2(t[1][3] - st[q].m));
+        // the sum adds up the ROUNDED weights, the ones the matrix core multiplies
+        float l = st[q].l;
+        l = dot2_bf16(pw.x, ones, l);
+        l = dot2_bf16(pw.y, ones, l);
+        l = dot2_bf16(pw.z, ones, l);
+        l = dot2_bf16(pw.w, ones, l);
+        st[q].l = l;
+        pf[q] = __builtin_bit_cast(bf16x8, pw);
     }
-    const uint32_t ones = 0x3f803f80u;   // (1.0, 1.0) in bf16
-    u32x4 pw;
-    pw.x = pack_bf16(fast_exp2(t[0][0] - st.m), fast_exp2(t[0][1] - st.m));
-    pw.y = pack_bf16(fast_exp2(t[0][2] - st.m), fast_exp2(t[0][3] - st.m));
-    pw.z = pack_bf16(fast_exp2(t[1][0] - st.m), fast_exp2(t[1][1] - st.m));
-    pw.w = pack_bf16(fast_exp2(t[1][2] - st.m), fast_exp2(t[1][3] - st.m));
-    // the sum adds up the ROUNDED weights, the ones the matrix core multiplies
-    float l = st.l;
-    l = dot2_bf16(pw.x, ones, l);
-    l = dot2_bf16(pw.y, ones, l);
-    l = dot2_bf16(pw.z, ones, l);
-    l = dot2_bf16(pw.w, ones, l);
-    st.l = l;
-    const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
     // ---- O^T += V^T P^T: for every block of 16 dims, eight keys of one dim per lane.  In each
     // group of 16 lanes, lane s names the 8 bytes (4 dims) of key 4 c + s / 4 at dims
     // 16 db + 4 (s % 4) .., and receives dim 16 db + s of the four keys 4 c .. 4 c + 3. ----
@@ -181,18 +193,21 @@ __device__ __forceinline__ void process_block(const BlockRegs& r, const bf16x8 (
         const s16x4 a0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(TA_LDS_PTR(s16x4, at));
         const s16x4 a1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(TA_LDS_PTR(s16x4, at + kPageSize * kHeadDim * 2));
         const bf16x8 a = __builtin_bit_cast(bf16x8, __builtin_shufflevector(a0, a1, 0, 1, 2, 3, 4, 5, 6, 7));
-        st.o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pf, st.o[db], 0, 0, 0);
+#pragma unroll
+        for (int q = 0; q < SETS; ++q) st[q].o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, pf[q], st[q].o[db], 0, 0, 0);
     }
 }
 
 // DIRECT: every program is one item (its whole context); the workgroup normalises and writes the
 // bf16 output itself.
 // SHARED: an item is a bulk chunk that `members` programs have in common (their block tables
-// name the same pages there): the sixteen columns of the score tile hold the heads of all of
-// them (column = member * group + head), the pages are streamed once, and every member gets its
-// partial in its own slot.
+// name the same pages there): two sets of sixteen columns hold the heads of all of them
+// (column = member * group + head, up to 32 / group members), the pages are streamed once, every
+// operand serves both sets while it is in registers, and every member gets its partial in its
+// own slot.
 template <bool DIRECT, bool SHARED>
 __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int32_t group) {
+    constexpr int SETS = SHARED ? 2 : 1;
     // the waves' V tiles during the walk, the waves' results afterwards
     __shared__ __attribute__((aligned(16))) char smem[kWaves * kStageBytes];
     __shared__ float sm_m[kWaves][kMaxGroup];
@@ -248,11 +263,15 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
         return int64_t(__builtin_amdgcn_readfirstlane(sm_ids[idx])) * p.stride_page_bytes;
     };
 
-    // B operands: head r16 of the group (zero columns beyond it), dims 16 (c + 4 i) + 8 hf ..
-    bf16x8 qop[2][2];
-    {
-        const bool head_ok = r16 < members * group;
-        const int member = head_ok ? r16 / group : 0, head = head_ok ? r16 % group : 0;
+    // B operands: column 16 q + r16 of set q is head (column % group) of member (column / group),
+    // zero beyond the last member; dims 16 (c + 4 i) + 8 hf ..
+    bf16x8 qop[SETS][2][2];
+    SoftmaxState st[SETS];
+#pragma unroll
+    for (int q = 0; q < SETS; ++q) {
+        const int col = 16 * q + r16;
+        const bool head_ok = col < members * group;
+        const int member = head_ok ? col / group : 0, head = head_ok ? col % group : 0;
         const int q_program = SHARED ? p.order[first_pos + member] : b;
         const uint16_t* qrow = p.q + (int64_t(q_program) * p.num_q_heads + g * group + head) * kHeadDim;
 #pragma unroll
@@ -261,15 +280,13 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
             for (int hf = 0; hf < 2; ++hf) {
                 u32x4 w = {0u, 0u, 0u, 0u};
                 if (head_ok) w = *reinterpret_cast<const u32x4*>(qrow + 16 * (c + 4 * i) + 8 * hf);
-                qop[i][hf] = __builtin_bit_cast(bf16x8, w);
+                qop[q][i][hf] = __builtin_bit_cast(bf16x8, w);
             }
-    }
-
-    SoftmaxState st;
-    st.m = kNegBig;
-    st.l = 0.0f;
+        st[q].m = kNegBig;
+        st[q].l = 0.0f;
 #pragma unroll
-    for (int db = 0; db < 8; ++db) st.o[db] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        for (int db = 0; db < 8; ++db) st[q].o[db] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
 
     const char* k_head = p.k_pool + int64_t(g) * p.stride_head_bytes;
     const char* v_head = p.v_pool + int64_t(g) * p.stride_head_bytes;
@@ -292,18 +309,18 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
         for (; j + 2 < n_mine; j += 2) {
             load_block(bufB, j + 1);
             __builtin_amdgcn_sched_barrier(0);
-            process_block<false>(bufA, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
+            process_block<false, SETS>(bufA, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
             load_block(bufA, j + 2);
             __builtin_amdgcn_sched_barrier(0);
-            process_block<false>(bufB, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
+            process_block<false, SETS>(bufB, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
         }
         if (j + 1 < n_mine) {
             load_block(bufB, j + 1);
             __builtin_amdgcn_sched_barrier(0);
-            process_block<false>(bufA, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
-            process_block<false>(bufB, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
+            process_block<false, SETS>(bufA, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
+            process_block<false, SETS>(bufB, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
         } else {
-            process_block<false>(bufA, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
+            process_block<false, SETS>(bufA, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
         }
     }
     if (rest_pages > 0 && (full_blocks & (kWaves - 1)) == wave) {
@@ -319,29 +336,34 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
             const int64_t o1 = page_off(2 * full_blocks + 1);
             load_page(t, 1, k_head + o1, v_head + o1, lane);
         }
-        process_block<true>(t, qop, st, stage, p.scale_log2, lane, rest_valid);
+        process_block<true, SETS>(t, qop, st, stage, p.scale_log2, lane, rest_valid);
     }
 
-    // ---- the four lanes of a head add up their shares; the waves meet in LDS ----
-    float lt = st.l;
+    // ---- the four lanes of a head add up their shares; the waves meet in LDS, one set of columns
+    // at a time ----
+    float* sm_o = reinterpret_cast<float*>(smem);      // [wave][column of the set][128]
+#pragma unroll
+    for (int q = 0; q < SETS; ++q) {
+    const int cols_here = members * group - 16 * q < 16 ? members * group - 16 * q : 16;     // may be <= 0
+    float lt = st[q].l;
     lt += __shfl_xor(lt, 16);
     lt += __shfl_xor(lt, 32);
-    __syncthreads();                                   // every wave is done with its V tile
-    float* sm_o = reinterpret_cast<float*>(smem);      // [wave][head][128]
-    if (r16 < members * group) {
+    __syncthreads();                                   // every wave is done with its V tile (and with the set before)
+    if (r16 < cols_here) {
         float* dst = sm_o + (wave * kMaxGroup + r16) * kHeadDim + 4 * c;
 #pragma unroll
-        for (int db = 0; db < 8; ++db) *reinterpret_cast<f32x4*>(dst + 16 * db) = st.o[db];
+        for (int db = 0; db < 8; ++db) *reinterpret_cast<f32x4*>(dst + 16 * db) = st[q].o[db];
         if (c == 0) {
-            sm_m[wave][r16] = st.m;
+            sm_m[wave][r16] = st[q].m;
             sm_l[wave][r16] = lt;
         }
     }
     __syncthreads();
 
     // thread t owns two neighbouring dims of one head
-    for (int idx = threadIdx.x; idx < members * group * (kHeadDim / 2); idx += kThreads) {
-        const int h = idx / (kHeadDim / 2);
+    for (int idx = threadIdx.x; idx < cols_here * (kHeadDim / 2); idx += kThreads) {
+        const int h = idx / (kHeadDim / 2);           // column of this set
+        const int col = 16 * q + h;
         const int d0 = 2 * (idx % (kHeadDim / 2));
         float mt = sm_m[0][h];
 #pragma unroll
@@ -363,16 +385,17 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
             if (p.lse != nullptr && d0 == 0)
                 p.lse[rid] = sum > 0.0f ? (mt + __builtin_amdgcn_logf(sum)) * kLn2 : -INFINITY;
         } else {
-            // (shared form: column h is head h % group of member h / group, whose partial of this chunk
+            // (shared form: column col is head col % group of member col / group, whose partial of this chunk
             // sits at its own first slot + chunk)
-            const int my_slot = SHARED ? p.chunk_start[p.order[first_pos + h / group]] + chunk : slot;
-            const int64_t rowid = int64_t(my_slot) * p.num_q_heads + g * group + (SHARED ? h % group : h);
+            const int my_slot = SHARED ? p.chunk_start[p.order[first_pos + col / group]] + chunk : slot;
+            const int64_t rowid = int64_t(my_slot) * p.num_q_heads + g * group + (SHARED ? col % group : h);
             *reinterpret_cast<float2*>(p.part_o + rowid * kHeadDim + d0) = make_float2(a0, a1);
             if (d0 == 0) {
                 p.part_ml[rowid * 2 + 0] = mt;    // already in the log2 domain
                 p.part_ml[rowid * 2 + 1] = sum;
             }
         }
+    }
     }
     if (!SHARED) break;
     __syncthreads();                               // the merge buffers are the next item's V tiles

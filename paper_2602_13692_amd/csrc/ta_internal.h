@@ -138,8 +138,8 @@ constexpr int kMaxItemPages = 128;      // vector-ALU kernel: two page ids per l
 constexpr int kMaxItemPagesFp8 = 512;   // FP8 kernel: the item's page ids sit in LDS
 
 // The item kernel for pools of E4M3 codes (matrix cores, any group size up to 16).  Shared form:
-// one workgroup per (shared chunk, kv head) computes the partials of up to 16 / group programs at
-// once (their heads fill the sixteen columns of the score tile).
+// one workgroup per (shared chunk, kv head) computes the partials of up to 32 / group programs at
+// once (their heads fill two sets of sixteen columns of the score tile).
 int launch_fp8_items(const ChunkParams& p, int32_t group, bool direct, bool shared, unsigned blocks, hipStream_t stream);
 
 // Widens the pages of a batch from E4M3 codes to bf16 code values (exact), program by program:

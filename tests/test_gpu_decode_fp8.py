@@ -125,7 +125,7 @@ def test_forked_programs_read_aliased_pages():
                                                              (16, 8, 3, 33, 8), (32, 8, 5, 300, 32), (64, 8, 16, 64, 128)])
 def test_shared_chunks_of_forked_programs_in_shuffled_order(Hq, Hkv, group, batch, chunk_pages):
     """Programs whose block tables start with the same pages share the chunks there: one workgroup
-    computes the partials of up to 16 / (heads per kv head) of them at once (groups larger than that
+    computes the partials of up to 32 / (heads per kv head) of them at once (groups larger than that
     are cut), wherever the members sit in the batch."""
     wb = wl.forked_decode(DEV, seed=wl.SEED_BASE + 3720 + group, batch=batch, group=group, prefix_len=3072, suffix_lo=1,
                           suffix_hi=700, num_q_heads=Hq, num_kv_heads=Hkv)
