@@ -92,3 +92,33 @@ def test_prefill_random_shapes(seed):
     ref, ref_lse = gu.oracle_prefill(wb)
     gu.assert_close(out, lse, ref, ref_lse, f"prefill seed={seed} Hq={Hq} Hkv={Hkv} B={batch}",
                     lse_tol=gu.LSE_TOL)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_fp8_cache_random_shapes(seed):
+    """The same over an FP8 cache: ragged batches and forked groups (whose shared chunks one workgroup
+    computes for up to 32 / (heads per kv head) members at once), any supported head shape."""
+    rng = np.random.default_rng(wl.SEED_BASE + 5800 + seed)
+    Hq, Hkv = [(32, 8), (8, 8), (64, 8), (16, 8), (8, 2), (4, 1), (2, 2), (16, 2)][seed % 8]
+    if seed % 2 == 0:
+        group = int(rng.choice([2, 3, 5, 16, 33, 40]))
+        n_groups = int(rng.integers(1, 4))
+        wb = wl.forked_decode(DEV, seed=wl.SEED_BASE + 5900 + seed, batch=group * n_groups, group=group,
+                              prefix_len=16 * int(rng.integers(8, 400)), suffix_lo=1,
+                              suffix_hi=int(rng.choice([5, 300, 2000])), num_q_heads=Hq, num_kv_heads=Hkv)
+        perm = rng.permutation(wb.batch)
+        wb.q = wb.q[torch.from_numpy(perm).to(wb.q.device)].contiguous()
+        wb.block_table = np.ascontiguousarray(wb.block_table[perm])
+        wb.context_lens = np.ascontiguousarray(wb.context_lens[perm])
+    else:
+        batch = int(rng.integers(1, 40))
+        firsts = [int(x) for x in rng.choice([0, 1, 15, 16, 17, 31, 32, 33, 2047, 2048, 2049, 8191, 8193], size=min(batch, 4))]
+        wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 5900 + seed, batch=batch, len_lo=1,
+                               len_hi=int(rng.choice([40, 1500, 9000])), num_q_heads=Hq, num_kv_heads=Hkv,
+                               first_lens=firsts)
+    if seed % 3 == 0:
+        wl.poison_padding(wb)
+    fc = wl.to_fp8_cache(wb)
+    out, lse = gu.gpu_decode_fp8(wb, fc, chunk_pages=int(rng.choice([0, 0, 8, 32, 128, 512])))
+    ref, ref_lse = gu.oracle_decode_fp8(wb, fc)
+    gu.assert_close(out, lse, ref, ref_lse, f"fp8 seed={seed} Hq={Hq} Hkv={Hkv} B={wb.batch}", lse_tol=gu.LSE_TOL_FP8)
