@@ -220,185 +220,185 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
     // than it usually has, so a bounded number of workgroups walks the list)
     const int item_step = SHARED ? int(gridDim.x) / p.num_kv_heads : 0;
     for (int item = blockIdx.x / p.num_kv_heads;; item += item_step) {
-    int b, page0, n_here, slot = 0, members = 1, chunk = 0, first_pos = 0;
-    if (SHARED) {
-        if (item >= p.counts[1]) return;
-        const int4 it = p.shared_items[item];
-        first_pos = it.x; members = it.y; chunk = it.z; b = it.w;
-        n_here = p.counts[3];                      // a whole bulk chunk, every key of it exists
-        page0 = chunk * n_here;
-    } else if (DIRECT) {
-        b = item;
-        page0 = 0;
-    } else {
-        if (item >= p.counts[0]) return;
-        const int4 it = p.items[item];
-        b = it.x; page0 = it.y; n_here = it.z; slot = it.w;
-    }
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int r16 = lane & 15, c = lane >> 4;
-
-    const int L = p.context_lens[b];
-    int n_pages_b = L > 0 ? (L + kPageSize - 1) / kPageSize : 0;
-    if (DIRECT) {
-        n_pages_b = n_pages_b > p.max_pages ? p.max_pages : n_pages_b;
-        n_here = n_pages_b;
-    }
-    const int tail_valid = L - (n_pages_b - 1) * kPageSize;           // 1..16 where the program's last page is reached
-    const bool has_tail = !SHARED && n_here > 0 && (page0 + n_here == n_pages_b) && tail_valid < kPageSize;
-    const int n_full_pages = has_tail ? n_here - 1 : n_here;
-    const int full_blocks = n_full_pages >> 1;                         // blocks of two complete pages
-    const int rest_pages = n_here - 2 * full_blocks;                   // 0, 1 or 2 pages in a last, masked block
-    const int rest_valid = rest_pages == 0 ? 0 : (rest_pages - 1) * kPageSize + (has_tail ? tail_valid : kPageSize);
-
-    // page ids of this item (up to 512: the start of an item costs its workgroup a microsecond
-    // in which it streams nothing, so items are as long as the batch allows), kept in LDS
-    {
-        const int32_t* table = p.block_table + int64_t(b) * p.block_table_stride + page0;
-        for (int i = threadIdx.x; i < n_here; i += kThreads) sm_ids[i] = table[i];
-        __syncthreads();
-    }
-    auto page_off = [&](int idx) -> int64_t {                          // idx is wave-uniform
-        return int64_t(__builtin_amdgcn_readfirstlane(sm_ids[idx])) * p.stride_page_bytes;
-    };
-
-    // B operands: column 16 q + r16 of set q is head (column % group) of member (column / group),
-    // zero beyond the last member; dims 16 (c + 4 i) + 8 hf ..
-    bf16x8 qop[SETS][2][2];
-    SoftmaxState st[SETS];
-#pragma unroll
-    for (int q = 0; q < SETS; ++q) {
-        const int col = 16 * q + r16;
-        const bool head_ok = col < members * group;
-        const int member = head_ok ? col / group : 0, head = head_ok ? col % group : 0;
-        const int q_program = SHARED ? p.order[first_pos + member] : b;
-        const uint16_t* qrow = p.q + (int64_t(q_program) * p.num_q_heads + g * group + head) * kHeadDim;
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int hf = 0; hf < 2; ++hf) {
-                u32x4 w = {0u, 0u, 0u, 0u};
-                if (head_ok) w = *reinterpret_cast<const u32x4*>(qrow + 16 * (c + 4 * i) + 8 * hf);
-                qop[q][i][hf] = __builtin_bit_cast(bf16x8, w);
-            }
-        st[q].m = kNegBig;
-        st[q].l = 0.0f;
-#pragma unroll
-        for (int db = 0; db < 8; ++db) st[q].o[db] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-    }
-
-    const char* k_head = p.k_pool + int64_t(g) * p.stride_head_bytes;
-    const char* v_head = p.v_pool + int64_t(g) * p.stride_head_bytes;
-    char* stage = smem + wave * kStageBytes;
-
-    // this wave's full blocks: wave, wave + 4, ...  Two block buffers: each is refilled right
-    // after its block has been consumed and is consumed one block later; no load is issued for a
-    // page that is not used.
-    const int n_mine = full_blocks > wave ? (full_blocks - wave + kWaves - 1) / kWaves : 0;
-    if (n_mine > 0) {
-        auto load_block = [&](BlockRegs& r, int j) {
-            const int blk = wave + kWaves * j;
-            const int64_t o0 = page_off(2 * blk), o1 = page_off(2 * blk + 1);
-            load_page(r, 0, k_head + o0, v_head + o0, lane);
-            load_page(r, 1, k_head + o1, v_head + o1, lane);
-        };
-        BlockRegs bufA, bufB;
-        load_block(bufA, 0);
-        int j = 0;
-        for (; j + 2 < n_mine; j += 2) {
-            load_block(bufB, j + 1);
-            __builtin_amdgcn_sched_barrier(0);
-            process_block<false, SETS>(bufA, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
-            load_block(bufA, j + 2);
-            __builtin_amdgcn_sched_barrier(0);
-            process_block<false, SETS>(bufB, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
-        }
-        if (j + 1 < n_mine) {
-            load_block(bufB, j + 1);
-            __builtin_amdgcn_sched_barrier(0);
-            process_block<false, SETS>(bufA, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
-            process_block<false, SETS>(bufB, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
+        int b, page0, n_here, slot = 0, members = 1, chunk = 0, first_pos = 0;
+        if (SHARED) {
+            if (item >= p.counts[1]) return;
+            const int4 it = p.shared_items[item];
+            first_pos = it.x; members = it.y; chunk = it.z; b = it.w;
+            n_here = p.counts[3];                      // a whole bulk chunk, every key of it exists
+            page0 = chunk * n_here;
+        } else if (DIRECT) {
+            b = item;
+            page0 = 0;
         } else {
-            process_block<false, SETS>(bufA, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
+            if (item >= p.counts[0]) return;
+            const int4 it = p.items[item];
+            b = it.x; page0 = it.y; n_here = it.z; slot = it.w;
         }
-    }
-    if (rest_pages > 0 && (full_blocks & (kWaves - 1)) == wave) {
-        BlockRegs t;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            t.k[1][i] = u32x4{0u, 0u, 0u, 0u};
-            t.v[1][i] = u32x4{0u, 0u, 0u, 0u};
-        }
-        const int64_t o0 = page_off(2 * full_blocks);
-        load_page(t, 0, k_head + o0, v_head + o0, lane);
-        if (rest_pages > 1) {
-            const int64_t o1 = page_off(2 * full_blocks + 1);
-            load_page(t, 1, k_head + o1, v_head + o1, lane);
-        }
-        process_block<true, SETS>(t, qop, st, stage, p.scale_log2, lane, rest_valid);
-    }
+        const int lane = threadIdx.x & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int r16 = lane & 15, c = lane >> 4;
 
-    // ---- the four lanes of a head add up their shares; the waves meet in LDS, one set of columns
-    // at a time ----
-    float* sm_o = reinterpret_cast<float*>(smem);      // [wave][column of the set][128]
-#pragma unroll
-    for (int q = 0; q < SETS; ++q) {
-    const int cols_here = members * group - 16 * q < 16 ? members * group - 16 * q : 16;     // may be <= 0
-    float lt = st[q].l;
-    lt += __shfl_xor(lt, 16);
-    lt += __shfl_xor(lt, 32);
-    __syncthreads();                                   // every wave is done with its V tile (and with the set before)
-    if (r16 < cols_here) {
-        float* dst = sm_o + (wave * kMaxGroup + r16) * kHeadDim + 4 * c;
-#pragma unroll
-        for (int db = 0; db < 8; ++db) *reinterpret_cast<f32x4*>(dst + 16 * db) = st[q].o[db];
-        if (c == 0) {
-            sm_m[wave][r16] = st[q].m;
-            sm_l[wave][r16] = lt;
-        }
-    }
-    __syncthreads();
-
-    // thread t owns two neighbouring dims of one head
-    for (int idx = threadIdx.x; idx < cols_here * (kHeadDim / 2); idx += kThreads) {
-        const int h = idx / (kHeadDim / 2);           // column of this set
-        const int col = 16 * q + h;
-        const int d0 = 2 * (idx % (kHeadDim / 2));
-        float mt = sm_m[0][h];
-#pragma unroll
-        for (int w = 1; w < kWaves; ++w) mt = fmaxf(mt, sm_m[w][h]);
-        float sum = 0.0f, a0 = 0.0f, a1 = 0.0f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float wt = fast_exp2(sm_m[w][h] - mt);
-            sum = fmaf(sm_l[w][h], wt, sum);
-            const float2 v = *reinterpret_cast<const float2*>(sm_o + (w * kMaxGroup + h) * kHeadDim + d0);
-            a0 = fmaf(v.x, wt, a0);
-            a1 = fmaf(v.y, wt, a1);
-        }
+        const int L = p.context_lens[b];
+        int n_pages_b = L > 0 ? (L + kPageSize - 1) / kPageSize : 0;
         if (DIRECT) {
-            const float inv = sum > 0.0f ? p.out_scale / sum : 0.0f;
-            const int64_t rid = int64_t(b) * p.num_q_heads + g * group + h;
-            *reinterpret_cast<uint32_t*>(p.out + rid * kHeadDim + d0) =
-                uint32_t(to_bf16_rne(a0 * inv)) | (uint32_t(to_bf16_rne(a1 * inv)) << 16);
-            if (p.lse != nullptr && d0 == 0)
-                p.lse[rid] = sum > 0.0f ? (mt + __builtin_amdgcn_logf(sum)) * kLn2 : -INFINITY;
-        } else {
-            // (shared form: column col is head col % group of member col / group, whose partial of this chunk
-            // sits at its own first slot + chunk)
-            const int my_slot = SHARED ? p.chunk_start[p.order[first_pos + col / group]] + chunk : slot;
-            const int64_t rowid = int64_t(my_slot) * p.num_q_heads + g * group + (SHARED ? col % group : h);
-            *reinterpret_cast<float2*>(p.part_o + rowid * kHeadDim + d0) = make_float2(a0, a1);
-            if (d0 == 0) {
-                p.part_ml[rowid * 2 + 0] = mt;    // already in the log2 domain
-                p.part_ml[rowid * 2 + 1] = sum;
+            n_pages_b = n_pages_b > p.max_pages ? p.max_pages : n_pages_b;
+            n_here = n_pages_b;
+        }
+        const int tail_valid = L - (n_pages_b - 1) * kPageSize;           // 1..16 where the program's last page is reached
+        const bool has_tail = !SHARED && n_here > 0 && (page0 + n_here == n_pages_b) && tail_valid < kPageSize;
+        const int n_full_pages = has_tail ? n_here - 1 : n_here;
+        const int full_blocks = n_full_pages >> 1;                         // blocks of two complete pages
+        const int rest_pages = n_here - 2 * full_blocks;                   // 0, 1 or 2 pages in a last, masked block
+        const int rest_valid = rest_pages == 0 ? 0 : (rest_pages - 1) * kPageSize + (has_tail ? tail_valid : kPageSize);
+
+        // page ids of this item (up to 512: the start of an item costs its workgroup a microsecond
+        // in which it streams nothing, so items are as long as the batch allows), kept in LDS
+        {
+            const int32_t* table = p.block_table + int64_t(b) * p.block_table_stride + page0;
+            for (int i = threadIdx.x; i < n_here; i += kThreads) sm_ids[i] = table[i];
+            __syncthreads();
+        }
+        auto page_off = [&](int idx) -> int64_t {                          // idx is wave-uniform
+            return int64_t(__builtin_amdgcn_readfirstlane(sm_ids[idx])) * p.stride_page_bytes;
+        };
+
+        // B operands: column 16 q + r16 of set q is head (column % group) of member (column / group),
+        // zero beyond the last member; dims 16 (c + 4 i) + 8 hf ..
+        bf16x8 qop[SETS][2][2];
+        SoftmaxState st[SETS];
+#pragma unroll
+        for (int q = 0; q < SETS; ++q) {
+            const int col = 16 * q + r16;
+            const bool head_ok = col < members * group;
+            const int member = head_ok ? col / group : 0, head = head_ok ? col % group : 0;
+            const int q_program = SHARED ? p.order[first_pos + member] : b;
+            const uint16_t* qrow = p.q + (int64_t(q_program) * p.num_q_heads + g * group + head) * kHeadDim;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int hf = 0; hf < 2; ++hf) {
+                    u32x4 w = {0u, 0u, 0u, 0u};
+                    if (head_ok) w = *reinterpret_cast<const u32x4*>(qrow + 16 * (c + 4 * i) + 8 * hf);
+                    qop[q][i][hf] = __builtin_bit_cast(bf16x8, w);
+                }
+            st[q].m = kNegBig;
+            st[q].l = 0.0f;
+#pragma unroll
+            for (int db = 0; db < 8; ++db) st[q].o[db] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        }
+
+        const char* k_head = p.k_pool + int64_t(g) * p.stride_head_bytes;
+        const char* v_head = p.v_pool + int64_t(g) * p.stride_head_bytes;
+        char* stage = smem + wave * kStageBytes;
+
+        // this wave's full blocks: wave, wave + 4, ...  Two block buffers: each is refilled right
+        // after its block has been consumed and is consumed one block later; no load is issued for a
+        // page that is not used.
+        const int n_mine = full_blocks > wave ? (full_blocks - wave + kWaves - 1) / kWaves : 0;
+        if (n_mine > 0) {
+            auto load_block = [&](BlockRegs& r, int j) {
+                const int blk = wave + kWaves * j;
+                const int64_t o0 = page_off(2 * blk), o1 = page_off(2 * blk + 1);
+                load_page(r, 0, k_head + o0, v_head + o0, lane);
+                load_page(r, 1, k_head + o1, v_head + o1, lane);
+            };
+            BlockRegs bufA, bufB;
+            load_block(bufA, 0);
+            int j = 0;
+            for (; j + 2 < n_mine; j += 2) {
+                load_block(bufB, j + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                process_block<false, SETS>(bufA, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
+                load_block(bufA, j + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                process_block<false, SETS>(bufB, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
+            }
+            if (j + 1 < n_mine) {
+                load_block(bufB, j + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                process_block<false, SETS>(bufA, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
+                process_block<false, SETS>(bufB, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
+            } else {
+                process_block<false, SETS>(bufA, qop, st, stage, p.scale_log2, lane, 2 * kPageSize);
             }
         }
-    }
-    }
-    if (!SHARED) break;
-    __syncthreads();                               // the merge buffers are the next item's V tiles
+        if (rest_pages > 0 && (full_blocks & (kWaves - 1)) == wave) {
+            BlockRegs t;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                t.k[1][i] = u32x4{0u, 0u, 0u, 0u};
+                t.v[1][i] = u32x4{0u, 0u, 0u, 0u};
+            }
+            const int64_t o0 = page_off(2 * full_blocks);
+            load_page(t, 0, k_head + o0, v_head + o0, lane);
+            if (rest_pages > 1) {
+                const int64_t o1 = page_off(2 * full_blocks + 1);
+                load_page(t, 1, k_head + o1, v_head + o1, lane);
+            }
+            process_block<true, SETS>(t, qop, st, stage, p.scale_log2, lane, rest_valid);
+        }
+
+        // ---- the four lanes of a head add up their shares; the waves meet in LDS, one set of columns
+        // at a time ----
+        float* sm_o = reinterpret_cast<float*>(smem);      // [wave][column of the set][128]
+#pragma unroll
+        for (int q = 0; q < SETS; ++q) {
+            const int cols_here = members * group - 16 * q < 16 ? members * group - 16 * q : 16;     // may be <= 0
+            float lt = st[q].l;
+            lt += __shfl_xor(lt, 16);
+            lt += __shfl_xor(lt, 32);
+            __syncthreads();                                   // every wave is done with its V tile (and with the set before)
+            if (r16 < cols_here) {
+                float* dst = sm_o + (wave * kMaxGroup + r16) * kHeadDim + 4 * c;
+#pragma unroll
+                for (int db = 0; db < 8; ++db) *reinterpret_cast<f32x4*>(dst + 16 * db) = st[q].o[db];
+                if (c == 0) {
+                    sm_m[wave][r16] = st[q].m;
+                    sm_l[wave][r16] = lt;
+                }
+            }
+            __syncthreads();
+
+            // thread t owns two neighbouring dims of one head
+            for (int idx = threadIdx.x; idx < cols_here * (kHeadDim / 2); idx += kThreads) {
+                const int h = idx / (kHeadDim / 2);           // column of this set
+                const int col = 16 * q + h;
+                const int d0 = 2 * (idx % (kHeadDim / 2));
+                float mt = sm_m[0][h];
+#pragma unroll
+                for (int w = 1; w < kWaves; ++w) mt = fmaxf(mt, sm_m[w][h]);
+                float sum = 0.0f, a0 = 0.0f, a1 = 0.0f;
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) {
+                    const float wt = fast_exp2(sm_m[w][h] - mt);
+                    sum = fmaf(sm_l[w][h], wt, sum);
+                    const float2 v = *reinterpret_cast<const float2*>(sm_o + (w * kMaxGroup + h) * kHeadDim + d0);
+                    a0 = fmaf(v.x, wt, a0);
+                    a1 = fmaf(v.y, wt, a1);
+                }
+                if (DIRECT) {
+                    const float inv = sum > 0.0f ? p.out_scale / sum : 0.0f;
+                    const int64_t rid = int64_t(b) * p.num_q_heads + g * group + h;
+                    *reinterpret_cast<uint32_t*>(p.out + rid * kHeadDim + d0) =
+                        uint32_t(to_bf16_rne(a0 * inv)) | (uint32_t(to_bf16_rne(a1 * inv)) << 16);
+                    if (p.lse != nullptr && d0 == 0)
+                        p.lse[rid] = sum > 0.0f ? (mt + __builtin_amdgcn_logf(sum)) * kLn2 : -INFINITY;
+                } else {
+                    // (shared form: column col is head col % group of member col / group, whose partial of this chunk
+                    // sits at its own first slot + chunk)
+                    const int my_slot = SHARED ? p.chunk_start[p.order[first_pos + col / group]] + chunk : slot;
+                    const int64_t rowid = int64_t(my_slot) * p.num_q_heads + g * group + (SHARED ? col % group : h);
+                    *reinterpret_cast<float2*>(p.part_o + rowid * kHeadDim + d0) = make_float2(a0, a1);
+                    if (d0 == 0) {
+                        p.part_ml[rowid * 2 + 0] = mt;    // already in the log2 domain
+                        p.part_ml[rowid * 2 + 1] = sum;
+                    }
+                }
+            }
+        }
+        if (!SHARED) break;
+        __syncthreads();                               // the merge buffers are the next item's V tiles
     }
 }
 
