@@ -76,8 +76,8 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
 // Which kernel streams the private chunks of a bf16 cache.  The matrix-core tile kernel brings
 // K/V in through global-to-LDS loads with three tiles in flight per CU and spends no vector
 // instruction on them: with enough work to keep one eight-wave workgroup per CU on long items it
-// streams faster than the vector-ALU kernel (measured with one, two and four query heads per kv
-// head: from about 20,000 pages in the batch).
+// streams faster than the vector-ALU kernel (measured with four query heads per kv head on 4 to
+// 128 programs of 1k to 64k tokens: from about 5,000 to 10,000 pages in the batch).
 // Below that the vector-ALU kernel's finer items fill the chip better.  With eight query heads
 // per kv head the vector-ALU kernel does not exist (its per-head state would fill the register
 // file).  The host knows only the batch and the bound on the context length: it takes their
@@ -89,7 +89,7 @@ static bool decode_on_tiles(const Geometry& g, int32_t batch, int32_t max_contex
     // one, two or four heads per kv head.  The bound may be far above the real lengths (a serving
     // loop sizes it once): then every program is a single leftover item per kv head, and only a
     // batch with at least one such item per CU keeps the tile kernel's workgroups busy.
-    return g.decode_chunk_pages == 0 && int64_t(batch) * pages >= 40000 && int64_t(batch) * g.num_kv_heads >= 256;
+    return g.decode_chunk_pages == 0 && int64_t(batch) * pages >= 16000 && int64_t(batch) * g.num_kv_heads >= 256;
 }
 
 static int32_t choose_chunk_pages(const Geometry& g, int32_t batch, int32_t max_context_len) {
@@ -107,17 +107,11 @@ static int32_t choose_chunk_pages(const Geometry& g, int32_t batch, int32_t max_
             if (items >= 2048) return c;
         }
     }
-    if (!on_tiles) {
-        const int64_t items = int64_t(batch) * g.num_kv_heads * ((pages + 127) / 128);
-        if (items >= 2048 || pages <= 128) return 128;
-    }
-    // smaller batches: the longest chunk that still gives about 2048 items (measured on 8 to 128
-    // programs of 1k to 64k tokens: finer chunks than that lose more per item than they gain in balance)
-    for (int32_t c : {64, 32, 16}) {
-        const int64_t items = int64_t(batch) * g.num_kv_heads * ((pages + c - 1) / c);
-        if (items >= 2048) return c;
-    }
-    return 8;
+    // The vector-ALU kernel's longest item; the plan shortens the chunk on the device, from the real
+    // lengths, when a batch is too small to fill the chip with such items.
+    if (!on_tiles) return 128;
+    // (the tile route with a bound this small: the device-side choice does the rest)
+    return 128;
 }
 
 constexpr int kPrefillRowsPerBlock = 256;  // score rows (tokens x heads of a group) per workgroup
@@ -134,7 +128,10 @@ WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_l
         w.private_on_tiles = all_on_tiles ? 1 : 0;
         w.rem_pages = all_on_tiles ? w.chunk_pages : (w.chunk_pages >= 32 ? w.chunk_pages / 4 : 8);
         w.slots_per_program = static_cast<int32_t>(pages / w.chunk_pages + w.chunk_pages / w.rem_pages);
-        w.max_chunks = static_cast<int32_t>(int64_t(batch) * w.slots_per_program);
+        // (a chunk shortened on the device needs more slots than the host's chunk would: it is only
+        // shortened while the batch has fewer than about 1200 / Hkv chunks, plus four pieces each)
+        const int64_t slack = g.decode_chunk_pages == 0 ? 1200 / g.num_kv_heads + 1 : 0;
+        w.max_chunks = static_cast<int32_t>(int64_t(batch) * w.slots_per_program + slack);
         w.direct = (!all_on_tiles && pages <= w.chunk_pages) ? 1 : 0;
         w.max_tiles = 0;
         w.off_chunk_start = off; off = align256(off + sizeof(int32_t) * (size_t(batch) + 1));

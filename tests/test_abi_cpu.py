@@ -51,8 +51,9 @@ def test_workspace_size_and_descriptor_validation():
     n = ta.ta_workspace_bytes(good, 64, 1, 32768)
     assert n > 0 and n % 256 == 0
     # partials dominate: slots * Hq * 130 floats.  A batch this large streams on the tile kernel:
-    # a program of 32k tokens has 4 bulk chunks of 512 pages and one leftover item
-    assert 64 * (4 + 1) * 32 * 130 * 4 <= n < 64 * (4 + 2) * 32 * 130 * 4
+    # a program of 32k tokens has 4 bulk chunks of 512 pages and one leftover item (plus room for the
+    # about 150 more slots that a chunk shortened on the device can need)
+    assert 64 * (4 + 1) * 32 * 130 * 4 <= n < (64 * (4 + 2) + 160) * 32 * 130 * 4
     # a quarter of the programs stays on the vector-ALU kernel: 16 bulk chunks of 128 pages and up
     # to 4 pieces of the leftover
     assert ta.ta_workspace_bytes(good, 16, 1, 32768) >= 16 * (16 + 4) * 32 * 130 * 4
