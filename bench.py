@@ -393,6 +393,41 @@ def crossover(torch, ta, wl, dev, contexts=(1024, 2048, 4096, 8192, 16384, 32768
     return rows
 
 
+def decode_sweep(torch, ta, wl, dev, batches=(4, 8, 16, 32, 64, 128),
+                 ranges=((1024, 4096), (4096, 16384), (16384, 65536)), chunks=(32, 64, 128, 256, 512, 0)):
+    """ta_paged_decode (32 q / 8 kv heads) on batches of every size with the chunk length left to the
+    library (0) and forced to every value: microseconds per call, best of three runs of twenty calls.
+    Chunks of 256 and 512 pages run on the tile kernel, shorter ones on the vector-ALU kernel."""
+    rows = []
+    for batch in batches:
+        for lo, hi in ranges:
+            if batch * hi > 6_000_000:
+                continue
+            wb = wl.llama8b_decode(dev, seed=wl.SEED_BASE + 9, batch=batch, len_lo=lo, len_hi=hi)
+            kv = int(wb.context_lens.astype("int64").sum()) * wb.kv_bytes_per_token
+            bt = torch.from_numpy(wb.block_table).to(dev)
+            cl = torch.from_numpy(wb.context_lens).to(dev)
+            out = torch.empty_like(wb.q)
+            us = {}
+            for cp in chunks:
+                desc = ta.Desc(wb.num_q_heads, wb.num_kv_heads, decode_chunk_pages=cp)
+                ws = ta.alloc_workspace(desc, wb.batch, 1, wb.max_context_len, dev)
+                best = min(time_steps(lambda: ta.ta_paged_decode(desc, wb.q, wb.k_pool, wb.v_pool, bt, cl,
+                                                                 wb.max_context_len, out, None, ws), 20, 6, torch)
+                           for _ in range(3))
+                us[cp] = best * 1e3
+            forced = {cp: t for cp, t in us.items() if cp != 0}
+            best_cp = min(forced, key=forced.get)
+            rows.append({"programs": batch, "tokens": [lo, hi], "pages": int(((wb.context_lens + 15) // 16).sum()),
+                         "us_library_choice": round(us[0], 1), "frac_of_hbm_peak": round(kv / us[0] / 1e3 / HBM_PEAK_GBPS, 3),
+                         "best_forced_chunk_pages": best_cp, "us_best_forced": round(forced[best_cp], 1),
+                         "library_over_best": round(us[0] / forced[best_cp], 3),
+                         "us_by_forced_chunk_pages": {str(cp): round(t, 1) for cp, t in forced.items()}})
+            del wb, out
+            torch.cuda.empty_cache()
+    return rows
+
+
 def schedule_demo(torch, ta, wl, dev, decay_base: float, time_per_tick: float = 1.0, ticks: int = 48,
                   n_programs: int = 64, n_backends: int = 2, seed: int = 77, pool_tokens: int = 320 * 1024):
     """The policy simulator (ta_sim_*, host code) driving the kernels on a synthetic agent trace.
@@ -441,6 +476,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--crossover", action="store_true",
                     help="print the restore-versus-recompute table (one JSON line) instead of the benchmark")
+    ap.add_argument("--decode-sweep", action="store_true",
+                    help="time ta_paged_decode on 4 to 128 programs with the library's own choice of kernel and chunk "
+                         "and with every forced chunk length (one JSON line)")
     ap.add_argument("--schedule-demo", action="store_true",
                     help="drive the kernels with the scheduling tick on a synthetic agent trace (one JSON line)")
     ap.add_argument("--kernels-only", action="store_true",
@@ -473,6 +511,10 @@ def main():
         print(json.dumps({"metric": "schedule_demo_one_backend_one_layer", "data": "synthetic",
                           "runs": [schedule_demo(torch, ta, wl, dev, base, dt)
                                    for base, dt in ((2.0, 1.0), (2.0, 0.25), (1.0, 1.0))]}), flush=True)
+        return
+    if args.decode_sweep:
+        print(json.dumps({"metric": "paged_decode_route_and_chunk_sweep", "data": "synthetic",
+                          "rows": decode_sweep(torch, ta, wl, dev)}), flush=True)
         return
     if args.crossover:
         print(json.dumps({"metric": "restore_vs_recompute_one_layer", "data": "synthetic",
