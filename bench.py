@@ -38,7 +38,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # null until the counters are taken again.
 TRAFFIC_BYTES = {"9d52305fcf5496bb": 5081000000}
 # The same batch on the vector-ALU kernel (the library's choice for smaller batches).
-VECTOR_TRAFFIC_BYTES = {"1f00f73652711df5": 5081000000}
+VECTOR_TRAFFIC_BYTES = {"dca421588ed286ea": 5081000000}
 # The same for the FP8-cache decode kernel.
 FP8_TRAFFIC_BYTES = {"bdb0d2155170f1cb": 2554000000}
 # The same for the append-prefill tile kernel: bytes that left the L2 per launch (FETCH_SIZE scaled).

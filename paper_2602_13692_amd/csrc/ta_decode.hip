@@ -205,10 +205,11 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
         const int64_t total_pages = carry;
         // (item, kv head) pairs to aim for, and the shortest chunk worth having: measured on 4 to 128
         // programs of 1k to 64k tokens, the best chunk is the longest one that still gives about 500
-        // pairs on the vector-ALU kernel (512 on the tile kernel, whose items cost more), and below
-        // 32 pages an item's fixed cost outweighs the balance it buys
-        const int64_t target = private_on_tiles ? 512 : 500;
-        const int shortest = private_on_tiles ? kMinChunkPages : kMinAdaptedChunkPages;
+        // pairs on the vector-ALU kernel (whose leftovers come in quarters) and about 150 on the tile
+        // kernel (whose items cost more and whose leftovers are one item each); below 32 pages an
+        // item's fixed cost outweighs the balance it buys on either
+        const int64_t target = private_on_tiles ? 150 : 500;
+        const int shortest = kMinAdaptedChunkPages;
         int c = chunk_pages_max;
         while (adapt_chunk && c > shortest && total_pages * num_kv_heads / c < target) c >>= 1;
         set_chunk(c);

@@ -17,7 +17,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 // Finite stand-in for "no key seen yet": keeps (m_old - m_new) free of inf - inf.
 constexpr float kNegBig = -1.0e30f;
 constexpr int kMinChunkPages = 8;    // the shortest split-K chunk (two 64-key tiles)
-constexpr int kMinAdaptedChunkPages = 32;   // the shortest chunk the library picks by itself for the vector-ALU and FP8 kernels
+constexpr int kMinAdaptedChunkPages = 32;   // the shortest chunk the library picks by itself
 
 // Records a failed HIP call for ta_last_hip_error(); returns TA_ERR_HIP.
 int note_hip_error(hipError_t e);
