@@ -54,9 +54,9 @@ def test_workspace_size_and_descriptor_validation():
     # a program of 32k tokens has 4 bulk chunks of 512 pages and one leftover item (plus room for the
     # about 150 more slots that a chunk shortened on the device can need)
     assert 64 * (4 + 1) * 32 * 130 * 4 <= n < (64 * (4 + 2) + 160) * 32 * 130 * 4
-    # a quarter of the programs stays on the vector-ALU kernel: 16 bulk chunks of 128 pages and up
-    # to 4 pieces of the leftover
-    assert ta.ta_workspace_bytes(good, 16, 1, 32768) >= 16 * (16 + 4) * 32 * 130 * 4
+    # four programs stay on the vector-ALU kernel: 16 bulk chunks of 128 pages and up to 4 pieces of
+    # the leftover each
+    assert ta.ta_workspace_bytes(good, 4, 1, 32768) >= 4 * (16 + 4) * 32 * 130 * 4
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=64), 64, 1, 32768) >= 64 * 36 * 32 * 130 * 4
     assert ta.ta_workspace_bytes(good, 64, 2048, 34816) > 0
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, head_dim=64), 4, 1, 100) == 0
