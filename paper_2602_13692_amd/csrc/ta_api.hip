@@ -159,6 +159,41 @@ WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_l
         w.off_chunk_start = w.off_items = w.off_part_ml = w.off_part_o = off;
         w.off_tile_start = off; off = align256(off + sizeof(int32_t) * (size_t(batch) + 1));
         w.off_tiles = off;      off = align256(off + sizeof(int32_t) * 2 * size_t(w.max_tiles));
+        // A workgroup walks all the keys of its query tile, and a compute unit holds one workgroup:
+        // with few tiles (a tool result coming back for one or a few programs) most of the 256
+        // compute units would stand idle for the whole walk.  Then the keys are cut into chunks of
+        // even length and the chunks' partials merged afterwards.  The number of chunks is the one
+        // with the least estimated time, in key tiles: rounds of 256 workgroups, each as long as a
+        // chunk plus twelve tiles' worth of start, finish and merge (fitted to measured sweeps: what
+        // matters is that the last round is nearly full).  (chunk, kv head) streams are dealt to
+        // the eight XCDs in turn, so their number is kept a multiple of eight; cutting must win a
+        // tenth to be worth the partials.
+        w.prefill_split = 1;
+        w.prefill_chunk_tiles = 0;
+        {
+            const int64_t wgs = int64_t(w.max_tiles) * g.num_kv_heads;
+            const int64_t key_tiles = (int64_t(max_context_len) + 63) / 64;
+            if (wgs <= 512 && key_tiles >= 32) {
+                int64_t unit = 8;                                                  // 8 / gcd(8, kv heads)
+                for (int64_t h = g.num_kv_heads; unit > 1 && h % 2 == 0; h /= 2) unit /= 2;
+                auto estimate = [&](int64_t split) {
+                    return (wgs * split + 255) / 256 * ((key_tiles + split - 1) / split + 12);
+                };
+                const int64_t uncut = estimate(1);
+                int64_t best = uncut, best_split = 1;
+                for (int64_t split = unit == 1 ? 2 : unit; wgs * split <= 1024 && key_tiles / split >= 8; split += unit) {
+                    const int64_t e = estimate(split);
+                    if (e < best) { best = e; best_split = split; }
+                }
+                if (best_split > 1 && best * 10 <= uncut * 9) {
+                    w.prefill_split = static_cast<int32_t>(best_split);
+                    w.prefill_chunk_tiles = static_cast<int32_t>((key_tiles + best_split - 1) / best_split);
+                    const size_t rows = size_t(batch) * size_t(max_q_len) * size_t(g.num_q_heads);
+                    w.off_part_ml = off; off = align256(off + sizeof(float) * 2 * rows * size_t(best_split));
+                    w.off_part_o = off;  off = align256(off + sizeof(float) * kHeadDim * rows * size_t(best_split));
+                }
+            }
+        }
         if (g.kv_fp8) {
             // the tile kernel reads a bf16 copy of the batch's pages: room for every program's bound
             w.wide_width = static_cast<int32_t>(pages);

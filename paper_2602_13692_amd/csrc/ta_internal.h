@@ -67,6 +67,10 @@ struct WorkspaceLayout {
     int32_t direct;             // 1: every context fits one item: no plan, no partials, no merge
     int32_t private_on_tiles;   // 1: every chunk runs on the matrix-core tile kernel (groups of one program)
     int32_t max_tiles;          // upper bound on prefill query tiles (0 for decode)
+    // append-prefill of few query tiles: every tile's keys are cut into prefill_split chunks of
+    // prefill_chunk_tiles key tiles, one workgroup each, and their partials merged (1: no cutting)
+    int32_t prefill_split;
+    int32_t prefill_chunk_tiles;
     size_t off_chunk_start;     // int32 [batch + 1] first slot of each program
     size_t off_items;           // int4  [max_chunks] (program, first page, pages, slot)
     size_t off_part_ml;         // float [max_chunks][Hq][2]

@@ -82,6 +82,11 @@ struct PrefillParams {
     int32_t num_kv_heads;
     float scale_log2;
     float out_scale;             // append-prefill: multiplies the normalised output (the value scale of an FP8 cache, else 1)
+    // append-prefill with the keys of every query tile cut into `split` chunks of chunk_tiles key
+    // tiles (split = 1: not cut): a workgroup computes one chunk and writes the rows' partials to
+    // part_ml / part_o at [row * split + chunk], row = token * Hq + head
+    int32_t split;
+    int32_t chunk_tiles;
 };
 
 // plan: query tiles of tile_tokens tokens per program, listed flat.  Workgroups are dispatched
@@ -226,10 +231,28 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     };
     // (Claiming the next pair one item ahead hides the counter's round trip but costs more at the
     // end of the launch, where a claimed item waits for its owner: measured slower.)
+    // Append-prefill with the keys cut into `split` chunks: a stream = (chunk of keys, kv head), read
+    // by every query tile that reaches it.  Workgroups go to the eight XCDs in turn (workgroup i to
+    // XCD i % 8), each XCD with an L2 of its own: stream s belongs to XCD s % 8, which runs the
+    // stream's query tiles one after the other, so the stream comes out of memory once.  (Uncut,
+    // the tiles of a program are neighbours in the same way when there are eight kv heads.)
+    const int split = SHARED ? 1 : p.split;
+    const int n_streams = p.num_kv_heads * split;
+    const int blk_end = split > 1 ? ((n_streams + 7) >> 3) * 8 * n_items : n_items * p.num_kv_heads;
     int blk = SHARED ? take_pair() : int(blockIdx.x);
-    while (blk < n_items * p.num_kv_heads) {
-    const int tile_id = blk / p.num_kv_heads;
-    const int g = blk - tile_id * p.num_kv_heads;
+    while (blk < blk_end) {
+    int part = 0, tile_id, g;
+    if (split > 1) {
+        const int turn = (blk >> 3) / n_items;
+        const int stream = turn * 8 + (blk & 7);
+        if (stream >= n_streams) { blk += int(gridDim.x); continue; }
+        tile_id = (blk >> 3) - turn * n_items;
+        part = stream / p.num_kv_heads;
+        g = stream - part * p.num_kv_heads;
+    } else {
+        tile_id = blk / p.num_kv_heads;
+        g = blk - tile_id * p.num_kv_heads;
+    }
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -276,6 +299,15 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
         t_begin = 0;
         n_tiles = (keys_needed + kTileKeys - 1) / kTileKeys;
         n_unmasked = (prefix + t0 + 1) / kTileKeys;      // tiles every row sees completely
+        if (split > 1) {                                 // this workgroup's chunk of them
+            t_begin = part * p.chunk_tiles;
+            if (t_begin >= n_tiles) {                    // the tile's keys end before this chunk: nothing to write
+                blk += int(gridDim.x);
+                continue;
+            }
+            n_tiles = n_tiles < t_begin + p.chunk_tiles ? n_tiles : t_begin + p.chunk_tiles;
+            n_unmasked = n_unmasked < n_tiles ? n_unmasked : n_tiles;
+        }
     }
     const int n_pages_b = (p.context_lens[b] + kPageSize - 1) / kPageSize;
 
@@ -903,6 +935,22 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
                 p.part_ml[rowid * 2 + 0] = m[rb];
                 p.part_ml[rowid * 2 + 1] = total;
             }
+        } else if (split > 1) {
+            // the partial of this row over this chunk of keys (a row that sees none of them: an empty one)
+            const int64_t rowid = (out_row[rb] / kHeadDim) * split + part;
+            float* orow = p.part_o + rowid * kHeadDim;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const int dim = db * 32 + 8 * q4 + 4 * hl;
+                    *reinterpret_cast<float4*>(orow + dim) = make_float4(o[db][rb][4 * q4], o[db][rb][4 * q4 + 1],
+                                                                           o[db][rb][4 * q4 + 2], o[db][rb][4 * q4 + 3]);
+                }
+            if (hl == 0) {
+                p.part_ml[rowid * 2 + 0] = m[rb];
+                p.part_ml[rowid * 2 + 1] = total;
+            }
         } else {
             const float inv = total > 0.0f ? p.out_scale / total : 0.0f;
             uint16_t* orow = p.out + out_row[rb];
@@ -930,6 +978,50 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     __syncthreads();
     blk = SHARED ? take_pair() : blk + int(gridDim.x);
     }
+}
+
+// Append-prefill with the keys cut into chunks: one wave per output row adds up the row's partials
+// (those of the chunks that its query tile reaches: the others were never written).
+__global__ __launch_bounds__(256) void prefill_merge_kernel(PrefillParams p, int32_t total_q, int32_t tile_tokens) {
+    const int lane = threadIdx.x & 63;
+    const int64_t rid = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (rid >= int64_t(total_q) * p.num_q_heads) return;
+    const int token = static_cast<int>(rid / p.num_q_heads);
+    // the program of the token: the last b with cu_q_lens[b] <= token
+    int lo = 0, hi = p.batch;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (p.cu_q_lens[mid] <= token) lo = mid; else hi = mid;
+    }
+    const int b = lo;
+    const int q0 = p.cu_q_lens[b], nq = p.cu_q_lens[b + 1] - q0;
+    const int prefix = p.context_lens[b] - nq;
+    const int tile = (token - q0) / tile_tokens;
+    int t_end = (tile + 1) * tile_tokens;
+    t_end = t_end > nq ? nq : t_end;
+    const int n_tiles = (prefix + t_end + kTileKeys - 1) / kTileKeys;
+    const int n_chunks = (n_tiles + p.chunk_tiles - 1) / p.chunk_tiles;      // 1 .. split
+
+    const float* ml = p.part_ml + rid * p.split * 2;
+    const float* po = p.part_o + rid * p.split * kHeadDim;
+    float mt = kNegBig;
+    for (int c = lane; c < n_chunks; c += 64) mt = fmaxf(mt, ml[c * 2]);
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) mt = fmaxf(mt, __shfl_xor(mt, s));
+    float lt = 0.0f, o0 = 0.0f, o1 = 0.0f;
+#pragma unroll 4
+    for (int c = 0; c < n_chunks; ++c) {
+        const float wt = __builtin_amdgcn_exp2f(ml[c * 2] - mt);
+        lt = fmaf(ml[c * 2 + 1], wt, lt);
+        const float2 v = *reinterpret_cast<const float2*>(po + c * kHeadDim + 2 * lane);
+        o0 = fmaf(v.x, wt, o0);
+        o1 = fmaf(v.y, wt, o1);
+    }
+    const float inv = lt > 0.0f ? p.out_scale / lt : 0.0f;
+    reinterpret_cast<uint32_t*>(p.out + rid * kHeadDim)[lane] =
+        uint32_t(to_bf16_rne(o0 * inv)) | (uint32_t(to_bf16_rne(o1 * inv)) << 16);
+    if (p.lse != nullptr && lane == 0)
+        p.lse[rid] = lt > 0.0f ? (mt + __builtin_amdgcn_logf(lt)) * kLn2 : -INFINITY;
 }
 
 // 128 KiB of dynamic LDS is above the default 64 KiB limit: raised once per kernel instance and
@@ -1018,13 +1110,27 @@ int launch_prefill(const Geometry& g, const PrefillArgs& a, const WorkspaceLayou
     pp.num_q_heads = g.num_q_heads;
     pp.num_kv_heads = g.num_kv_heads;
 
-    const int64_t blocks = max_tiles * g.num_kv_heads;
+    pp.split = w.prefill_split;
+    pp.chunk_tiles = w.prefill_chunk_tiles;
+    if (pp.split > 1) {
+        pp.part_ml = reinterpret_cast<float*>(workspace + w.off_part_ml);
+        pp.part_o = reinterpret_cast<float*>(workspace + w.off_part_o);
+    }
+
+    const int64_t blocks = pp.split > 1 ? (int64_t(g.num_kv_heads) * pp.split + 7) / 8 * 8 * max_tiles
+                                        : max_tiles * g.num_kv_heads;
     if (blocks > 0x7fffffff) return TA_ERR_INVALID_ARG;
     const ProfileEvents ev = profile_events();
     if (ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
     const int rc = launch_tile_kernel<false>(g.group, static_cast<unsigned>(blocks), pp, stream);
     if (rc != TA_OK) return rc;
     if (ev.stop != nullptr) TA_HIP_TRY(hipEventRecord(ev.stop, stream));
+    if (pp.split > 1) {
+        const int64_t rows = int64_t(a.total_q) * g.num_q_heads;
+        hipLaunchKernelGGL(prefill_merge_kernel, dim3(static_cast<unsigned>((rows + 3) / 4)), dim3(256), 0, stream, pp,
+                           a.total_q, tile_tokens);
+        TA_HIP_TRY(hipGetLastError());
+    }
     return TA_OK;
 }
 

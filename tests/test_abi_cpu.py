@@ -59,6 +59,12 @@ def test_workspace_size_and_descriptor_validation():
     assert ta.ta_workspace_bytes(good, 4, 1, 32768) >= 4 * (16 + 4) * 32 * 130 * 4
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=64), 64, 1, 32768) >= 64 * 36 * 32 * 130 * 4
     assert ta.ta_workspace_bytes(good, 64, 2048, 34816) > 0
+    # append-prefill of few query tiles cuts every tile's keys into chunks and keeps a partial
+    # (130 floats) per row and chunk: one program's 64 new tokens on 32k cached tokens fill the
+    # chip with about 256 workgroups, 8 kv heads x 32 chunks; a batch that fills it anyway needs none
+    few = ta.ta_workspace_bytes(good, 1, 64, 32832)
+    assert 64 * 32 * 24 * 130 * 4 <= few <= 64 * 32 * 40 * 130 * 4
+    assert ta.ta_workspace_bytes(good, 64, 64, 32832) < 64 * 64 * 32 * 130 * 4
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, head_dim=64), 4, 1, 100) == 0
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, page_size=32), 4, 1, 100) == 0
     assert ta.ta_workspace_bytes(ta.Desc(32, 5), 4, 1, 100) == 0

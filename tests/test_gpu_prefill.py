@@ -100,3 +100,35 @@ def test_long_causal_sequences_without_a_prefix():
     rng = np.random.default_rng(wl.SEED_BASE + 951)
     gu.check_sampled_rows(wb, out, lse, rng, n_programs=3, rows_per_program=24, what="long causal",
                           lse_tol=gu.LSE_TOL)
+
+
+@pytest.mark.parametrize("batch,n_lo,n_hi,p_lo,p_hi,Hq,Hkv", [
+    (1, 1, 1, 20000, 20000, 32, 8),          # one token onto a long context
+    (1, 64, 64, 32768, 32768, 32, 8),        # a tool result coming back for one program
+    (1, 256, 256, 9000, 9000, 8, 8),
+    (2, 100, 300, 3000, 12000, 8, 2),
+    (3, 1, 40, 2000, 70000, 64, 8),          # one long context among short ones
+    (4, 200, 256, 16000, 16400, 8, 1),
+    (1, 1500, 1500, 900, 900, 32, 8),        # the new tokens themselves span several chunks of keys
+])
+def test_few_programs_whose_keys_are_cut_into_chunks(batch, n_lo, n_hi, p_lo, p_hi, Hq, Hkv):
+    """With few query tiles the keys of every tile are cut into chunks of whole kilotokens, one
+    workgroup each, and the chunks' partials merged: rows whose visible keys end inside a chunk, or
+    before it begins, and programs too short to reach the later chunks are all among these."""
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 960 + batch + Hq, batch=batch, new_lo=n_lo, new_hi=n_hi,
+                           prefix_lo=p_lo, prefix_hi=p_hi, num_q_heads=Hq, num_kv_heads=Hkv)
+    wl.poison_padding(wb)
+    out, lse = gu.gpu_prefill(wb)
+    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+    rng = np.random.default_rng(wl.SEED_BASE + 961)
+    gu.check_sampled_rows(wb, out, lse, rng, n_programs=batch, rows_per_program=12, dense_programs=1,
+                          dense_tokens=20, what=f"chunked keys B={batch} n<={n_hi} prefix<={p_hi}", lse_tol=gu.LSE_TOL)
+
+
+def test_chunked_keys_over_an_fp8_cache():
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 970, batch=2, new_lo=30, new_hi=90, prefix_lo=2500,
+                           prefix_hi=6000, num_q_heads=16, num_kv_heads=4)
+    fc = wl.to_fp8_cache(wb)
+    out, lse = gu.gpu_prefill_fp8(wb, fc)
+    ref, ref_lse = gu.oracle_prefill_fp8(wb, fc)
+    gu.assert_close(out, lse, ref, ref_lse, "chunked keys, fp8 cache", lse_tol=gu.LSE_TOL_FP8)
