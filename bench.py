@@ -428,6 +428,49 @@ def decode_sweep(torch, ta, wl, dev, batches=(4, 8, 16, 32, 64, 128),
     return rows
 
 
+def prefill_sweep(torch, ta, wl, dev,
+                  shapes=((1, 1, 32768), (1, 16, 131072), (1, 64, 32768), (1, 256, 32768), (1, 1024, 32768),
+                          (2, 128, 20000), (4, 64, 4096), (4, 256, 16384), (8, 64, 32768), (3, 200, 40000),
+                          (6, 100, 12000), (10, 32, 24000), (5, 256, 20000), (12, 256, 16384), (8, 512, 16384),
+                          (16, 256, 8192)),
+                  chunk_counts=(0, 1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64)):
+    """ta_append_prefill (32 q / 8 kv heads) of a few programs, each appending the same number of new
+    tokens onto a cached prefix: microseconds per call, best of two runs of thirty calls, with the
+    number of key chunks per query tile left to the library (0), switched off (1) and forced."""
+    rows = []
+    for batch, new, prefix in shapes:
+        wb = wl.append_prefill(dev, seed=wl.SEED_BASE + 77, batch=batch, new_lo=new, new_hi=new,
+                               prefix_lo=prefix, prefix_hi=prefix)
+        flops = 4.0 * wb.head_dim * wb.num_q_heads * wb.unmasked_pairs()
+        bt = torch.from_numpy(wb.block_table).to(dev)
+        cl = torch.from_numpy(wb.context_lens).to(dev)
+        cu = torch.from_numpy(wb.cu_q_lens).to(dev)
+        out = torch.empty_like(wb.q)
+        key_tiles = (wb.max_context_len + 63) // 64
+        us = {}
+        for n in chunk_counts:
+            if n > 1 and (key_tiles // n < 4 or n * batch * ((new + 63) // 64) * wb.num_kv_heads > 4096):
+                continue
+            desc = ta.Desc(wb.num_q_heads, wb.num_kv_heads, prefill_key_chunks=n)
+            ws = ta.alloc_workspace(desc, wb.batch, max(wb.max_q_len, 2), wb.max_context_len, dev)
+            us[n] = 1e3 * min(time_steps(lambda: ta.ta_append_prefill(desc, wb.q, cu, wb.k_pool, wb.v_pool, bt, cl,
+                                                                       wb.total_q, wb.max_q_len, wb.max_context_len,
+                                                                       out, None, ws), 30, 5, torch)
+                              for _ in range(2))
+            del ws
+        forced = {n: t for n, t in us.items() if n != 0}
+        best_n = min(forced, key=forced.get)
+        rows.append({"programs": batch, "new_tokens": new, "cached_tokens": prefix,
+                     "us_library_choice": round(us[0], 1), "tflops": round(flops / us[0] / 1e6, 1),
+                     "us_uncut": round(us[1], 1), "best_forced_chunks": best_n,
+                     "us_best_forced": round(forced[best_n], 1),
+                     "library_over_best": round(us[0] / forced[best_n], 3),
+                     "us_by_forced_chunks": {str(n): round(t, 1) for n, t in forced.items()}})
+        del wb, out
+        torch.cuda.empty_cache()
+    return rows
+
+
 def schedule_demo(torch, ta, wl, dev, decay_base: float, time_per_tick: float = 1.0, ticks: int = 48,
                   n_programs: int = 64, n_backends: int = 2, seed: int = 77, pool_tokens: int = 320 * 1024):
     """The policy simulator (ta_sim_*, host code) driving the kernels on a synthetic agent trace.
@@ -479,6 +522,8 @@ def main():
     ap.add_argument("--decode-sweep", action="store_true",
                     help="time ta_paged_decode on 4 to 128 programs with the library's own choice of kernel and chunk "
                          "and with every forced chunk length (one JSON line)")
+    ap.add_argument("--prefill-sweep", action="store_true",
+                    help="time ta_append_prefill of few programs with the library's number of key chunks and every forced one")
     ap.add_argument("--schedule-demo", action="store_true",
                     help="drive the kernels with the scheduling tick on a synthetic agent trace (one JSON line)")
     ap.add_argument("--kernels-only", action="store_true",
@@ -515,6 +560,10 @@ def main():
     if args.decode_sweep:
         print(json.dumps({"metric": "paged_decode_route_and_chunk_sweep", "data": "synthetic",
                           "rows": decode_sweep(torch, ta, wl, dev)}), flush=True)
+        return
+    if args.prefill_sweep:
+        print(json.dumps({"metric": "append_prefill_key_chunk_sweep", "data": "synthetic",
+                          "rows": prefill_sweep(torch, ta, wl, dev)}), flush=True)
         return
     if args.crossover:
         print(json.dumps({"metric": "restore_vs_recompute_one_layer", "data": "synthetic",

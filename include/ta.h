@@ -96,6 +96,14 @@ typedef struct ta_attn_desc {
     int32_t kv_format;         /* TA_KV_BF16 (0) or TA_KV_FP8_E4M3 (1), see below */
     float k_scale;             /* TA_KV_FP8_E4M3: a cached key element is code value * k_scale; > 0, finite */
     float v_scale;             /* TA_KV_FP8_E4M3: a cached value element is code value * v_scale; > 0, finite */
+    int32_t prefill_key_chunks; /* ta_append_prefill: into how many chunks of even length the keys of every
+                                   query tile are cut, one workgroup per (tile, kv head, chunk), the chunks'
+                                   partial results merged by a second kernel.  0 lets the library choose
+                                   (it cuts when the batch's query tiles alone would leave most compute
+                                   units idle: few programs appending onto long contexts), 1 never cuts,
+                                   2 .. 1024 asks for that many (fewer when a chunk would have less than
+                                   four key tiles of 64 tokens).  The same value must be given to
+                                   ta_workspace_bytes. */
 } ta_attn_desc;
 
 /*
@@ -220,6 +228,10 @@ TA_API int ta_paged_decode_static(const ta_attn_desc *desc, const void *q, const
  *   lse           DEVICE fp32 [total_q][Hq] or NULL
  *   workspace     DEVICE, at least ta_workspace_bytes(desc, batch, max_q_len, max_context_len)
  * Other arguments as for ta_paged_decode.
+ * When the batch has few query tiles (batch * ceil(max_q_len / (256 / (Hq / Hkv))) * Hkv below about
+ * 500) and long contexts, the keys of every tile are cut into chunks that run side by side and a
+ * second kernel merges their partial results (desc->prefill_key_chunks); the result is the same
+ * up to fp32 summation order.
  */
 TA_API int ta_append_prefill(const ta_attn_desc *desc, const void *q, const int32_t *cu_q_lens,
                       const void *k_pool, const void *v_pool, const int32_t *block_table,

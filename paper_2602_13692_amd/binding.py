@@ -60,6 +60,7 @@ class AttnDesc(ctypes.Structure):
         ("kv_format", ctypes.c_int32),
         ("k_scale", ctypes.c_float),
         ("v_scale", ctypes.c_float),
+        ("prefill_key_chunks", ctypes.c_int32),
     ]
 
 
@@ -78,12 +79,13 @@ class Desc:
     kv_format: int = 0          # KV_BF16 or KV_FP8_E4M3
     k_scale: float = 0.0
     v_scale: float = 0.0
+    prefill_key_chunks: int = 0
 
     def c(self) -> AttnDesc:
         return AttnDesc(self.num_q_heads, self.num_kv_heads, self.head_dim, self.page_size,
                         self.scale, self.pool_pages, self.pool_stride_page, self.pool_stride_head,
                         self.pool_stride_token, self.decode_chunk_pages, self.kv_format, self.k_scale,
-                        self.v_scale)
+                        self.v_scale, self.prefill_key_chunks)
 
 
 _LIB = None

@@ -53,11 +53,13 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
     // for one also asks for that kernel
     if (cp != 0 && cp != 8 && cp != 16 && cp != 32 && cp != 64 && cp != 128 && cp != 256 && cp != 512)
         return TA_ERR_INVALID_ARG;
+    if (d->prefill_key_chunks < 0 || d->prefill_key_chunks > 1024) return TA_ERR_INVALID_ARG;
     g->num_q_heads = d->num_q_heads;
     g->num_kv_heads = d->num_kv_heads;
     g->group = group;
     g->pool_pages = d->pool_pages;
     g->decode_chunk_pages = cp;
+    g->prefill_key_chunks = d->prefill_key_chunks;
     g->scale = d->scale > 0.0f ? d->scale : 1.0f / std::sqrt(static_cast<float>(kHeadDim));
     g->scale_log2 = g->scale * kLog2e;
     g->stride_page_bytes = sp * elem_bytes;
@@ -173,7 +175,14 @@ WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_l
         {
             const int64_t wgs = int64_t(w.max_tiles) * g.num_kv_heads;
             const int64_t key_tiles = (int64_t(max_context_len) + 63) / 64;
-            if (wgs <= 512 && key_tiles >= 32) {
+            if (g.prefill_key_chunks > 1) {                   // the caller's choice
+                int64_t split = g.prefill_key_chunks;
+                while (split > 1 && key_tiles / split < 4) --split;
+                if (split > 1) {
+                    w.prefill_split = static_cast<int32_t>(split);
+                    w.prefill_chunk_tiles = static_cast<int32_t>((key_tiles + split - 1) / split);
+                }
+            } else if (g.prefill_key_chunks == 0 && wgs <= 512 && key_tiles >= 32) {
                 int64_t unit = 8;                                                  // 8 / gcd(8, kv heads)
                 for (int64_t h = g.num_kv_heads; unit > 1 && h % 2 == 0; h /= 2) unit /= 2;
                 auto estimate = [&](int64_t split) {
@@ -188,10 +197,12 @@ WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_l
                 if (best_split > 1 && best * 10 <= uncut * 9) {
                     w.prefill_split = static_cast<int32_t>(best_split);
                     w.prefill_chunk_tiles = static_cast<int32_t>((key_tiles + best_split - 1) / best_split);
-                    const size_t rows = size_t(batch) * size_t(max_q_len) * size_t(g.num_q_heads);
-                    w.off_part_ml = off; off = align256(off + sizeof(float) * 2 * rows * size_t(best_split));
-                    w.off_part_o = off;  off = align256(off + sizeof(float) * kHeadDim * rows * size_t(best_split));
                 }
+            }
+            if (w.prefill_split > 1) {
+                const size_t rows = size_t(batch) * size_t(max_q_len) * size_t(g.num_q_heads);
+                w.off_part_ml = off; off = align256(off + sizeof(float) * 2 * rows * size_t(w.prefill_split));
+                w.off_part_o = off;  off = align256(off + sizeof(float) * kHeadDim * rows * size_t(w.prefill_split));
             }
         }
         if (g.kv_fp8) {

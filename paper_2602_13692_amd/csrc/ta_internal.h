@@ -42,6 +42,7 @@ struct Geometry {
     int32_t group;            // Hq / Hkv
     int32_t pool_pages;       // pages per pool as stated by the caller (0 = not stated; debug checks only)
     int32_t decode_chunk_pages;  // the caller's split-K chunk length, 0 = chosen by the library
+    int32_t prefill_key_chunks;  // the caller's number of key chunks per query tile of append-prefill, 0 = chosen by the library
     bool kv_fp8;              // pools hold E4M3 codes (one byte per element)
     float k_scale;            // fp8 only
     float v_scale;            // fp8 only

@@ -91,9 +91,9 @@ def oracle_decode_fp8(wb, fc):
                                    fc.k_scale, fc.v_scale, wb.block_table, wb.context_lens)
 
 
-def gpu_prefill(wb, stream=None):
+def gpu_prefill(wb, stream=None, key_chunks=0):
     dev = wb.q.device
-    desc = desc_of(wb)
+    desc = desc_of(wb, prefill_key_chunks=key_chunks)
     bt = torch.from_numpy(wb.block_table).to(dev)
     cl = torch.from_numpy(wb.context_lens).to(dev)
     cu = torch.from_numpy(wb.cu_q_lens).to(dev)

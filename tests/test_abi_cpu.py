@@ -103,6 +103,11 @@ def test_host_side_rejections_need_no_device():
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, decode_chunk_pages=256), 4, 1, 100) > 0
     assert ta.ta_workspace_bytes(ta.Desc(64, 8, decode_chunk_pages=512), 4, 1, 100) > 0
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, pool_pages=-1), 4, 1, 100) == 0
+    # the number of key chunks of append-prefill: 0 .. 1024; asking for chunks costs their partials
+    assert ta.ta_workspace_bytes(ta.Desc(32, 8, prefill_key_chunks=-1), 4, 64, 5000) == 0
+    assert ta.ta_workspace_bytes(ta.Desc(32, 8, prefill_key_chunks=1025), 4, 64, 5000) == 0
+    uncut = ta.ta_workspace_bytes(ta.Desc(32, 8, prefill_key_chunks=1), 64, 64, 5000)
+    assert ta.ta_workspace_bytes(ta.Desc(32, 8, prefill_key_chunks=4), 64, 64, 5000) >= uncut + 64 * 64 * 32 * 4 * 130 * 4
     # the FP8 cache format needs its two scales, positive and finite; other formats do not exist
     fp8 = dict(kv_format=ta.KV_FP8_E4M3)
     assert ta.ta_workspace_bytes(ta.Desc(32, 8, k_scale=0.02, v_scale=0.02, **fp8), 4, 1, 100) > 0

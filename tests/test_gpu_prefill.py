@@ -132,3 +132,14 @@ def test_chunked_keys_over_an_fp8_cache():
     out, lse = gu.gpu_prefill_fp8(wb, fc)
     ref, ref_lse = gu.oracle_prefill_fp8(wb, fc)
     gu.assert_close(out, lse, ref, ref_lse, "chunked keys, fp8 cache", lse_tol=gu.LSE_TOL_FP8)
+
+
+@pytest.mark.parametrize("key_chunks", [1, 2, 3, 7, 40, 1024])
+def test_any_number_of_key_chunks_gives_the_same_result(key_chunks):
+    """The caller's number of chunks (1 = never cut; more than the keys allow is reduced): every choice
+    agrees with the oracle, on a ragged batch whose short programs do not reach the later chunks."""
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 980, batch=5, new_lo=1, new_hi=200, prefix_lo=0,
+                           prefix_hi=3000, num_q_heads=16, num_kv_heads=2)
+    out, lse = gu.gpu_prefill(wb, key_chunks=key_chunks)
+    ref, ref_lse = gu.oracle_prefill(wb)
+    gu.assert_close(out, lse, ref, ref_lse, f"key chunks {key_chunks}", lse_tol=gu.LSE_TOL)
