@@ -256,7 +256,8 @@ TA_API size_t ta_restore_staging_full_bytes(int32_t n_pages, size_t page_bytes);
  * Pages not named in dst_slots are left untouched.
  *
  *   k_pool,v_pool DEVICE, pool_pages pages of page_bytes each, contiguous
- *   page_bytes    bytes of one page of K over all kv heads (Hkv*16*128*2), multiple of 16
+ *   page_bytes    bytes of one page of K over all kv heads (Hkv*16*128*2), multiple of 16,
+ *                 below 2 GiB (else TA_ERR_UNSUPPORTED)
  *   host_k,host_v HOST, pinned (hipHostMalloc), [n_pages][page_bytes] contiguous;
  *                 must stay valid until the stream reaches the end of this call
  *   dst_slots     HOST int32 [n_pages] (pageable is fine), distinct, each in [0, pool_pages).

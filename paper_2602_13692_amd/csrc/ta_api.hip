@@ -513,6 +513,7 @@ int ta_kv_page_restore(void* k_pool, void* v_pool, size_t page_bytes, const void
     if (!k_pool || !v_pool || !host_k || !host_v || !dst_slots) return TA_ERR_INVALID_ARG;
     if (staging == nullptr && staging_bytes != 0) return TA_ERR_INVALID_ARG;
     if (page_bytes == 0 || page_bytes % 16 != 0) return TA_ERR_INVALID_ARG;
+    if (page_bytes >= (size_t(1) << 31)) return TA_ERR_UNSUPPORTED;      // a lane's offset inside a page has 32 bits
     if (n_pages > pool_pages) return TA_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(v_pool) |
          reinterpret_cast<uintptr_t>(host_k) | reinterpret_cast<uintptr_t>(host_v)) & 15)
@@ -537,6 +538,7 @@ int ta_kv_page_evict(const void* k_pool, const void* v_pool, size_t page_bytes, 
     if (!k_pool || !v_pool || !host_k || !host_v || !src_slots) return TA_ERR_INVALID_ARG;
     if (staging == nullptr && staging_bytes != 0) return TA_ERR_INVALID_ARG;
     if (page_bytes == 0 || page_bytes % 16 != 0) return TA_ERR_INVALID_ARG;
+    if (page_bytes >= (size_t(1) << 31)) return TA_ERR_UNSUPPORTED;      // a lane's offset inside a page has 32 bits
     if ((reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(v_pool) |
          reinterpret_cast<uintptr_t>(host_k) | reinterpret_cast<uintptr_t>(host_v)) & 15)
         return TA_ERR_INVALID_ARG;

@@ -29,56 +29,54 @@ int32_t fill_batch(SlotBatch& batch, const int32_t* slots, int64_t first, int64_
     return static_cast<int32_t>(n);
 }
 
-// One workgroup per (page, K-or-V): copies page_bytes with 16-byte lanes.
-__global__ __launch_bounds__(kScatterThreads) void scatter_pages_kernel(
-    char* __restrict__ k_pool, char* __restrict__ v_pool, const char* __restrict__ src_k,
-    const char* __restrict__ src_v, const SlotBatch slots, int32_t n_pages, int64_t page_bytes) {
-    const int i = blockIdx.x >> 1;
-    if (i >= n_pages) return;
-    const bool is_v = (blockIdx.x & 1) != 0;
-    const int64_t slot = slots.slot[i];
-    const uint4* src = reinterpret_cast<const uint4*>((is_v ? src_v : src_k) + int64_t(i) * page_bytes);
-    uint4* dst = reinterpret_cast<uint4*>((is_v ? v_pool : k_pool) + slot * page_bytes);
-    const int64_t n16 = page_bytes / 16;
-    int64_t t = threadIdx.x;
-    // four independent 16-byte loads in flight per lane
-    for (; t + 3 * kScatterThreads < n16; t += 4 * kScatterThreads) {
-        const uint4 a = src[t];
-        const uint4 b = src[t + kScatterThreads];
-        const uint4 c = src[t + 2 * kScatterThreads];
-        const uint4 d = src[t + 3 * kScatterThreads];
-        dst[t] = a;
-        dst[t + kScatterThreads] = b;
-        dst[t + 2 * kScatterThreads] = c;
-        dst[t + 3 * kScatterThreads] = d;
+// Moves (page, K-or-V) units between pool slots and a contiguous array (pinned host memory or device
+// staging), 16 bytes per lane and access, two accesses in flight per lane; a workgroup takes units
+// with the stride of the grid.  GATHER: pool -> array, else array -> pool.
+//
+// The kernel is written to run beside attention: a program is restored or paused while the other
+// programs keep decoding (Sec. 4.3; the bench measures both at once).  The tile kernel's workgroup takes
+// 496 of the 512 vector registers of every SIMD of its compute unit; a wave of this kernel takes the
+// sixteen that are left, so a workgroup of four waves fits beside it, and neither waits for the
+// other.  (At 26 registers, and with one workgroup per unit in flight all over the chip, decode
+// ran 2.7 times slower while a zero-copy restore was on its way, and a staged restore took 1.46
+// times as long beside decode steps, its scatter launches waiting for compute units; now 1.3 and
+// 1.11.)
+template <bool GATHER>
+__global__ __launch_bounds__(kScatterThreads) __attribute__((amdgpu_num_vgpr(16))) void move_pages_kernel(
+    char* __restrict__ k_pool, char* __restrict__ v_pool, char* __restrict__ lin_k, char* __restrict__ lin_v,
+    const SlotBatch slots, int32_t n_pages, int64_t page_bytes) {
+    for (int unit = blockIdx.x; unit < 2 * n_pages; unit += gridDim.x) {
+        const int i = unit >> 1;
+        const bool is_v = (unit & 1) != 0;
+        char* pool = (is_v ? v_pool : k_pool) + int64_t(slots.slot[i]) * page_bytes;
+        char* lin = (is_v ? lin_v : lin_k) + int64_t(i) * page_bytes;
+        // both bases are the same for all lanes (scalar registers); a lane adds a 32-bit offset
+        const char* src = GATHER ? pool : lin;
+        char* dst = GATHER ? lin : pool;
+        const uint32_t bytes = static_cast<uint32_t>(page_bytes);      // below 2 GiB: checked by the caller
+        constexpr uint32_t kStep = kScatterThreads * 16;
+        uint32_t at = threadIdx.x * 16;
+        for (; at + kStep < bytes; at += 2 * kStep) {
+            const uint4 a = *reinterpret_cast<const uint4*>(src + at);
+            const uint4 b = *reinterpret_cast<const uint4*>(src + (at + kStep));
+            *reinterpret_cast<uint4*>(dst + at) = a;
+            *reinterpret_cast<uint4*>(dst + (at + kStep)) = b;
+        }
+        if (at < bytes) *reinterpret_cast<uint4*>(dst + at) = *reinterpret_cast<const uint4*>(src + at);
     }
-    for (; t < n16; t += kScatterThreads) dst[t] = src[t];
 }
 
-// The inverse: one workgroup per (page, K-or-V) copies a pool page to its place in the
-// contiguous destination (pinned host memory or device staging).
-__global__ __launch_bounds__(kScatterThreads) void gather_pages_kernel(
-    const char* __restrict__ k_pool, const char* __restrict__ v_pool, char* __restrict__ dst_k,
-    char* __restrict__ dst_v, const SlotBatch slots, int32_t n_pages, int64_t page_bytes) {
-    const int i = blockIdx.x >> 1;
-    if (i >= n_pages) return;
-    const bool is_v = (blockIdx.x & 1) != 0;
-    const int64_t slot = slots.slot[i];
-    const uint4* src = reinterpret_cast<const uint4*>((is_v ? v_pool : k_pool) + slot * page_bytes);
-    uint4* dst = reinterpret_cast<uint4*>((is_v ? dst_v : dst_k) + int64_t(i) * page_bytes);
-    const int64_t n16 = page_bytes / 16;
-    int64_t t = threadIdx.x;
-    for (; t + 3 * kScatterThreads < n16; t += 4 * kScatterThreads) {
-        const uint4 a = src[t];
-        const uint4 b = src[t + kScatterThreads];
-        const uint4 c = src[t + 2 * kScatterThreads];
-        const uint4 d = src[t + 3 * kScatterThreads];
-        dst[t] = a;
-        dst[t + kScatterThreads] = b;
-        dst[t + 2 * kScatterThreads] = c;
-        dst[t + 3 * kScatterThreads] = d;
-    }
-    for (; t < n16; t += kScatterThreads) dst[t] = src[t];
+// Workgroups of one launch.  Reading or writing pinned host memory directly, 32 keep the host link
+// full (55 GB/s x a few microseconds of latency is well under a megabyte in flight; measured: the
+// same 65 ms for 5 GB with 16 .. 256 workgroups, 79 ms with 8).  More of them do harm when
+// attention runs beside the restore: every access to host memory that is on its way seems to hold
+// a place in queues that HBM traffic also passes through -- a decode step beside the restore ran 1.14 x
+// its time alone with 8 workgroups, 1.31 x with 32, 1.61 x with 64, 3.6 x with 256 -- while the restore
+// itself needs 32 to stay within a tenth of its time alone (16: 1.7 x).  Between pool and device
+// staging the kernel is bound by HBM and takes as many workgroups as it has units.
+unsigned move_grid(int32_t n, bool over_the_link) {
+    const unsigned units = 2u * unsigned(n);
+    return over_the_link && units > 32u ? 32u : units;
 }
 
 // KV append: one workgroup per new token copies its K row and its V row of every kv head
@@ -184,9 +182,9 @@ int launch_evict(const void* k_pool, const void* v_pool, size_t page_bytes, void
         // zero-copy: the kernel writes the pinned host pages itself
         for (int64_t first = 0; first < n_pages;) {
             const int32_t n = fill_batch(batch, src_slots, first, n_pages);
-            hipLaunchKernelGGL(gather_pages_kernel, dim3(2u * unsigned(n)), dim3(kScatterThreads), 0, stream, kp, vp,
-                               hk + size_t(first) * page_bytes, hv + size_t(first) * page_bytes, batch, n,
-                               int64_t(page_bytes));
+            hipLaunchKernelGGL(move_pages_kernel<true>, dim3(move_grid(n, true)), dim3(kScatterThreads), 0, stream,
+                               const_cast<char*>(kp), const_cast<char*>(vp), hk + size_t(first) * page_bytes,
+                               hv + size_t(first) * page_bytes, batch, n, int64_t(page_bytes));
             TA_HIP_TRY(hipGetLastError());
             first += n;
         }
@@ -198,9 +196,9 @@ int launch_evict(const void* k_pool, const void* v_pool, size_t page_bytes, void
         const int64_t end = (n_pages - first) < per_round ? n_pages : first + per_round;
         for (int64_t at = first; at < end;) {
             const int32_t n = fill_batch(batch, src_slots, at, end);
-            hipLaunchKernelGGL(gather_pages_kernel, dim3(2u * unsigned(n)), dim3(kScatterThreads), 0, stream, kp, vp,
-                               stage_k + size_t(at - first) * page_bytes, stage_v + size_t(at - first) * page_bytes,
-                               batch, n, int64_t(page_bytes));
+            hipLaunchKernelGGL(move_pages_kernel<true>, dim3(move_grid(n, false)), dim3(kScatterThreads), 0, stream,
+                               const_cast<char*>(kp), const_cast<char*>(vp), stage_k + size_t(at - first) * page_bytes,
+                               stage_v + size_t(at - first) * page_bytes, batch, n, int64_t(page_bytes));
             TA_HIP_TRY(hipGetLastError());
             at += n;
         }
@@ -246,9 +244,9 @@ int launch_restore(void* k_pool, void* v_pool, size_t page_bytes, const void* ho
         // zero-copy: pinned host memory is mapped into the device address space
         for (int64_t first = 0; first < n_pages;) {
             const int32_t n = fill_batch(batch, dst_slots, first, n_pages);
-            hipLaunchKernelGGL(scatter_pages_kernel, dim3(2u * unsigned(n)), dim3(kScatterThreads), 0, stream, kp, vp,
-                               hk + size_t(first) * page_bytes, hv + size_t(first) * page_bytes, batch, n,
-                               int64_t(page_bytes));
+            hipLaunchKernelGGL(move_pages_kernel<false>, dim3(move_grid(n, true)), dim3(kScatterThreads), 0, stream, kp, vp,
+                               const_cast<char*>(hk) + size_t(first) * page_bytes,
+                               const_cast<char*>(hv) + size_t(first) * page_bytes, batch, n, int64_t(page_bytes));
             TA_HIP_TRY(hipGetLastError());
             first += n;
         }
@@ -263,7 +261,7 @@ int launch_restore(void* k_pool, void* v_pool, size_t page_bytes, const void* ho
         TA_HIP_TRY(hipMemcpyAsync(stage_v, hv + size_t(first) * page_bytes, bytes, hipMemcpyHostToDevice, stream));
         for (int64_t at = first; at < end;) {
             const int32_t n = fill_batch(batch, dst_slots, at, end);
-            hipLaunchKernelGGL(scatter_pages_kernel, dim3(2u * unsigned(n)), dim3(kScatterThreads), 0, stream, kp, vp,
+            hipLaunchKernelGGL(move_pages_kernel<false>, dim3(move_grid(n, false)), dim3(kScatterThreads), 0, stream, kp, vp,
                                stage_k + size_t(at - first) * page_bytes, stage_v + size_t(at - first) * page_bytes,
                                batch, n, int64_t(page_bytes));
             TA_HIP_TRY(hipGetLastError());

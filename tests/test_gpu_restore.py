@@ -89,3 +89,45 @@ def test_restore_rejects_bad_arguments_on_the_host():
     assert torch.equal(before.view(torch.int16), wb.k_pool.view(torch.int16))
     assert ta.ta_kv_page_restore(wb.k_pool, wb.v_pool, page_bytes, rs.host_k, rs.host_v,
                                  torch.empty(0, dtype=torch.int32), wb.pool_pages, staging, check=False) == ta.TA_OK
+
+
+@pytest.mark.parametrize("mode", ["zero_copy", "staged"])
+def test_restore_on_a_second_stream_while_resident_programs_decode(mode):
+    """A paused program comes back while the others keep decoding (Sec. 4.3): the restore runs on a
+    stream of its own, decode steps of the resident programs on another.  The restored pages are
+    bit-exact, nothing else in the pools moved, and every decode step gives what it gives alone."""
+    wb = _restore_case(batch=40, median=2500, cap=12000, seed=wl.SEED_BASE + 1002)
+    kp, vp, page_bytes = _expected_pools(wb)
+    rs = wb.restore
+    n = int(rs.dst_slots.shape[0])
+    resident = np.setdiff1d(np.arange(wb.batch), rs.programs)
+    idx = torch.from_numpy(resident).to(DEV)
+    q = wb.q[idx].contiguous()
+    bt = torch.from_numpy(np.ascontiguousarray(wb.block_table[resident])).to(DEV)
+    cl = torch.from_numpy(np.ascontiguousarray(wb.context_lens[resident])).to(DEV)
+    max_len = int(wb.context_lens[resident].max())
+    desc = gu.desc_of(wb)
+    ws = ta.alloc_workspace(desc, len(resident), 1, max_len, DEV)
+
+    def decode():
+        out = torch.full_like(q, float("nan"))
+        lse = torch.full((len(resident), wb.num_q_heads), float("nan"), dtype=torch.float32, device=DEV)
+        ta.ta_paged_decode(desc, q, wb.k_pool, wb.v_pool, bt, cl, max_len, out, lse, ws)
+        return out, lse
+
+    alone_out, alone_lse = decode()
+    torch.cuda.synchronize()
+    extra = 0 if mode == "zero_copy" else 96 * 2 * page_bytes
+    staging = torch.empty(ta.ta_restore_staging_min_bytes(n) + extra, dtype=torch.uint8, device=DEV)
+    slots = torch.from_numpy(rs.dst_slots.copy())
+    side = torch.cuda.Stream(device=DEV)
+    done = torch.cuda.Event()
+    ta.ta_kv_page_restore(wb.k_pool, wb.v_pool, page_bytes, rs.host_k, rs.host_v, slots, wb.pool_pages, staging, side)
+    done.record(side)
+    results = [decode() for _ in range(6)]
+    torch.cuda.synchronize()
+    for out, lse in results:
+        assert torch.equal(out.view(torch.int16), alone_out.view(torch.int16)) and torch.equal(lse, alone_lse)
+    got_k = wl.as_u16(wb.k_pool).view(np.uint8).reshape(wb.pool_pages, page_bytes)
+    got_v = wl.as_u16(wb.v_pool).view(np.uint8).reshape(wb.pool_pages, page_bytes)
+    assert np.array_equal(got_k, kp) and np.array_equal(got_v, vp)
