@@ -87,6 +87,9 @@ struct PrefillParams {
     // part_ml / part_o at [row * split + chunk], row = token * Hq + head
     int32_t split;
     int32_t chunk_tiles;
+    // tiles == nullptr (batches of up to 64 programs whose keys are cut into chunks): every wave works
+    // the tile list out for itself from cu_q_lens, at most tiles_per_program_max tiles a program
+    int32_t tiles_per_program_max;
 };
 
 // plan: query tiles of tile_tokens tokens per program, listed flat.  Workgroups are dispatched
@@ -219,7 +222,35 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     // counter as they finish one: items differ in length by a factor of four, and a fixed
     // stride left the tail of the launch unbalanced.  Every item writes its own partial slots,
     // so the result does not depend on which workgroup ran it.
-    const int n_items = SHARED ? p.counts[1] : p.tile_start[p.batch];
+    // Append-prefill of a few programs is a short launch, and a plan kernel in front of it plus two
+    // more dependent loads here (tile -> program -> its lengths) are a fifth of its time: there
+    // lane l of every wave takes program l, and a scan over the wave gives the tile list.
+    const bool plan_here = !SHARED && p.tiles == nullptr;
+    __shared__ int plan_tiles[64], plan_tiles_through[64];   // tiles of program l; of programs 0 .. l
+    int tiles_through_mine = 0;
+    if (plan_here) {
+        const int l = threadIdx.x & 63;
+        int tiles_mine = 0;
+        if (l < p.batch) {
+            const int nq = p.cu_q_lens[l + 1] - p.cu_q_lens[l];
+            tiles_mine = nq > 0 ? (nq + kTileTokens - 1) / kTileTokens : 0;
+            tiles_mine = tiles_mine < p.tiles_per_program_max ? tiles_mine : p.tiles_per_program_max;
+        }
+        tiles_through_mine = tiles_mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int below = __shfl_up(tiles_through_mine, d);
+            if (l >= d) tiles_through_mine += below;
+        }
+        if (threadIdx.x < 64) {          // kept in LDS: registers are what this kernel is short of
+            plan_tiles[l] = tiles_mine;
+            plan_tiles_through[l] = tiles_through_mine;
+        }
+        __syncthreads();
+    }
+    const int n_items = SHARED      ? p.counts[1]
+                        : plan_here ? __builtin_amdgcn_readlane(tiles_through_mine, 63)
+                                    : p.tile_start[p.batch];
     const int tiles_per_chunk = SHARED ? p.counts[3] / 4 : 0;   // read once: the line it shares with the work counter is busy
     __shared__ int next_pair;
     auto take_pair = [&]() {
@@ -286,7 +317,14 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
             n_unmasked = L / kTileKeys < n_tiles ? L / kTileKeys : n_tiles;
         }
     } else {
-        const int2 tl = p.tiles[tile_id];
+        int2 tl;
+        if (plan_here) {
+            // the program of the tile: the first whose tiles reach beyond it (programs without tiles are passed over)
+            tl.x = __builtin_popcountll(__builtin_amdgcn_ballot_w64(plan_tiles_through[threadIdx.x & 63] <= tile_id));
+            tl.y = tile_id - (plan_tiles_through[tl.x] - plan_tiles[tl.x]);
+        } else {
+            tl = p.tiles[tile_id];
+        }
         b = tl.x;
         q0 = p.cu_q_lens[b];
         nq = p.cu_q_lens[b + 1] - q0;
@@ -1066,12 +1104,16 @@ int launch_prefill(const Geometry& g, const PrefillArgs& a, const WorkspaceLayou
     const int64_t max_tiles = int64_t(per_prog) * a.batch;
     if (max_tiles > w.max_tiles) return TA_ERR_INVALID_ARG;
 
-    // one workgroup, as small as the batch allows (its sort and scan are all barriers)
-    unsigned plan_threads = 64;
-    while (plan_threads < 1024 && plan_threads < static_cast<unsigned>(a.batch)) plan_threads <<= 1;
-    hipLaunchKernelGGL(plan_tiles_kernel, dim3(1), dim3(plan_threads), 0, stream, a.cu_q_lens, a.context_lens, a.batch,
-                       tile_tokens, per_prog, tile_start, tiles);
-    TA_HIP_TRY(hipGetLastError());
+    // (with the keys cut into chunks and up to 64 programs the tile kernel works the list out itself)
+    const bool plan_in_tile_kernel = w.prefill_split > 1 && a.batch <= 64;
+    if (!plan_in_tile_kernel) {
+        // one workgroup, as small as the batch allows (its sort and scan are all barriers)
+        unsigned plan_threads = 64;
+        while (plan_threads < 1024 && plan_threads < static_cast<unsigned>(a.batch)) plan_threads <<= 1;
+        hipLaunchKernelGGL(plan_tiles_kernel, dim3(1), dim3(plan_threads), 0, stream, a.cu_q_lens, a.context_lens,
+                           a.batch, tile_tokens, per_prog, tile_start, tiles);
+        TA_HIP_TRY(hipGetLastError());
+    }
 
     PrefillParams pp{};
     pp.q = a.q;
@@ -1103,7 +1145,8 @@ int launch_prefill(const Geometry& g, const PrefillArgs& a, const WorkspaceLayou
     pp.context_lens = a.context_lens;
     pp.cu_q_lens = a.cu_q_lens;
     pp.tile_start = tile_start;
-    pp.tiles = tiles;
+    pp.tiles = plan_in_tile_kernel ? nullptr : tiles;
+    pp.tiles_per_program_max = per_prog;
     pp.out = a.out;
     pp.lse = a.lse;
     pp.batch = a.batch;
