@@ -251,6 +251,7 @@ __global__ __launch_bounds__(kThreads, 1) void attention_tile_kernel(PrefillPara
     const int n_items = SHARED      ? p.counts[1]
                         : plan_here ? __builtin_amdgcn_readlane(tiles_through_mine, 63)
                                     : p.tile_start[p.batch];
+    if (SHARED && n_items == 0) return;   // nothing shared in this batch (the usual case off the tile route): no trip to the counter
     const int tiles_per_chunk = SHARED ? p.counts[3] / 4 : 0;   // read once: the line it shares with the work counter is busy
     __shared__ int next_pair;
     auto take_pair = [&]() {
