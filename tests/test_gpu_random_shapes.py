@@ -94,6 +94,32 @@ def test_prefill_random_shapes(seed):
                     lse_tol=gu.LSE_TOL)
 
 
+@pytest.mark.parametrize("seed", range(20))
+def test_prefill_random_shapes_with_cut_keys(seed):
+    """Few programs with the keys of every query tile cut into chunks (the library's count or a forced
+    one): ragged lengths, so that tiles end inside, at and before chunk boundaries, every group size."""
+    rng = np.random.default_rng(wl.SEED_BASE + 6000 + seed)
+    Hq, Hkv = [(32, 8), (8, 8), (64, 8), (16, 8), (8, 2), (4, 1), (2, 2), (16, 2), (8, 1), (12, 3)][seed % 10]
+    batch = int(rng.integers(1, 7))
+    new_hi = int(rng.choice([1, 20, 150, 400]))
+    prefix_hi = int(rng.choice([300, 2500, 6000, 12000]))
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 6100 + seed, batch=batch, new_lo=1, new_hi=new_hi,
+                           prefix_lo=0, prefix_hi=prefix_hi, num_q_heads=Hq, num_kv_heads=Hkv)
+    if seed % 2:
+        wl.poison_padding(wb)
+    chunks = int(rng.choice([0, 0, 2, 3, 5, 8, 13, 32]))
+    out, lse = gu.gpu_prefill(wb, key_chunks=chunks)
+    if batch * new_hi * prefix_hi * Hq <= 40_000_000:
+        ref, ref_lse = gu.oracle_prefill(wb)
+        gu.assert_close(out, lse, ref, ref_lse, f"cut keys seed={seed} Hq={Hq} Hkv={Hkv} B={batch} chunks={chunks}",
+                        lse_tol=gu.LSE_TOL)
+    else:
+        assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+        gu.check_sampled_rows(wb, out, lse, rng, n_programs=batch, rows_per_program=16, dense_programs=1,
+                              dense_tokens=8, what=f"cut keys seed={seed} Hq={Hq} Hkv={Hkv} B={batch} chunks={chunks}",
+                              lse_tol=gu.LSE_TOL)
+
+
 @pytest.mark.parametrize("seed", range(16))
 def test_fp8_cache_random_shapes(seed):
     """The same over an FP8 cache: ragged batches and forked groups (whose shared chunks one workgroup
