@@ -36,13 +36,13 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16
 # (FETCH_SIZE + WRITE_SIZE, each scaled by the same counter on a 1 GiB device copy), keyed by the
 # hash of the kernel source's code (comments aside) they were taken with.  A changed kernel gives
 # null until the counters are taken again.
-TRAFFIC_BYTES = {"9d52305fcf5496bb": 5081000000}
+TRAFFIC_BYTES = {"bf4ede3c947c6fcb": 5081000000}
 # The same batch on the vector-ALU kernel (the library's choice for smaller batches).
 VECTOR_TRAFFIC_BYTES = {"dca421588ed286ea": 5081000000}
 # The same for the FP8-cache decode kernel.
 FP8_TRAFFIC_BYTES = {"bdb0d2155170f1cb": 2554000000}
 # The same for the append-prefill tile kernel: bytes that left the L2 per launch (FETCH_SIZE scaled).
-PREFILL_TRAFFIC_BYTES = {"9d52305fcf5496bb": 16850000000}
+PREFILL_TRAFFIC_BYTES = {"bf4ede3c947c6fcb": 16480000000}
 
 
 def source_hash(name: str) -> str:
