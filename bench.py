@@ -471,11 +471,11 @@ def prefill_sweep(torch, ta, wl, dev,
     return rows
 
 
-def restore_while_decoding(wb, torch, ta, page_bytes, slots):
-    """The restore of config 5 on one stream while the programs that stayed resident keep decoding on
-    another (both at the default priority): what each loses to the other.  Decode steps are issued one
-    at a time until the restore's last event has passed; only steps that began and ended inside the
-    restore count."""
+def restore_while_decoding(wb, torch, ta, page_bytes, slots, back_k, back_v):
+    """The restore of config 5 (and the eviction of the same pages: the Pause side) on one stream while
+    the programs that stayed resident keep decoding on another (both at the default priority): what each
+    loses to the other.  Decode steps are issued one at a time until the transfer's last event has
+    passed; only steps that began and ended inside the transfer count."""
     import numpy as np
 
     dev = wb.q.device
@@ -499,38 +499,44 @@ def restore_while_decoding(wb, torch, ta, page_bytes, slots):
     alone_ms = time_steps(decode, 10, 3, torch)
     res = {"resident_programs": int(len(resident)), "decode_ms_alone": round(alone_ms, 4),
            "decode_kv_gbps_alone": round(kv / alone_ms / 1e6, 1)}
-    for mode, nbytes in (("zero_copy", ta.ta_restore_staging_min_bytes(n)),
-                         ("staged", ta.ta_restore_staging_min_bytes(n) + 2 * (256 << 20))):
-        staging = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    for what in ("restore", "evict"):
+        for mode, nbytes in (("zero_copy", ta.ta_restore_staging_min_bytes(n)),
+                             ("staged", ta.ta_restore_staging_min_bytes(n) + 2 * (256 << 20))):
+            staging = torch.empty(nbytes, dtype=torch.uint8, device=dev)
 
-        def restore(stream=None):
-            ta.ta_kv_page_restore(wb.k_pool, wb.v_pool, page_bytes, rs.host_k, rs.host_v, slots, wb.pool_pages,
-                                  staging, stream)
+            def transfer(stream=None):
+                if what == "restore":
+                    ta.ta_kv_page_restore(wb.k_pool, wb.v_pool, page_bytes, rs.host_k, rs.host_v, slots,
+                                          wb.pool_pages, staging, stream)
+                else:
+                    ta.ta_kv_page_evict(wb.k_pool, wb.v_pool, page_bytes, back_k, back_v, slots, wb.pool_pages,
+                                        staging, stream)
 
-        restore_alone_ms = time_steps(restore, 2, 1, torch)
-        torch.cuda.synchronize()
-        r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        steps = []
-        with torch.cuda.stream(side):
-            r0.record(side)
-            restore(side)
-            r1.record(side)
-        while not r1.query() and len(steps) < 2000:
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            decode()
-            e1.record()
-            e1.synchronize()
-            steps.append((e0, e1))
-        torch.cuda.synchronize()
-        inside = [a.elapsed_time(b) for a, b in steps if r0.elapsed_time(a) >= 0.0 and b.elapsed_time(r1) >= 0.0]
-        both_ms = r0.elapsed_time(r1)
-        res[mode] = {"restore_ms_alone": round(restore_alone_ms, 2), "restore_ms_while_decoding": round(both_ms, 2),
-                     "decode_steps_inside": len(inside),
-                     "decode_ms_while_restoring": round(float(np.mean(inside)), 4) if inside else None,
-                     "decode_slowdown": round(float(np.mean(inside)) / alone_ms, 3) if inside else None,
-                     "restore_slowdown": round(both_ms / restore_alone_ms, 3)}
-        del staging
+            transfer_alone_ms = time_steps(transfer, 2, 1, torch)
+            torch.cuda.synchronize()
+            r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            steps = []
+            with torch.cuda.stream(side):
+                r0.record(side)
+                transfer(side)
+                r1.record(side)
+            while not r1.query() and len(steps) < 2000:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                decode()
+                e1.record()
+                e1.synchronize()
+                steps.append((e0, e1))
+            torch.cuda.synchronize()
+            inside = [a.elapsed_time(b) for a, b in steps if r0.elapsed_time(a) >= 0.0 and b.elapsed_time(r1) >= 0.0]
+            both_ms = r0.elapsed_time(r1)
+            res[f"{what}_{mode}"] = {
+                "ms_alone": round(transfer_alone_ms, 2), "ms_while_decoding": round(both_ms, 2),
+                "decode_steps_inside": len(inside),
+                "decode_ms_meanwhile": round(float(np.mean(inside)), 4) if inside else None,
+                "decode_slowdown": round(float(np.mean(inside)) / alone_ms, 3) if inside else None,
+                "transfer_slowdown": round(both_ms / transfer_alone_ms, 3)}
+            del staging
     return res
 
 
@@ -896,8 +902,9 @@ def main():
             del staging
         d2h_ms = time_steps(lambda: back_k.copy_(big, non_blocking=True), 3, 1, torch)
         d2h_gbps = n * page_bytes / d2h_ms / 1e6
+        overlapped = (None if args.kernels_only
+                      else restore_while_decoding(wb, torch, ta, page_bytes, slots, back_k, back_v))
         del big, back_k, back_v
-        overlapped = None if args.kernels_only else restore_while_decoding(wb, torch, ta, page_bytes, slots)
         kv5 = int(wb.context_lens.astype("int64").sum()) * wb.kv_bytes_per_token
         ms, kernel_ms, out, lse = run_decode(wb, max(2, min(args.steps, 10)), 2, torch, ta)
         best = min(res.values(), key=lambda r: r["ms"])
@@ -912,7 +919,7 @@ def main():
             "decode_ms": round(ms, 4), "decode_kv_gbps": round(kv5 / ms / 1e6, 1),
             "decode_kernel_frac_of_hbm_peak": round(kv5 / kernel_ms / 1e6 / HBM_PEAK_GBPS, 4),
             "restore_to_decode_time_ratio": round(best["ms"] / ms, 1),
-            "restore_while_resident_programs_decode": overlapped,
+            "transfers_while_resident_programs_decode": overlapped,
         }
         del wb, out, lse
         torch.cuda.empty_cache()

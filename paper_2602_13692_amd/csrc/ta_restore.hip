@@ -66,17 +66,21 @@ __global__ __launch_bounds__(kScatterThreads) __attribute__((amdgpu_num_vgpr(16)
     }
 }
 
-// Workgroups of one launch.  Reading or writing pinned host memory directly, 32 keep the host link
+// Workgroups of one launch.  Reading or writing pinned host memory directly, a few keep the host link
 // full (55 GB/s x a few microseconds of latency is well under a megabyte in flight; measured: the
-// same 65 ms for 5 GB with 16 .. 256 workgroups, 79 ms with 8).  More of them do harm when
-// attention runs beside the restore: every access to host memory that is on its way seems to hold
-// a place in queues that HBM traffic also passes through -- a decode step beside the restore ran 1.14 x
+// same 65 ms for 3.7 GB read with 16 .. 256 workgroups, 79 ms with 8).  More of them do harm when
+// attention runs beside the transfer: every access to host memory that is on its way seems to hold
+// a place in queues that HBM traffic also passes through -- a decode step beside a restore ran 1.14 x
 // its time alone with 8 workgroups, 1.31 x with 32, 1.61 x with 64, 3.6 x with 256 -- while the restore
-// itself needs 32 to stay within a tenth of its time alone (16: 1.7 x).  Between pool and device
-// staging the kernel is bound by HBM and takes as many workgroups as it has units.
-unsigned move_grid(int32_t n, bool over_the_link) {
+// itself needs 32 to stay within a tenth of its time alone beside decode steps (16: 1.7 x).  Writes to
+// host memory weigh more (decode 1.27 x with 16 workgroups, 1.72 x with 32) and an eviction is less
+// pressed than a restore, for which a program waits: 16 there (1.29 x its time alone beside decode
+// steps, 1.03 x when nothing else runs).  Between pool and device staging the kernel is bound by HBM
+// and takes as many workgroups as it has units.
+unsigned move_grid(int32_t n, bool over_the_link, bool to_host) {
     const unsigned units = 2u * unsigned(n);
-    return over_the_link && units > 32u ? 32u : units;
+    const unsigned cap = to_host ? 16u : 32u;
+    return over_the_link && units > cap ? cap : units;
 }
 
 // KV append: one workgroup per new token copies its K row and its V row of every kv head
@@ -182,7 +186,7 @@ int launch_evict(const void* k_pool, const void* v_pool, size_t page_bytes, void
         // zero-copy: the kernel writes the pinned host pages itself
         for (int64_t first = 0; first < n_pages;) {
             const int32_t n = fill_batch(batch, src_slots, first, n_pages);
-            hipLaunchKernelGGL(move_pages_kernel<true>, dim3(move_grid(n, true)), dim3(kScatterThreads), 0, stream,
+            hipLaunchKernelGGL(move_pages_kernel<true>, dim3(move_grid(n, true, true)), dim3(kScatterThreads), 0, stream,
                                const_cast<char*>(kp), const_cast<char*>(vp), hk + size_t(first) * page_bytes,
                                hv + size_t(first) * page_bytes, batch, n, int64_t(page_bytes));
             TA_HIP_TRY(hipGetLastError());
@@ -196,7 +200,7 @@ int launch_evict(const void* k_pool, const void* v_pool, size_t page_bytes, void
         const int64_t end = (n_pages - first) < per_round ? n_pages : first + per_round;
         for (int64_t at = first; at < end;) {
             const int32_t n = fill_batch(batch, src_slots, at, end);
-            hipLaunchKernelGGL(move_pages_kernel<true>, dim3(move_grid(n, false)), dim3(kScatterThreads), 0, stream,
+            hipLaunchKernelGGL(move_pages_kernel<true>, dim3(move_grid(n, false, false)), dim3(kScatterThreads), 0, stream,
                                const_cast<char*>(kp), const_cast<char*>(vp), stage_k + size_t(at - first) * page_bytes,
                                stage_v + size_t(at - first) * page_bytes, batch, n, int64_t(page_bytes));
             TA_HIP_TRY(hipGetLastError());
@@ -244,7 +248,7 @@ int launch_restore(void* k_pool, void* v_pool, size_t page_bytes, const void* ho
         // zero-copy: pinned host memory is mapped into the device address space
         for (int64_t first = 0; first < n_pages;) {
             const int32_t n = fill_batch(batch, dst_slots, first, n_pages);
-            hipLaunchKernelGGL(move_pages_kernel<false>, dim3(move_grid(n, true)), dim3(kScatterThreads), 0, stream, kp, vp,
+            hipLaunchKernelGGL(move_pages_kernel<false>, dim3(move_grid(n, true, false)), dim3(kScatterThreads), 0, stream, kp, vp,
                                const_cast<char*>(hk) + size_t(first) * page_bytes,
                                const_cast<char*>(hv) + size_t(first) * page_bytes, batch, n, int64_t(page_bytes));
             TA_HIP_TRY(hipGetLastError());
@@ -261,7 +265,7 @@ int launch_restore(void* k_pool, void* v_pool, size_t page_bytes, const void* ho
         TA_HIP_TRY(hipMemcpyAsync(stage_v, hv + size_t(first) * page_bytes, bytes, hipMemcpyHostToDevice, stream));
         for (int64_t at = first; at < end;) {
             const int32_t n = fill_batch(batch, dst_slots, at, end);
-            hipLaunchKernelGGL(move_pages_kernel<false>, dim3(move_grid(n, false)), dim3(kScatterThreads), 0, stream, kp, vp,
+            hipLaunchKernelGGL(move_pages_kernel<false>, dim3(move_grid(n, false, false)), dim3(kScatterThreads), 0, stream, kp, vp,
                                stage_k + size_t(at - first) * page_bytes, stage_v + size_t(at - first) * page_bytes,
                                batch, n, int64_t(page_bytes));
             TA_HIP_TRY(hipGetLastError());
