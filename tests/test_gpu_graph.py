@@ -47,8 +47,10 @@ def test_decode_replays_from_a_graph(Hq):
     assert torch.equal(out, fresh) and torch.equal(lse, fresh_lse)
 
 
-def test_append_prefill_replays_from_a_graph():
-    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 1301, batch=5, new_lo=10, new_hi=300, prefix_lo=100, prefix_hi=2000)
+@pytest.mark.parametrize("prefix_lo,prefix_hi", [(100, 1500), (3000, 9000)])   # the second: keys cut into chunks, merged
+def test_append_prefill_replays_from_a_graph(prefix_lo, prefix_hi):
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 1301, batch=5, new_lo=10, new_hi=300, prefix_lo=prefix_lo,
+                           prefix_hi=prefix_hi)
     desc = gu.desc_of(wb)
     bt = torch.from_numpy(wb.block_table).to(DEV)
     cl = torch.from_numpy(wb.context_lens).to(DEV)
