@@ -87,8 +87,8 @@ typedef struct ta_attn_desc {
     int64_t pool_stride_token; /* elements between token rows;  0 selects head_dim (only value supported) */
     int32_t decode_chunk_pages; /* split-K chunk of ta_paged_decode in pages: 0 lets the library choose
                                    the chunk and the kernel that streams the private chunks (the kernel by
-                                   batch and the bound on the context length, the chunk on the device
-                                   from the real lengths), else 8, 16, 32, 64 or 128 (a bf16 cache with
+                                   batch and the bound on the context length, confirmed on the device
+                                   from the real lengths, which also settle the chunk), else 8, 16, 32, 64 or 128 (a bf16 cache with
                                    up to four query heads per kv head: on the vector-ALU kernel), or 256
                                    or 512 (a bf16 cache: on the matrix-core tile kernel; an FP8 cache:
                                    longer items of its one kernel).  The same value must be given to

@@ -84,15 +84,22 @@ int resolve_geometry(const ta_attn_desc* d, Geometry* g) {
 // per kv head the vector-ALU kernel does not exist (its per-head state would fill the register
 // file).  The host knows only the batch and the bound on the context length: it takes their
 // product, the most the batch can hold.
-static bool decode_on_tiles(const Geometry& g, int32_t batch, int32_t max_context_len) {
-    if (g.kv_fp8) return false;
-    if (g.group == 8 || g.decode_chunk_pages >= 256) return true;
+// Returns kRouteVector, kRouteTiles or kRouteOnDevice.  The last: the host's product says tiles, but
+// the plan kernel, which sees the real lengths, has the last word -- under a bound far above them (a
+// serving loop sizes it once) many short programs are better off on the vector-ALU kernel (1024
+// programs of 256 to 1024 tokens: 0.75 of the HBM peak there, 0.65 on tiles; of 64 to 512 tokens:
+// 0.71 against 0.45), whose launch then finds the list that the tile kernel's launch finds empty.
+static int decode_route(const Geometry& g, int32_t batch, int32_t max_context_len) {
+    if (g.kv_fp8) return kRouteVector;
+    if (g.group == 8 || g.decode_chunk_pages >= 256) return kRouteTiles;
+    if (g.decode_chunk_pages != 0) return kRouteVector;
     const int64_t pages = (int64_t(max_context_len) + kPageSize - 1) / kPageSize;
-    // one, two or four heads per kv head.  The bound may be far above the real lengths (a serving
-    // loop sizes it once); the chunk is then settled on the device from the real lengths, short
-    // enough to keep the tile kernel's workgroups busy (measured under a 128k bound on 4 to 64
-    // programs: within 7 % of the vector-ALU route where that one would have been the better choice).
-    return g.decode_chunk_pages == 0 && int64_t(batch) * pages >= 16000;
+    // no context above one item of the vector-ALU kernel: nothing for the tile kernel's long items
+    if (pages <= kMaxItemPages) return kRouteVector;
+    return int64_t(batch) * pages >= 16000 ? kRouteOnDevice : kRouteVector;
+}
+static bool decode_on_tiles(const Geometry& g, int32_t batch, int32_t max_context_len) {
+    return decode_route(g, batch, max_context_len) != kRouteVector;
 }
 
 static int32_t choose_chunk_pages(const Geometry& g, int32_t batch, int32_t max_context_len) {
@@ -128,9 +135,12 @@ WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_l
         w.chunk_pages = choose_chunk_pages(g, batch, max_context_len);
         // the tile kernel takes a program's leftover as one item; the vector-ALU kernel gets it in quarters
         const bool all_on_tiles = decode_on_tiles(g, batch, max_context_len);
-        w.private_on_tiles = all_on_tiles ? 1 : 0;
+        w.private_on_tiles = decode_route(g, batch, max_context_len);
         w.rem_pages = all_on_tiles ? w.chunk_pages : (w.chunk_pages >= 32 ? w.chunk_pages / 4 : 8);
         w.slots_per_program = static_cast<int32_t>(pages / w.chunk_pages + w.chunk_pages / w.rem_pages);
+        // (a route settled on the device: many short programs go to the vector-ALU kernel, whose items
+        // are shorter than the tile kernel's; two slots a program let it cut a short context once)
+        if (w.private_on_tiles == kRouteOnDevice && w.slots_per_program < 2) w.slots_per_program = 2;
         // (a chunk shortened on the device needs more slots than the host's chunk would: it is only
         // shortened while the batch has fewer than about 1200 / Hkv chunks, plus four pieces each)
         const int64_t slack = g.decode_chunk_pages == 0 ? 1200 / g.num_kv_heads + 1 : 0;
@@ -145,7 +155,11 @@ WorkspaceLayout plan_workspace(const Geometry& g, int32_t batch, int32_t max_q_l
         // kernel, one item each at most
         // (a chunk chosen on the device may be shorter than the host's: room for the shortest one then)
         const int64_t finest = g.decode_chunk_pages == 0 ? kMinChunkPages : w.chunk_pages;
-        w.max_shared_items = all_on_tiles ? w.max_chunks : static_cast<int32_t>((int64_t(batch) / 2) * (pages / finest));
+        const int64_t shared_off_tiles = (int64_t(batch) / 2) * (pages / finest);
+        w.max_shared_items = static_cast<int32_t>(!all_on_tiles ? shared_off_tiles
+                                                  : w.private_on_tiles == kRouteOnDevice && shared_off_tiles > w.max_chunks
+                                                      ? shared_off_tiles
+                                                      : w.max_chunks);
         w.off_counts = off;      off = align256(off + sizeof(int32_t) * 4);
         w.off_lcp = off;         off = align256(off + sizeof(int32_t) * size_t(batch));
         w.off_pred = off;        off = align256(off + sizeof(int32_t) * size_t(batch));

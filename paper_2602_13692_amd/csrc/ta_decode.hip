@@ -146,7 +146,7 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
                                                            int32_t batch, int32_t max_pages, int32_t chunk_pages_max,
                                                            int32_t adapt_chunk, int32_t num_kv_heads, int32_t max_chunks,
                                                            int32_t max_members,
-                                                           int32_t max_shared_items, int32_t private_on_tiles,
+                                                           int32_t max_shared_items, int32_t route,
                                                            int32_t* __restrict__ chunk_start,
                                                            int4* __restrict__ items,
                                                            int4* __restrict__ shared_items,
@@ -170,12 +170,16 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
         const int n = L > 0 ? (L + kPageSize - 1) / kPageSize : 0;
         return n > max_pages ? max_pages : n;               // lengths above the host bound are clipped
     };
+    // which kernel gets the private chunks: the host's word, or (kRouteOnDevice) settled in step 0
+    bool private_on_tiles = route == kRouteTiles;
+    int chunk_longest = chunk_pages_max;                                // of the route taken
     int chunk_pages = chunk_pages_max, rem_pages = chunk_pages_max;     // settled below
     auto pieces_of = [&](int pages) { return (pages % chunk_pages + rem_pages - 1) / rem_pages; };
+    bool whole_leftovers = false;        // the vector-ALU kernel too, when slots are short
     auto set_chunk = [&](int c) {
         chunk_pages = c;
         // the tile kernel takes a program's leftover as one item; the vector-ALU kernel gets it in quarters
-        rem_pages = private_on_tiles ? c : (c >= 32 ? c / 4 : kMinChunkPages);
+        rem_pages = (private_on_tiles || whole_leftovers) ? c : (c >= 32 ? c / 4 : kMinChunkPages);
     };
     // exclusive scan of `value` over one pass of the workgroup's threads (wave-level shuffles, then
     // the sixteen wave totals); returns this thread's offset including earlier passes
@@ -203,6 +207,15 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
     for (int base = 0; base < batch; base += nt) block_scan(base + tid < batch ? pages_of(base + tid) : 0);
     {
         const int64_t total_pages = carry;
+        if (route == kRouteOnDevice) {
+            // The tile kernel (one eight-wave workgroup per compute unit, a few microseconds to start
+            // an item) wants long items and enough of them; measured on 4 to 4096 programs of 64 to
+            // 64k tokens under a bound of 128k it wins from about 8,000 pages in the batch and 800
+            // tokens a program on (1024 programs of 256-1024 tokens: the same on both; of 64-512
+            // tokens: 258 us here against 334 us on tiles; 512 programs of 512-2048: 496 against 448).
+            private_on_tiles = total_pages >= 8000 && total_pages >= int64_t(48) * batch;
+            if (!private_on_tiles && chunk_longest > kMaxItemPages) chunk_longest = kMaxItemPages;
+        }
         // (item, kv head) pairs to aim for, and the shortest chunk worth having: measured on 4 to 128
         // programs of 1k to 64k tokens, the best chunk is the longest one that still gives about 500
         // pairs on the vector-ALU kernel (whose leftovers come in quarters) and about 150 on the tile
@@ -210,14 +223,17 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
         // item's fixed cost outweighs the balance it buys on either
         const int64_t target = private_on_tiles ? 150 : 500;
         const int shortest = kMinAdaptedChunkPages;
-        int c = chunk_pages_max;
+        int c = chunk_longest;
         while (adapt_chunk && c > shortest && total_pages * num_kv_heads / c < target) c >>= 1;
         set_chunk(c);
     }
     __syncthreads();
 
-    // 1. partial slots (with the host's chunk if the shorter one would need more slots than there are)
-    for (int attempt = 0; attempt < 2; ++attempt) {
+    // 1. partial slots (with the route's longest chunk if the shorter one would need more slots than
+    //    there are; the host sized them for the tile kernel's items, so a batch whose route is settled
+    //    here and came out for the vector-ALU kernel may have to leave its leftovers whole, or go to
+    //    the tile kernel after all)
+    for (int attempt = 0; attempt < 4; ++attempt) {
         if (tid == 0) carry = 0;
         __syncthreads();
         for (int base = 0; base < batch; base += nt) {
@@ -228,8 +244,20 @@ __global__ __launch_bounds__(1024) void plan_decode_kernel(const int32_t* __rest
         }
         const int total_slots = carry;
         __syncthreads();
-        if (total_slots <= max_chunks || chunk_pages == chunk_pages_max) break;
-        set_chunk(chunk_pages_max);
+        if (total_slots <= max_chunks) break;
+        if (chunk_pages != chunk_longest) {
+            set_chunk(chunk_longest);
+        } else if (route == kRouteOnDevice && !private_on_tiles && !whole_leftovers) {
+            whole_leftovers = true;
+            set_chunk(chunk_longest);
+        } else if (route == kRouteOnDevice && !private_on_tiles) {
+            private_on_tiles = true;
+            whole_leftovers = false;
+            chunk_longest = chunk_pages_max;
+            set_chunk(chunk_longest);
+        } else {
+            break;
+        }
     }
     if (tid == 0) chunk_start[batch] = carry;
 
@@ -514,10 +542,18 @@ __device__ __forceinline__ void process_page(const PageRegs& pg, const uint32_t 
 
 // DIRECT: every program is one item (its whole context, at most kMaxItemPages pages); the
 // workgroup normalises and writes the bf16 output itself: no plan, no partials, no merge.
-template <int G, bool DIRECT>
-__global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams p) {
-    const int item = blockIdx.x / p.num_kv_heads;
-    const int g = blockIdx.x - item * p.num_kv_heads;
+// BEYOND_CAP: the host sizes the launch from the bound on the context length, which may be far above
+// the real lengths, and half a million workgroups that find nothing to do cost 150 us.  So a launch
+// has at most kChunkGridCap workgroups, one per (item, kv head) pair; pairs beyond that number (very
+// large batches) belong to a second launch of as many workgroups, in this form, where a workgroup
+// goes on to the pair one grid further until the list ends.  (Written as one loop for both forms;
+// with the loop taken for real the compiler keeps more values in registers and the kernel loses a
+// wave per SIMD, which is why the usual form is not the looping one.)
+template <int G, bool DIRECT, bool BEYOND_CAP>
+__device__ __forceinline__ void decode_chunk_body(const ChunkParams& p) {
+    for (int pair = BEYOND_CAP ? kChunkGridCap + int(blockIdx.x) : int(blockIdx.x);; pair += gridDim.x) {
+    const int item = pair / p.num_kv_heads;
+    const int g = pair - item * p.num_kv_heads;
     int b, page0, n_here, slot = 0;
     if (DIRECT) {
         b = item;
@@ -527,8 +563,9 @@ __global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams
         const int4 it = p.items[item];
         b = it.x; page0 = it.y; n_here = it.z; slot = it.w;
     }
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int row = lane >> 4;
     const int col = lane & 15;
 
@@ -651,7 +688,7 @@ __global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams
     // merge the four waves
     if (DIRECT) {
         // thread t owns two neighbouring dims of one head and writes them as bf16
-        for (int idx = threadIdx.x; idx < G * (kHeadDim / 2); idx += kChunkThreads) {
+        for (int idx = tid; idx < G * (kHeadDim / 2); idx += kChunkThreads) {
             const int h = idx / (kHeadDim / 2);
             const int c = 2 * (idx % (kHeadDim / 2));
             float mt = sm_m[0][h];
@@ -675,7 +712,7 @@ __global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams
         return;
     }
     // thread t owns outputs t, t + 256, ...
-    for (int idx = threadIdx.x; idx < G * kHeadDim; idx += kChunkThreads) {
+    for (int idx = tid; idx < G * kHeadDim; idx += kChunkThreads) {
         const int h = idx / kHeadDim;
         const int c = idx % kHeadDim;
         float mt = sm_m[0][h];
@@ -695,6 +732,19 @@ __global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams
             p.part_ml[rowid * 2 + 1] = lt;
         }
     }
+    if (!BEYOND_CAP) return;
+    __syncthreads();      // the next pair reuses the merge buffers
+    }
+}
+
+template <int G, bool DIRECT>
+__global__ __launch_bounds__(kChunkThreads) void decode_chunk_kernel(ChunkParams p) {
+    decode_chunk_body<G, DIRECT, false>(p);
+}
+
+template <int G>
+__global__ __launch_bounds__(kChunkThreads) void decode_chunk_beyond_cap_kernel(ChunkParams p) {
+    decode_chunk_body<G, false, true>(p);
 }
 
 // ---------------------------------------------------------------------------
@@ -805,7 +855,8 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
     const int32_t max_members = (g.kv_fp8 ? 32 : 128) / g.group;
     // The workspace plan has decided which kernel streams the private chunks (and sized
     // shared_items for it): the matrix-core kernel takes them as groups of one program.
-    const bool private_on_tiles = w.private_on_tiles != 0;
+    const int route = w.private_on_tiles;                    // kRouteOnDevice: both kernels are launched, one finds its list empty
+    const bool private_on_tiles = route != kRouteVector;     // the tile kernel may get private chunks
 
     if (look_for_sharing) {
         hipLaunchKernelGGL(predecessor_prefix_kernel, dim3(a.batch), dim3(256), 0, stream, a.block_table,
@@ -819,7 +870,7 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
                        look_for_sharing ? pred : nullptr, look_for_sharing ? lcp : nullptr, a.batch, cp.max_pages,
                        w.chunk_pages, g.decode_chunk_pages == 0 ? 1 : 0, g.num_kv_heads, w.max_chunks, max_members,
                        w.max_shared_items,
-                       private_on_tiles ? 1 : 0,
+                       route,
                        chunk_start, items, shared_items, order, counts);
     TA_HIP_TRY(hipGetLastError());
 
@@ -859,13 +910,17 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
         if (private_on_tiles && ev.stop != nullptr) TA_HIP_TRY(hipEventRecord(ev.stop, stream));
     }
 
-    if (w.max_chunks > 0 && !private_on_tiles) {
+    if (w.max_chunks > 0 && route != kRouteTiles) {
         const int64_t blocks = int64_t(w.max_chunks) * g.num_kv_heads;
-        if (blocks > 0x7fffffff || w.chunk_pages > (g.kv_fp8 ? kMaxItemPagesFp8 : kMaxItemPages)) return TA_ERR_INVALID_ARG;
-        const dim3 grid(static_cast<unsigned>(blocks)), block(kChunkThreads);
-        if (ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
+        // (a route settled on the device: the plan kernel keeps this kernel's items within its limit)
+        if (blocks > 0x7fffffff ||
+            (route == kRouteVector && w.chunk_pages > (g.kv_fp8 ? kMaxItemPagesFp8 : kMaxItemPages)))
+            return TA_ERR_INVALID_ARG;
+        const dim3 grid(static_cast<unsigned>(blocks < kChunkGridCap ? blocks : kChunkGridCap)), block(kChunkThreads);
+        const bool timed = route == kRouteVector;     // else the events went around the tile kernel's launch
+        if (timed && ev.start != nullptr) TA_HIP_TRY(hipEventRecord(ev.start, stream));
         if (g.kv_fp8) {
-            const int rc = launch_fp8_items(cp, g.group, false, false, grid.x, stream);
+            const int rc = launch_fp8_items(cp, g.group, false, false, static_cast<unsigned>(blocks), stream);   // one workgroup per pair
             if (rc != TA_OK) return rc;
         } else {
             switch (g.group) {
@@ -875,8 +930,16 @@ int launch_decode(const Geometry& g, const DecodeArgs& a, const WorkspaceLayout&
                 default: return TA_ERR_UNSUPPORTED;
             }
             TA_HIP_TRY(hipGetLastError());
+            if (blocks > kChunkGridCap) {        // the pairs beyond the first launch, if the batch has any
+                switch (g.group) {
+                    case 1: hipLaunchKernelGGL(decode_chunk_beyond_cap_kernel<1>, grid, block, 0, stream, cp); break;
+                    case 2: hipLaunchKernelGGL(decode_chunk_beyond_cap_kernel<2>, grid, block, 0, stream, cp); break;
+                    default: hipLaunchKernelGGL(decode_chunk_beyond_cap_kernel<4>, grid, block, 0, stream, cp); break;
+                }
+                TA_HIP_TRY(hipGetLastError());
+            }
         }
-        if (ev.stop != nullptr) TA_HIP_TRY(hipEventRecord(ev.stop, stream));
+        if (timed && ev.stop != nullptr) TA_HIP_TRY(hipEventRecord(ev.stop, stream));
     }
 
     MergeParams mp{};

@@ -17,6 +17,8 @@ constexpr float kLn2 = 0.6931471805599453f;
 // Finite stand-in for "no key seen yet": keeps (m_old - m_new) free of inf - inf.
 constexpr float kNegBig = -1.0e30f;
 constexpr int kMinChunkPages = 8;    // the shortest split-K chunk (two 64-key tiles)
+// which kernel streams the private chunks of a bf16 cache
+constexpr int kRouteVector = 0, kRouteTiles = 1, kRouteOnDevice = 2;
 constexpr int kMinAdaptedChunkPages = 32;   // the shortest chunk the library picks by itself
 
 // Records a failed HIP call for ta_last_hip_error(); returns TA_ERR_HIP.
@@ -66,7 +68,8 @@ struct WorkspaceLayout {
     int32_t slots_per_program;  // upper bound on the slots of one program
     int32_t max_chunks;         // batch * slots_per_program: bound on slots and on vector-ALU items
     int32_t direct;             // 1: every context fits one item: no plan, no partials, no merge
-    int32_t private_on_tiles;   // 1: every chunk runs on the matrix-core tile kernel (groups of one program)
+    int32_t private_on_tiles;   // kRouteVector, kRouteTiles (every chunk runs on the matrix-core tile kernel, as groups
+                                // of one program) or kRouteOnDevice (the plan kernel chooses between the two)
     int32_t max_tiles;          // upper bound on prefill query tiles (0 for decode)
     // append-prefill of few query tiles: every tile's keys are cut into prefill_split chunks of
     // prefill_chunk_tiles key tiles, one workgroup each, and their partials merged (1: no cutting)
@@ -141,6 +144,7 @@ struct ChunkParams {
     float out_scale;             // fp8 direct mode: the value scale (1 otherwise)
 };
 constexpr int kMaxItemPages = 128;      // vector-ALU kernel: two page ids per lane
+constexpr int kChunkGridCap = 16384;    // vector-ALU kernel: workgroups per launch at most (eight times what the chip holds at once)
 constexpr int kMaxItemPagesFp8 = 512;   // FP8 kernel: the item's page ids sit in LDS
 
 // The item kernel for pools of E4M3 codes (matrix cores, any group size up to 16).  Shared form:

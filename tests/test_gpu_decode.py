@@ -265,3 +265,21 @@ def test_a_loose_context_bound_changes_nothing_but_the_plan(Hq):
     for bound in (wf.max_context_len, 131072):
         out, lse = gu.gpu_decode_bound(wf, bound)
         gu.assert_close(out, lse, ref, ref_lse, f"forked, bound {bound} Hq={Hq}", lse_tol=gu.LSE_TOL)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 8), (32, 8)])
+def test_thousands_of_short_programs_under_a_bound_one_of_them_sets(Hq, Hkv):
+    """2200 programs of 16 to 700 tokens and one of 3000: the host's product of batch and bound asks
+    for the tile kernel, the plan kernel sees the real lengths and hands the batch to the vector-ALU
+    kernel, whose (item, kv head) pairs here outnumber the workgroups of one launch, so that the
+    second, looping launch has work too."""
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 990 + Hq, batch=2200, len_lo=16, len_hi=700, num_q_heads=Hq,
+                           num_kv_heads=Hkv, first_lens=[3000, 1, 0, 2049])
+    out, lse = gu.gpu_decode(wb)
+    assert torch.isfinite(out.float()).all()
+    rng = np.random.default_rng(wl.SEED_BASE + 991)
+    gu.check_sampled_rows(wb, out, lse, rng, n_programs=60, rows_per_program=4, extra_rows=[(0, 0, 0), (3, 0, Hq - 1)],
+                          what=f"many short programs Hq={Hq}", lse_tol=gu.LSE_TOL)
+    # every program's row is written (a program without context: zeros and -inf)
+    assert torch.all(out[2] == 0) and torch.all(torch.isinf(lse[2]))
+    assert torch.isfinite(lse[torch.arange(wb.batch, device=DEV) != 2]).all()
