@@ -12,10 +12,13 @@
 // returns, needs no copy from pageable memory and waits for nothing on the stream.
 #include "ta_internal.h"
 
+#include <mutex>
+
 namespace ta {
 namespace {
 
 constexpr int kScatterThreads = 256;
+constexpr int kTwoRoundPages = 256;    // shortest round worth a stream of its own (8 MiB of K at eight kv heads)
 constexpr int kSlotsPerLaunch = 960;   // 3840 bytes of the 4 KiB a kernel's arguments may take
 
 struct SlotBatch {
@@ -81,6 +84,47 @@ unsigned move_grid(int32_t n, bool over_the_link, bool to_host) {
     const unsigned units = 2u * unsigned(n);
     const unsigned cap = to_host ? 16u : 32u;
     return over_the_link && units > cap ? cap : units;
+}
+
+// The staged routes alternate between copies over the host link (DMA engines) and kernels between
+// staging and pool.  On one stream each waits for the other: the link idles while a kernel runs, and
+// beside attention, where a kernel launch waits for compute units behind a decode step, it idles
+// for that wait too (a staged restore took 1.12 x its time alone there).  With staging for two
+// rounds the copies go to a stream of the library's own, one per GPU, at the default priority like
+// the caller's, tied to the caller's stream by events in both directions:
+//   restore   side: [wait until the kernels of round i - 2 have read buffer i % 2] copy round i
+//             caller's: [wait for that copy] scatter round i
+//   evict     caller's: [wait until the copies of round i - 2 have left buffer i % 2] gather round i
+//             side: [wait for that gather] copy round i;  at the end the caller's stream waits for both buffers
+// so whatever the caller enqueues after the call still comes after all of it, and the side stream
+// starts only after what the caller enqueued before.  A stream that is being captured into a graph
+// keeps the single-stream order.
+struct SideLane {
+    hipStream_t stream = nullptr;
+    hipEvent_t begin = nullptr, copied[2] = {nullptr, nullptr}, moved[2] = {nullptr, nullptr};
+    bool tried = false, ok = false;
+};
+constexpr int kMaxDevices = 64;
+SideLane g_lanes[kMaxDevices];
+std::mutex g_lane_mutex;      // creation, and one staged call at a time enqueues on a GPU's lane
+
+// The current device's lane, or nullptr if it cannot be had (the caller then stays on one stream).
+SideLane* side_lane(hipStream_t caller) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(caller, &capturing) != hipSuccess || capturing != hipStreamCaptureStatusNone) return nullptr;
+    SideLane& lane = g_lanes[dev];
+    if (!lane.tried) {
+        lane.tried = true;
+        bool ok = hipStreamCreateWithFlags(&lane.stream, hipStreamNonBlocking) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&lane.begin, hipEventDisableTiming) == hipSuccess;
+        for (int i = 0; i < 2 && ok; ++i)
+            ok = hipEventCreateWithFlags(&lane.copied[i], hipEventDisableTiming) == hipSuccess &&
+                 hipEventCreateWithFlags(&lane.moved[i], hipEventDisableTiming) == hipSuccess;
+        lane.ok = ok;
+    }
+    return lane.ok ? &lane : nullptr;
 }
 
 // KV append: one workgroup per new token copies its K row and its V row of every kv head
@@ -196,19 +240,41 @@ int launch_evict(const void* k_pool, const void* v_pool, size_t page_bytes, void
     }
     char* stage_k = static_cast<char*>(staging);
     char* stage_v = stage_k + half;
-    for (int64_t first = 0; first < n_pages; first += per_round) {
-        const int64_t end = (n_pages - first) < per_round ? n_pages : first + per_round;
+    // staging for two rounds of at least kTwoRoundPages pages each, and more than one round to go: copies on the side stream
+    const int64_t per_buffer = per_round / 2;
+    std::unique_lock<std::mutex> hold(g_lane_mutex);
+    SideLane* lane = (per_buffer >= kTwoRoundPages && n_pages > per_buffer) ? side_lane(stream) : nullptr;
+    if (lane == nullptr) hold.unlock();
+    const int64_t step = lane != nullptr ? per_buffer : per_round;
+    int64_t round = 0;
+    for (int64_t first = 0; first < n_pages; first += step, ++round) {
+        const int64_t end = (n_pages - first) < step ? n_pages : first + step;
+        const int buf = lane != nullptr ? int(round & 1) : 0;
+        char* sk = stage_k + size_t(buf) * size_t(per_buffer) * page_bytes;
+        char* sv = stage_v + size_t(buf) * size_t(per_buffer) * page_bytes;
+        if (lane != nullptr && round >= 2) TA_HIP_TRY(hipStreamWaitEvent(stream, lane->copied[buf], 0));
         for (int64_t at = first; at < end;) {
             const int32_t n = fill_batch(batch, src_slots, at, end);
             hipLaunchKernelGGL(move_pages_kernel<true>, dim3(move_grid(n, false, false)), dim3(kScatterThreads), 0, stream,
-                               const_cast<char*>(kp), const_cast<char*>(vp), stage_k + size_t(at - first) * page_bytes,
-                               stage_v + size_t(at - first) * page_bytes, batch, n, int64_t(page_bytes));
+                               const_cast<char*>(kp), const_cast<char*>(vp), sk + size_t(at - first) * page_bytes,
+                               sv + size_t(at - first) * page_bytes, batch, n, int64_t(page_bytes));
             TA_HIP_TRY(hipGetLastError());
             at += n;
         }
         const size_t bytes = size_t(end - first) * page_bytes;
-        TA_HIP_TRY(hipMemcpyAsync(hk + size_t(first) * page_bytes, stage_k, bytes, hipMemcpyDeviceToHost, stream));
-        TA_HIP_TRY(hipMemcpyAsync(hv + size_t(first) * page_bytes, stage_v, bytes, hipMemcpyDeviceToHost, stream));
+        hipStream_t copy_stream = stream;
+        if (lane != nullptr) {
+            TA_HIP_TRY(hipEventRecord(lane->moved[buf], stream));
+            TA_HIP_TRY(hipStreamWaitEvent(lane->stream, lane->moved[buf], 0));
+            copy_stream = lane->stream;
+        }
+        TA_HIP_TRY(hipMemcpyAsync(hk + size_t(first) * page_bytes, sk, bytes, hipMemcpyDeviceToHost, copy_stream));
+        TA_HIP_TRY(hipMemcpyAsync(hv + size_t(first) * page_bytes, sv, bytes, hipMemcpyDeviceToHost, copy_stream));
+        if (lane != nullptr) TA_HIP_TRY(hipEventRecord(lane->copied[buf], lane->stream));
+    }
+    if (lane != nullptr) {      // the call is over, on the caller's stream, when the last copies are
+        TA_HIP_TRY(hipStreamWaitEvent(stream, lane->copied[0], 0));
+        if (round >= 2) TA_HIP_TRY(hipStreamWaitEvent(stream, lane->copied[1], 0));
     }
     return TA_OK;
 }
@@ -258,19 +324,42 @@ int launch_restore(void* k_pool, void* v_pool, size_t page_bytes, const void* ho
     }
     char* stage_k = static_cast<char*>(staging);
     char* stage_v = stage_k + half;
-    for (int64_t first = 0; first < n_pages; first += per_round) {
-        const int64_t end = (n_pages - first) < per_round ? n_pages : first + per_round;
+    const int64_t per_buffer = per_round / 2;
+    std::unique_lock<std::mutex> hold(g_lane_mutex);
+    SideLane* lane = (per_buffer >= kTwoRoundPages && n_pages > per_buffer) ? side_lane(stream) : nullptr;
+    if (lane == nullptr) hold.unlock();
+    const int64_t step = lane != nullptr ? per_buffer : per_round;
+    if (lane != nullptr) {      // the copies start after what the caller enqueued before this call
+        TA_HIP_TRY(hipEventRecord(lane->begin, stream));
+        TA_HIP_TRY(hipStreamWaitEvent(lane->stream, lane->begin, 0));
+    }
+    int64_t round = 0;
+    for (int64_t first = 0; first < n_pages; first += step, ++round) {
+        const int64_t end = (n_pages - first) < step ? n_pages : first + step;
         const size_t bytes = size_t(end - first) * page_bytes;
-        TA_HIP_TRY(hipMemcpyAsync(stage_k, hk + size_t(first) * page_bytes, bytes, hipMemcpyHostToDevice, stream));
-        TA_HIP_TRY(hipMemcpyAsync(stage_v, hv + size_t(first) * page_bytes, bytes, hipMemcpyHostToDevice, stream));
+        const int buf = lane != nullptr ? int(round & 1) : 0;
+        char* sk = stage_k + size_t(buf) * size_t(per_buffer) * page_bytes;
+        char* sv = stage_v + size_t(buf) * size_t(per_buffer) * page_bytes;
+        hipStream_t copy_stream = stream;
+        if (lane != nullptr) {
+            copy_stream = lane->stream;
+            if (round >= 2) TA_HIP_TRY(hipStreamWaitEvent(copy_stream, lane->moved[buf], 0));
+        }
+        TA_HIP_TRY(hipMemcpyAsync(sk, hk + size_t(first) * page_bytes, bytes, hipMemcpyHostToDevice, copy_stream));
+        TA_HIP_TRY(hipMemcpyAsync(sv, hv + size_t(first) * page_bytes, bytes, hipMemcpyHostToDevice, copy_stream));
+        if (lane != nullptr) {
+            TA_HIP_TRY(hipEventRecord(lane->copied[buf], copy_stream));
+            TA_HIP_TRY(hipStreamWaitEvent(stream, lane->copied[buf], 0));
+        }
         for (int64_t at = first; at < end;) {
             const int32_t n = fill_batch(batch, dst_slots, at, end);
             hipLaunchKernelGGL(move_pages_kernel<false>, dim3(move_grid(n, false, false)), dim3(kScatterThreads), 0, stream, kp, vp,
-                               stage_k + size_t(at - first) * page_bytes, stage_v + size_t(at - first) * page_bytes,
+                               sk + size_t(at - first) * page_bytes, sv + size_t(at - first) * page_bytes,
                                batch, n, int64_t(page_bytes));
             TA_HIP_TRY(hipGetLastError());
             at += n;
         }
+        if (lane != nullptr) TA_HIP_TRY(hipEventRecord(lane->moved[buf], stream));
     }
     return TA_OK;
 }

@@ -18,7 +18,7 @@ def _page_bytes(wb):
 
 
 @pytest.mark.parametrize("n", [301, 2203])      # the second needs several launches per slot list
-@pytest.mark.parametrize("mode", ["zero_copy", "staged_small", "staged_all"])
+@pytest.mark.parametrize("mode", ["zero_copy", "staged_small", "staged_all", "staged_rounds"])
 def test_evict_is_bit_exact_and_leaves_the_pool_alone(mode, n):
     wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 1100, batch=12, len_lo=100, len_hi=3000)
     page_bytes = _page_bytes(wb)
@@ -33,6 +33,8 @@ def test_evict_is_bit_exact_and_leaves_the_pool_alone(mode, n):
         nbytes = ta.ta_restore_staging_min_bytes(n)
     elif mode == "staged_small":
         nbytes = ta.ta_restore_staging_full_bytes(n, page_bytes) + 7 * 2 * page_bytes
+    elif mode == "staged_rounds":      # two buffers of 260 pages: copies on the library's side stream
+        nbytes = ta.ta_restore_staging_min_bytes(n) + 4 * 260 * page_bytes
     else:
         nbytes = ta.ta_restore_staging_min_bytes(n) + 2 * n * page_bytes + 512
     staging = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
