@@ -269,13 +269,14 @@ TA_API size_t ta_restore_staging_full_bytes(int32_t n_pages, size_t page_bytes);
  *                 large host-to-device copies into staging and a kernel scatters them;
  *                 with less, the scatter kernel reads the pinned host pages directly.
  *                 With staging for two rounds of at least 256 pages (4 * 256 * page_bytes)
- *                 and more pages than one round, the copies of one round run beside the
- *                 scatter of the round before, on a stream of the library's own (one per
- *                 GPU, default priority, created at the first such call), which starts
- *                 after everything enqueued on hip_stream before the call and which
- *                 hip_stream has waited for when it reaches the end of the call: the
- *                 ordering the caller sees is that of a single stream.  (Not while
- *                 hip_stream is being captured into a graph: then one stream does it all.)
+ *                 and more pages than one round, the copies of one round (on hip_stream)
+ *                 run beside the scatter of the round before, which goes to a stream of
+ *                 the library's own (one per GPU, default priority, created at the first
+ *                 such call); that stream starts after everything enqueued on hip_stream
+ *                 before the call, and hip_stream has waited for it when it reaches the
+ *                 end of the call: the ordering the caller sees is that of a single
+ *                 stream.  (Not while hip_stream is being captured into a graph: then one
+ *                 stream does it all.)
  *                 This is the route to take when attention runs on another stream
  *                 meanwhile: the host link stays busy while a scatter launch waits for
  *                 compute units.  Staged calls on one GPU enqueue one at a time (a lock).
@@ -299,8 +300,8 @@ TA_API int ta_kv_page_restore(void *k_pool, void *v_pool, size_t page_bytes, con
  *                 ta_restore_staging_full_bytes on the pages are gathered into it and
  *                 leave through large device-to-host copies, below that the gather kernel
  *                 writes the pinned host pages itself.  With staging for two rounds the
- *                 copies run on the library's own stream beside the next gather, as for
- *                 ta_kv_page_restore.
+ *                 gathers run on the library's own stream beside the copy of the round
+ *                 before, as for ta_kv_page_restore.
  * host_k / host_v hold the pages once hip_stream has reached the end of the call.
  * Errors as for ta_kv_page_restore (nothing is enqueued when the slot list is bad).
  */

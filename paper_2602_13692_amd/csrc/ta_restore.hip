@@ -90,15 +90,18 @@ unsigned move_grid(int32_t n, bool over_the_link, bool to_host) {
 // staging and pool.  On one stream each waits for the other: the link idles while a kernel runs, and
 // beside attention, where a kernel launch waits for compute units behind a decode step, it idles
 // for that wait too (a staged restore took 1.12 x its time alone there).  With staging for two
-// rounds the copies go to a stream of the library's own, one per GPU, at the default priority like
+// rounds the kernels go to a stream of the library's own, one per GPU, at the default priority like
 // the caller's, tied to the caller's stream by events in both directions:
-//   restore   side: [wait until the kernels of round i - 2 have read buffer i % 2] copy round i
-//             caller's: [wait for that copy] scatter round i
-//   evict     caller's: [wait until the copies of round i - 2 have left buffer i % 2] gather round i
-//             side: [wait for that gather] copy round i;  at the end the caller's stream waits for both buffers
+//   restore   caller's: [wait until the scatter of round i - 2 has read buffer i % 2] copy round i
+//             side: [wait for that copy] scatter round i;  at the end the caller's stream waits for both buffers
+//   evict     side: [wait until the copy of round i - 2 has left buffer i % 2] gather round i
+//             caller's: [wait for that gather] copy round i
 // so whatever the caller enqueues after the call still comes after all of it, and the side stream
-// starts only after what the caller enqueued before.  A stream that is being captured into a graph
-// keeps the single-stream order.
+// starts only after what the caller enqueued before.  (The copies stay on the caller's stream on
+// purpose: the runtime gives a stream's copies to a DMA engine only if it finds one free for that
+// stream, else to a copy kernel, which reads host memory at half the link's rate; measured with
+// the copies on the side stream after other streams had made copies: 120 ms instead of 66.)  A
+// stream that is being captured into a graph keeps the single-stream order.
 struct SideLane {
     hipStream_t stream = nullptr;
     hipEvent_t begin = nullptr, copied[2] = {nullptr, nullptr}, moved[2] = {nullptr, nullptr};
@@ -240,41 +243,42 @@ int launch_evict(const void* k_pool, const void* v_pool, size_t page_bytes, void
     }
     char* stage_k = static_cast<char*>(staging);
     char* stage_v = stage_k + half;
-    // staging for two rounds of at least kTwoRoundPages pages each, and more than one round to go: copies on the side stream
+    // staging for two rounds of at least kTwoRoundPages pages each, and more than one round to go: gathers on the side stream
     const int64_t per_buffer = per_round / 2;
     std::unique_lock<std::mutex> hold(g_lane_mutex);
     SideLane* lane = (per_buffer >= kTwoRoundPages && n_pages > per_buffer) ? side_lane(stream) : nullptr;
     if (lane == nullptr) hold.unlock();
     const int64_t step = lane != nullptr ? per_buffer : per_round;
+    hipStream_t kernel_stream = stream;
+    if (lane != nullptr) {      // the gathers start after what the caller enqueued before this call
+        kernel_stream = lane->stream;
+        TA_HIP_TRY(hipEventRecord(lane->begin, stream));
+        TA_HIP_TRY(hipStreamWaitEvent(kernel_stream, lane->begin, 0));
+    }
     int64_t round = 0;
     for (int64_t first = 0; first < n_pages; first += step, ++round) {
         const int64_t end = (n_pages - first) < step ? n_pages : first + step;
         const int buf = lane != nullptr ? int(round & 1) : 0;
         char* sk = stage_k + size_t(buf) * size_t(per_buffer) * page_bytes;
         char* sv = stage_v + size_t(buf) * size_t(per_buffer) * page_bytes;
-        if (lane != nullptr && round >= 2) TA_HIP_TRY(hipStreamWaitEvent(stream, lane->copied[buf], 0));
+        if (lane != nullptr && round >= 2) TA_HIP_TRY(hipStreamWaitEvent(kernel_stream, lane->copied[buf], 0));
         for (int64_t at = first; at < end;) {
             const int32_t n = fill_batch(batch, src_slots, at, end);
-            hipLaunchKernelGGL(move_pages_kernel<true>, dim3(move_grid(n, false, false)), dim3(kScatterThreads), 0, stream,
-                               const_cast<char*>(kp), const_cast<char*>(vp), sk + size_t(at - first) * page_bytes,
-                               sv + size_t(at - first) * page_bytes, batch, n, int64_t(page_bytes));
+            hipLaunchKernelGGL(move_pages_kernel<true>, dim3(move_grid(n, false, false)), dim3(kScatterThreads), 0,
+                               kernel_stream, const_cast<char*>(kp), const_cast<char*>(vp),
+                               sk + size_t(at - first) * page_bytes, sv + size_t(at - first) * page_bytes, batch, n,
+                               int64_t(page_bytes));
             TA_HIP_TRY(hipGetLastError());
             at += n;
         }
         const size_t bytes = size_t(end - first) * page_bytes;
-        hipStream_t copy_stream = stream;
         if (lane != nullptr) {
-            TA_HIP_TRY(hipEventRecord(lane->moved[buf], stream));
-            TA_HIP_TRY(hipStreamWaitEvent(lane->stream, lane->moved[buf], 0));
-            copy_stream = lane->stream;
+            TA_HIP_TRY(hipEventRecord(lane->moved[buf], kernel_stream));
+            TA_HIP_TRY(hipStreamWaitEvent(stream, lane->moved[buf], 0));
         }
-        TA_HIP_TRY(hipMemcpyAsync(hk + size_t(first) * page_bytes, sk, bytes, hipMemcpyDeviceToHost, copy_stream));
-        TA_HIP_TRY(hipMemcpyAsync(hv + size_t(first) * page_bytes, sv, bytes, hipMemcpyDeviceToHost, copy_stream));
-        if (lane != nullptr) TA_HIP_TRY(hipEventRecord(lane->copied[buf], lane->stream));
-    }
-    if (lane != nullptr) {      // the call is over, on the caller's stream, when the last copies are
-        TA_HIP_TRY(hipStreamWaitEvent(stream, lane->copied[0], 0));
-        if (round >= 2) TA_HIP_TRY(hipStreamWaitEvent(stream, lane->copied[1], 0));
+        TA_HIP_TRY(hipMemcpyAsync(hk + size_t(first) * page_bytes, sk, bytes, hipMemcpyDeviceToHost, stream));
+        TA_HIP_TRY(hipMemcpyAsync(hv + size_t(first) * page_bytes, sv, bytes, hipMemcpyDeviceToHost, stream));
+        if (lane != nullptr) TA_HIP_TRY(hipEventRecord(lane->copied[buf], stream));
     }
     return TA_OK;
 }
@@ -329,10 +333,7 @@ int launch_restore(void* k_pool, void* v_pool, size_t page_bytes, const void* ho
     SideLane* lane = (per_buffer >= kTwoRoundPages && n_pages > per_buffer) ? side_lane(stream) : nullptr;
     if (lane == nullptr) hold.unlock();
     const int64_t step = lane != nullptr ? per_buffer : per_round;
-    if (lane != nullptr) {      // the copies start after what the caller enqueued before this call
-        TA_HIP_TRY(hipEventRecord(lane->begin, stream));
-        TA_HIP_TRY(hipStreamWaitEvent(lane->stream, lane->begin, 0));
-    }
+    hipStream_t kernel_stream = lane != nullptr ? lane->stream : stream;
     int64_t round = 0;
     for (int64_t first = 0; first < n_pages; first += step, ++round) {
         const int64_t end = (n_pages - first) < step ? n_pages : first + step;
@@ -340,26 +341,26 @@ int launch_restore(void* k_pool, void* v_pool, size_t page_bytes, const void* ho
         const int buf = lane != nullptr ? int(round & 1) : 0;
         char* sk = stage_k + size_t(buf) * size_t(per_buffer) * page_bytes;
         char* sv = stage_v + size_t(buf) * size_t(per_buffer) * page_bytes;
-        hipStream_t copy_stream = stream;
-        if (lane != nullptr) {
-            copy_stream = lane->stream;
-            if (round >= 2) TA_HIP_TRY(hipStreamWaitEvent(copy_stream, lane->moved[buf], 0));
-        }
-        TA_HIP_TRY(hipMemcpyAsync(sk, hk + size_t(first) * page_bytes, bytes, hipMemcpyHostToDevice, copy_stream));
-        TA_HIP_TRY(hipMemcpyAsync(sv, hv + size_t(first) * page_bytes, bytes, hipMemcpyHostToDevice, copy_stream));
-        if (lane != nullptr) {
-            TA_HIP_TRY(hipEventRecord(lane->copied[buf], copy_stream));
-            TA_HIP_TRY(hipStreamWaitEvent(stream, lane->copied[buf], 0));
+        if (lane != nullptr && round >= 2) TA_HIP_TRY(hipStreamWaitEvent(stream, lane->moved[buf], 0));
+        TA_HIP_TRY(hipMemcpyAsync(sk, hk + size_t(first) * page_bytes, bytes, hipMemcpyHostToDevice, stream));
+        TA_HIP_TRY(hipMemcpyAsync(sv, hv + size_t(first) * page_bytes, bytes, hipMemcpyHostToDevice, stream));
+        if (lane != nullptr) {      // (the first scatter thereby also comes after what the caller enqueued before the call)
+            TA_HIP_TRY(hipEventRecord(lane->copied[buf], stream));
+            TA_HIP_TRY(hipStreamWaitEvent(kernel_stream, lane->copied[buf], 0));
         }
         for (int64_t at = first; at < end;) {
             const int32_t n = fill_batch(batch, dst_slots, at, end);
-            hipLaunchKernelGGL(move_pages_kernel<false>, dim3(move_grid(n, false, false)), dim3(kScatterThreads), 0, stream, kp, vp,
-                               sk + size_t(at - first) * page_bytes, sv + size_t(at - first) * page_bytes,
-                               batch, n, int64_t(page_bytes));
+            hipLaunchKernelGGL(move_pages_kernel<false>, dim3(move_grid(n, false, false)), dim3(kScatterThreads), 0,
+                               kernel_stream, kp, vp, sk + size_t(at - first) * page_bytes,
+                               sv + size_t(at - first) * page_bytes, batch, n, int64_t(page_bytes));
             TA_HIP_TRY(hipGetLastError());
             at += n;
         }
-        if (lane != nullptr) TA_HIP_TRY(hipEventRecord(lane->moved[buf], stream));
+        if (lane != nullptr) TA_HIP_TRY(hipEventRecord(lane->moved[buf], kernel_stream));
+    }
+    if (lane != nullptr) {      // the call is over, on the caller's stream, when the last scatters are
+        TA_HIP_TRY(hipStreamWaitEvent(stream, lane->moved[0], 0));
+        if (round >= 2) TA_HIP_TRY(hipStreamWaitEvent(stream, lane->moved[1], 0));
     }
     return TA_OK;
 }
