@@ -15,7 +15,11 @@ The same JSON line carries
   cpu_baseline  the fp64 oracle timed on this host's cores on the same batch;
   extra         the same batch on the vector-ALU kernel and over an FP8 cache,
                 append-prefill (MFMA, TFLOP/s), forked-prefix decode,
-                restore-then-decode, restore against recompute, the policy simulator.
+                restore-then-decode (also: restore and evict on a second stream while
+                the resident programs decode), restore against recompute, the policy
+                simulator.
+Other modes print a table of their own: --decode-sweep, --prefill-sweep, --crossover,
+--schedule-demo.
 """
 from __future__ import annotations
 
