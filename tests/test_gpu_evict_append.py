@@ -139,3 +139,34 @@ def test_append_and_evict_reject_bad_arguments():
     assert ta.ta_kv_page_evict(wb.k_pool, wb.v_pool, page_bytes, host, host.clone().pin_memory(), bad,
                                wb.pool_pages, staging, check=False) == ta.TA_ERR_INVALID_ARG
     assert not host.any()
+
+
+@pytest.mark.parametrize("mode", ["zero_copy", "staged_rounds"])
+def test_evict_on_a_second_stream_while_the_batch_decodes(mode):
+    """A program is paused while the batch keeps decoding (Sec. 4.3): the eviction only reads the
+    pools, on a stream of its own; the pages arrive bit-exact and every decode step beside it gives
+    what it gives alone."""
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 1120, batch=24, len_lo=500, len_hi=6000)
+    page_bytes = _page_bytes(wb)
+    rng = np.random.default_rng(wl.SEED_BASE + 1121)
+    n = 1500
+    src = rng.integers(0, wb.pool_pages, size=n).astype(np.int32)
+    kp = wl.as_u16(wb.k_pool).copy().view(np.uint8).reshape(wb.pool_pages, page_bytes)
+    vp = wl.as_u16(wb.v_pool).copy().view(np.uint8).reshape(wb.pool_pages, page_bytes)
+    want_k = np.zeros((n, page_bytes), np.uint8)
+    want_v = np.zeros((n, page_bytes), np.uint8)
+    assert oracle.kv_page_evict(kp, vp, page_bytes, want_k, want_v, src, wb.pool_pages) == 0
+    alone_out, alone_lse = gu.gpu_decode(wb)
+    extra = 0 if mode == "zero_copy" else 4 * 260 * page_bytes
+    staging = torch.empty(ta.ta_restore_staging_min_bytes(n) + extra, dtype=torch.uint8, device=DEV)
+    host_k = torch.zeros((n, page_bytes), dtype=torch.uint8).pin_memory()
+    host_v = torch.zeros((n, page_bytes), dtype=torch.uint8).pin_memory()
+    side = torch.cuda.Stream(device=DEV)
+    torch.cuda.synchronize()
+    ta.ta_kv_page_evict(wb.k_pool, wb.v_pool, page_bytes, host_k, host_v, torch.from_numpy(src.copy()), wb.pool_pages,
+                        staging, side)
+    results = [gu.gpu_decode(wb) for _ in range(4)]
+    torch.cuda.synchronize()
+    for out, lse in results:
+        assert torch.equal(out.view(torch.int16), alone_out.view(torch.int16)) and torch.equal(lse, alone_lse)
+    assert np.array_equal(host_k.numpy(), want_k) and np.array_equal(host_v.numpy(), want_v)
