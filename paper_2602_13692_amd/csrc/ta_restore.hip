@@ -113,10 +113,19 @@ std::mutex g_lane_mutex;      // creation, and one staged call at a time enqueue
 
 // The current device's lane, or nullptr if it cannot be had (the caller then stays on one stream).
 SideLane* side_lane(hipStream_t caller) {
+    // (a query that fails here only means "stay on one stream": its error must not be found later by
+    // the checks after the kernel launches)
     int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
     hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(caller, &capturing) != hipSuccess || capturing != hipStreamCaptureStatusNone) return nullptr;
+    if (hipStreamIsCapturing(caller, &capturing) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    if (capturing != hipStreamCaptureStatusNone) return nullptr;
     SideLane& lane = g_lanes[dev];
     if (!lane.tried) {
         lane.tried = true;
@@ -126,6 +135,7 @@ SideLane* side_lane(hipStream_t caller) {
             ok = hipEventCreateWithFlags(&lane.copied[i], hipEventDisableTiming) == hipSuccess &&
                  hipEventCreateWithFlags(&lane.moved[i], hipEventDisableTiming) == hipSuccess;
         lane.ok = ok;
+        if (!ok) (void)hipGetLastError();
     }
     return lane.ok ? &lane : nullptr;
 }

@@ -80,3 +80,46 @@ def test_append_prefill_replays_from_a_graph(prefix_lo, prefix_hi):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(out, eager) and torch.equal(lse, eager_lse), f"replay {replay}"
+
+
+def test_staged_restore_replays_from_a_graph():
+    """With staging for two rounds the library would put the scatter kernels on a stream of its own; a
+    stream under capture keeps everything on the one stream, and the graph replays bit-exactly."""
+    import numpy as np
+    import oracle
+
+    wb = wl.long_horizon_restore(DEV, seed=wl.SEED_BASE + 1310, batch=24, median=2000, sigma=0.75, len_lo=16, len_cap=9000)
+    rs = wb.restore
+    page_bytes = wb.num_kv_heads * 16 * 128 * 2
+    n = int(rs.dst_slots.shape[0])
+    assert n > 600
+    kp = wl.as_u16(wb.k_pool).copy().view(np.uint8).reshape(wb.pool_pages, page_bytes)
+    vp = wl.as_u16(wb.v_pool).copy().view(np.uint8).reshape(wb.pool_pages, page_bytes)
+    hk = wl.as_u16(rs.host_k).view(np.uint8).reshape(-1, page_bytes)
+    hv = wl.as_u16(rs.host_v).view(np.uint8).reshape(-1, page_bytes)
+    assert oracle.kv_page_restore(kp, vp, page_bytes, hk, hv, rs.dst_slots, wb.pool_pages) == 0
+    staging = torch.empty(4 * 260 * page_bytes, dtype=torch.uint8, device=DEV)
+    slots = torch.from_numpy(rs.dst_slots.copy())
+    k0, v0 = wb.k_pool.clone(), wb.v_pool.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+
+    def call():
+        ta.ta_kv_page_restore(wb.k_pool, wb.v_pool, page_bytes, rs.host_k, rs.host_v, slots, wb.pool_pages, staging, side)
+
+    with torch.cuda.stream(side):
+        call()                       # eager: kernels on the library's side stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            call()                   # captured: one stream
+    torch.cuda.synchronize()
+    for replay in range(2):
+        wb.k_pool.copy_(k0)
+        wb.v_pool.copy_(v0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got_k = wl.as_u16(wb.k_pool).view(np.uint8).reshape(wb.pool_pages, page_bytes)
+        got_v = wl.as_u16(wb.v_pool).view(np.uint8).reshape(wb.pool_pages, page_bytes)
+        assert np.array_equal(got_k, kp) and np.array_equal(got_v, vp), f"replay {replay}"
