@@ -205,8 +205,8 @@ __device__ __forceinline__ void process_block(const BlockRegs& r, const bf16x8 (
 // (column = member * group + head, up to 32 / group members), the pages are streamed once, every
 // operand serves both sets while it is in registers, and every member gets its partial in its
 // own slot.
-template <bool DIRECT, bool SHARED>
-__global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int32_t group) {
+template <bool DIRECT, bool SHARED, bool BEYOND_CAP>
+__device__ __forceinline__ void decode_fp8_body(const ChunkParams& p, int32_t group) {
     constexpr int SETS = SHARED ? 2 : 1;
     // the waves' V tiles during the walk, the waves' results afterwards
     __shared__ __attribute__((aligned(16))) char smem[kWaves * kStageBytes];
@@ -216,10 +216,16 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
     static_assert(kWaves * kStageBytes >= kWaves * kMaxGroup * kHeadDim * 4, "the merge reuses the V tiles' memory");
 
     const int g = blockIdx.x % p.num_kv_heads;
-    // (shared form: the launch is sized for the most shared chunks a batch could have, far more
-    // than it usually has, so a bounded number of workgroups walks the list)
-    const int item_step = SHARED ? int(gridDim.x) / p.num_kv_heads : 0;
-    for (int item = blockIdx.x / p.num_kv_heads;; item += item_step) {
+    // The launches are sized for the most items a batch could have under its bound on the context
+    // length, often far more than it has (half a million workgroups that find nothing to do cost
+    // 150 us).  Shared form: a bounded number of workgroups walks the list.  Private form: a launch
+    // has at most kChunkGridCap workgroups, one item each; items beyond that number (very large
+    // batches) belong to a second launch of as many workgroups, in the BEYOND_CAP form, which walks
+    // the rest of the list.  (The walking form of the private kernel needs 226 registers instead
+    // of 180 and streamed config 2 four per cent slower: hence two forms.)
+    const int per_grid = int(gridDim.x) / p.num_kv_heads;
+    const int item_step = (SHARED || BEYOND_CAP) ? per_grid : 0;
+    for (int item = blockIdx.x / p.num_kv_heads + (BEYOND_CAP ? per_grid : 0);; item += item_step) {
         int b, page0, n_here, slot = 0, members = 1, chunk = 0, first_pos = 0;
         if (SHARED) {
             if (item >= p.counts[1]) return;
@@ -397,9 +403,18 @@ __global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int
                 }
             }
         }
-        if (!SHARED) break;
+        if (!SHARED && !BEYOND_CAP) break;
         __syncthreads();                               // the merge buffers are the next item's V tiles
     }
+}
+
+template <bool DIRECT, bool SHARED>
+__global__ __launch_bounds__(kThreads) void decode_fp8_kernel(ChunkParams p, int32_t group) {
+    decode_fp8_body<DIRECT, SHARED, false>(p, group);
+}
+
+__global__ __launch_bounds__(kThreads) void decode_fp8_beyond_cap_kernel(ChunkParams p, int32_t group) {
+    decode_fp8_body<false, false, true>(p, group);
 }
 
 // Append-prefill over an FP8 cache runs the bf16 tile kernel on a widened copy of the batch's
@@ -451,7 +466,16 @@ int launch_fp8_items(const ChunkParams& p, int32_t group, bool direct, bool shar
     if (group < 1 || group > kMaxGroup || (direct && shared)) return TA_ERR_UNSUPPORTED;
     if (shared) hipLaunchKernelGGL((decode_fp8_kernel<false, true>), dim3(blocks), dim3(kThreads), 0, stream, p, group);
     else if (direct) hipLaunchKernelGGL((decode_fp8_kernel<true, false>), dim3(blocks), dim3(kThreads), 0, stream, p, group);
-    else hipLaunchKernelGGL((decode_fp8_kernel<false, false>), dim3(blocks), dim3(kThreads), 0, stream, p, group);
+    else {
+        // at most kChunkGridCap workgroups, a whole number of kv-head sets (the kernel steps by grid / kv heads items)
+        const unsigned sets = kChunkGridCap / unsigned(p.num_kv_heads) > 0 ? kChunkGridCap / unsigned(p.num_kv_heads) : 1u;
+        const unsigned cap = sets * unsigned(p.num_kv_heads);
+        hipLaunchKernelGGL((decode_fp8_kernel<false, false>), dim3(blocks < cap ? blocks : cap), dim3(kThreads), 0, stream, p, group);
+        if (blocks > cap) {
+            TA_HIP_TRY(hipGetLastError());
+            hipLaunchKernelGGL(decode_fp8_beyond_cap_kernel, dim3(cap), dim3(kThreads), 0, stream, p, group);
+        }
+    }
     TA_HIP_TRY(hipGetLastError());
     return TA_OK;
 }

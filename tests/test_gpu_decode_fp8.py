@@ -245,3 +245,15 @@ def test_a_cache_grown_by_append_decodes_like_the_oracles():
     out, lse = gu.gpu_decode_fp8(wb, fc)
     ref, ref_lse = gu.oracle_decode_fp8(wb, fc)
     gu.assert_close(out, lse, ref, ref_lse, "fp8 cache grown by append", lse_tol=gu.LSE_TOL_FP8)
+
+
+def test_thousands_of_short_programs_over_an_fp8_cache():
+    """2200 programs of 16 to 700 tokens and one of 3000 (so the call is not the single-launch form): the
+    batch has more (item, kv head) pairs than one launch has workgroups, and the second, walking launch
+    of the kernel has work too.  Every row against the oracle."""
+    wb = wl.llama8b_decode(DEV, seed=wl.SEED_BASE + 995, batch=2200, len_lo=16, len_hi=700, num_q_heads=16,
+                           num_kv_heads=8, first_lens=[3000, 1, 0, 2049])
+    fc = wl.to_fp8_cache(wb)
+    out, lse = gu.gpu_decode_fp8(wb, fc)
+    ref, ref_lse = gu.oracle_decode_fp8(wb, fc)
+    gu.assert_close(out, lse, ref, ref_lse, "many short programs, fp8 cache", lse_tol=gu.LSE_TOL_FP8)
