@@ -44,7 +44,7 @@ TRAFFIC_BYTES = {"bf4ede3c947c6fcb": 5081000000}
 # The same batch on the vector-ALU kernel (the library's choice for smaller batches).
 VECTOR_TRAFFIC_BYTES = {"3c00f0907d8a1e28": 5081000000}
 # The same for the FP8-cache decode kernel.
-FP8_TRAFFIC_BYTES = {"bdb0d2155170f1cb": 2554000000}
+FP8_TRAFFIC_BYTES = {"cd0f3df5654f75cc": 2554000000}
 # The same for the append-prefill tile kernel: bytes that left the L2 per launch (FETCH_SIZE scaled).
 PREFILL_TRAFFIC_BYTES = {"bf4ede3c947c6fcb": 16480000000}
 
