@@ -143,3 +143,18 @@ def test_any_number_of_key_chunks_gives_the_same_result(key_chunks):
     out, lse = gu.gpu_prefill(wb, key_chunks=key_chunks)
     ref, ref_lse = gu.oracle_prefill(wb)
     gu.assert_close(out, lse, ref, ref_lse, f"key chunks {key_chunks}", lse_tol=gu.LSE_TOL)
+
+
+@pytest.mark.parametrize("Hq,Hkv,chunks", [(8, 1, 0), (4, 2, 4)])
+def test_cut_keys_with_more_programs_than_a_wave_has_lanes(Hq, Hkv, chunks):
+    """Eighty programs of a few tokens each with one or two kv heads: few enough (tile, kv head) pairs
+    for the keys to be cut (the library's own choice with one kv head, asked for with two), too many
+    programs for the tile kernel to work the tile list out in one wave, so the plan kernel's list is
+    used together with the chunks."""
+    wb = wl.append_prefill(DEV, seed=wl.SEED_BASE + 985, batch=80, new_lo=1, new_hi=20, prefix_lo=2500,
+                           prefix_hi=6000, num_q_heads=Hq, num_kv_heads=Hkv)
+    assert ta.ta_workspace_bytes(gu.desc_of(wb, prefill_key_chunks=chunks), wb.batch, wb.max_q_len, wb.max_context_len) > \
+        ta.ta_workspace_bytes(gu.desc_of(wb, prefill_key_chunks=1), wb.batch, wb.max_q_len, wb.max_context_len)
+    out, lse = gu.gpu_prefill(wb, key_chunks=chunks)
+    ref, ref_lse = gu.oracle_prefill(wb)
+    gu.assert_close(out, lse, ref, ref_lse, f"cut keys, 80 programs, Hq={Hq} Hkv={Hkv}", lse_tol=gu.LSE_TOL)
